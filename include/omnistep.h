@@ -1,0 +1,212 @@
+/*
+ * omnistep — one synchronous dynamic-batching SGD step for K simulated
+ * heterogeneous workers on one MI355X (gfx950).
+ *
+ * The library follows OmniLearn (arXiv 2503.17469): a proportional controller
+ * sizes each worker's mini-batch b_k from its throughput while the global batch
+ * B = sum_k b_k stays fixed (section "Dynamic-Batching", equations
+ * itrtimeerror / dynbszadjust / dynbszGlobalBFixed, procedure getBsz of
+ * Algorithm 1); every worker computes the mean gradient over its own b_k
+ * samples; the gradients are combined with weights lambda_k = b_k / sum_i b_i
+ * (equation bspweightedgrads) and applied as theta <- theta - eta * sum_k
+ * lambda_k g_k (equation bspvariableSGD; the AllReduce and update lines of
+ * procedure Train in Algorithm 1).
+ *
+ * The K workers' samples arrive as ONE ragged batch: worker k owns rows
+ * off[k] .. off[k+1]-1 of the concatenated input, off being the exclusive
+ * prefix sum of b.  Re-sizing the b_k therefore costs O(K) host integers, not a
+ * re-batching of data.
+ *
+ * Conventions for every call
+ *   - returns OMNI_OK (0) or a negative error code; never throws, never aborts;
+ *     omni_last_error() gives a thread-local message for the last failure;
+ *   - "host" pointers are ordinary process memory, "dev" pointers are device
+ *     memory of the current HIP device; the library never frees or keeps
+ *     caller memory beyond what is stated;
+ *   - GPU work is enqueued on the hipStream_t passed as `void* stream`
+ *     (NULL = the default stream) and the call returns without synchronising;
+ *     buffers must stay alive until the stream has passed the enqueued work;
+ *   - host-side validation happens before anything is launched: on error no
+ *     kernel has been enqueued.
+ */
+#ifndef OMNISTEP_H
+#define OMNISTEP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  OMNI_OK = 0,
+  OMNI_EINVAL = -1,      /* malformed argument (NULL, non-positive size, b_k < 1, off/b mismatch, ...) */
+  OMNI_EINFEASIBLE = -2, /* bounds cannot be met with sum b_k = B */
+  OMNI_EOVERFLOW = -3,   /* an integer product would not fit */
+  OMNI_ECAPACITY = -4,   /* K > K_max, B > B_max, or a compiled-in limit exceeded */
+  OMNI_EHIP = -5         /* a HIP runtime call failed */
+};
+
+enum { OMNI_F32 = 0, OMNI_BF16 = 1 };
+
+/* Largest K any call accepts (segment tables are passed to kernels by value). */
+#define OMNI_MAX_WORKERS 64
+
+const char* omni_last_error(void);
+const char* omni_version(void);
+
+/* ------------------------------------------------------------------ controller
+ * Host only, integers only, no GPU needed.
+ *
+ * Given per-worker throughputs T_k (samples per unit time in any common
+ * unit), the proportional controller of section "Dynamic-Batching" moves every
+ * worker to the batch size that takes the cluster-average time, b_k - T_k *
+ * tau_k = T_k * mean(t); the fixed-global-batch rule then rescales so that
+ * sum_k b_k = B.  Together: b_k = B * T_k / sum_j T_j, which does not depend on
+ * the previous batch sizes, so the controller is stateless.  The rescaling is
+ * multiplicative (the paper's text) rather than the equal-share subtraction of
+ * the printed equation.  Real values become integers by largest remainder,
+ * ties to the lowest worker index.  Bounds b_min <= b_k <= b_max (procedure
+ * getBsz) are enforced by clamping the violating side with the larger total
+ * violation and re-apportioning the remaining workers, repeated until none
+ * violates.
+ */
+typedef struct omni_ctl omni_ctl;
+
+/* K in [1, OMNI_MAX_WORKERS], B >= K, 1 <= b_min <= b_max; b_max = 0 means B.
+ * OMNI_EINFEASIBLE if K*b_min > B or K*b_max < B. *out is owned by the caller
+ * and released with omni_ctl_destroy. */
+int omni_ctl_create(int32_t K, int32_t B, int32_t b_min, int32_t b_max, omni_ctl** out);
+
+/* T: host [K], every entry > 0 (else OMNI_EINVAL); copied. */
+int omni_ctl_set_throughputs(omni_ctl* ctl, const uint64_t* T);
+
+/* Writes b_out host [K] and off_out host [K+1] (off[0] = 0, off[K] = B).
+ * OMNI_EINVAL if no throughputs were set; OMNI_EINFEASIBLE if clamping cannot
+ * reach sum B.  Exact integer arithmetic (128-bit products): results are
+ * reproducible bit for bit. */
+int omni_ctl_run(omni_ctl* ctl, int32_t* b_out, int32_t* off_out);
+
+void omni_ctl_destroy(omni_ctl* ctl);
+
+/* ------------------------------------------------------------------ network
+ * A network is a list of layers over channels-last activations [rows, H, W, C].
+ * `src` / `src2` name the producing layer (-1 = the network input); src2 is
+ * used by OMNI_OP_ADD only.  The last layer's output is the logits [rows, C].
+ *
+ *   OMNI_OP_LINEAR   y = x W^T + bias     W [cout][cin], input flattened (h,w,c)
+ *   OMNI_OP_CONV     ksize x ksize, stride, zero pad; W [cout][kh][kw][cin]
+ *   OMNI_OP_RELU     max(x, 0); derivative 0 at 0
+ *   OMNI_OP_MAXPOOL2 2x2 window, stride 2; gradient to the first maximum in
+ *                    (dy, dx) scan order
+ *   OMNI_OP_BN       batch norm with the statistics of EACH WORKER'S OWN ROWS
+ *                    (biased variance, eps = 1e-5), channels = cin
+ *   OMNI_OP_ADD      elementwise sum of two equal-shaped tensors
+ *   OMNI_OP_GAP      mean over H and W
+ *
+ * Parameters are one flat fp32 vector in layer order: weight then bias (if
+ * `bias` != 0) for LINEAR / CONV, gamma then beta for BN.
+ */
+enum {
+  OMNI_OP_LINEAR = 0,
+  OMNI_OP_CONV = 1,
+  OMNI_OP_RELU = 2,
+  OMNI_OP_MAXPOOL2 = 3,
+  OMNI_OP_BN = 4,
+  OMNI_OP_ADD = 5,
+  OMNI_OP_GAP = 6
+};
+
+typedef struct omni_layer_desc {
+  int32_t op;
+  int32_t src;
+  int32_t src2;
+  int32_t cin;
+  int32_t cout;
+  int32_t ksize;
+  int32_t stride;
+  int32_t pad;
+  int32_t bias;
+} omni_layer_desc;
+
+typedef struct omni_net omni_net;
+
+/* Builds the launch plan for (layers, input shape, dtype, K_max, B_max).  Host
+ * only: allocates no device memory and compiles nothing, now or later.
+ * dtype OMNI_F32: fp32 operands and activations.  dtype OMNI_BF16: bf16
+ * operands and stored activations, fp32 accumulation, fp32 master parameters,
+ * gradients and loss.  OMNI_EINVAL on a malformed layer list or an unsupported
+ * combination. */
+int omni_net_create(const omni_layer_desc* layers, int32_t n_layers,
+                    int32_t in_h, int32_t in_w, int32_t in_c,
+                    int32_t dtype, int32_t K_max, int32_t B_max, omni_net** out);
+
+/* Number of fp32 parameters P. */
+size_t omni_net_param_count(const omni_net* net);
+
+/* Bytes of device workspace omni_step needs (activations, activation
+ * gradients, the K_max per-worker gradient rows, small tables).  The caller
+ * allocates it (256-byte aligned) and may reuse it across steps. */
+size_t omni_net_workspace_bytes(const omni_net* net);
+
+/* Row stride, in floats, of the per-worker gradient matrix (>= P, multiple of 64). */
+size_t omni_net_grad_stride(const omni_net* net);
+
+/* One training step (Algorithm 1, procedure Train: gradient, AllReduce, update).
+ *
+ *   params          dev [P] fp32, read and overwritten with theta - lr * g
+ *   x               dev, off[K] rows of in_h*in_w*in_c values, fp32 or bf16 per dtype
+ *   labels          dev [off[K]] int32 in [0, classes)
+ *   off, b          host [K+1], [K]: off[0] = 0, off[k+1] - off[k] = b[k] >= 1,
+ *                   off[K] <= B_max, K <= K_max           (else OMNI_EINVAL / OMNI_ECAPACITY)
+ *   lr              finite
+ *   workspace       dev, omni_net_workspace_bytes(net) bytes
+ *   loss_per_worker dev [K] fp32: L_k = mean loss over worker k's rows
+ *   loss            dev [1] fp32: sum_k lambda_k L_k
+ *   flags           OMNI_STEP_NO_UPDATE leaves params untouched (gradients only)
+ *
+ * After the step the workspace holds g_k (mean gradient of worker k) in row k
+ * of the matrix returned by omni_net_worker_grads.  A label outside
+ * [0, classes) sets bit 0 of the status word (omni_net_status) and contributes
+ * zero loss and zero gradient. */
+enum { OMNI_STEP_NO_UPDATE = 1u };
+
+int omni_step(omni_net* net, void* stream, float* params, const void* x,
+              const int32_t* labels, const int32_t* off, const int32_t* b, int32_t K,
+              float lr, void* workspace, float* loss_per_worker, float* loss,
+              uint32_t flags);
+
+/* Views into a workspace (device pointers; valid while the workspace is). */
+const float* omni_net_worker_grads(const omni_net* net, const void* workspace);
+const uint32_t* omni_net_status(const omni_net* net, const void* workspace);
+/* Output of layer `layer` as stored by the last step: *ptr dev pointer (fp32 or
+ * bf16 per dtype), *elems_per_row its row length.  Layers fused away into a
+ * neighbour alias that neighbour's tensor.  OMNI_EINVAL on a bad index. */
+int omni_net_activation(const omni_net* net, const void* workspace, int32_t layer,
+                        const void** ptr, size_t* elems_per_row);
+
+void omni_net_destroy(omni_net* net);
+
+/* ------------------------------------------------------------------ single kernels
+ * The aggregation + update of equations bspweightedgrads / bspvariableSGD on
+ * its own: params[j] -= lr * sum_k (b[k] / sum_i b[i]) * grads[k*stride + j].
+ *   params dev [P] in/out; grads dev [K][stride] fp32; b host [K], each >= 1;
+ *   shadow_bf16: dev [P] uint16 receiving the updated params rounded to bf16
+ *   (nearest even), or NULL. */
+int omni_weighted_sgd(void* stream, float* params, const float* grads, size_t stride,
+                      size_t P, const int32_t* b, int32_t K, float lr, void* shadow_bf16);
+
+/* Softmax cross-entropy over a ragged batch: for row s of worker k,
+ * loss_rows[s] = -log softmax(z_s)[y_s] and dz_s = (softmax(z_s) - e_{y_s}) / b_k
+ * (the 1/|b_k| of equation bspweightedgrads), then L_k and sum_k lambda_k L_k.
+ *   z dev [off[K]][C] fp32, labels dev int32, dz dev like z, loss_rows dev [off[K]],
+ *   loss_per_worker dev [K], loss dev [1], status dev [1] (bit 0: bad label), off host [K+1]. */
+int omni_softmax_xent(void* stream, const float* z, const int32_t* labels, int32_t C,
+                      const int32_t* off, int32_t K, float* dz, float* loss_rows,
+                      float* loss_per_worker, float* loss, uint32_t* status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OMNISTEP_H */

@@ -1,0 +1,10 @@
+"""MI355X-native ragged, batch-size-weighted SGD step (OmniLearn dynamic batching).
+
+Thin Python face of libomnistep.so; see include/omnistep.h for the contract.
+"""
+from . import binding
+from .binding import (  # noqa: F401
+    OmniError, ctl_create, ctl_destroy, ctl_run, ctl_set_throughputs, last_error, net_activation,
+    net_create, net_destroy, net_grad_stride, net_param_count, net_status, net_worker_grads,
+    net_workspace_bytes, softmax_xent, step, weighted_sgd,
+)

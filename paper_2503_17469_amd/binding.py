@@ -1,0 +1,208 @@
+"""ctypes binding of libomnistep.so: argument marshalling only.
+
+Every function maps one to one onto an `omni_*` entry point of
+include/omnistep.h.  Device buffers are torch tensors used purely as owners of
+HBM; their `data_ptr()` and the current stream's handle are what crosses the
+boundary.  Nothing here computes: if the shared library is missing the import
+fails loudly, there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Sequence
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libomnistep.so")
+
+OK, EINVAL, EINFEASIBLE, EOVERFLOW, ECAPACITY, EHIP = 0, -1, -2, -3, -4, -5
+F32, BF16 = 0, 1
+MAX_WORKERS = 64
+STEP_NO_UPDATE = 1
+OPS = {"linear": 0, "conv": 1, "relu": 2, "maxpool2": 3, "bn": 4, "add": 5, "gap": 6}
+
+EXPORTS = [
+    "omni_last_error", "omni_version",
+    "omni_ctl_create", "omni_ctl_set_throughputs", "omni_ctl_run", "omni_ctl_destroy",
+    "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
+    "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
+    "omni_weighted_sgd", "omni_softmax_xent",
+]
+
+
+class OmniError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"omnistep error {code}: {msg}")
+        self.code = code
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("op", "src", "src2", "cin", "cout", "ksize", "stride", "pad", "bias")]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    lib = C.CDLL(LIB_PATH)
+    vp, i32, u64, sz, f32, u32 = C.c_void_p, C.c_int32, C.c_uint64, C.c_size_t, C.c_float, C.c_uint32
+    P = C.POINTER
+    lib.omni_last_error.restype = C.c_char_p
+    lib.omni_version.restype = C.c_char_p
+    lib.omni_ctl_create.argtypes = [i32, i32, i32, i32, P(vp)]
+    lib.omni_ctl_set_throughputs.argtypes = [vp, P(u64)]
+    lib.omni_ctl_run.argtypes = [vp, P(i32), P(i32)]
+    lib.omni_ctl_destroy.argtypes = [vp]
+    lib.omni_ctl_destroy.restype = None
+    lib.omni_net_create.argtypes = [P(LayerDesc), i32, i32, i32, i32, i32, i32, i32, P(vp)]
+    lib.omni_net_param_count.argtypes = [vp]
+    lib.omni_net_param_count.restype = sz
+    lib.omni_net_workspace_bytes.argtypes = [vp]
+    lib.omni_net_workspace_bytes.restype = sz
+    lib.omni_net_grad_stride.argtypes = [vp]
+    lib.omni_net_grad_stride.restype = sz
+    lib.omni_step.argtypes = [vp, vp, vp, vp, vp, P(i32), P(i32), i32, f32, vp, vp, vp, u32]
+    lib.omni_net_worker_grads.argtypes = [vp, vp]
+    lib.omni_net_worker_grads.restype = vp
+    lib.omni_net_status.argtypes = [vp, vp]
+    lib.omni_net_status.restype = vp
+    lib.omni_net_activation.argtypes = [vp, vp, i32, P(vp), P(sz)]
+    lib.omni_net_destroy.argtypes = [vp]
+    lib.omni_net_destroy.restype = None
+    lib.omni_weighted_sgd.argtypes = [vp, vp, vp, sz, sz, P(i32), i32, f32, vp]
+    lib.omni_softmax_xent.argtypes = [vp, vp, vp, i32, P(i32), i32, vp, vp, vp, vp, vp]
+    return lib
+
+
+lib = _load()
+
+
+def last_error() -> str:
+    return lib.omni_last_error().decode()
+
+
+def _check(rc):
+    if rc != OK:
+        raise OmniError(rc, last_error())
+
+
+def _i32(seq: Sequence[int]):
+    return (C.c_int32 * len(seq))(*[int(v) for v in seq])
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else C.c_void_p(0)
+
+
+# ------------------------------------------------------------------ controller
+def ctl_create(K: int, B: int, b_min: int = 1, b_max: int = 0):
+    h = C.c_void_p()
+    _check(lib.omni_ctl_create(K, B, b_min, b_max, C.byref(h)))
+    return h
+
+
+def ctl_set_throughputs(ctl, T: Sequence[int]):
+    arr = (C.c_uint64 * len(T))(*[int(t) for t in T])
+    _check(lib.omni_ctl_set_throughputs(ctl, arr))
+
+
+def ctl_run(ctl, K: int):
+    b = (C.c_int32 * K)()
+    off = (C.c_int32 * (K + 1))()
+    _check(lib.omni_ctl_run(ctl, b, off))
+    return list(b), list(off)
+
+
+def ctl_destroy(ctl):
+    lib.omni_ctl_destroy(ctl)
+
+
+# ------------------------------------------------------------------ network
+def net_create(layers, in_shape, dtype: str, K_max: int, B_max: int):
+    descs = (LayerDesc * len(layers))()
+    for d, L in zip(descs, layers):
+        d.op = OPS[L["op"]]
+        d.src = L.get("src", -1)
+        d.src2 = L.get("src2", -1)
+        d.cin = L.get("cin", L.get("c", 0))
+        d.cout = L.get("cout", L.get("c", 0))
+        d.ksize = L.get("k", 0)
+        d.stride = L.get("stride", 1)
+        d.pad = L.get("pad", 0)
+        d.bias = 1 if L.get("bias", False) else 0
+    h = C.c_void_p()
+    _check(lib.omni_net_create(descs, len(layers), in_shape[0], in_shape[1], in_shape[2],
+                               {"f32": F32, "bf16": BF16}[dtype], K_max, B_max, C.byref(h)))
+    return h
+
+
+def net_param_count(net) -> int:
+    return lib.omni_net_param_count(net)
+
+
+def net_workspace_bytes(net) -> int:
+    return lib.omni_net_workspace_bytes(net)
+
+
+def net_grad_stride(net) -> int:
+    return lib.omni_net_grad_stride(net)
+
+
+def net_destroy(net):
+    lib.omni_net_destroy(net)
+
+
+def step(net, params, x, labels, off, b, lr, workspace, loss_per_worker, loss, flags: int = 0, stream=None):
+    K = len(b)
+    _check(lib.omni_step(net, stream if stream is not None else _stream(), _ptr(params), _ptr(x), _ptr(labels),
+                         _i32(off), _i32(b), K, float(lr), _ptr(workspace), _ptr(loss_per_worker), _ptr(loss),
+                         flags))
+
+
+def net_worker_grads(net, workspace, K: int):
+    """[K, P] view (a torch tensor aliasing the workspace)."""
+    import torch
+    P, stride = net_param_count(net), net_grad_stride(net)
+    base = lib.omni_net_worker_grads(net, _ptr(workspace))
+    byte_off = base - workspace.data_ptr()
+    flat = workspace.view(torch.uint8)[byte_off:byte_off + K * stride * 4].view(torch.float32)
+    return flat.view(K, stride)[:, :P]
+
+
+def net_status(net, workspace) -> int:
+    import torch
+    base = lib.omni_net_status(net, _ptr(workspace))
+    byte_off = base - workspace.data_ptr()
+    return int(workspace.view(torch.uint8)[byte_off:byte_off + 4].view(torch.int32).item()) & 0xFFFFFFFF
+
+
+def net_activation(net, workspace, layer: int, rows: int, dtype: str = "f32"):
+    import torch
+    p = C.c_void_p()
+    n = C.c_size_t()
+    _check(lib.omni_net_activation(net, _ptr(workspace), layer, C.byref(p), C.byref(n)))
+    byte_off = p.value - workspace.data_ptr()
+    if dtype == "f32":
+        return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 4].view(torch.float32).view(rows, n.value)
+    return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 2].view(torch.bfloat16).view(rows, n.value)
+
+
+# ------------------------------------------------------------------ single kernels
+def weighted_sgd(params, grads, b, lr, shadow_bf16=None, P=None, stream=None):
+    K = len(b)
+    stride = grads.stride(0)
+    P = params.numel() if P is None else P
+    _check(lib.omni_weighted_sgd(stream if stream is not None else _stream(), _ptr(params), _ptr(grads), stride, P,
+                                 _i32(b), K, float(lr), _ptr(shadow_bf16)))
+
+
+def softmax_xent(z, labels, off, dz, loss_rows, loss_per_worker, loss, status, stream=None):
+    K = len(off) - 1
+    _check(lib.omni_softmax_xent(stream if stream is not None else _stream(), _ptr(z), _ptr(labels), z.shape[1],
+                                 _i32(off), K, _ptr(dz), _ptr(loss_rows), _ptr(loss_per_worker), _ptr(loss),
+                                 _ptr(status)))

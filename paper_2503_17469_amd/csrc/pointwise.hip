@@ -1,0 +1,192 @@
+// Bandwidth-bound kernels of the step: softmax cross-entropy over the ragged
+// batch, and the fused weighted gradient aggregation + SGD update.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace omni {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+namespace {
+
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+// Worker that owns row s (segments are few; a linear scan over kernel arguments).
+__device__ inline int owner(const Segments& seg, int s) {
+  int k = 0;
+  while (k + 1 < seg.K && s >= seg.off[k + 1]) ++k;
+  return k;
+}
+
+// One wavefront per row.  loss_row = logsumexp(z) - z[y]; dz = (softmax - onehot) / b_k:
+// the 1/|b_k| of equation bspweightedgrads, so that the backward pass yields
+// each worker's MEAN gradient.
+__global__ __launch_bounds__(256) void softmax_xent_kernel(const float* __restrict__ z,
+                                                           const int32_t* __restrict__ labels, int C,
+                                                           Segments seg, float* __restrict__ dz,
+                                                           float* __restrict__ loss_rows,
+                                                           uint32_t* __restrict__ status) {
+  const int lane = threadIdx.x & 63;
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int rows = seg.off[seg.K];
+  if (row >= rows) return;
+  const int k = owner(seg, row);
+  const float inv_b = 1.0f / (float)(seg.off[k + 1] - seg.off[k]);
+  const float* zr = z + (size_t)row * C;
+  float* dr = dz + (size_t)row * C;
+  const int y = labels[row];
+  if (y < 0 || y >= C) {
+    if (lane == 0) {
+      atomicOr(status, 1u);
+      loss_rows[row] = 0.f;
+    }
+    for (int c = lane; c < C; c += 64) dr[c] = 0.f;
+    return;
+  }
+  float m = -INFINITY;
+  for (int c = lane; c < C; c += 64) m = fmaxf(m, zr[c]);
+  m = wave_max(m);
+  float s = 0.f;
+  for (int c = lane; c < C; c += 64) s += expf(zr[c] - m);
+  s = wave_sum(s);
+  const float lse = logf(s);
+  if (lane == 0) loss_rows[row] = lse - (zr[y] - m);
+  for (int c = lane; c < C; c += 64) {
+    float p = expf(zr[c] - m - lse);
+    if (c == y) p -= 1.0f;
+    dr[c] = p * inv_b;
+  }
+}
+
+// One workgroup.  L_k = (1/b_k) sum of the worker's row losses (fixed-order tree,
+// so results repeat bit for bit), loss = sum_k (b_k/B) L_k.
+__global__ __launch_bounds__(256) void loss_reduce_kernel(const float* __restrict__ loss_rows, Segments seg,
+                                                          float* __restrict__ loss_per_worker,
+                                                          float* __restrict__ loss) {
+  __shared__ float red[256];
+  const int t = threadIdx.x;
+  const float invB = 1.0f / (float)seg.off[seg.K];
+  float total = 0.f;
+  for (int k = 0; k < seg.K; ++k) {
+    float a = 0.f;
+    for (int s = seg.off[k] + t; s < seg.off[k + 1]; s += 256) a += loss_rows[s];
+    red[t] = a;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if (t < w) red[t] += red[t + w];
+      __syncthreads();
+    }
+    if (t == 0) {
+      const float bk = (float)(seg.off[k + 1] - seg.off[k]);
+      const float Lk = red[0] / bk;
+      loss_per_worker[k] = Lk;
+      total += bk * invB * Lk;
+    }
+    __syncthreads();
+  }
+  if (t == 0) loss[0] = total;
+}
+
+struct Lambdas {
+  float v[OMNI_MAX_WORKERS];
+};
+
+__device__ inline uint16_t bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// theta[j] -= lr * sum_k lambda_k G[k][j]  (equations bspweightedgrads and
+// bspvariableSGD fused: the K gradient rows and theta are each read once, theta
+// written once).  Rows of G are 256-byte aligned, so 16-byte loads throughout.
+template <bool SHADOW>
+__global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ params,
+                                                           const float* __restrict__ grads, size_t stride,
+                                                           size_t P, int K, Lambdas lam, float lr,
+                                                           uint16_t* __restrict__ shadow) {
+  const size_t n4 = P / 4;
+  const size_t step = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
+    v4f g = {0.f, 0.f, 0.f, 0.f};
+    int k = 0;
+    for (; k + 4 <= K; k += 4) {
+      const v4f g0 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 0) * stride + 4 * i);
+      const v4f g1 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 1) * stride + 4 * i);
+      const v4f g2 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 2) * stride + 4 * i);
+      const v4f g3 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 3) * stride + 4 * i);
+      g += lam.v[k] * g0;
+      g += lam.v[k + 1] * g1;
+      g += lam.v[k + 2] * g2;
+      g += lam.v[k + 3] * g3;
+    }
+    for (; k < K; ++k) g += lam.v[k] * *reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * i);
+    v4f th = *reinterpret_cast<const v4f*>(params + 4 * i);
+    th -= lr * g;
+    *reinterpret_cast<v4f*>(params + 4 * i) = th;
+    if (SHADOW) {
+      ushort4 s;
+      s.x = bf16_rne(th[0]); s.y = bf16_rne(th[1]); s.z = bf16_rne(th[2]); s.w = bf16_rne(th[3]);
+      *reinterpret_cast<ushort4*>(shadow + 4 * i) = s;
+    }
+  }
+  // tail (P not a multiple of 4)
+  if (blockIdx.x == 0 && threadIdx.x < (P & 3)) {
+    const size_t j = n4 * 4 + threadIdx.x;
+    float g = 0.f;
+    for (int k = 0; k < K; ++k) g += lam.v[k] * grads[(size_t)k * stride + j];
+    const float th = params[j] - lr * g;
+    params[j] = th;
+    if (SHADOW) shadow[j] = bf16_rne(th);
+  }
+}
+
+__global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+}  // namespace
+
+void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int C, const Segments& seg,
+                      float* dz, float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status) {
+  const int rows = seg.off[seg.K];
+  hipLaunchKernelGGL(softmax_xent_kernel, dim3((rows + 3) / 4), dim3(256), 0, st, z, labels, C, seg, dz,
+                     loss_rows, status);
+  hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, st, loss_rows, seg, loss_per_worker, loss);
+}
+
+void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
+                      const Segments& seg, float lr, uint16_t* shadow_bf16) {
+  Lambdas lam{};
+  const double B = (double)seg.off[seg.K];
+  for (int k = 0; k < seg.K; ++k) lam.v[k] = (float)((double)(seg.off[k + 1] - seg.off[k]) / B);
+  const size_t n4 = P / 4;
+  size_t blocks = (n4 + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  if (blocks < 1) blocks = 1;
+  if (shadow_bf16)
+    hipLaunchKernelGGL(weighted_sgd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, params, grads, stride,
+                       P, seg.K, lam, lr, shadow_bf16);
+  else
+    hipLaunchKernelGGL(weighted_sgd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, params, grads, stride,
+                       P, seg.K, lam, lr, shadow_bf16);
+}
+
+void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v) {
+  if (n == 0) return;
+  hipLaunchKernelGGL(fill_u32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, p, n, v);
+}
+
+}  // namespace omni

@@ -1,0 +1,71 @@
+"""Helpers for the GPU parity tests: run the library on a workload, compare tensors."""
+import numpy as np
+
+
+def rel_err(got, ref):
+    """(max-norm error / max-norm of ref, l2 error / l2 of ref)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    d = got - ref
+    mx = np.abs(ref).max()
+    l2 = np.sqrt((ref ** 2).sum())
+    return (np.abs(d).max() / mx if mx > 0 else np.abs(d).max(),
+            np.sqrt((d ** 2).sum()) / l2 if l2 > 0 else np.sqrt((d ** 2).sum()))
+
+
+def assert_close(got, ref, tol, what=""):
+    e_max, e_l2 = rel_err(got, ref)
+    assert np.all(np.isfinite(np.asarray(got, dtype=np.float64))), what
+    assert e_max <= tol and e_l2 <= tol, f"{what}: max-norm rel {e_max:.3e}, l2 rel {e_l2:.3e} > {tol}"
+    return e_max, e_l2
+
+
+def param_tensor_slices(layers):
+    import synth
+    out = []
+    for i, d in enumerate(synth.param_slices(layers)):
+        for name, (s, e) in d.items():
+            out.append((f"layer{i}.{name}", s, e))
+    return out
+
+
+class GpuRun:
+    """One network instance on the GPU with its buffers."""
+
+    def __init__(self, layers, in_shape, dtype, K_max, B_max):
+        import torch
+        import paper_2503_17469_amd as omni
+        self.omni, self.torch = omni, torch
+        self.layers, self.in_shape, self.dtype = layers, in_shape, dtype
+        self.net = omni.net_create(layers, in_shape, dtype, K_max, B_max)
+        self.P = omni.net_param_count(self.net)
+        self.ws = torch.zeros(omni.net_workspace_bytes(self.net), dtype=torch.uint8, device="cuda")
+        self.K_max = K_max
+        self.lpw = torch.zeros(K_max, dtype=torch.float32, device="cuda")
+        self.loss = torch.zeros(1, dtype=torch.float32, device="cuda")
+
+    def close(self):
+        self.omni.net_destroy(self.net)
+
+    def step(self, params_np, x_np, labels_np, off, lr, flags=0):
+        torch = self.torch
+        B = off[-1]
+        b = [off[k + 1] - off[k] for k in range(len(off) - 1)]
+        params = torch.from_numpy(np.ascontiguousarray(params_np, dtype=np.float32)).cuda()
+        x = torch.from_numpy(np.ascontiguousarray(x_np[:B], dtype=np.float32).reshape(B, -1)).cuda()
+        if self.dtype == "bf16":
+            x = x.to(torch.bfloat16)          # exact: the generator put x on the bf16 grid
+        labels = torch.from_numpy(np.ascontiguousarray(labels_np[:B], dtype=np.int32)).cuda()
+        self.omni.step(self.net, params, x, labels, off, b, lr, self.ws, self.lpw, self.loss, flags)
+        torch.cuda.synchronize()
+        K = len(b)
+        return dict(
+            params=params.cpu().numpy(),
+            loss=float(self.loss.item()),
+            loss_per_worker=self.lpw[:K].cpu().numpy(),
+            worker_grads=self.omni.net_worker_grads(self.net, self.ws, K).cpu().numpy(),
+            status=self.omni.net_status(self.net, self.ws),
+        )
+
+    def activation(self, layer, rows):
+        return self.omni.net_activation(self.net, self.ws, layer, rows, self.dtype).float().cpu().numpy()

@@ -1,0 +1,120 @@
+"""CPU-side checks of the C-ABI library: it loads, exports what the header declares,
+and its host controller agrees bit for bit with the oracle."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+
+import paper_2503_17469_amd as omni
+from paper_2503_17469_amd import binding
+from oracle import controller as OC
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "omnistep.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(omni_[a-z0-9_]+)\s*\(", text))
+    assert declared, "no declarations found"
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert "omnistep" in binding.lib.omni_version().decode()
+
+
+def _run(T, B, lo=1, hi=0):
+    c = omni.ctl_create(len(T), B, lo, hi)
+    try:
+        omni.ctl_set_throughputs(c, T)
+        return omni.ctl_run(c, len(T))
+    finally:
+        omni.ctl_destroy(c)
+
+
+def test_controller_benchmark_vectors():
+    assert _run([1, 2, 4, 8], 480) == ([32, 64, 128, 256], [0, 32, 96, 224, 480])
+    assert _run([1000, 3000], 32) == ([8, 24], [0, 8, 32])
+    assert _run([12, 12, 8, 16], 128)[0] == [32, 32, 21, 43]
+    assert _run([6, 6, 4, 32], 128)[0] == [16, 16, 11, 85]
+
+
+def test_controller_matches_oracle_random():
+    rnd = random.Random(3)
+    for it in range(4000):
+        K = rnd.randint(1, 16)
+        B = rnd.randint(K, 4096)
+        scale = rnd.choice([1, 1000, 10**9, 2**50])
+        T = [rnd.randint(1, 8000) * scale for _ in range(K)]
+        want = OC.controller_run(T, B)
+        assert _run(T, B) == (want[0], want[1]), (T, B)
+
+
+def test_controller_matches_oracle_with_bounds():
+    rnd = random.Random(4)
+    n_ok = n_bad = 0
+    for it in range(4000):
+        K = rnd.randint(1, 8)
+        B = rnd.randint(K, 300)
+        T = [rnd.randint(1, 64) for _ in range(K)]
+        lo = rnd.randint(1, 12)
+        hi = rnd.randint(lo, 96)
+        try:
+            want = OC.controller_run(T, B, lo, hi)
+        except OC.InfeasibleError:
+            with pytest.raises(omni.OmniError) as e:
+                _run(T, B, lo, hi)
+            assert e.value.code == binding.EINFEASIBLE
+            n_bad += 1
+            continue
+        assert _run(T, B, lo, hi) == (want[0], want[1]), (T, B, lo, hi)
+        n_ok += 1
+    assert n_ok > 500 and n_bad > 100
+
+
+def test_controller_extreme_values():
+    T = [2**64 - 1, 2**63, 1, 2**40]
+    want = OC.controller_run(T, 2**31 - 1)
+    assert _run(T, 2**31 - 1) == (want[0], want[1])
+    K = 64
+    T = [k + 1 for k in range(K)]
+    want = OC.controller_run(T, 5000)
+    assert _run(T, 5000) == (want[0], want[1])
+
+
+def test_controller_errors():
+    with pytest.raises(omni.OmniError) as e:
+        omni.ctl_create(0, 10)
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(omni.OmniError) as e:
+        omni.ctl_create(65, 1000)
+    assert e.value.code == binding.ECAPACITY
+    with pytest.raises(omni.OmniError) as e:
+        omni.ctl_create(4, 3)
+    assert e.value.code == binding.EINFEASIBLE
+    c = omni.ctl_create(2, 10)
+    with pytest.raises(omni.OmniError) as e:
+        omni.ctl_run(c, 2)                       # throughputs never set
+    assert e.value.code == binding.EINVAL
+    with pytest.raises(omni.OmniError) as e:
+        omni.ctl_set_throughputs(c, [5, 0])
+    assert e.value.code == binding.EINVAL and "T[1]" in omni.last_error()
+    omni.ctl_destroy(c)
+
+
+def test_net_create_validation_needs_no_gpu():
+    import synth
+    w = synth.workload(1, with_data=False)
+    n = omni.net_create(w.layers, w.in_shape, "f32", 4, 480)
+    assert omni.net_param_count(n) == w.P == 4206602
+    assert omni.net_grad_stride(n) % 64 == 0 and omni.net_grad_stride(n) >= w.P
+    assert omni.net_workspace_bytes(n) > 4 * 4 * w.P
+    omni.net_destroy(n)
+    bad = [dict(op="linear", src=-1, cin=7, cout=3, bias=True)]
+    with pytest.raises(omni.OmniError):
+        omni.net_create(bad, (1, 1, 8), "f32", 1, 4)
+    with pytest.raises(omni.OmniError):
+        omni.net_create(w.layers, w.in_shape, "f32", 65, 480)
