@@ -44,6 +44,10 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()')")
+    # The process must hold ONE HIP runtime.  torch brings its own copy of
+    # libamdhip64; importing torch first makes the loader resolve this library's
+    # dependency on the HIP runtime (same soname) to that already-loaded copy.
+    import torch  # noqa: F401
     lib = C.CDLL(LIB_PATH)
     vp, i32, u64, sz, f32, u32 = C.c_void_p, C.c_int32, C.c_uint64, C.c_size_t, C.c_float, C.c_uint32
     P = C.POINTER

@@ -69,3 +69,39 @@ class GpuRun:
 
     def activation(self, layer, rows):
         return self.omni.net_activation(self.net, self.ws, layer, rows, self.dtype).float().cpu().numpy()
+
+
+def away_from_kinks(layers, in_shape, params, x, seed, margin=2e-5):
+    """Re-draw (seeded, N(0,1)) every input row that puts some ReLU argument within
+    `margin` (relative to that layer's rms pre-activation) of zero.
+
+    A ReLU's derivative jumps at zero: an fp32 forward pass and the fp64 oracle can
+    land on different sides for an argument of order 1e-7, and the two gradients then
+    differ by a whole rank-one term although both are right for their own forward
+    pass.  The fp32 parity cases therefore use inputs on which the decision is not
+    in doubt.  Only the oracle's forward pass is consulted; rows are independent
+    (no batch norm in these nets), so re-drawing one row does not disturb the others.
+    Returns (x, number of rows re-drawn)."""
+    from oracle import step as OS
+    assert not any(L["op"] in ("bn", "maxpool2") for L in layers)
+    x = np.array(x, dtype=np.float32, copy=True)
+    rng = np.random.default_rng(seed)
+    n = x.shape[0]
+    todo = np.arange(n)
+    redrawn = 0
+    for _ in range(50):
+        xs = x[todo].reshape((len(todo),) + tuple(in_shape))
+        _, _, acts = OS.forward_backward(layers, params, xs, np.zeros(len(todo), dtype=np.int64), 0.0,
+                                         keep_acts=True)
+        bad = np.zeros(len(todo), dtype=bool)
+        for li, L in enumerate(layers):
+            if L["op"] == "relu":
+                pre = acts[L["src"]].reshape(len(todo), -1)
+                scale = np.sqrt((pre ** 2).mean())
+                bad |= (np.abs(pre) < margin * scale).any(axis=1)
+        if not bad.any():
+            return x, redrawn
+        todo = todo[bad]
+        redrawn += len(todo)
+        x[todo] = rng.standard_normal((len(todo),) + x.shape[1:]).astype(np.float32)
+    raise RuntimeError("could not move inputs away from ReLU kinks")

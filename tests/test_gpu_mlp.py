@@ -6,7 +6,7 @@ import synth
 from oracle import step as OS
 from oracle.controller import controller_run
 
-from gpu_util import GpuRun, assert_close, param_tensor_slices
+from gpu_util import GpuRun, assert_close, away_from_kinks, param_tensor_slices
 
 pytestmark = pytest.mark.gpu
 
@@ -15,7 +15,8 @@ TOL = 1e-4      # relative, fp32 path (max-norm and l2, per tensor)
 
 def _check_step(layers, in_shape, params, x, labels, off, lr, tol=TOL, tag=""):
     K = len(off) - 1
-    print(f"case {tag}: K={K} off={off}", flush=True)
+    x, redrawn = away_from_kinks(layers, in_shape, params, x, seed=K + off[-1])
+    print(f"case {tag}: K={K} off={off} rows re-drawn away from ReLU kinks: {redrawn}", flush=True)
     run = GpuRun(layers, in_shape, "f32", K, off[-1])
     try:
         got = run.step(params, x, labels, off, lr)
