@@ -1,0 +1,155 @@
+#!/usr/bin/env python3
+"""Throughput of one ragged, batch-size-weighted SGD step on one MI355X.
+
+A "step" is the whole hot path on one synthetic batch already resident in HBM:
+controller (throughputs -> b_k, offsets) + forward + loss + backward with
+per-worker gradients + weighted aggregation + SGD update.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mlp3072]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# fp32 dense MFMA peak and HBM peak of one MI355X (published figures)
+PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+PEAK_HBM_GBS = 8000.0
+
+# kernel whose roofline is reported, per workload: (timing class, layer index, description)
+DOMINANT = {
+    "tiny_mlp": ("linear_wgrad", 0),
+    "mlp3072": ("linear_wgrad", 0),
+}
+
+
+def linear_layer_flops(layers, li, rows):
+    L = layers[li]
+    return 2.0 * rows * L["cin"] * L["cout"]
+
+
+def cpu_baseline(w, off, budget_s=12.0):
+    """The CPU oracle, as it stands, timed on the host cores on the same workload."""
+    from oracle import step as oracle_step
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
+    except Exception:
+        threads = os.cpu_count() or 1
+    x = w.x
+    n = 0
+    t0 = time.perf_counter()
+    while True:
+        oracle_step.sgd_step(w.layers, w.params, x, w.labels, off, w.lr)
+        n += 1
+        el = time.perf_counter() - t0
+        if el >= budget_s:
+            break
+    return {"value": w.B * n / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} full steps of the same workload (B={w.B}), fp64 numpy, {el:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--workload", default="mlp3072")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives or sharding exist here)")
+
+    import numpy as np
+    import torch
+
+    import paper_2503_17469_amd as omni
+    import synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    idx = synth.CONFIG_NAMES.index(args.workload)
+    w = synth.workload(idx)
+
+    ctl = omni.ctl_create(w.K, w.B)
+    omni.ctl_set_throughputs(ctl, w.T)
+    b, off = omni.ctl_run(ctl, w.K)
+
+    net = omni.net_create(w.layers, w.in_shape, w.dtype, w.K, w.B)
+    ws = torch.zeros(omni.net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
+    params = torch.from_numpy(w.params).cuda()
+    x = torch.from_numpy(w.x.reshape(w.B, -1)).cuda()
+    if w.dtype == "bf16":
+        x = x.to(torch.bfloat16)
+    y = torch.from_numpy(w.labels).cuda()
+    lpw = torch.zeros(w.K, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    # a small learning rate keeps the synthetic problem finite over thousands of steps
+    lr = 1e-3
+
+    def one_step():
+        omni.ctl_set_throughputs(ctl, w.T)
+        bb, oo = omni.ctl_run(ctl, w.K)
+        omni.step(net, params, x, y, oo, bb, lr, ws, lpw, loss)
+
+    for _ in range(args.warmup):
+        one_step()
+    torch.cuda.synchronize()
+
+    kcls, klayer = DOMINANT[w.name]
+    omni.net_timing_enable(net, kcls, klayer, args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        one_step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    k_ms, k_n = omni.net_timing_read(net)
+    omni.net_timing_enable(net, -1, -1, 1)
+    final_loss = float(loss.item())
+    assert np.isfinite(final_loss), "loss diverged"
+
+    ms_per_step = dt / args.steps * 1e3
+    value = w.B * args.steps / dt
+
+    kernel_s = k_ms / max(k_n, 1) * 1e-3
+    flops = linear_layer_flops(w.layers, klayer, w.B)
+    achieved = flops / kernel_s / 1e12
+    peak = PEAK_TFLOPS[w.dtype]
+    roofline = {"bound": "mfma", "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
+                "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "avg_launch_us": kernel_s * 1e6, "launches": int(k_n)}
+
+    out = {
+        "metric": "samples/sec per ragged weighted SGD step (fwd+bwd+reduce+update)",
+        "value": value,
+        "unit": "samples/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "data": "synthetic",
+        "config": {"workload": w.name, "K": w.K, "B": w.B, "b": b, "params": int(w.P),
+                   "net": "MLP 3072-1024-1024-10" if w.name == "mlp3072" else w.name,
+                   "includes": "controller+offsets+fwd+loss+bwd+weighted reduce+SGD"},
+        "roofline": roofline,
+        "final_loss": final_loss,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, off)
+    omni.net_destroy(net)
+    omni.ctl_destroy(ctl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -186,6 +186,28 @@ const uint32_t* omni_net_status(const omni_net* net, const void* workspace);
 int omni_net_activation(const omni_net* net, const void* workspace, int32_t layer,
                         const void** ptr, size_t* elems_per_row);
 
+/* Optional device-side timing of one kernel class inside omni_step, for
+ * roofline reports.  After omni_net_timing_enable, every launch of that class
+ * (for layer `layer`, or all layers if layer < 0) is bracketed by a pair of HIP
+ * events recorded on the step's stream; at most `max_launches` launches are
+ * recorded until the next read.  omni_net_timing_read waits for the recorded
+ * events, returns their summed elapsed time and count, and clears the record.
+ * kernel_class < 0 disables timing.  Events are created inside the enable call
+ * (never inside omni_step).  Returns OMNI_EINVAL on a bad class. */
+enum {
+  OMNI_KERNEL_LINEAR_FWD = 0,
+  OMNI_KERNEL_LINEAR_DGRAD = 1,
+  OMNI_KERNEL_LINEAR_WGRAD = 2,
+  OMNI_KERNEL_LOSS = 3,
+  OMNI_KERNEL_UPDATE = 4,
+  OMNI_KERNEL_CONV_FWD = 5,
+  OMNI_KERNEL_CONV_DGRAD = 6,
+  OMNI_KERNEL_CONV_WGRAD = 7,
+  OMNI_KERNEL_CLASSES = 8
+};
+int omni_net_timing_enable(omni_net* net, int32_t kernel_class, int32_t layer, int32_t max_launches);
+int omni_net_timing_read(omni_net* net, double* total_ms, int64_t* launches);
+
 void omni_net_destroy(omni_net* net);
 
 /* ------------------------------------------------------------------ single kernels

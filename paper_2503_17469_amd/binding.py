@@ -26,8 +26,10 @@ EXPORTS = [
     "omni_ctl_create", "omni_ctl_set_throughputs", "omni_ctl_run", "omni_ctl_destroy",
     "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
-    "omni_weighted_sgd", "omni_softmax_xent",
+    "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
 ]
+KERNEL_CLASSES = {"linear_fwd": 0, "linear_dgrad": 1, "linear_wgrad": 2, "loss": 3, "update": 4,
+                  "conv_fwd": 5, "conv_dgrad": 6, "conv_wgrad": 7}
 
 
 class OmniError(RuntimeError):
@@ -73,6 +75,8 @@ def _load():
     lib.omni_net_activation.argtypes = [vp, vp, i32, P(vp), P(sz)]
     lib.omni_net_destroy.argtypes = [vp]
     lib.omni_net_destroy.restype = None
+    lib.omni_net_timing_enable.argtypes = [vp, i32, i32, i32]
+    lib.omni_net_timing_read.argtypes = [vp, P(C.c_double), P(C.c_int64)]
     lib.omni_weighted_sgd.argtypes = [vp, vp, vp, sz, sz, P(i32), i32, f32, vp]
     lib.omni_softmax_xent.argtypes = [vp, vp, vp, i32, P(i32), i32, vp, vp, vp, vp, vp]
     return lib
@@ -194,6 +198,19 @@ def net_activation(net, workspace, layer: int, rows: int, dtype: str = "f32"):
     if dtype == "f32":
         return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 4].view(torch.float32).view(rows, n.value)
     return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 2].view(torch.bfloat16).view(rows, n.value)
+
+
+def net_timing_enable(net, kernel_class, layer: int = -1, max_launches: int = 4096):
+    cls = KERNEL_CLASSES[kernel_class] if isinstance(kernel_class, str) else int(kernel_class)
+    _check(lib.omni_net_timing_enable(net, cls, layer, max_launches))
+
+
+def net_timing_read(net):
+    """(total milliseconds, launches) of the timed kernel class since the last read."""
+    ms = C.c_double()
+    n = C.c_int64()
+    _check(lib.omni_net_timing_read(net, C.byref(ms), C.byref(n)))
+    return ms.value, n.value
 
 
 # ------------------------------------------------------------------ single kernels

@@ -49,7 +49,35 @@ struct omni_net {
   size_t ws_bytes = 0;
   size_t grads_off = 0, loss_rows_off = 0, status_off = 0;
   int classes = 0;
+  // optional event timing of one kernel class
+  int time_class = -1, time_layer = -1;
+  std::vector<hipEvent_t> ev;   // pairs: start, stop
+  size_t ev_used = 0;           // events recorded since the last read
+
+  ~omni_net() {
+    for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+  }
 };
+
+namespace {
+// Records an event pair around the launches made while it is alive, if the
+// network is timing this (class, layer) and has event pairs left.
+struct TimedScope {
+  omni_net* net;
+  hipStream_t st;
+  bool on;
+  TimedScope(omni_net* n, hipStream_t s, int cls, int layer) : net(n), st(s) {
+    on = n->time_class == cls && (n->time_layer < 0 || n->time_layer == layer) && n->ev_used + 2 <= n->ev.size();
+    if (on) (void)hipEventRecord(net->ev[net->ev_used], st);
+  }
+  ~TimedScope() {
+    if (on) {
+      (void)hipEventRecord(net->ev[net->ev_used + 1], st);
+      net->ev_used += 2;
+    }
+  }
+};
+}  // namespace
 
 using omni::fail;
 
@@ -160,6 +188,37 @@ int omni_net_activation(const omni_net* net, const void* ws, int32_t layer, cons
 
 void omni_net_destroy(omni_net* net) { delete net; }
 
+int omni_net_timing_enable(omni_net* net, int32_t kernel_class, int32_t layer, int32_t max_launches) {
+  if (!net) return fail(OMNI_EINVAL, "omni_net_timing_enable: NULL net");
+  if (kernel_class >= OMNI_KERNEL_CLASSES) return fail(OMNI_EINVAL, "omni_net_timing_enable: bad class %d", kernel_class);
+  net->ev_used = 0;
+  if (kernel_class < 0) { net->time_class = -1; return OMNI_OK; }
+  if (max_launches < 1 || max_launches > (1 << 20)) return fail(OMNI_EINVAL, "omni_net_timing_enable: bad max_launches");
+  while (net->ev.size() < (size_t)max_launches * 2) {
+    hipEvent_t e;
+    OMNI_HIP_CHECK(hipEventCreate(&e));
+    net->ev.push_back(e);
+  }
+  net->time_class = kernel_class;
+  net->time_layer = layer;
+  return OMNI_OK;
+}
+
+int omni_net_timing_read(omni_net* net, double* total_ms, int64_t* launches) {
+  if (!net || !total_ms || !launches) return fail(OMNI_EINVAL, "omni_net_timing_read: NULL argument");
+  double tot = 0.0;
+  for (size_t i = 0; i + 1 < net->ev_used; i += 2) {
+    OMNI_HIP_CHECK(hipEventSynchronize(net->ev[i + 1]));
+    float ms = 0.f;
+    OMNI_HIP_CHECK(hipEventElapsedTime(&ms, net->ev[i], net->ev[i + 1]));
+    tot += ms;
+  }
+  *total_ms = tot;
+  *launches = (int64_t)(net->ev_used / 2);
+  net->ev_used = 0;
+  return OMNI_OK;
+}
+
 int omni_step(omni_net* net, void* stream, float* params, const void* x, const int32_t* labels,
               const int32_t* off, const int32_t* b, int32_t K, float lr, void* workspace,
               float* loss_per_worker, float* loss, uint32_t flags) {
@@ -200,18 +259,23 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   for (const Layer& L : net->layers) {
     if (L.fused_away) continue;
     switch (L.d.op) {
-      case OMNI_OP_LINEAR:
+      case OMNI_OP_LINEAR: {
+        TimedScope ts(net, st, OMNI_KERNEL_LINEAR_FWD, (int)(&L - net->layers.data()));
         omni::linear_fwd_f32(st, act(L.in0), params + L.w_off, L.has_b ? params + L.b_off : nullptr, actw(L.out),
                              rows, L.d.cin, L.d.cout, net->tensors[L.out].relu);
         break;
+      }
       default: break;
     }
   }
 
   // ---- loss: dz already carries 1/b_k, so everything downstream is a per-worker mean gradient
   const int logits = net->layers.back().out;
-  omni::softmax_xent_f32(st, act(logits), labels, net->classes, seg, grad(logits), loss_rows, loss_per_worker,
-                         loss, status);
+  {
+    TimedScope ts(net, st, OMNI_KERNEL_LOSS, (int)net->layers.size() - 1);
+    omni::softmax_xent_f32(st, act(logits), labels, net->classes, seg, grad(logits), loss_rows, loss_per_worker,
+                           loss, status);
+  }
 
   // ---- backward: input gradients on all rows, parameter gradients per worker
   std::vector<char> written(net->tensors.size(), 0);
@@ -220,10 +284,14 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
     if (L.fused_away) continue;
     switch (L.d.op) {
       case OMNI_OP_LINEAR: {
-        omni::linear_wgrad_f32(st, grad(L.out), act(L.in0), G + L.w_off, L.has_b ? G + L.b_off : nullptr,
-                               net->P_stride, seg, L.d.cin, L.d.cout);
+        {
+          TimedScope ts(net, st, OMNI_KERNEL_LINEAR_WGRAD, i);
+          omni::linear_wgrad_f32(st, grad(L.out), act(L.in0), G + L.w_off, L.has_b ? G + L.b_off : nullptr,
+                                 net->P_stride, seg, L.d.cin, L.d.cout);
+        }
         if (L.in0 >= 0) {
           const Tensor& ti = net->tensors[L.in0];
+          TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
           omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, ti.relu ? act(L.in0) : nullptr, grad(L.in0),
                                  rows, L.d.cin, L.d.cout, written[L.in0] != 0);
           written[L.in0] = 1;
@@ -235,8 +303,10 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   }
 
   // ---- weighted aggregation + update
-  if (!(flags & OMNI_STEP_NO_UPDATE))
+  if (!(flags & OMNI_STEP_NO_UPDATE)) {
+    TimedScope ts(net, st, OMNI_KERNEL_UPDATE, -1);
     omni::weighted_sgd_f32(st, params, G, net->P_stride, net->P, seg, lr, nullptr);
+  }
 
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(OMNI_EHIP, "omni_step: launch failed: %s", hipGetErrorString(e));
