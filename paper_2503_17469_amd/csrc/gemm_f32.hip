@@ -10,11 +10,23 @@
 // One kernel template serves all three.  It computes C[i][j] = sum_kk A(i,kk) *
 // B(j,kk) where each operand is either "k-contiguous" (element (r,kk) at
 // base[r*ld + kk]) or "row-contiguous" (element (r,kk) at base[kk*ld + r]).
-// A workgroup is 4 wavefronts in a 2x2 grid; each wavefront owns TM x TN
-// accumulator blocks of 32x32.  Operand slabs of BK reduction steps are staged
-// through LDS with register prefetch of the next slab (double-buffered LDS,
-// one barrier per slab).
+// A workgroup is 4 wavefronts in a 2x2 grid over a 64x64 output tile; each
+// wavefront owns one 32x32 accumulator block.  Operand slabs of BK reduction
+// steps are staged through LDS with register prefetch of the next slab
+// (double-buffered LDS, one barrier per slab).
+//
+// Filling 256 compute units when the batch is small:
+//   * forward / dgrad split the reduction over gridDim.y workgroups per tile;
+//     each writes its partial tile, the last one to arrive (a per-tile counter)
+//     adds the partials in split order and runs the epilogue, so the sum order
+//     is fixed and results repeat bit for bit;
+//   * wgrad gives every workgroup one output tile position and lets it walk
+//     through ALL workers' row ranges one after the other, flushing the
+//     accumulator into worker k's gradient when k's rows end.  Every workgroup
+//     then does the same amount of work however ragged the b_k are.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
 
 #include "common.h"
 #include "kernels.h"
@@ -27,6 +39,7 @@ typedef float v16f __attribute__((ext_vector_type(16)));
 namespace {
 
 constexpr int kThreads = 256;
+constexpr int kTile = 64;
 
 // Staging of one operand slab: R rows x BK reduction steps.
 template <int R, int BK, bool MC>
@@ -39,50 +52,60 @@ struct Slab {
   static constexpr int kStride = MC ? (R + 8) : (BK + 4);
   static constexpr int kFloats = MC ? BK * (R + 8) : R * (BK + 4);
 
+  // Loads never branch: an element outside the operand is fetched from the
+  // operand's first element instead and zeroed when the slab is written to LDS
+  // (`ok` carries 4 validity bits per piece).  Branch-free loads let the compiler
+  // keep them in flight across the whole MFMA section of the current slab.
+  // VEC requires the contiguous extent (kk for k-contiguous, rows for
+  // row-contiguous operands) to be a multiple of 4 and 16-byte aligned rows, so a
+  // 4-element piece is either wholly inside or wholly outside.
   template <bool VEC>
-  __device__ static inline void load(v4f (&reg)[kPerThread], const float* __restrict__ base, int ld,
+  __device__ static inline void load(v4f (&reg)[kPerThread], uint32_t& ok, const float* __restrict__ base, int ld,
                                      int row0, int rows, int k0, int kend, int tid) {
+    ok = 0;
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       const int c = tid + kThreads * i;
+      int gr, gk;
       if (!MC) {
-        const int r = c / (BK / 4), kc = (c % (BK / 4)) * 4;
-        const int gr = row0 + r, gk = k0 + kc;
-        const float* p = base + (size_t)gr * ld + gk;
-        if (VEC && gr < rows && gk + 3 < kend) {
-          reg[i] = *reinterpret_cast<const v4f*>(p);
-        } else {
-          v4f v;
-#pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = (gr < rows && gk + e < kend) ? p[e] : 0.f;
-          reg[i] = v;
-        }
+        gr = row0 + c / (BK / 4);
+        gk = k0 + (c % (BK / 4)) * 4;
       } else {
-        const int kk = c / (R / 4), rc = (c % (R / 4)) * 4;
-        const int gk = k0 + kk, gr = row0 + rc;
-        const float* p = base + (size_t)gk * ld + gr;
-        if (VEC && gk < kend && gr + 3 < rows) {
-          reg[i] = *reinterpret_cast<const v4f*>(p);
-        } else {
-          v4f v;
+        gk = k0 + c / (R / 4);
+        gr = row0 + (c % (R / 4)) * 4;
+      }
+      if (VEC) {
+        const bool in = MC ? (gk < kend && gr + 3 < rows) : (gr < rows && gk + 3 < kend);
+        const size_t o = MC ? (size_t)gk * ld + gr : (size_t)gr * ld + gk;
+        reg[i] = *reinterpret_cast<const v4f*>(base + (in ? o : 0));
+        ok |= (in ? 0xFu : 0u) << (4 * i);
+      } else {
+        v4f v;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) v[e] = (gk < kend && gr + e < rows) ? p[e] : 0.f;
-          reg[i] = v;
+        for (int e = 0; e < 4; ++e) {
+          const bool in = MC ? (gk < kend && gr + e < rows) : (gr < rows && gk + e < kend);
+          const size_t o = MC ? (size_t)gk * ld + gr + e : (size_t)gr * ld + gk + e;
+          v[e] = base[in ? o : 0];
+          ok |= (in ? 1u : 0u) << (4 * i + e);
         }
+        reg[i] = v;
       }
     }
   }
 
-  __device__ static inline void store(const v4f (&reg)[kPerThread], float* lds, int tid) {
+  __device__ static inline void store(const v4f (&reg)[kPerThread], uint32_t ok, float* lds, int tid) {
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       const int c = tid + kThreads * i;
+      v4f v = reg[i];
+#pragma unroll
+      for (int e = 0; e < 4; ++e) v[e] = ((ok >> (4 * i + e)) & 1u) ? v[e] : 0.f;
       if (!MC) {
         const int r = c / (BK / 4), kc = (c % (BK / 4)) * 4;
-        *reinterpret_cast<v4f*>(lds + r * kStride + kc) = reg[i];
+        *reinterpret_cast<v4f*>(lds + r * kStride + kc) = v;
       } else {
         const int kk = c / (R / 4), rc = (c % (R / 4)) * 4;
-        *reinterpret_cast<v4f*>(lds + kk * kStride + rc) = reg[i];
+        *reinterpret_cast<v4f*>(lds + kk * kStride + rc) = v;
       }
     }
   }
@@ -117,153 +140,254 @@ struct GemmParams {
   const float* mask;   // DGRAD: [M][ldc]; the value passes where mask > 0, may be null
   int relu;            // FWD
   int accumulate;      // DGRAD: C += result
+  int xcd_remap;       // FWD / DGRAD: 1 if the tile grid is re-ordered per XCD
+  float* partial;      // FWD / DGRAD split-K: [tiles][splits][16][256] floats
+  uint32_t* counters;  // FWD / DGRAD split-K: one per tile, zero between launches
   size_t c_worker_stride;  // WGRAD: floats between consecutive workers' outputs
   float* bias_grad;        // WGRAD: per worker column sums of A (at + worker*c_worker_stride), may be null
 };
 
-template <int TM, int TN, int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
+template <int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
 __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segments seg) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
-  using SA = Slab<BM, BK, A_MC>;
-  using SB = Slab<BN, BK, B_MC>;
-  __shared__ __attribute__((aligned(16))) float lds[2 * (SA::kFloats + SB::kFloats)];
+  using SA = Slab<kTile, BK, A_MC>;
+  using SB = Slab<kTile, BK, B_MC>;
   constexpr int kStage = SA::kFloats + SB::kFloats;
+  __shared__ __attribute__((aligned(16))) float lds[2 * kStage];
+  __shared__ uint32_t arrival;
   auto sA = [&](int stage) { return lds + stage * kStage; };
   auto sB = [&](int stage) { return lds + stage * kStage + SA::kFloats; };
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int tiles_n = (p.N + BN - 1) / BN;
-  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
-  const int row0 = tile_m * BM, col0 = tile_n * BN;
-  const int wrow = (wave >> 1) * 32 * TM, wcol = (wave & 1) * 32 * TN;
+  const int tiles_n = (p.N + kTile - 1) / kTile;
+  int tile = blockIdx.x;
+  if (MODE != MODE_WGRAD && p.xcd_remap) {
+    // Workgroups are dealt to the 8 XCDs round-robin by index; give each XCD a
+    // contiguous run of tiles so that tiles sharing B rows meet in one L2.
+    const int per = gridDim.x >> 3;
+    tile = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  }
+  // tile_n major: consecutive tiles share the same rows of B
+  const int tiles_m = (p.M + kTile - 1) / kTile;
+  const int tile_n = (MODE == MODE_WGRAD) ? tile % tiles_n : tile / tiles_m;
+  const int tile_m = (MODE == MODE_WGRAD) ? tile / tiles_n : tile % tiles_m;
+  const int row0 = tile_m * kTile, col0 = tile_n * kTile;
+  const int wrow = (wave >> 1) * 32, wcol = (wave & 1) * 32;
 
-  int kbeg = 0, kend = p.kred;
-  float* C = p.C;
+  // The reduction is a stream of slabs over one or more consecutive ranges
+  // ("workers"); the accumulator is flushed whenever a range ends.  A slab is
+  // (range index w, start k0, end of its range kend); w == nrange marks the end.
+  const int splits = gridDim.y, split = blockIdx.y;
+  const int nrange = (MODE == MODE_WGRAD) ? seg.K : 1;
+  int w0 = 0, k00, kend0;
   if (MODE == MODE_WGRAD) {
-    const int w = blockIdx.y;
-    kbeg = seg.off[w];
-    kend = seg.off[w + 1];
-    C += (size_t)w * p.c_worker_stride;
+    k00 = seg.off[0];
+    kend0 = seg.off[1];
+  } else {
+    const int slabs = (p.kred + BK - 1) / BK;
+    const int per = (slabs + splits - 1) / splits;
+    k00 = min(split * per * BK, p.kred);
+    kend0 = min((split + 1) * per * BK, p.kred);
+  }
+#define OMNI_NEXT_SLAB(W, K0, KEND, NW, NK0, NKEND)       \
+  int NW = W, NK0 = K0 + BK, NKEND = KEND;                \
+  if (NK0 >= KEND) {                                      \
+    NW = W + 1;                                           \
+    if (MODE == MODE_WGRAD && NW < nrange) {              \
+      NK0 = seg.off[NW];                                  \
+      NKEND = seg.off[NW + 1];                            \
+    }                                                     \
   }
 
-  v16f acc[TM][TN];
+  // Two accumulator chains (even / odd reduction steps) keep consecutive MFMAs independent.
+  v16f acc, acc2;
 #pragma unroll
-  for (int a = 0; a < TM; ++a)
-#pragma unroll
-    for (int b = 0; b < TN; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
+  for (int v = 0; v < 16; ++v) acc[v] = acc2[v] = 0.f;
   const bool want_bias_grad = (MODE == MODE_WGRAD) && p.bias_grad != nullptr && tile_n == 0;
   float bsum = 0.f;
 
-  v4f ra[SA::kPerThread], rb[SB::kPerThread];
-  const int nslab = (kend - kbeg + BK - 1) / BK;
-  if (nslab > 0) {
-    SA::template load<VEC>(ra, p.A, p.lda, row0, p.M, kbeg, kend, tid);
-    SB::template load<VEC>(rb, p.B, p.ldb, col0, p.N, kbeg, kend, tid);
-    SA::store(ra, sA(0), tid);
-    SB::store(rb, sB(0), tid);
-  }
-  __syncthreads();
-
-  for (int s = 0; s < nslab; ++s) {
-    const int cur = s & 1;
-    if (s + 1 < nslab) {
-      const int k0 = kbeg + (s + 1) * BK;
-      SA::template load<VEC>(ra, p.A, p.lda, row0, p.M, k0, kend, tid);
-      SB::template load<VEC>(rb, p.B, p.ldb, col0, p.N, k0, kend, tid);
-    }
-#pragma unroll
-    for (int ks = 0; ks < BK / 8; ++ks) {
-      v4f fa[TM], fb[TN];
-#pragma unroll
-      for (int a = 0; a < TM; ++a) fa[a] = SA::frag(sA(cur), wrow + a * 32, ks, lane);
-#pragma unroll
-      for (int b = 0; b < TN; ++b) fb[b] = SB::frag(sB(cur), wcol + b * 32, ks, lane);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int a = 0; a < TM; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b)
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[a][q], fb[b][q], acc[a][b], 0, 0, 0);
-    }
-    if (want_bias_grad && tid < BM) {
-      // A is the output-gradient slab [kk][row]: its column sums are the bias gradient.
-#pragma unroll 8
-      for (int kk = 0; kk < BK; ++kk) bsum += sA(cur)[kk * SA::kStride + tid];
-    }
-    if (s + 1 < nslab) {
-      SA::store(ra, sA(cur ^ 1), tid);
-      SB::store(rb, sB(cur ^ 1), tid);
-    }
-    __syncthreads();
-  }
-
-  if (want_bias_grad && tid < BM && row0 + tid < p.M)
-    p.bias_grad[(size_t)blockIdx.y * p.c_worker_stride + row0 + tid] = bsum;
-
   // Accumulator layout of the 32x32 block: register v of lane l holds
   // row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  const int j = col0 + wcol + (lane & 31);
+  const int ibase = row0 + wrow + 4 * (lane >> 5);
+
+  // Two register sets hold the slabs one and two steps ahead of the one being
+  // multiplied, so every global load has two MFMA sections to arrive in.
+  v4f ra0[SA::kPerThread], rb0[SB::kPerThread], ra1[SA::kPerThread], rb1[SB::kPerThread];
+  uint32_t oka0 = 0, okb0 = 0, oka1 = 0, okb1 = 0;
+  OMNI_NEXT_SLAB(w0, k00, kend0, w1, k01, kend1)
+  SA::template load<VEC>(ra0, oka0, p.A, p.lda, row0, p.M, k00, kend0, tid);
+  SB::template load<VEC>(rb0, okb0, p.B, p.ldb, col0, p.N, k00, kend0, tid);
+  // Prefetches past the end of the stream are still issued (they re-read element
+  // 0 and are discarded): a load that is issued on one path only would force
+  // every later wait to assume it is not there and drain the whole queue.
+  if (w1 >= nrange) kend1 = 0;
+  SA::template load<VEC>(ra1, oka1, p.A, p.lda, row0, p.M, k01, kend1, tid);
+  SB::template load<VEC>(rb1, okb1, p.B, p.ldb, col0, p.N, k01, kend1, tid);
+  SA::store(ra0, oka0, sA(0), tid);
+  SB::store(rb0, okb0, sB(0), tid);
+  __syncthreads();
+
+  int cur = 0;
+  // One pipeline step: multiply slab 0 (already in LDS stage `cur`), fetch the
+  // slab two ahead into the free register set (LA/LB), then move the slab one
+  // ahead from its register set (NA/NB) into the other LDS stage.
+#define OMNI_STEP(LA, LB, LOKA, LOKB, NA, NB, NOKA, NOKB)                                               \
+  {                                                                                                     \
+    int w2 = nrange, k02 = 0, kend2 = 0;                                                                \
+    if (w1 < nrange) {                                                                                  \
+      OMNI_NEXT_SLAB(w1, k01, kend1, tw, tk0, tkend)                                                    \
+      w2 = tw; k02 = tk0; kend2 = tkend;                                                                \
+    }                                                                                                   \
+    if (w2 >= nrange) kend2 = 0;                                                                        \
+    SA::template load<VEC>(LA, LOKA, p.A, p.lda, row0, p.M, k02, kend2, tid);                           \
+    SB::template load<VEC>(LB, LOKB, p.B, p.ldb, col0, p.N, k02, kend2, tid);                           \
+    __builtin_amdgcn_sched_barrier(0); /* keep the fetches ahead of the MFMA section */                 \
+    _Pragma("unroll") for (int ks = 0; ks < BK / 8; ++ks) {                                             \
+      const v4f fa = SA::frag(sA(cur), wrow, ks, lane);                                                 \
+      const v4f fb = SB::frag(sB(cur), wcol, ks, lane);                                                 \
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0], fb[0], acc, 0, 0, 0);                           \
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1], fb[1], acc2, 0, 0, 0);                         \
+      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[2], fb[2], acc, 0, 0, 0);                           \
+      acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[3], fb[3], acc2, 0, 0, 0);                         \
+    }                                                                                                   \
+    if (want_bias_grad && tid < kTile) {                                                                \
+      /* A is the output-gradient slab [kk][row]: its column sums are the bias gradient. */             \
+      _Pragma("unroll 8") for (int kk = 0; kk < BK; ++kk) bsum += sA(cur)[kk * SA::kStride + tid];      \
+    }                                                                                                   \
+    if (MODE == MODE_WGRAD && w1 != w0) {                                                               \
+      /* this worker's rows are done: its tile goes out (stores only; the prefetch stays in flight) */ \
+      float* C = p.C + (size_t)w0 * p.c_worker_stride;                                                  \
+      if (j < p.N) {                                                                                    \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                \
+          const int i = ibase + 8 * (v / 4) + (v % 4);                                                  \
+          if (i < p.M) C[(size_t)i * p.ldc + j] = acc[v] + acc2[v];                                     \
+        }                                                                                               \
+      }                                                                                                 \
+      if (want_bias_grad && tid < kTile && row0 + tid < p.M)                                            \
+        p.bias_grad[(size_t)w0 * p.c_worker_stride + row0 + tid] = bsum;                                \
+      bsum = 0.f;                                                                                       \
+      _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[v] = acc2[v] = 0.f;                            \
+    }                                                                                                   \
+    if (w1 >= nrange) break;                                                                            \
+    SA::store(NA, NOKA, sA(cur ^ 1), tid);                                                              \
+    SB::store(NB, NOKB, sB(cur ^ 1), tid);                                                              \
+    __syncthreads();                                                                                    \
+    cur ^= 1;                                                                                           \
+    w0 = w1; k00 = k01; kend0 = kend1;                                                                  \
+    w1 = w2; k01 = k02; kend1 = kend2;                                                                  \
+  }
+  for (;;) {
+    OMNI_STEP(ra0, rb0, oka0, okb0, ra1, rb1, oka1, okb1)
+    OMNI_STEP(ra1, rb1, oka1, okb1, ra0, rb0, oka0, okb0)
+  }
+#undef OMNI_STEP
+#undef OMNI_NEXT_SLAB
+
+  if (MODE != MODE_WGRAD) {
 #pragma unroll
-  for (int a = 0; a < TM; ++a)
+    for (int v = 0; v < 16; ++v) acc[v] += acc2[v];
+    bool finish = true;
+    if (splits > 1) {
+      // Park this split's partial tile; whoever arrives last adds them up.
+      // The tiles travel through device-scope (L2-bypassing) stores and loads,
+      // so no whole-cache write-back or invalidate is needed between the
+      // chiplets: each thread drains its own stores, the barrier collects
+      // the workgroup, then one thread bumps the tile's arrival counter.
+      float* mine = p.partial + ((size_t)tile * splits + split) * (16 * kThreads);
 #pragma unroll
-    for (int b = 0; b < TN; ++b) {
-      const int j = col0 + wcol + b * 32 + (lane & 31);
-      if (j >= p.N) continue;
+      for (int v = 0; v < 16; ++v)
+        __hip_atomic_store(mine + v * kThreads + tid, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+      __syncthreads();
+      if (tid == 0)
+        arrival = __hip_atomic_fetch_add(&p.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      __syncthreads();
+      finish = (arrival == (uint32_t)splits - 1);
+      if (finish) {
+        const float* all = p.partial + (size_t)tile * splits * (16 * kThreads);
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+        for (int s = 0; s < splits; ++s)
+#pragma unroll
+          for (int v = 0; v < 16; ++v)
+            acc[v] += __hip_atomic_load(all + ((size_t)s * 16 + v) * kThreads + tid, __ATOMIC_RELAXED,
+                                        __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0) p.counters[tile] = 0u;   // ready for the next launch
+      }
+    }
+    if (finish && j < p.N) {
       float bj = 0.f;
       if (MODE == MODE_FWD && p.bias) bj = p.bias[j];
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int i = row0 + wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+        const int i = ibase + 8 * (v / 4) + (v % 4);
         if (i >= p.M) continue;
-        float val = acc[a][b][v];
+        float val = acc[v];
         const size_t idx = (size_t)i * p.ldc + j;
         if (MODE == MODE_FWD) {
           val += bj;
           if (p.relu) val = val > 0.f ? val : 0.f;
-        } else if (MODE == MODE_DGRAD) {
+        } else {
           if (p.mask) val = p.mask[idx] > 0.f ? val : 0.f;
-          if (p.accumulate) val += C[idx];
+          if (p.accumulate) val += p.C[idx];
         }
-        C[idx] = val;
+        p.C[idx] = val;
       }
     }
+  }
 }
 
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-template <int TM, int TN, int BK, bool A_MC, bool B_MC, int MODE>
-void launch(hipStream_t st, const GemmParams& p, const Segments& seg, int workers, bool vec) {
-  constexpr int BM = 64 * TM, BN = 64 * TN;
-  dim3 grid(((p.M + BM - 1) / BM) * ((p.N + BN - 1) / BN), workers, 1);
+template <int BK, bool A_MC, bool B_MC, int MODE>
+void launch(hipStream_t st, GemmParams& p, const Segments& seg, int splits, bool vec) {
+  const int tiles = ((p.M + kTile - 1) / kTile) * ((p.N + kTile - 1) / kTile);
+  p.xcd_remap = (MODE != MODE_WGRAD && tiles % 8 == 0) ? 1 : 0;
+  dim3 grid(tiles, splits, 1);
   if (vec)
-    hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, BK, A_MC, B_MC, MODE, true>), grid, dim3(kThreads), 0, st, p, seg);
+    hipLaunchKernelGGL((gemm_f32_kernel<BK, A_MC, B_MC, MODE, true>), grid, dim3(kThreads), 0, st, p, seg);
   else
-    hipLaunchKernelGGL((gemm_f32_kernel<TM, TN, BK, A_MC, B_MC, MODE, false>), grid, dim3(kThreads), 0, st, p, seg);
+    hipLaunchKernelGGL((gemm_f32_kernel<BK, A_MC, B_MC, MODE, false>), grid, dim3(kThreads), 0, st, p, seg);
+}
+
+// Number of reduction splits that brings a forward / dgrad launch to roughly two
+// workgroups per compute unit, never leaving a split without at least 4 slabs.
+int pick_splits(int tiles, int kred, int bk, const SplitWorkspace& sw) {
+  if (!sw.partial || !sw.counters || tiles > kSplitMaxTiles) return 1;
+  int s = (512 + tiles - 1) / tiles;
+  const int slabs = (kred + bk - 1) / bk;
+  s = std::min(s, std::max(1, slabs / 4));
+  s = std::min(s, 16);
+  while (s > 1 && (size_t)tiles * s * 16 * kThreads > kSplitPartialFloats) --s;
+  // every split must own at least one slab
+  while (s > 1 && ((slabs + s - 1) / s) * (s - 1) >= slabs) --s;
+  return std::max(s, 1);
 }
 
 }  // namespace
 
+static int gemm_tiles(int rows, int cols) { return ((rows + kTile - 1) / kTile) * ((cols + kTile - 1) / kTile); }
+
 void linear_fwd_f32(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
-                    int rows, int cin, int cout, bool relu) {
+                    int rows, int cin, int cout, bool relu, const SplitWorkspace& sw) {
   GemmParams p{};
   p.A = x; p.B = w; p.C = y; p.M = rows; p.N = cout; p.lda = cin; p.ldb = cin; p.ldc = cout;
   p.kred = cin; p.bias = bias; p.relu = relu ? 1 : 0;
+  p.partial = sw.partial; p.counters = sw.counters;
   Segments seg{};
-  const bool vec = aligned16(x) && aligned16(w) && (cin % 4 == 0);
-  launch<1, 1, 32, false, false, MODE_FWD>(st, p, seg, 1, vec);
+  const bool vec = aligned16(x) && aligned16(w) && (cin % 4 == 0);   // both operands k-contiguous
+  launch<32, false, false, MODE_FWD>(st, p, seg, pick_splits(gemm_tiles(rows, cout), cin, 32, sw), vec);
 }
 
 void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
-                      int rows, int cin, int cout, bool accumulate) {
+                      int rows, int cin, int cout, bool accumulate, const SplitWorkspace& sw) {
   GemmParams p{};
   p.A = dy; p.B = w; p.C = dx; p.M = rows; p.N = cin; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.kred = cout; p.mask = mask; p.accumulate = accumulate ? 1 : 0;
+  p.partial = sw.partial; p.counters = sw.counters;
   Segments seg{};
   const bool vec = aligned16(dy) && aligned16(w) && (cout % 4 == 0) && (cin % 4 == 0);
-  launch<1, 1, 32, false, true, MODE_DGRAD>(st, p, seg, 1, vec);
+  launch<32, false, true, MODE_DGRAD>(st, p, seg, pick_splits(gemm_tiles(rows, cin), cout, 32, sw), vec);
 }
 
 void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw, float* gb,
@@ -272,11 +396,7 @@ void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw
   p.A = dy; p.B = x; p.C = gw; p.M = cout; p.N = cin; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.c_worker_stride = worker_stride; p.bias_grad = gb;
   const bool vec = aligned16(dy) && aligned16(x) && (cout % 4 == 0) && (cin % 4 == 0);
-  const long tiles128 = (long)((cout + 127) / 128) * ((cin + 127) / 128) * seg.K;
-  if (tiles128 >= 512)
-    launch<2, 2, 16, true, true, MODE_WGRAD>(st, p, seg, seg.K, vec);
-  else
-    launch<1, 1, 32, true, true, MODE_WGRAD>(st, p, seg, seg.K, vec);
+  launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, vec);
 }
 
 }  // namespace omni

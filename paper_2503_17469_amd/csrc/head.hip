@@ -1,0 +1,285 @@
+// Classifier head: the last fully connected layer (few outputs), the softmax
+// cross-entropy loss over the ragged batch and the first backward step, fused.
+//
+// With 10 or 100 classes the last layer is far too thin for a matrix-core tile
+// and far too small to fill the chip; what it costs is launches and round trips
+// through HBM.  Two kernels replace six:
+//   1. one wavefront per row: logits z = x w^T + bias, loss_row = logsumexp(z) -
+//      z[y], dz = (softmax(z) - onehot(y)) / b_k  (the 1/|b_k| of equation
+//      bspweightedgrads: everything downstream is worker k's MEAN gradient), and
+//      the input gradient dx = dz w (masked by the folded ReLU);
+//   2. per worker: gw_k = dz_k^T x_k and gb_k = sum of dz_k rows, plus (in one
+//      extra workgroup) L_k, the lambda-weighted total loss and the label check.
+#include <hip/hip_runtime.h>
+
+#include "common.h"
+#include "kernels.h"
+
+namespace omni {
+
+typedef float v4f __attribute__((ext_vector_type(4)));
+
+namespace {
+
+constexpr int kMaxClasses = 128;
+
+__device__ inline float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ inline float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+__device__ inline int owner(const Segments& seg, int s) {
+  int k = 0;
+  while (k + 1 < seg.K && s >= seg.off[k + 1]) ++k;
+  return k;
+}
+__device__ inline float dot4(v4f a, v4f b) { return a[0] * b[0] + a[1] * b[1] + a[2] * b[2] + a[3] * b[3]; }
+
+// NV = 16-byte pieces of the input row each lane keeps in registers; one piece
+// per lane covers 256 consecutive inputs across the wavefront, so cin <= 256 * NV.
+template <int NV>
+__global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
+    const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
+    const int32_t* __restrict__ labels, int cin, int C, Segments seg, float* __restrict__ z,
+    float* __restrict__ dz, float* __restrict__ loss_rows, const float* __restrict__ mask,
+    float* __restrict__ dx, int accumulate) {
+  constexpr int CH = NV <= 4 ? 8 : 4;   // classes whose weight rows are in flight together
+  __shared__ float zbuf[4][kMaxClasses];
+  const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int rows = seg.off[seg.K];
+  const int row_raw = blockIdx.x * 4 + wv;
+  const bool live = row_raw < rows;
+  const int row = live ? row_raw : rows - 1;   // idle wavefronts shadow the last row and write nothing
+  const float* xr = x + (size_t)row * cin;
+
+  // ---- logits: the row stays in registers, weight rows stream past it
+  // Loads are unconditional (an out-of-range piece re-reads piece 0 and is zeroed
+  // afterwards): guarded loads would serialise behind per-load waits.
+  v4f a[NV];
+  int kk[NV];
+#pragma unroll
+  for (int i = 0; i < NV; ++i) {
+    const int k = lane * 4 + 256 * i;
+    kk[i] = k < cin ? k : 0;
+    a[i] = *reinterpret_cast<const v4f*>(xr + kk[i]);
+  }
+#pragma unroll
+  for (int i = 0; i < NV; ++i)
+    if (lane * 4 + 256 * i >= cin) a[i] = v4f{0.f, 0.f, 0.f, 0.f};
+  for (int c0 = 0; c0 < C; c0 += CH) {
+    float acc[CH];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      acc[j] = 0.f;
+      const int c = min(c0 + j, C - 1);
+#pragma unroll
+      for (int i = 0; i < NV; ++i) acc[j] += dot4(a[i], *reinterpret_cast<const v4f*>(w + (size_t)c * cin + kk[i]));
+    }
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+      const float s = wave_sum(acc[j]);
+      if (lane == j && c0 + j < C) zbuf[wv][c0 + j] = s + (bias ? bias[c0 + j] : 0.f);
+    }
+  }
+  __syncthreads();
+
+  // ---- loss and dz
+  const int k_own = owner(seg, row);
+  const float inv_b = 1.0f / (float)(seg.off[k_own + 1] - seg.off[k_own]);
+  const int y = labels[row];
+  const bool bad = (y < 0 || y >= C);
+  float m = -INFINITY;
+  for (int c = lane; c < C; c += 64) m = fmaxf(m, zbuf[wv][c]);
+  m = wave_max(m);
+  float s = 0.f;
+  for (int c = lane; c < C; c += 64) s += expf(zbuf[wv][c] - m);
+  s = wave_sum(s);
+  const float lse = logf(s);
+  if (live && lane == 0) loss_rows[row] = bad ? 0.f : lse - (zbuf[wv][bad ? 0 : y] - m);
+  for (int c = lane; c < C; c += 64) {
+    const float zc = zbuf[wv][c];
+    float p = expf(zc - m - lse);
+    if (c == y) p -= 1.0f;
+    p = bad ? 0.f : p * inv_b;
+    if (live) {
+      z[(size_t)row * C + c] = zc;
+      dz[(size_t)row * C + c] = p;
+    }
+    zbuf[wv][c] = p;        // the lane that read this slot overwrites it
+  }
+  __syncthreads();
+
+  // ---- input gradient dx = dz w, masked by the folded ReLU
+  if (dx != nullptr && live) {
+    v4f g[NV];
+#pragma unroll
+    for (int i = 0; i < NV; ++i) g[i] = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int c = 0; c < C; ++c) {
+      const float d = zbuf[wv][c];
+#pragma unroll
+      for (int i = 0; i < NV; ++i) g[i] += d * *reinterpret_cast<const v4f*>(w + (size_t)c * cin + kk[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < NV; ++i) {
+      const int k = lane * 4 + 256 * i;
+      if (k >= cin) continue;
+      const size_t idx = (size_t)row * cin + k;
+      v4f gi = g[i];
+      if (mask) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) gi[e] = a[i][e] > 0.f ? gi[e] : 0.f;   // mask is the input row itself
+      }
+      if (accumulate) gi += *reinterpret_cast<const v4f*>(dx + idx);
+      *reinterpret_cast<v4f*>(dx + idx) = gi;
+    }
+  }
+}
+
+// grid.x = K * ceil(cin/16) + 1, grid.y = ceil(C/16).  A workgroup is 16 input
+// columns x 16 row groups; each thread walks its share of the worker's rows.
+__global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
+    const float* __restrict__ dz, const float* __restrict__ x, const int32_t* __restrict__ labels, int cin, int C,
+    Segments seg, float* __restrict__ gw, float* __restrict__ gb, size_t worker_stride,
+    const float* __restrict__ loss_rows, float* __restrict__ loss_per_worker, float* __restrict__ loss,
+    uint32_t* __restrict__ status) {
+  __shared__ float red[16][16][17];
+  const int tid = threadIdx.x;
+  const int jchunks = (cin + 15) / 16;
+
+  if ((int)blockIdx.x == seg.K * jchunks) {
+    // ---- the extra workgroup: losses and label check
+    if (blockIdx.y != 0) return;
+    float* r1 = &red[0][0][0];
+    const int rows = seg.off[seg.K];
+    const float invB = 1.0f / (float)rows;
+    float total = 0.f;
+    for (int k = 0; k < seg.K; ++k) {
+      float a = 0.f;
+      for (int s = seg.off[k] + tid; s < seg.off[k + 1]; s += 256) a += loss_rows[s];
+      r1[tid] = a;
+      __syncthreads();
+      for (int h = 128; h > 0; h >>= 1) {
+        if (tid < h) r1[tid] += r1[tid + h];
+        __syncthreads();
+      }
+      if (tid == 0) {
+        const float bk = (float)(seg.off[k + 1] - seg.off[k]);
+        const float Lk = r1[0] / bk;
+        loss_per_worker[k] = Lk;
+        total += bk * invB * Lk;
+      }
+      __syncthreads();
+    }
+    uint32_t badl = 0;
+    for (int s = tid; s < rows; s += 256) badl |= (labels[s] < 0 || labels[s] >= C) ? 1u : 0u;
+    r1[tid] = (float)badl;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+      if (tid < h) r1[tid] = fmaxf(r1[tid], r1[tid + h]);
+      __syncthreads();
+    }
+    if (tid == 0) {
+      loss[0] = total;
+      status[0] = r1[0] > 0.f ? 1u : 0u;
+    }
+    return;
+  }
+
+  const int wk = blockIdx.x / jchunks, jc = blockIdx.x % jchunks;
+  const int jl = tid & 15, rs = tid >> 4;
+  const int j = jc * 16 + jl;
+  const int c0 = blockIdx.y * 16;
+  const int nc = min(16, C - c0);
+  const int s_end = seg.off[wk + 1];
+  float acc[16];
+#pragma unroll
+  for (int c = 0; c < 16; ++c) acc[c] = 0.f;
+  if (j < cin) {
+    int s = seg.off[wk] + rs;
+    for (; s + 48 < s_end; s += 64) {          // four rows per trip: their loads overlap
+      float av[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) av[u] = x[(size_t)(s + 16 * u) * cin + j];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float* d = dz + (size_t)(s + 16 * u) * C + c0;
+#pragma unroll
+        for (int c = 0; c < 16; ++c) acc[c] += d[c < nc ? c : 0] * av[u];   // columns >= nc are never stored
+      }
+    }
+    for (; s < s_end; s += 16) {
+      const float a = x[(size_t)s * cin + j];
+      const float* d = dz + (size_t)s * C + c0;
+#pragma unroll
+      for (int c = 0; c < 16; ++c) acc[c] += d[c < nc ? c : 0] * a;
+    }
+  }
+#pragma unroll
+  for (int c = 0; c < 16; ++c) red[rs][c][jl] = acc[c];
+  __syncthreads();
+  {
+    const int c = tid >> 4, jj = tid & 15;
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) t += red[r][c][jj];
+    if (c < nc && jc * 16 + jj < cin)
+      gw[(size_t)wk * worker_stride + (size_t)(c0 + c) * cin + jc * 16 + jj] = t;
+  }
+  if (jc == 0 && gb != nullptr) {
+    // bias gradient: column sums of dz over the worker's rows, 16 row groups x 16 classes
+    __syncthreads();
+    const int c = tid & 15, rg = tid >> 4;
+    float t = 0.f;
+    if (c < nc)
+      for (int s = seg.off[wk] + rg; s < s_end; s += 16) t += dz[(size_t)s * C + c0 + c];
+    float* r2 = &red[0][0][0];
+    r2[rg * 16 + c] = t;
+    __syncthreads();
+    if (tid < 16 && tid < nc) {
+      float u = 0.f;
+      for (int r = 0; r < 16; ++r) u += r2[r * 16 + tid];
+      gb[(size_t)wk * worker_stride + c0 + tid] = u;
+    }
+  }
+}
+
+}  // namespace
+
+bool head_supported(int cin, int classes, const void* x, const void* w) {
+  return classes >= 1 && classes <= kMaxClasses && cin % 4 == 0 && cin <= 256 * 8 &&
+         (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && (reinterpret_cast<uintptr_t>(w) & 15u) == 0;
+}
+
+void head_fwd_loss_dgrad_f32(hipStream_t st, const float* x, const float* w, const float* bias,
+                             const int32_t* labels, int cin, int classes, const Segments& seg, float* z,
+                             float* dz, float* loss_rows, const float* mask, float* dx, bool accumulate) {
+  const int rows = seg.off[seg.K];
+  const int nv = (cin + 255) / 256;
+  const dim3 grid((rows + 3) / 4), block(256);
+  const int acc = accumulate ? 1 : 0;
+#define OMNI_HEAD(NV)                                                                                          \
+  hipLaunchKernelGGL(head_fwd_loss_dgrad_kernel<NV>, grid, block, 0, st, x, w, bias, labels, cin, classes, seg, \
+                     z, dz, loss_rows, mask, dx, acc)
+  if (nv <= 1) OMNI_HEAD(1);
+  else if (nv <= 2) OMNI_HEAD(2);
+  else if (nv <= 4) OMNI_HEAD(4);
+  else OMNI_HEAD(8);
+#undef OMNI_HEAD
+}
+
+void head_wgrad_loss_f32(hipStream_t st, const float* dz, const float* x, const int32_t* labels, int cin,
+                         int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
+                         const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status) {
+  const int jchunks = (cin + 15) / 16;
+  dim3 grid(seg.K * jchunks + 1, (classes + 15) / 16, 1);
+  hipLaunchKernelGGL(head_wgrad_loss_kernel, grid, dim3(256), 0, st, dz, x, labels, cin, classes, seg, gw, gb,
+                     worker_stride, loss_rows, loss_per_worker, loss, status);
+}
+
+}  // namespace omni

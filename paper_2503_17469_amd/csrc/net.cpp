@@ -47,8 +47,9 @@ struct omni_net {
   int dtype, K_max, B_max;
   size_t P = 0, P_stride = 0;
   size_t ws_bytes = 0;
-  size_t grads_off = 0, loss_rows_off = 0, status_off = 0;
+  size_t grads_off = 0, loss_rows_off = 0, status_off = 0, partial_off = 0, counters_off = 0;
   int classes = 0;
+  const void* ws_ready = nullptr;   // workspace whose arrival counters are known to be zero
   // optional event timing of one kernel class
   int time_class = -1, time_layer = -1;
   std::vector<hipEvent_t> ev;   // pairs: start, stop
@@ -155,6 +156,8 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
   net->grads_off = pos; pos += align_up((size_t)K_max * net->P_stride * sizeof(float), kAlign);
   net->loss_rows_off = pos; pos += align_up((size_t)B_max * sizeof(float), kAlign);
   net->status_off = pos; pos += kAlign;
+  net->counters_off = pos; pos += align_up(omni::kSplitMaxTiles * sizeof(uint32_t), kAlign);
+  net->partial_off = pos; pos += align_up(omni::kSplitPartialFloats * sizeof(float), kAlign);
   for (Tensor& t : net->tensors) {
     const size_t bytes = align_up((size_t)B_max * t.elems * sizeof(float), kAlign);
     t.act_off = pos; pos += bytes;
@@ -253,16 +256,30 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   auto actw = [&](int t) { return reinterpret_cast<float*>(ws + net->tensors[t].act_off); };
   auto grad = [&](int t) { return reinterpret_cast<float*>(ws + net->tensors[t].grad_off); };
 
-  omni::fill_u32(st, status, 1, 0u);
+  // Arrival counters of the split reductions must start at zero; every launch
+  // returns them to zero, so this runs once per workspace.
+  omni::SplitWorkspace sw;
+  sw.partial = reinterpret_cast<float*>(ws + net->partial_off);
+  sw.counters = reinterpret_cast<uint32_t*>(ws + net->counters_off);
+  if (net->ws_ready != workspace) {
+    omni::fill_u32(st, sw.counters, omni::kSplitMaxTiles, 0u);
+    net->ws_ready = workspace;
+  }
+
+  const int n_layers = (int)net->layers.size();
+  const Layer& last = net->layers[n_layers - 1];
+  const bool fused_head = last.d.op == OMNI_OP_LINEAR &&
+                          omni::head_supported(last.d.cin, last.d.cout, act(last.in0), params + last.w_off);
 
   // ---- forward over the concatenated batch
   for (const Layer& L : net->layers) {
     if (L.fused_away) continue;
+    if (fused_head && &L == &last) continue;
     switch (L.d.op) {
       case OMNI_OP_LINEAR: {
         TimedScope ts(net, st, OMNI_KERNEL_LINEAR_FWD, (int)(&L - net->layers.data()));
         omni::linear_fwd_f32(st, act(L.in0), params + L.w_off, L.has_b ? params + L.b_off : nullptr, actw(L.out),
-                             rows, L.d.cin, L.d.cout, net->tensors[L.out].relu);
+                             rows, L.d.cin, L.d.cout, net->tensors[L.out].relu, sw);
         break;
       }
       default: break;
@@ -270,18 +287,31 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   }
 
   // ---- loss: dz already carries 1/b_k, so everything downstream is a per-worker mean gradient
-  const int logits = net->layers.back().out;
-  {
-    TimedScope ts(net, st, OMNI_KERNEL_LOSS, (int)net->layers.size() - 1);
+  const int logits = last.out;
+  std::vector<char> written(net->tensors.size(), 0);
+  if (fused_head) {
+    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
+    const bool need_dx = last.in0 >= 0;
+    omni::head_fwd_loss_dgrad_f32(st, act(last.in0), params + last.w_off, last.has_b ? params + last.b_off : nullptr,
+                                  labels, last.d.cin, last.d.cout, seg, actw(logits), grad(logits), loss_rows,
+                                  need_dx && net->tensors[last.in0].relu ? act(last.in0) : nullptr,
+                                  need_dx ? grad(last.in0) : nullptr, false);
+    if (need_dx) written[last.in0] = 1;
+    omni::head_wgrad_loss_f32(st, grad(logits), act(last.in0), labels, last.d.cin, last.d.cout, seg, G + last.w_off,
+                              last.has_b ? G + last.b_off : nullptr, net->P_stride, loss_rows, loss_per_worker, loss,
+                              status);
+  } else {
+    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
+    omni::fill_u32(st, status, 1, 0u);
     omni::softmax_xent_f32(st, act(logits), labels, net->classes, seg, grad(logits), loss_rows, loss_per_worker,
                            loss, status);
   }
 
   // ---- backward: input gradients on all rows, parameter gradients per worker
-  std::vector<char> written(net->tensors.size(), 0);
-  for (int i = (int)net->layers.size() - 1; i >= 0; --i) {
+  for (int i = n_layers - 1; i >= 0; --i) {
     const Layer& L = net->layers[i];
     if (L.fused_away) continue;
+    if (fused_head && i == n_layers - 1) continue;
     switch (L.d.op) {
       case OMNI_OP_LINEAR: {
         {
@@ -293,7 +323,7 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
           const Tensor& ti = net->tensors[L.in0];
           TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
           omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, ti.relu ? act(L.in0) : nullptr, grad(L.in0),
-                                 rows, L.d.cin, L.d.cout, written[L.in0] != 0);
+                                 rows, L.d.cin, L.d.cout, written[L.in0] != 0, sw);
           written[L.in0] = 1;
         }
         break;
