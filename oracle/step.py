@@ -60,7 +60,9 @@ def forward_backward(net, theta, x, labels, loss_scale, segments=None, store: Op
     yields the mean loss and mean gradient over these n rows.  `segments`
     (prefix offsets within x) makes batch norm use each segment's own
     statistics; None means all rows form one segment.  `store`, if given, is
-    applied to every layer output as it is written (bf16 storage model).
+    applied to every layer output except the logits as it is written (model of
+    a pipeline that stores activations in bf16 and keeps the logits in fp32), so
+    that ReLU masks and pooling arg-maxima are decided on the stored values.
 
     Returns (per-row losses, gradient [P], activations list or None)."""
     theta = np.asarray(theta, dtype=np.float64)
@@ -105,7 +107,7 @@ def forward_backward(net, theta, x, labels, loss_scale, segments=None, store: Op
             y = L.gap_fwd(a)
         else:
             raise ValueError(op)
-        acts.append(st(y))
+        acts.append(st(y) if lay is not net[-1] else y)
         caches.append(cache)
 
     z = acts[-1].reshape(n, -1)

@@ -1,0 +1,522 @@
+// bf16 convolutions and fully connected layers as implicit GEMMs on the CDNA4
+// matrix cores (v_mfma_f32_32x32x16_bf16, fp32 accumulation).
+//
+// These are the contractions inside the per-worker gradient of Algorithm 1
+// (procedure Train, gradient line) for the convolutional networks:
+//   forward  Y[m][co]  = sum_{u,v,ci} X[n, h*s+u-p, w*s+v-p, ci] * W[co][u][v][ci]
+//   dgrad    dX[m][ci] = sum_{u,v,co} dY[n, (h+p-u)/s, (w+p-v)/s, co] * Wt[ci][u][v][co]
+//   wgrad    G_k[co][u][v][ci] = sum over worker k's rows and all positions of
+//                                dY[m][co] * X[n, h*s+u-p, w*s+v-p, ci]
+// with channels-last activations, m = (n, h, w).  Forward and dgrad see all
+// workers' rows in one launch; wgrad writes one output per worker.
+//
+// Kernel A (forward / dgrad): 128 x (64*TN) output tile per workgroup, 4
+// wavefronts in a 2x2 grid, each 64 x (32*TN).  The left operand is gathered
+// on the fly (no im2col buffer): a 16-byte piece holds 8 consecutive channels of
+// one filter tap, so it is contiguous in memory.  Slabs of 32 reduction
+// elements go through LDS (double buffered, next slab prefetched to registers).
+//
+// Kernel B (wgrad): the reduction runs over positions m, which is the SLOW index
+// of both operands, while the matrix instruction wants 8 consecutive reduction
+// elements per lane.  Each thread therefore loads 4 consecutive positions of
+// one 8-channel piece and transposes them in registers into 8 four-position
+// words before writing LDS.  Each worker's position range is cut into equal
+// chunks, one workgroup per (tile, chunk): every workgroup does the same amount
+// of work however ragged the b_k are.  Chunks of one worker park partial tiles;
+// the last to arrive adds them in chunk order (bit-reproducible).
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+
+#include "bf16.h"
+#include "common.h"
+#include "kernels.h"
+
+namespace omni {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+
+namespace {
+
+constexpr int kThreads = 256;
+constexpr int BM = 128;
+constexpr int BK = 32;
+constexpr int kMaxPieces = 1024;   // reduction pieces (8 channels of one tap) a kernel can index: K <= 8192
+
+__device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
+
+// q-th 8-channel piece of the reduction -> (filter row u, filter column v, first channel)
+__device__ inline void build_tap_table(int* tab, const ConvGeom& g, int tid) {
+  for (int q = tid; q * 8 < g.K && q < kMaxPieces; q += kThreads) {
+    const int k = q * 8;
+    const int tap = k / g.Cs, ci = k - tap * g.Cs;
+    const int u = tap / g.ks, v = tap - u * g.ks;
+    tab[q] = u | (v << 4) | (ci << 8);
+  }
+}
+
+// Source element offset of (sample n, position h,w, tap u,v, channel ci); -1 if it falls in the padding.
+__device__ inline long gather_offset(const ConvGeom& g, int n, int h, int w, int u, int v, int ci) {
+  int hs, ws;
+  bool ok;
+  if (!g.transposed) {
+    hs = h * g.stride + u - g.pad;
+    ws = w * g.stride + v - g.pad;
+    ok = hs >= 0 && hs < g.Hs && ws >= 0 && ws < g.Ws;
+  } else {
+    const int th = h + g.pad - u, tw = w + g.pad - v;
+    ok = th >= 0 && tw >= 0;
+    if (g.stride == 1) {
+      hs = th; ws = tw;
+    } else {
+      ok = ok && (th % g.stride == 0) && (tw % g.stride == 0);
+      hs = th / g.stride; ws = tw / g.stride;
+    }
+    ok = ok && hs < g.Hs && ws < g.Ws;
+  }
+  return ok ? (((long)n * g.Hs + hs) * g.Ws + ws) * g.Cs + ci : -1;
+}
+
+// position index m -> (n, h, w); m < 2^24 so the float quotient is exact after one correction
+__device__ inline void decode_pos(const ConvGeom& g, int m, int& n, int& h, int& w) {
+  const int hw = g.Hp * g.Wp;
+  n = (int)((float)m * (1.0f / (float)hw));
+  if (n * hw > m) --n;
+  if ((n + 1) * hw <= m) ++n;
+  const int r = m - n * hw;
+  h = (int)((float)r * (1.0f / (float)g.Wp));
+  if (h * g.Wp > r) --h;
+  if ((h + 1) * g.Wp <= r) ++h;
+  w = r - h * g.Wp;
+}
+
+// ------------------------------------------------------------------ kernel A
+struct ConvParams {
+  const bf16_t* src;   // gathered tensor [rows][Hs][Ws][Cs]
+  const bf16_t* wgt;   // [N][K]
+  bf16_t* out;         // [M][N]
+  int M, N;
+  ConvGeom g;
+  const float* bias;   // [N] or null
+  const bf16_t* mask;  // [M][N] or null: the value passes where mask > 0
+  int relu, accumulate;
+};
+
+template <int TN>
+__global__ __launch_bounds__(kThreads) void conv_gemm_kernel(ConvParams p) {
+  constexpr int BN = 64 * TN;
+  constexpr int kRow = BK + 8;               // LDS row pitch in bf16 (80 bytes: 16-byte reads, rows 20 banks apart)
+  constexpr int kA = BM * kRow, kB = BN * kRow;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (kA + kB)];
+  __shared__ int tab[kMaxPieces];
+  auto sA = [&](int s) { return lds + s * (kA + kB); };
+  auto sB = [&](int s) { return lds + s * (kA + kB) + kA; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tiles_n = (p.N + BN - 1) / BN;
+  const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  const int wrow = (wave >> 1) * 64, wcol = (wave & 1) * 32 * TN;
+  const ConvGeom g = p.g;
+
+  build_tap_table(tab, g, tid);
+
+  // this thread's two left-operand rows (fixed for the whole reduction)
+  int an[2], ah[2], aw[2];
+  bool arow_ok[2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int m = row0 + ((tid + kThreads * i) >> 2);
+    arow_ok[i] = m < p.M;
+    decode_pos(g, arow_ok[i] ? m : 0, an[i], ah[i], aw[i]);
+  }
+  const int akc = tid & 3;   // piece within the slab (same for both rows: 256 % 4 == 0)
+  __syncthreads();           // tap table ready
+
+  v16f acc[2][TN];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  u32x4 ra[2], rb[TN];
+  uint32_t ok = 0;   // bit i: left piece i valid; bit 4+i: right piece i valid
+  auto load_slab = [&](int k0) {
+    ok = 0;
+    const int q = (k0 >> 3) + akc;
+    const bool kin = q * 8 < g.K;
+    const int t = tab[kin ? q : 0];
+    const int u = t & 15, v = (t >> 4) & 15, ci = t >> 8;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const long o = gather_offset(g, an[i], ah[i], aw[i], u, v, ci);
+      const bool in = kin && arow_ok[i] && o >= 0;
+      ra[i] = *reinterpret_cast<const u32x4*>(p.src + (in ? o : 0));
+      ok |= (in ? 1u : 0u) << i;
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      const int c = tid + kThreads * i;
+      const int r = col0 + (c >> 2), k = k0 + (c & 3) * 8;
+      const bool in = r < p.N && k < g.K;
+      rb[i] = *reinterpret_cast<const u32x4*>(p.wgt + (in ? (size_t)r * g.K + k : 0));
+      ok |= (in ? 1u : 0u) << (4 + i);
+    }
+  };
+  auto store_slab = [&](int s) {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = tid + kThreads * i;
+      *reinterpret_cast<u32x4*>(sA(s) + (c >> 2) * kRow + (c & 3) * 8) = ((ok >> i) & 1u) ? ra[i] : zero;
+    }
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+      const int c = tid + kThreads * i;
+      *reinterpret_cast<u32x4*>(sB(s) + (c >> 2) * kRow + (c & 3) * 8) = ((ok >> (4 + i)) & 1u) ? rb[i] : zero;
+    }
+  };
+
+  const int nslab = (g.K + BK - 1) / BK;
+  load_slab(0);
+  store_slab(0);
+  __syncthreads();
+  for (int s = 0; s < nslab; ++s) {
+    const int cur = s & 1;
+    // always issued (past the end it re-reads element 0 and is dropped): a load
+    // issued on one path only would make every later wait drain the queue
+    load_slab(s + 1 < nslab ? (s + 1) * BK : g.K);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[2], fb[TN];
+      const int ko = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+        fa[a] = as_bf16x8(*reinterpret_cast<const u32x4*>(sA(cur) + (wrow + a * 32 + (lane & 31)) * kRow + ko));
+#pragma unroll
+      for (int b = 0; b < TN; ++b)
+        fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(sB(cur) + (wcol + b * 32 + (lane & 31)) * kRow + ko));
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    }
+    if (s + 1 < nslab) {
+      store_slab(cur ^ 1);
+      __syncthreads();
+    }
+  }
+
+  // accumulator layout of a 32x32 block: register v of lane l holds row
+  // 8*(v/4) + 4*(l/32) + v%4, column l%32
+#pragma unroll
+  for (int b = 0; b < TN; ++b) {
+    const int j = col0 + wcol + b * 32 + (lane & 31);
+    if (j >= p.N) continue;
+    const float bj = p.bias ? p.bias[j] : 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = row0 + wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+        if (i >= p.M) continue;
+        const size_t idx = (size_t)i * p.N + j;
+        float val = acc[a][b][v] + bj;
+        if (p.relu) val = val > 0.f ? val : 0.f;
+        if (p.mask) val = bf16_to_f32(p.mask[idx]) > 0.f ? val : 0.f;
+        if (p.accumulate) val += bf16_to_f32(p.out[idx]);
+        p.out[idx] = f32_to_bf16(val);
+      }
+  }
+}
+
+// ------------------------------------------------------------------ kernel B
+struct WgradParams {
+  const bf16_t* dy;    // [positions][Cout]
+  const bf16_t* src;   // layer input [rows][Hs][Ws][Cs]
+  float* gw;           // worker w: gw + w*worker_stride, [Cout][taps][cin_real]
+  float* gb;           // worker w: gb + w*worker_stride, [Cout]; may be null
+  size_t worker_stride;
+  int Cout, cin_real;
+  ConvGeom g;          // Hp, Wp: output positions; gather as in the forward pass
+  int chunk;           // positions per workgroup (multiple of BK)
+  float* partial;      // [(tile * total_chunks + chunk index)][TM*TN*16][256] (+ bias tail)
+  uint32_t* counters;  // [tile * K + worker], zero between launches
+};
+struct ChunkTable {
+  int32_t first[OMNI_MAX_WORKERS + 1];   // first chunk index of every worker; first[K] = total
+};
+
+template <int TN>
+__global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Segments seg, ChunkTable ct) {
+  constexpr int BN = 64 * TN;
+  constexpr int kRow = BK + 4;               // 72-byte rows: 8-byte accesses, 8 rows apart lands 16 banks apart
+  constexpr int kA = BM * kRow, kB = BN * kRow;
+  constexpr int kTileFloats = 2 * TN * 16 * kThreads;
+  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (kA + kB)];
+  __shared__ int tab[kMaxPieces];
+  __shared__ uint32_t arrival;
+  auto sA = [&](int s) { return lds + s * (kA + kB); };
+  auto sB = [&](int s) { return lds + s * (kA + kB) + kA; };
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const ConvGeom g = p.g;
+  const int N = g.K;
+  const int tiles_n = (N + BN - 1) / BN;
+  const int tile = blockIdx.x;
+  const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  const int wrow = (wave >> 1) * 64, wcol = (wave & 1) * 32 * TN;
+
+  // which worker and which chunk of its positions
+  int wk = 0;
+  while (wk + 1 < seg.K && (int)blockIdx.y >= ct.first[wk + 1]) ++wk;
+  const int chunk_idx = blockIdx.y - ct.first[wk];
+  const int nchunks = ct.first[wk + 1] - ct.first[wk];
+  const int hw = g.Hp * g.Wp;
+  const int mbeg = seg.off[wk] * hw + chunk_idx * p.chunk;
+  const int mend = min(seg.off[wk + 1] * hw, mbeg + p.chunk);
+
+  build_tap_table(tab, g, tid);
+  __syncthreads();
+
+  // Staging tasks.  Threads 0..127: 16 output-channel pieces x 8 groups of 4
+  // positions of dY.  Threads 128..: (BN/8) reduction pieces x 8 groups of the
+  // gathered input.
+  const bool is_a = tid < 128;
+  const int t2 = is_a ? tid : tid - 128;
+  const int npiece = is_a ? 16 : BN / 8;
+  const int piece = t2 % npiece, mg = t2 / npiece;
+  const bool task = mg < 8;
+  int bu = 0, bv = 0, bci = 0;
+  bool piece_ok;
+  if (is_a) {
+    piece_ok = row0 + piece * 8 < p.Cout;
+  } else {
+    const int q = (col0 >> 3) + piece;
+    piece_ok = q * 8 < g.K;
+    const int t = tab[piece_ok ? q : 0];
+    bu = t & 15; bv = (t >> 4) & 15; bci = t >> 8;
+  }
+
+  v16f acc[2][TN];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < TN; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+  const bool want_bias = p.gb != nullptr && tile_n == 0;
+  float bsum = 0.f;
+
+  u32x4 r[4];
+  uint32_t ok = 0;
+  auto load_slab = [&](int m0) {
+    ok = 0;
+    const int mfirst = m0 + mg * 4;
+    int n = 0, h = 0, w = 0;
+    if (!is_a) decode_pos(g, min(mfirst, max(mend - 1, 0)), n, h, w);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int m = mfirst + q;
+      bool in = task && piece_ok && m < mend;
+      long o;
+      if (is_a) {
+        o = (long)m * p.Cout + row0 + piece * 8;
+      } else {
+        o = gather_offset(g, n, h, w, bu, bv, bci);
+        in = in && o >= 0;
+        if (++w == g.Wp) { w = 0; if (++h == g.Hp) { h = 0; ++n; } }
+      }
+      const bf16_t* base = is_a ? p.dy : p.src;
+      r[q] = *reinterpret_cast<const u32x4*>(base + (in ? o : 0));
+      ok |= (in ? 1u : 0u) << q;
+    }
+  };
+  auto store_slab = [&](int s) {
+    if (!task) return;
+    u32x4 c[4];
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) c[q] = ((ok >> q) & 1u) ? r[q] : zero;
+    bf16_t* dst = (is_a ? sA(s) : sB(s)) + (piece * 8) * kRow + mg * 4;
+    // word d of piece q holds channels 2d (low half) and 2d+1 (high half) of position q
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+      u32x2 lo, hi;
+      lo[0] = (c[0][d] & 0xFFFFu) | (c[1][d] << 16);
+      lo[1] = (c[2][d] & 0xFFFFu) | (c[3][d] << 16);
+      hi[0] = (c[0][d] >> 16) | (c[1][d] & 0xFFFF0000u);
+      hi[1] = (c[2][d] >> 16) | (c[3][d] & 0xFFFF0000u);
+      *reinterpret_cast<u32x2*>(dst + (2 * d) * kRow) = lo;
+      *reinterpret_cast<u32x2*>(dst + (2 * d + 1) * kRow) = hi;
+    }
+  };
+  auto frag = [&](const bf16_t* base, int row, int ko) {
+    const u32x2 lo = *reinterpret_cast<const u32x2*>(base + row * kRow + ko);
+    const u32x2 hi = *reinterpret_cast<const u32x2*>(base + row * kRow + ko + 4);
+    return as_bf16x8(u32x4{lo[0], lo[1], hi[0], hi[1]});
+  };
+
+  const int nslab = (mend - mbeg + BK - 1) / BK;
+  load_slab(mbeg);
+  store_slab(0);
+  __syncthreads();
+  for (int s = 0; s < nslab; ++s) {
+    const int cur = s & 1;
+    load_slab(s + 1 < nslab ? mbeg + (s + 1) * BK : mend);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      bf16x8 fa[2], fb[TN];
+      const int ko = ks * 16 + (lane >> 5) * 8;
+#pragma unroll
+      for (int a = 0; a < 2; ++a) fa[a] = frag(sA(cur), wrow + a * 32 + (lane & 31), ko);
+#pragma unroll
+      for (int b = 0; b < TN; ++b) fb[b] = frag(sB(cur), wcol + b * 32 + (lane & 31), ko);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+    }
+    if (want_bias && tid < BM) {
+      // rows of the dY slab are output channels: their sums over positions are the bias gradient
+      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA(cur) + tid * kRow);
+#pragma unroll
+      for (int d = 0; d < BK / 2; ++d) bsum += bf16_lo(rowp[d]) + bf16_hi(rowp[d]);
+    }
+    if (s + 1 < nslab) {
+      store_slab(cur ^ 1);
+      __syncthreads();
+    }
+  }
+
+  // ---- combine the chunks of this worker (fixed order), then write its gradient tile
+  bool finish = true;
+  if (nchunks > 1) {
+    float* mine = p.partial + ((size_t)tile * ct.first[seg.K] + blockIdx.y) * (kTileFloats + BM);
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < TN; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          __hip_atomic_store(mine + ((a * TN + b) * 16 + v) * kThreads + tid, acc[a][b][v], __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+    if (want_bias && tid < BM)
+      __hip_atomic_store(mine + kTileFloats + tid, bsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    uint32_t* ctr = p.counters + (size_t)tile * seg.K + wk;
+    if (tid == 0) arrival = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __syncthreads();
+    finish = (arrival == (uint32_t)nchunks - 1);
+    if (finish) {
+      const float* all = p.partial + ((size_t)tile * ct.first[seg.K] + ct.first[wk]) * (kTileFloats + BM);
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int b = 0; b < TN; ++b)
+#pragma unroll
+          for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+      bsum = 0.f;
+      for (int c = 0; c < nchunks; ++c) {
+        const float* src = all + (size_t)c * (kTileFloats + BM);
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < TN; ++b)
+#pragma unroll
+            for (int v = 0; v < 16; ++v)
+              acc[a][b][v] += __hip_atomic_load(src + ((a * TN + b) * 16 + v) * kThreads + tid, __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT);
+        if (want_bias && tid < BM)
+          bsum += __hip_atomic_load(src + kTileFloats + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (tid == 0) *ctr = 0u;
+    }
+  }
+  if (!finish) return;
+
+  const int taps = g.ks * g.ks;
+  float* gw = p.gw + (size_t)wk * p.worker_stride;
+#pragma unroll
+  for (int b = 0; b < TN; ++b) {
+    const int kcol = col0 + wcol + b * 32 + (lane & 31);
+    if (kcol >= g.K) continue;
+    const int tap = kcol / g.Cs, ci = kcol - tap * g.Cs;
+    if (ci >= p.cin_real) continue;   // padding channels of the first layer
+    const int colreal = tap * p.cin_real + ci;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = row0 + wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+        if (co < p.Cout) gw[(size_t)co * (taps * p.cin_real) + colreal] = acc[a][b][v];
+      }
+  }
+  if (want_bias && tid < BM && row0 + tid < p.Cout) p.gb[(size_t)wk * p.worker_stride + row0 + tid] = bsum;
+}
+
+}  // namespace
+
+size_t conv_wgrad_partial_floats() { return (size_t)kConvMaxPartialTiles * (2 * 2 * 16 * kThreads + BM); }
+
+bool conv_shape_supported(const ConvGeom& g, long positions) {
+  return g.Cs % 8 == 0 && g.K <= kMaxPieces * 8 && g.ks >= 1 && g.ks <= 15 && positions < (1L << 24);
+}
+
+void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                    const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
+  ConvParams p{};
+  p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
+  p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
+  const int tiles_m = (M + BM - 1) / BM;
+  if (N > 64) {
+    dim3 grid(tiles_m * ((N + 127) / 128));
+    hipLaunchKernelGGL(conv_gemm_kernel<2>, grid, dim3(kThreads), 0, st, p);
+  } else {
+    dim3 grid(tiles_m * ((N + 63) / 64));
+    hipLaunchKernelGGL(conv_gemm_kernel<1>, grid, dim3(kThreads), 0, st, p);
+  }
+}
+
+void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
+                     size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
+                     float* partial, uint32_t* counters) {
+  WgradParams p{};
+  p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
+  p.Cout = Cout; p.cin_real = cin_real; p.g = g; p.partial = partial; p.counters = counters;
+  const int tn = g.K > 64 ? 2 : 1;
+  const int tiles = ((Cout + BM - 1) / BM) * ((g.K + 64 * tn - 1) / (64 * tn));
+  const long hw = (long)g.Hp * g.Wp;
+  const long total = (long)seg.off[seg.K] * hw;
+  // chunk length: aim at ~2048 workgroups, at least 8 slabs each, within the scratch and counter budgets
+  long want = std::max<long>(1, 2048 / tiles);
+  long chunk = std::max<long>((total + want - 1) / want, 8 * BK);
+  chunk = (chunk + BK - 1) / BK * BK;
+  ChunkTable ct{};
+  for (;;) {
+    int acc = 0;
+    for (int k = 0; k < seg.K; ++k) {
+      ct.first[k] = acc;
+      acc += (int)(((long)(seg.off[k + 1] - seg.off[k]) * hw + chunk - 1) / chunk);
+    }
+    ct.first[seg.K] = acc;
+    // one chunk per worker needs neither scratch nor counters
+    if (acc == seg.K || ((long)tiles * acc <= kConvMaxPartialTiles && (long)tiles * seg.K <= kConvCounters)) break;
+    chunk *= 2;
+  }
+  p.chunk = (int)chunk;
+  dim3 grid(tiles, ct.first[seg.K]);
+  if (tn == 2)
+    hipLaunchKernelGGL(conv_wgrad_kernel<2>, grid, dim3(kThreads), 0, st, p, seg, ct);
+  else
+    hipLaunchKernelGGL(conv_wgrad_kernel<1>, grid, dim3(kThreads), 0, st, p, seg, ct);
+}
+
+}  // namespace omni

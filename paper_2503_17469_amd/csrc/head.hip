@@ -12,12 +12,11 @@
 //      extra workgroup) L_k, the lambda-weighted total loss and the label check.
 #include <hip/hip_runtime.h>
 
+#include "bf16.h"
 #include "common.h"
 #include "kernels.h"
 
 namespace omni {
-
-typedef float v4f __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -40,37 +39,42 @@ __device__ inline int owner(const Segments& seg, int s) {
 }
 __device__ inline float dot4(v4f a, v4f b) { return a[0] * b[0] + a[1] * b[1] + a[2] * b[2] + a[3] * b[3]; }
 
-// NV = 16-byte pieces of the input row each lane keeps in registers; one piece
-// per lane covers 256 consecutive inputs across the wavefront, so cin <= 256 * NV.
-template <int NV>
+// T is the storage type of the input rows, the weights and the input gradient
+// (fp32, or bf16 with fp32 arithmetic).  NV = 16-byte pieces of the input row
+// each lane keeps in registers; one piece per lane covers 64 * EL consecutive
+// inputs across the wavefront, so cin <= 64 * EL * NV.
+template <typename T, int NV>
 __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
-    const float* __restrict__ x, const float* __restrict__ w, const float* __restrict__ bias,
+    const T* __restrict__ x, const T* __restrict__ w, const float* __restrict__ bias,
     const int32_t* __restrict__ labels, int cin, int C, Segments seg, float* __restrict__ z,
-    float* __restrict__ dz, float* __restrict__ loss_rows, const float* __restrict__ mask,
-    float* __restrict__ dx, int accumulate) {
-  constexpr int CH = NV <= 4 ? 8 : 4;   // classes whose weight rows are in flight together
+    float* __restrict__ dz, float* __restrict__ loss_rows, int use_mask, T* __restrict__ dx, int accumulate) {
+  constexpr int EL = Piece<T>::EL;
+  constexpr int CH = NV * EL <= 16 ? 8 : 4;   // classes whose weight rows are in flight together
   __shared__ float zbuf[4][kMaxClasses];
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int rows = seg.off[seg.K];
   const int row_raw = blockIdx.x * 4 + wv;
   const bool live = row_raw < rows;
   const int row = live ? row_raw : rows - 1;   // idle wavefronts shadow the last row and write nothing
-  const float* xr = x + (size_t)row * cin;
+  const T* xr = x + (size_t)row * cin;
 
-  // ---- logits: the row stays in registers, weight rows stream past it
+  // ---- logits: the row stays in registers, weight rows stream past it.
   // Loads are unconditional (an out-of-range piece re-reads piece 0 and is zeroed
   // afterwards): guarded loads would serialise behind per-load waits.
-  v4f a[NV];
+  float a[NV][EL];
   int kk[NV];
 #pragma unroll
   for (int i = 0; i < NV; ++i) {
-    const int k = lane * 4 + 256 * i;
+    const int k = (lane + 64 * i) * EL;
     kk[i] = k < cin ? k : 0;
-    a[i] = *reinterpret_cast<const v4f*>(xr + kk[i]);
+    Piece<T>::load(xr + kk[i], a[i]);
   }
 #pragma unroll
   for (int i = 0; i < NV; ++i)
-    if (lane * 4 + 256 * i >= cin) a[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    if ((lane + 64 * i) * EL >= cin) {
+#pragma unroll
+      for (int e = 0; e < EL; ++e) a[i][e] = 0.f;
+    }
   for (int c0 = 0; c0 < C; c0 += CH) {
     float acc[CH];
 #pragma unroll
@@ -78,7 +82,12 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
       acc[j] = 0.f;
       const int c = min(c0 + j, C - 1);
 #pragma unroll
-      for (int i = 0; i < NV; ++i) acc[j] += dot4(a[i], *reinterpret_cast<const v4f*>(w + (size_t)c * cin + kk[i]));
+      for (int i = 0; i < NV; ++i) {
+        float wv_[EL];
+        Piece<T>::load(w + (size_t)c * cin + kk[i], wv_);
+#pragma unroll
+        for (int e = 0; e < EL; ++e) acc[j] += a[i][e] * wv_[e];
+      }
     }
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
@@ -114,37 +123,49 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
   }
   __syncthreads();
 
-  // ---- input gradient dx = dz w, masked by the folded ReLU
+  // ---- input gradient dx = dz w, masked by the folded ReLU (the input row itself)
   if (dx != nullptr && live) {
-    v4f g[NV];
+    float g[NV][EL];
 #pragma unroll
-    for (int i = 0; i < NV; ++i) g[i] = v4f{0.f, 0.f, 0.f, 0.f};
+    for (int i = 0; i < NV; ++i)
+#pragma unroll
+      for (int e = 0; e < EL; ++e) g[i][e] = 0.f;
 #pragma unroll 4
     for (int c = 0; c < C; ++c) {
       const float d = zbuf[wv][c];
 #pragma unroll
-      for (int i = 0; i < NV; ++i) g[i] += d * *reinterpret_cast<const v4f*>(w + (size_t)c * cin + kk[i]);
+      for (int i = 0; i < NV; ++i) {
+        float wv_[EL];
+        Piece<T>::load(w + (size_t)c * cin + kk[i], wv_);
+#pragma unroll
+        for (int e = 0; e < EL; ++e) g[i][e] += d * wv_[e];
+      }
     }
 #pragma unroll
     for (int i = 0; i < NV; ++i) {
-      const int k = lane * 4 + 256 * i;
+      const int k = (lane + 64 * i) * EL;
       if (k >= cin) continue;
       const size_t idx = (size_t)row * cin + k;
-      v4f gi = g[i];
-      if (mask) {
+      if (use_mask) {
 #pragma unroll
-        for (int e = 0; e < 4; ++e) gi[e] = a[i][e] > 0.f ? gi[e] : 0.f;   // mask is the input row itself
+        for (int e = 0; e < EL; ++e) g[i][e] = a[i][e] > 0.f ? g[i][e] : 0.f;
       }
-      if (accumulate) gi += *reinterpret_cast<const v4f*>(dx + idx);
-      *reinterpret_cast<v4f*>(dx + idx) = gi;
+      if (accumulate) {
+        float old[EL];
+        Piece<T>::load(dx + idx, old);
+#pragma unroll
+        for (int e = 0; e < EL; ++e) g[i][e] += old[e];
+      }
+      Piece<T>::store(dx + idx, g[i]);
     }
   }
 }
 
 // grid.x = K * ceil(cin/16) + 1, grid.y = ceil(C/16).  A workgroup is 16 input
 // columns x 16 row groups; each thread walks its share of the worker's rows.
+template <typename T>
 __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
-    const float* __restrict__ dz, const float* __restrict__ x, const int32_t* __restrict__ labels, int cin, int C,
+    const float* __restrict__ dz, const T* __restrict__ x, const int32_t* __restrict__ labels, int cin, int C,
     Segments seg, float* __restrict__ gw, float* __restrict__ gb, size_t worker_stride,
     const float* __restrict__ loss_rows, float* __restrict__ loss_per_worker, float* __restrict__ loss,
     uint32_t* __restrict__ status) {
@@ -205,7 +226,7 @@ __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
     for (; s + 48 < s_end; s += 64) {          // four rows per trip: their loads overlap
       float av[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) av[u] = x[(size_t)(s + 16 * u) * cin + j];
+      for (int u = 0; u < 4; ++u) av[u] = Piece<T>::get(x + (size_t)(s + 16 * u) * cin + j);
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const float* d = dz + (size_t)(s + 16 * u) * C + c0;
@@ -214,7 +235,7 @@ __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
       }
     }
     for (; s < s_end; s += 16) {
-      const float a = x[(size_t)s * cin + j];
+      const float a = Piece<T>::get(x + (size_t)s * cin + j);
       const float* d = dz + (size_t)s * C + c0;
 #pragma unroll
       for (int c = 0; c < 16; ++c) acc[c] += d[c < nc ? c : 0] * a;
@@ -251,35 +272,52 @@ __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
 
 }  // namespace
 
-bool head_supported(int cin, int classes, const void* x, const void* w) {
-  return classes >= 1 && classes <= kMaxClasses && cin % 4 == 0 && cin <= 256 * 8 &&
+bool head_supported(int cin, int classes, const void* x, const void* w, bool bf16) {
+  const int el = bf16 ? 8 : 4;
+  return classes >= 1 && classes <= kMaxClasses && cin % el == 0 && cin <= 2048 &&
          (reinterpret_cast<uintptr_t>(x) & 15u) == 0 && (reinterpret_cast<uintptr_t>(w) & 15u) == 0;
 }
 
-void head_fwd_loss_dgrad_f32(hipStream_t st, const float* x, const float* w, const float* bias,
-                             const int32_t* labels, int cin, int classes, const Segments& seg, float* z,
-                             float* dz, float* loss_rows, const float* mask, float* dx, bool accumulate) {
+template <typename T>
+static void launch_head_fwd(hipStream_t st, const T* x, const T* w, const float* bias, const int32_t* labels, int cin,
+                            int classes, const Segments& seg, float* z, float* dz, float* loss_rows, bool use_mask,
+                            T* dx, bool accumulate) {
   const int rows = seg.off[seg.K];
-  const int nv = (cin + 255) / 256;
+  const int nv = (cin + 64 * Piece<T>::EL - 1) / (64 * Piece<T>::EL);
   const dim3 grid((rows + 3) / 4), block(256);
-  const int acc = accumulate ? 1 : 0;
-#define OMNI_HEAD(NV)                                                                                          \
-  hipLaunchKernelGGL(head_fwd_loss_dgrad_kernel<NV>, grid, block, 0, st, x, w, bias, labels, cin, classes, seg, \
-                     z, dz, loss_rows, mask, dx, acc)
+  const int acc = accumulate ? 1 : 0, um = use_mask ? 1 : 0;
+#define OMNI_HEAD(NV)                                                                                    \
+  hipLaunchKernelGGL((head_fwd_loss_dgrad_kernel<T, NV>), grid, block, 0, st, x, w, bias, labels, cin, classes, seg, \
+                     z, dz, loss_rows, um, dx, acc)
   if (nv <= 1) OMNI_HEAD(1);
   else if (nv <= 2) OMNI_HEAD(2);
   else if (nv <= 4) OMNI_HEAD(4);
-  else OMNI_HEAD(8);
+  else if constexpr (Piece<T>::EL == 4) OMNI_HEAD(8);
 #undef OMNI_HEAD
 }
 
-void head_wgrad_loss_f32(hipStream_t st, const float* dz, const float* x, const int32_t* labels, int cin,
-                         int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
-                         const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status) {
+void head_fwd_loss_dgrad(hipStream_t st, bool bf16, const void* x, const void* w, const float* bias,
+                         const int32_t* labels, int cin, int classes, const Segments& seg, float* z, float* dz,
+                         float* loss_rows, bool use_mask, void* dx, bool accumulate) {
+  if (bf16)
+    launch_head_fwd<bf16_t>(st, static_cast<const bf16_t*>(x), static_cast<const bf16_t*>(w), bias, labels, cin,
+                            classes, seg, z, dz, loss_rows, use_mask, static_cast<bf16_t*>(dx), accumulate);
+  else
+    launch_head_fwd<float>(st, static_cast<const float*>(x), static_cast<const float*>(w), bias, labels, cin, classes,
+                           seg, z, dz, loss_rows, use_mask, static_cast<float*>(dx), accumulate);
+}
+
+void head_wgrad_loss(hipStream_t st, bool bf16, const float* dz, const void* x, const int32_t* labels, int cin,
+                     int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
+                     const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status) {
   const int jchunks = (cin + 15) / 16;
   dim3 grid(seg.K * jchunks + 1, (classes + 15) / 16, 1);
-  hipLaunchKernelGGL(head_wgrad_loss_kernel, grid, dim3(256), 0, st, dz, x, labels, cin, classes, seg, gw, gb,
-                     worker_stride, loss_rows, loss_per_worker, loss, status);
+  if (bf16)
+    hipLaunchKernelGGL(head_wgrad_loss_kernel<bf16_t>, grid, dim3(256), 0, st, dz, static_cast<const bf16_t*>(x),
+                       labels, cin, classes, seg, gw, gb, worker_stride, loss_rows, loss_per_worker, loss, status);
+  else
+    hipLaunchKernelGGL(head_wgrad_loss_kernel<float>, grid, dim3(256), 0, st, dz, static_cast<const float*>(x),
+                       labels, cin, classes, seg, gw, gb, worker_stride, loss_rows, loss_per_worker, loss, status);
 }
 
 }  // namespace omni

@@ -32,18 +32,55 @@ void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw
                       size_t worker_stride, const Segments& seg, int cin, int cout);
 
 // ---- classifier head (head.hip): last fully connected layer with few outputs ----
+// `bf16` selects the storage type of x, w and dx (bf16 words) versus fp32; the
+// arithmetic, logits, dz and all gradients of parameters are fp32 either way.
 // True if the fused head kernels can take this shape (else use the generic path).
-bool head_supported(int cin, int classes, const void* x, const void* w);
+bool head_supported(int cin, int classes, const void* x, const void* w, bool bf16);
 // z = x w^T + bias; loss_rows, dz = (softmax(z) - onehot)/b_k; optionally
-// dx (+)= dz w masked by mask > 0 (dx may be null when the input needs no gradient).
-void head_fwd_loss_dgrad_f32(hipStream_t st, const float* x, const float* w, const float* bias,
-                             const int32_t* labels, int cin, int classes, const Segments& seg, float* z,
-                             float* dz, float* loss_rows, const float* mask, float* dx, bool accumulate);
+// dx (+)= dz w, zeroed where x <= 0 if use_mask (dx may be null when the input needs no gradient).
+void head_fwd_loss_dgrad(hipStream_t st, bool bf16, const void* x, const void* w, const float* bias,
+                         const int32_t* labels, int cin, int classes, const Segments& seg, float* z, float* dz,
+                         float* loss_rows, bool use_mask, void* dx, bool accumulate);
 // Per worker: gw_k = dz_k^T x_k, gb_k = column sums of dz_k; plus L_k, the total
 // loss and the status word (bit 0: some label outside [0, classes)).
-void head_wgrad_loss_f32(hipStream_t st, const float* dz, const float* x, const int32_t* labels, int cin,
-                         int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
-                         const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status);
+void head_wgrad_loss(hipStream_t st, bool bf16, const float* dz, const void* x, const int32_t* labels, int cin,
+                     int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
+                     const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status);
+
+// ---- bf16 convolutions / fully connected layers as implicit GEMMs (conv_bf16.hip) ----
+typedef uint16_t bf16_t;   // raw bfloat16 bits
+// How the left operand of an implicit GEMM is gathered from a channels-last tensor.
+struct ConvGeom {
+  int rows;             // samples
+  int Hs, Ws, Cs;       // gathered tensor: height, width, channels (multiple of 8)
+  int Hp, Wp;           // positions enumerated by the GEMM rows: m = (n*Hp + h)*Wp + w
+  int ks, stride, pad;  // filter size, stride, zero padding of the forward convolution
+  int transposed;       // 0: source = h*stride + u - pad.  1 (dgrad): t = h + pad - u, source = t/stride if divisible
+  int K;                // ks*ks*Cs
+};
+constexpr int kConvMaxPartialTiles = 2048;   // (tile, chunk) slots of wgrad scratch
+constexpr int kConvCounters = 16384;         // (tile, worker) arrival counters
+size_t conv_wgrad_partial_floats();
+bool conv_shape_supported(const ConvGeom& g, long positions);
+// out[M][N] = gather(src)[M][K] * wgt[N][K]^T (+bias) (ReLU) (masked where mask <= 0) (+= out)
+void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                    const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate);
+// Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).
+void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
+                     size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
+                     float* partial, uint32_t* counters);
+
+// ---- bf16 pointwise kernels (pointwise_bf16.hip) ----
+// fp32 weights [cout][taps][cin_real] -> bf16 [cout][taps][cin_pad] (zero padded) and,
+// if w_t is not null, the transposed copy [cin_pad][taps][cout] used by dgrad.
+void cast_weights_bf16(hipStream_t st, const float* w, bf16_t* w_fwd, bf16_t* w_t, int cout, int taps,
+                       int cin_real, int cin_pad);
+void pad_channels_bf16(hipStream_t st, const bf16_t* x, bf16_t* xp, long pixels, int c_real, int c_pad);
+void maxpool2_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, int H, int W, int C);
+// din = dout routed to the first maximum of each 2x2 window (scan order), zero elsewhere;
+// with relu_mask also zero where the maximum is not positive.
+void maxpool2_bwd_bf16(hipStream_t st, const bf16_t* in, const bf16_t* dout, bf16_t* din, int rows, int H, int W,
+                       int C, bool relu_mask);
 
 // ---- loss and update (pointwise.hip) ----
 void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int C, const Segments& seg,

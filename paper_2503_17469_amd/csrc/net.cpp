@@ -23,6 +23,7 @@ inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 struct Tensor {
   int h = 0, w = 0, c = 0;
   size_t elems = 0;        // per row
+  size_t esize = 4;        // bytes per element of the stored activation and its gradient
   size_t act_off = 0;      // byte offsets into the workspace
   size_t grad_off = 0;
   bool relu = false;       // ReLU folded into the producer; grad buffer is w.r.t. the pre-ReLU value
@@ -33,9 +34,15 @@ struct Layer {
   omni_layer_desc d;
   int out = -1;            // tensor index
   int in0 = -1, in1 = -1;  // tensor indices (-1 = network input)
+  int ih = 0, iw = 0, ic = 0;   // input shape
   size_t w_off = 0, b_off = 0;  // float offsets into params
   bool has_b = false;
   bool fused_away = false;      // ReLU merged into its producer
+  // bf16 path
+  int cin_pad = 0;              // input channels as the kernels see them (multiple of 8)
+  size_t wsh_off = 0;           // bf16 weight copy [cout][taps][cin_pad], element offset into the shadow area
+  size_t wt_off = 0;            // transposed copy [cin_pad][taps][cout] for dgrad
+  bool need_dgrad = false;
 };
 
 }  // namespace
@@ -48,6 +55,7 @@ struct omni_net {
   size_t P = 0, P_stride = 0;
   size_t ws_bytes = 0;
   size_t grads_off = 0, loss_rows_off = 0, status_off = 0, partial_off = 0, counters_off = 0;
+  size_t shadow_off = 0, shadow_elems = 0, xpad_off = 0, conv_partial_off = 0, conv_counters_off = 0;
   int classes = 0;
   const void* ws_ready = nullptr;   // workspace whose arrival counters are known to be zero
   // optional event timing of one kernel class
@@ -78,6 +86,8 @@ struct TimedScope {
     }
   }
 };
+
+bool is_param_op(int op) { return op == OMNI_OP_LINEAR || op == OMNI_OP_CONV; }
 }  // namespace
 
 using omni::fail;
@@ -92,7 +102,8 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
   if (in_h < 1 || in_w < 1 || in_c < 1) return fail(OMNI_EINVAL, "omni_net_create: bad input shape");
   if (K_max < 1 || B_max < K_max) return fail(OMNI_EINVAL, "omni_net_create: need 1 <= K_max <= B_max");
   if (K_max > OMNI_MAX_WORKERS) return fail(OMNI_ECAPACITY, "omni_net_create: K_max exceeds %d", OMNI_MAX_WORKERS);
-  if (dtype != OMNI_F32) return fail(OMNI_EINVAL, "omni_net_create: dtype %d not supported", dtype);
+  if (dtype != OMNI_F32 && dtype != OMNI_BF16) return fail(OMNI_EINVAL, "omni_net_create: dtype %d not supported", dtype);
+  const bool bf = dtype == OMNI_BF16;
 
   omni_net* net = new (std::nothrow) omni_net();
   if (!net) return fail(OMNI_EINVAL, "omni_net_create: out of host memory");
@@ -104,8 +115,13 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
     if (t < 0) { h = in_h; w = in_w; c = in_c; }
     else { h = net->tensors[t].h; w = net->tensors[t].w; c = net->tensors[t].c; }
   };
+  auto new_tensor = [&](int h, int w, int c) {
+    Tensor t; t.h = h; t.w = w; t.c = c; t.elems = (size_t)h * w * c; t.esize = bf ? 2 : 4;
+    net->tensors.push_back(t);
+    return (int)net->tensors.size() - 1;
+  };
 
-  size_t ppos = 0;
+  size_t ppos = 0, shpos = 0;
   net->layers.resize(n);
   for (int i = 0; i < n; ++i) {
     Layer& L = net->layers[i];
@@ -116,14 +132,38 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
       return bail(fail(OMNI_EINVAL, "layer %d: reads layer %d before its ReLU, which was folded into it", i, L.d.src));
     int h, w, c;
     shape_of(L.in0, h, w, c);
+    L.ih = h; L.iw = w; L.ic = c;
     switch (L.d.op) {
       case OMNI_OP_LINEAR: {
         if (L.d.cin != h * w * c || L.d.cout < 1)
           return bail(fail(OMNI_EINVAL, "layer %d: linear cin=%d does not match input %dx%dx%d", i, L.d.cin, h, w, c));
-        Tensor t; t.h = 1; t.w = 1; t.c = L.d.cout; t.elems = (size_t)L.d.cout;
-        net->tensors.push_back(t);
-        L.out = (int)net->tensors.size() - 1;
+        L.out = new_tensor(1, 1, L.d.cout);
         L.w_off = ppos; ppos += (size_t)L.d.cout * L.d.cin;
+        L.has_b = L.d.bias != 0;
+        if (L.has_b) { L.b_off = ppos; ppos += (size_t)L.d.cout; }
+        if (bf) {
+          if (L.d.cin % 8 != 0) return bail(fail(OMNI_EINVAL, "layer %d: bf16 linear needs cin %% 8 == 0", i));
+          if (i != n - 1 && L.d.cout % 8 != 0)
+            return bail(fail(OMNI_EINVAL, "layer %d: a hidden bf16 linear layer needs cout %% 8 == 0", i));
+          L.cin_pad = L.d.cin;
+        }
+        break;
+      }
+      case OMNI_OP_CONV: {
+        if (!bf) return bail(fail(OMNI_EINVAL, "layer %d: convolution is implemented for dtype bf16 only", i));
+        const int k = L.d.ksize, s = L.d.stride, p = L.d.pad;
+        if (L.d.cin != c || L.d.cout < 1 || k < 1 || k > 7 || s < 1 || s > 4 || p < 0 || p >= k)
+          return bail(fail(OMNI_EINVAL, "layer %d: bad convolution (cin=%d on %d channels, k=%d s=%d p=%d)", i, L.d.cin, c, k, s, p));
+        const int ho = (h + 2 * p - k) / s + 1, wo = (w + 2 * p - k) / s + 1;
+        if (ho < 1 || wo < 1) return bail(fail(OMNI_EINVAL, "layer %d: convolution output is empty", i));
+        if (L.d.cout % 8 != 0) return bail(fail(OMNI_EINVAL, "layer %d: bf16 convolution needs cout %% 8 == 0", i));
+        L.cin_pad = (c + 7) / 8 * 8;
+        if (L.cin_pad != c && L.in0 >= 0)
+          return bail(fail(OMNI_EINVAL, "layer %d: only the network input may have a channel count off the multiples of 8", i));
+        if ((long)k * k * L.cin_pad > 8192 || (long)k * k * L.d.cout > 8192)
+          return bail(fail(OMNI_EINVAL, "layer %d: reduction length above 8192 is not supported", i));
+        L.out = new_tensor(ho, wo, L.d.cout);
+        L.w_off = ppos; ppos += (size_t)L.d.cout * k * k * c;
         L.has_b = L.d.bias != 0;
         if (L.has_b) { L.b_off = ppos; ppos += (size_t)L.d.cout; }
         break;
@@ -131,8 +171,9 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
       case OMNI_OP_RELU: {
         if (L.in0 < 0) return bail(fail(OMNI_EINVAL, "layer %d: ReLU on the network input is not supported", i));
         const Layer& prod = net->layers[L.d.src];
-        if (prod.d.op != OMNI_OP_LINEAR)
-          return bail(fail(OMNI_EINVAL, "layer %d: ReLU after op %d is not supported for this dtype", i, prod.d.op));
+        const bool ok_prod = prod.d.op == OMNI_OP_LINEAR || prod.d.op == OMNI_OP_CONV;
+        if (!ok_prod || prod.fused_away)
+          return bail(fail(OMNI_EINVAL, "layer %d: ReLU after op %d is not supported", i, prod.d.op));
         if (net->tensors[L.in0].consumers != 0 || net->tensors[L.in0].relu)
           return bail(fail(OMNI_EINVAL, "layer %d: ReLU input must have no other consumer", i));
         net->tensors[L.in0].relu = true;
@@ -140,28 +181,61 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
         L.fused_away = true;
         continue;  // not a consumer in its own right
       }
+      case OMNI_OP_MAXPOOL2: {
+        if (!bf) return bail(fail(OMNI_EINVAL, "layer %d: max pooling is implemented for dtype bf16 only", i));
+        if (L.in0 < 0 || h % 2 || w % 2 || c % 8)
+          return bail(fail(OMNI_EINVAL, "layer %d: max pooling needs even H, W, channels %% 8 == 0 and a layer input", i));
+        L.out = new_tensor(h / 2, w / 2, c);
+        break;
+      }
       default:
-        return bail(fail(OMNI_EINVAL, "layer %d: op %d not supported for this dtype", i, L.d.op));
+        return bail(fail(OMNI_EINVAL, "layer %d: op %d not supported", i, L.d.op));
     }
     if (L.in0 >= 0) net->tensors[L.in0].consumers++;
+    if (bf && is_param_op(L.d.op)) {
+      const size_t taps = L.d.op == OMNI_OP_CONV ? (size_t)L.d.ksize * L.d.ksize : 1;
+      const size_t cnt = align_up((size_t)L.d.cout * taps * L.cin_pad, 64);
+      L.wsh_off = shpos; shpos += cnt;
+      L.need_dgrad = L.in0 >= 0 && i != n - 1;   // the head computes its own input gradient
+      if (L.need_dgrad) { L.wt_off = shpos; shpos += cnt; }
+    }
   }
+  for (const Layer& L : net->layers)
+    if (L.d.op == OMNI_OP_MAXPOOL2 && net->tensors[L.in0].consumers != 1)
+      return bail(fail(OMNI_EINVAL, "the input of a max pooling layer must have no other consumer"));
   net->P = ppos;
   net->P_stride = align_up(ppos, 64);
-  const Tensor& last = net->tensors[net->layers[n - 1].out];
+  net->shadow_elems = shpos;
+  const Layer& lastL = net->layers[n - 1];
+  const Tensor& last = net->tensors[lastL.out];
   if (last.h != 1 || last.w != 1) return bail(fail(OMNI_EINVAL, "last layer must produce [rows][classes]"));
   if (last.relu) return bail(fail(OMNI_EINVAL, "logits must not pass through ReLU"));
   net->classes = last.c;
+  if (bf) {
+    if (lastL.d.op != OMNI_OP_LINEAR || lastL.d.cin > 2048 || lastL.d.cout > 128)
+      return bail(fail(OMNI_EINVAL, "bf16 networks must end in a linear layer with cin <= 2048 and at most 128 outputs"));
+    if ((long)B_max * in_h * in_w >= (1L << 24))
+      return bail(fail(OMNI_ECAPACITY, "B_max * H * W must stay below 2^24 positions"));
+    net->tensors[lastL.out].esize = 4;   // logits and their gradient stay fp32
+  }
 
   size_t pos = 0;
-  net->grads_off = pos; pos += align_up((size_t)K_max * net->P_stride * sizeof(float), kAlign);
-  net->loss_rows_off = pos; pos += align_up((size_t)B_max * sizeof(float), kAlign);
-  net->status_off = pos; pos += kAlign;
-  net->counters_off = pos; pos += align_up(omni::kSplitMaxTiles * sizeof(uint32_t), kAlign);
-  net->partial_off = pos; pos += align_up(omni::kSplitPartialFloats * sizeof(float), kAlign);
+  auto take = [&](size_t bytes) { const size_t o = pos; pos += align_up(bytes, kAlign); return o; };
+  net->grads_off = take((size_t)K_max * net->P_stride * sizeof(float));
+  net->loss_rows_off = take((size_t)B_max * sizeof(float));
+  net->status_off = take(kAlign);
+  net->counters_off = take(omni::kSplitMaxTiles * sizeof(uint32_t));
+  net->partial_off = take(omni::kSplitPartialFloats * sizeof(float));
+  if (bf) {
+    net->conv_counters_off = take(omni::kConvCounters * sizeof(uint32_t));
+    net->conv_partial_off = take(omni::conv_wgrad_partial_floats() * sizeof(float));
+    net->shadow_off = take(net->shadow_elems * 2);
+    if (in_c % 8 != 0) net->xpad_off = take((size_t)B_max * in_h * in_w * ((in_c + 7) / 8 * 8) * 2);
+  }
   for (Tensor& t : net->tensors) {
-    const size_t bytes = align_up((size_t)B_max * t.elems * sizeof(float), kAlign);
-    t.act_off = pos; pos += bytes;
-    t.grad_off = pos; pos += bytes;
+    const size_t bytes = (size_t)B_max * t.elems * t.esize;
+    t.act_off = take(bytes);
+    t.grad_off = take(bytes);
   }
   net->ws_bytes = pos;
   *out = net;
@@ -222,6 +296,218 @@ int omni_net_timing_read(omni_net* net, double* total_ms, int64_t* launches) {
   return OMNI_OK;
 }
 
+}  // extern "C"
+
+namespace {
+
+struct StepCtx {
+  omni_net* net;
+  hipStream_t st;
+  char* ws;
+  float* params;
+  const void* x;
+  const int32_t* labels;
+  int rows;
+  omni::Segments seg;
+  float* G;
+  float* loss_rows;
+  uint32_t* status;
+  float* loss_per_worker;
+  float* loss;
+};
+
+// ------------------------------------------------------------------ fp32 path
+void step_f32(StepCtx& c) {
+  omni_net* net = c.net;
+  hipStream_t st = c.st;
+  auto act = [&](int t) -> const float* {
+    return t < 0 ? static_cast<const float*>(c.x) : reinterpret_cast<const float*>(c.ws + net->tensors[t].act_off);
+  };
+  auto actw = [&](int t) { return reinterpret_cast<float*>(c.ws + net->tensors[t].act_off); };
+  auto grad = [&](int t) { return reinterpret_cast<float*>(c.ws + net->tensors[t].grad_off); };
+  float* params = c.params;
+  const int rows = c.rows;
+
+  omni::SplitWorkspace sw;
+  sw.partial = reinterpret_cast<float*>(c.ws + net->partial_off);
+  sw.counters = reinterpret_cast<uint32_t*>(c.ws + net->counters_off);
+
+  const int n_layers = (int)net->layers.size();
+  const Layer& last = net->layers[n_layers - 1];
+  const bool fused_head = last.d.op == OMNI_OP_LINEAR &&
+                          omni::head_supported(last.d.cin, last.d.cout, act(last.in0), params + last.w_off, false);
+
+  // ---- forward over the concatenated batch
+  for (int i = 0; i < n_layers; ++i) {
+    const Layer& L = net->layers[i];
+    if (L.fused_away || (fused_head && i == n_layers - 1)) continue;
+    TimedScope ts(net, st, OMNI_KERNEL_LINEAR_FWD, i);
+    omni::linear_fwd_f32(st, act(L.in0), params + L.w_off, L.has_b ? params + L.b_off : nullptr, actw(L.out), rows,
+                         L.d.cin, L.d.cout, net->tensors[L.out].relu, sw);
+  }
+
+  // ---- loss: dz already carries 1/b_k, so everything downstream is a per-worker mean gradient
+  const int logits = last.out;
+  std::vector<char> written(net->tensors.size(), 0);
+  if (fused_head) {
+    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
+    const bool need_dx = last.in0 >= 0;
+    omni::head_fwd_loss_dgrad(st, false, act(last.in0), params + last.w_off,
+                              last.has_b ? params + last.b_off : nullptr, c.labels, last.d.cin, last.d.cout, c.seg,
+                              actw(logits), grad(logits), c.loss_rows, need_dx && net->tensors[last.in0].relu,
+                              need_dx ? grad(last.in0) : nullptr, false);
+    if (need_dx) written[last.in0] = 1;
+    omni::head_wgrad_loss(st, false, grad(logits), act(last.in0), c.labels, last.d.cin, last.d.cout, c.seg,
+                          c.G + last.w_off, last.has_b ? c.G + last.b_off : nullptr, net->P_stride, c.loss_rows,
+                          c.loss_per_worker, c.loss, c.status);
+  } else {
+    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
+    omni::fill_u32(st, c.status, 1, 0u);
+    omni::softmax_xent_f32(st, act(logits), c.labels, net->classes, c.seg, grad(logits), c.loss_rows,
+                           c.loss_per_worker, c.loss, c.status);
+  }
+
+  // ---- backward: input gradients on all rows, parameter gradients per worker
+  for (int i = n_layers - 1; i >= 0; --i) {
+    const Layer& L = net->layers[i];
+    if (L.fused_away || (fused_head && i == n_layers - 1)) continue;
+    {
+      TimedScope ts(net, st, OMNI_KERNEL_LINEAR_WGRAD, i);
+      omni::linear_wgrad_f32(st, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
+                             net->P_stride, c.seg, L.d.cin, L.d.cout);
+    }
+    if (L.in0 >= 0) {
+      const Tensor& ti = net->tensors[L.in0];
+      TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
+      omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, ti.relu ? act(L.in0) : nullptr, grad(L.in0), rows,
+                             L.d.cin, L.d.cout, written[L.in0] != 0, sw);
+      written[L.in0] = 1;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ bf16 path
+void step_bf16(StepCtx& c) {
+  using omni::bf16_t;
+  omni_net* net = c.net;
+  hipStream_t st = c.st;
+  const int rows = c.rows;
+  bf16_t* shadow = reinterpret_cast<bf16_t*>(c.ws + net->shadow_off);
+  const int in_c_pad = (net->in_c + 7) / 8 * 8;
+  const bf16_t* x_in = static_cast<const bf16_t*>(c.x);
+  if (in_c_pad != net->in_c) {
+    bf16_t* xp = reinterpret_cast<bf16_t*>(c.ws + net->xpad_off);
+    omni::pad_channels_bf16(st, x_in, xp, (long)rows * net->in_h * net->in_w, net->in_c, in_c_pad);
+    x_in = xp;
+  }
+  auto act = [&](int t) -> const bf16_t* {
+    return t < 0 ? x_in : reinterpret_cast<const bf16_t*>(c.ws + net->tensors[t].act_off);
+  };
+  auto actw = [&](int t) { return reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].act_off); };
+  auto grad = [&](int t) { return reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].grad_off); };
+  float* conv_partial = reinterpret_cast<float*>(c.ws + net->conv_partial_off);
+  uint32_t* conv_counters = reinterpret_cast<uint32_t*>(c.ws + net->conv_counters_off);
+
+  const int n_layers = (int)net->layers.size();
+  const Layer& last = net->layers[n_layers - 1];
+
+  // geometry of a parameter layer's forward gather
+  auto fwd_geom = [&](const Layer& L) {
+    omni::ConvGeom g{};
+    g.rows = rows;
+    if (L.d.op == OMNI_OP_CONV) {
+      const Tensor& to = net->tensors[L.out];
+      g.Hs = L.ih; g.Ws = L.iw; g.Cs = L.cin_pad; g.Hp = to.h; g.Wp = to.w;
+      g.ks = L.d.ksize; g.stride = L.d.stride; g.pad = L.d.pad;
+    } else {
+      g.Hs = 1; g.Ws = 1; g.Cs = L.cin_pad; g.Hp = 1; g.Wp = 1; g.ks = 1; g.stride = 1; g.pad = 0;
+    }
+    g.transposed = 0;
+    g.K = g.ks * g.ks * g.Cs;
+    return g;
+  };
+
+  // ---- bf16 copies of the weights (forward layout, and transposed for dgrad)
+  for (const Layer& L : net->layers) {
+    if (!is_param_op(L.d.op)) continue;
+    const int taps = L.d.op == OMNI_OP_CONV ? L.d.ksize * L.d.ksize : 1;
+    const int cin_real = L.d.op == OMNI_OP_CONV ? L.d.cin : L.cin_pad;
+    omni::cast_weights_bf16(st, c.params + L.w_off, shadow + L.wsh_off, L.need_dgrad ? shadow + L.wt_off : nullptr,
+                            L.d.cout, taps, cin_real, L.cin_pad);
+  }
+
+  // ---- forward over the concatenated batch
+  for (int i = 0; i < n_layers - 1; ++i) {
+    const Layer& L = net->layers[i];
+    if (L.fused_away) continue;
+    if (is_param_op(L.d.op)) {
+      TimedScope ts(net, st, L.d.op == OMNI_OP_CONV ? OMNI_KERNEL_CONV_FWD : OMNI_KERNEL_LINEAR_FWD, i);
+      const omni::ConvGeom g = fwd_geom(L);
+      const Tensor& to = net->tensors[L.out];
+      omni::conv_gemm_bf16(st, act(L.in0), shadow + L.wsh_off, actw(L.out), rows * to.h * to.w, L.d.cout, g,
+                           L.has_b ? c.params + L.b_off : nullptr, nullptr, to.relu, false);
+    } else if (L.d.op == OMNI_OP_MAXPOOL2) {
+      omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
+    }
+  }
+
+  // ---- classifier head: logits, loss, dz (with 1/b_k), first input gradient, head parameter gradients
+  std::vector<char> written(net->tensors.size(), 0);
+  {
+    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
+    const int logits = last.out;
+    float* z = reinterpret_cast<float*>(c.ws + net->tensors[logits].act_off);
+    float* dz = reinterpret_cast<float*>(c.ws + net->tensors[logits].grad_off);
+    const bool need_dx = last.in0 >= 0;
+    omni::head_fwd_loss_dgrad(st, true, act(last.in0), shadow + last.wsh_off,
+                              last.has_b ? c.params + last.b_off : nullptr, c.labels, last.d.cin, last.d.cout, c.seg,
+                              z, dz, c.loss_rows, need_dx && net->tensors[last.in0].relu,
+                              need_dx ? grad(last.in0) : nullptr, false);
+    if (need_dx) written[last.in0] = 1;
+    omni::head_wgrad_loss(st, true, dz, act(last.in0), c.labels, last.d.cin, last.d.cout, c.seg, c.G + last.w_off,
+                          last.has_b ? c.G + last.b_off : nullptr, net->P_stride, c.loss_rows, c.loss_per_worker,
+                          c.loss, c.status);
+  }
+
+  // ---- backward
+  for (int i = n_layers - 2; i >= 0; --i) {
+    const Layer& L = net->layers[i];
+    if (L.fused_away) continue;
+    if (is_param_op(L.d.op)) {
+      const omni::ConvGeom g = fwd_geom(L);
+      const Tensor& to = net->tensors[L.out];
+      const bool conv = L.d.op == OMNI_OP_CONV;
+      {
+        TimedScope ts(net, st, conv ? OMNI_KERNEL_CONV_WGRAD : OMNI_KERNEL_LINEAR_WGRAD, i);
+        omni::conv_wgrad_bf16(st, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
+                              net->P_stride, L.d.cout, L.d.cin, g, c.seg, conv_partial, conv_counters);
+      }
+      if (L.in0 >= 0) {
+        TimedScope ts(net, st, conv ? OMNI_KERNEL_CONV_DGRAD : OMNI_KERNEL_LINEAR_DGRAD, i);
+        omni::ConvGeom d = g;
+        d.Hs = to.h; d.Ws = to.w; d.Cs = L.d.cout;      // gather from dY
+        d.Hp = L.ih; d.Wp = L.iw;                        // one GEMM row per input position
+        if (!conv) { d.Hp = 1; d.Wp = 1; }
+        d.transposed = 1;
+        d.K = d.ks * d.ks * d.Cs;
+        const Tensor& ti = net->tensors[L.in0];
+        const int m_rows = conv ? rows * L.ih * L.iw : rows;
+        omni::conv_gemm_bf16(st, grad(L.out), shadow + L.wt_off, grad(L.in0), m_rows, L.cin_pad, d, nullptr,
+                             ti.relu ? act(L.in0) : nullptr, false, written[L.in0] != 0);
+        written[L.in0] = 1;
+      }
+    } else if (L.d.op == OMNI_OP_MAXPOOL2) {
+      omni::maxpool2_bwd_bf16(st, act(L.in0), grad(L.out), grad(L.in0), rows, L.ih, L.iw, L.ic,
+                              net->tensors[L.in0].relu);
+      written[L.in0] = 1;
+    }
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
 int omni_step(omni_net* net, void* stream, float* params, const void* x, const int32_t* labels,
               const int32_t* off, const int32_t* b, int32_t K, float lr, void* workspace,
               float* loss_per_worker, float* loss, uint32_t flags) {
@@ -240,102 +526,38 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
       (reinterpret_cast<uintptr_t>(x) & 15u))
     return fail(OMNI_EINVAL, "omni_step: params/x must be 16-byte and workspace 256-byte aligned");
 
-  hipStream_t st = static_cast<hipStream_t>(stream);
-  char* ws = static_cast<char*>(workspace);
-  const int rows = off[K];
-  omni::Segments seg{};
-  seg.K = K;
-  for (int k = 0; k <= K; ++k) seg.off[k] = off[k];
-
-  float* G = reinterpret_cast<float*>(ws + net->grads_off);
-  float* loss_rows = reinterpret_cast<float*>(ws + net->loss_rows_off);
-  uint32_t* status = reinterpret_cast<uint32_t*>(ws + net->status_off);
-  auto act = [&](int t) -> const float* {
-    return t < 0 ? static_cast<const float*>(x) : reinterpret_cast<const float*>(ws + net->tensors[t].act_off);
-  };
-  auto actw = [&](int t) { return reinterpret_cast<float*>(ws + net->tensors[t].act_off); };
-  auto grad = [&](int t) { return reinterpret_cast<float*>(ws + net->tensors[t].grad_off); };
+  StepCtx c{};
+  c.net = net;
+  c.st = static_cast<hipStream_t>(stream);
+  c.ws = static_cast<char*>(workspace);
+  c.params = params;
+  c.x = x;
+  c.labels = labels;
+  c.rows = off[K];
+  c.seg.K = K;
+  for (int k = 0; k <= K; ++k) c.seg.off[k] = off[k];
+  c.G = reinterpret_cast<float*>(c.ws + net->grads_off);
+  c.loss_rows = reinterpret_cast<float*>(c.ws + net->loss_rows_off);
+  c.status = reinterpret_cast<uint32_t*>(c.ws + net->status_off);
+  c.loss_per_worker = loss_per_worker;
+  c.loss = loss;
 
   // Arrival counters of the split reductions must start at zero; every launch
   // returns them to zero, so this runs once per workspace.
-  omni::SplitWorkspace sw;
-  sw.partial = reinterpret_cast<float*>(ws + net->partial_off);
-  sw.counters = reinterpret_cast<uint32_t*>(ws + net->counters_off);
   if (net->ws_ready != workspace) {
-    omni::fill_u32(st, sw.counters, omni::kSplitMaxTiles, 0u);
+    omni::fill_u32(c.st, reinterpret_cast<uint32_t*>(c.ws + net->counters_off), omni::kSplitMaxTiles, 0u);
+    if (net->dtype == OMNI_BF16)
+      omni::fill_u32(c.st, reinterpret_cast<uint32_t*>(c.ws + net->conv_counters_off), omni::kConvCounters, 0u);
     net->ws_ready = workspace;
   }
 
-  const int n_layers = (int)net->layers.size();
-  const Layer& last = net->layers[n_layers - 1];
-  const bool fused_head = last.d.op == OMNI_OP_LINEAR &&
-                          omni::head_supported(last.d.cin, last.d.cout, act(last.in0), params + last.w_off);
-
-  // ---- forward over the concatenated batch
-  for (const Layer& L : net->layers) {
-    if (L.fused_away) continue;
-    if (fused_head && &L == &last) continue;
-    switch (L.d.op) {
-      case OMNI_OP_LINEAR: {
-        TimedScope ts(net, st, OMNI_KERNEL_LINEAR_FWD, (int)(&L - net->layers.data()));
-        omni::linear_fwd_f32(st, act(L.in0), params + L.w_off, L.has_b ? params + L.b_off : nullptr, actw(L.out),
-                             rows, L.d.cin, L.d.cout, net->tensors[L.out].relu, sw);
-        break;
-      }
-      default: break;
-    }
-  }
-
-  // ---- loss: dz already carries 1/b_k, so everything downstream is a per-worker mean gradient
-  const int logits = last.out;
-  std::vector<char> written(net->tensors.size(), 0);
-  if (fused_head) {
-    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
-    const bool need_dx = last.in0 >= 0;
-    omni::head_fwd_loss_dgrad_f32(st, act(last.in0), params + last.w_off, last.has_b ? params + last.b_off : nullptr,
-                                  labels, last.d.cin, last.d.cout, seg, actw(logits), grad(logits), loss_rows,
-                                  need_dx && net->tensors[last.in0].relu ? act(last.in0) : nullptr,
-                                  need_dx ? grad(last.in0) : nullptr, false);
-    if (need_dx) written[last.in0] = 1;
-    omni::head_wgrad_loss_f32(st, grad(logits), act(last.in0), labels, last.d.cin, last.d.cout, seg, G + last.w_off,
-                              last.has_b ? G + last.b_off : nullptr, net->P_stride, loss_rows, loss_per_worker, loss,
-                              status);
-  } else {
-    TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
-    omni::fill_u32(st, status, 1, 0u);
-    omni::softmax_xent_f32(st, act(logits), labels, net->classes, seg, grad(logits), loss_rows, loss_per_worker,
-                           loss, status);
-  }
-
-  // ---- backward: input gradients on all rows, parameter gradients per worker
-  for (int i = n_layers - 1; i >= 0; --i) {
-    const Layer& L = net->layers[i];
-    if (L.fused_away) continue;
-    if (fused_head && i == n_layers - 1) continue;
-    switch (L.d.op) {
-      case OMNI_OP_LINEAR: {
-        {
-          TimedScope ts(net, st, OMNI_KERNEL_LINEAR_WGRAD, i);
-          omni::linear_wgrad_f32(st, grad(L.out), act(L.in0), G + L.w_off, L.has_b ? G + L.b_off : nullptr,
-                                 net->P_stride, seg, L.d.cin, L.d.cout);
-        }
-        if (L.in0 >= 0) {
-          const Tensor& ti = net->tensors[L.in0];
-          TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
-          omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, ti.relu ? act(L.in0) : nullptr, grad(L.in0),
-                                 rows, L.d.cin, L.d.cout, written[L.in0] != 0, sw);
-          written[L.in0] = 1;
-        }
-        break;
-      }
-      default: break;
-    }
-  }
+  if (net->dtype == OMNI_F32) step_f32(c);
+  else step_bf16(c);
 
   // ---- weighted aggregation + update
   if (!(flags & OMNI_STEP_NO_UPDATE)) {
-    TimedScope ts(net, st, OMNI_KERNEL_UPDATE, -1);
-    omni::weighted_sgd_f32(st, params, G, net->P_stride, net->P, seg, lr, nullptr);
+    TimedScope ts(net, c.st, OMNI_KERNEL_UPDATE, -1);
+    omni::weighted_sgd_f32(c.st, params, c.G, net->P_stride, net->P, c.seg, lr, nullptr);
   }
 
   hipError_t e = hipGetLastError();

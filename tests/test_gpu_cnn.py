@@ -1,0 +1,101 @@
+"""GPU parity: bf16 convolutional path (bf16 operands and activations, fp32 accumulate) against
+the fp64 oracle evaluated on the same bf16-representable inputs and weights."""
+import numpy as np
+import pytest
+
+import synth
+from oracle import layers as OL
+from oracle import step as OS
+from oracle.controller import controller_run
+
+from gpu_util import GpuRun, assert_close, param_tensor_slices
+
+pytestmark = pytest.mark.gpu
+
+TOL = 2e-2      # relative (max-norm and l2 per tensor), bf16 storage with fp32 accumulation
+
+
+def _check_step(layers, in_shape, params, x, labels, off, lr, tag, tol=TOL, check_acts=True):
+    K = len(off) - 1
+    print(f"case {tag}: K={K} off={off}", flush=True)
+    run = GpuRun(layers, in_shape, "bf16", K, off[-1])
+    try:
+        got = run.step(params, x, labels, off, lr)
+        # Discrete decisions (ReLU masks, pooling arg-maxima) are taken on the values a bf16
+        # pipeline actually stores: the oracle rounds every stored activation to bf16, then
+        # works in fp64.  Without that, a sign flip of a near-zero pre-activation moves a
+        # whole gradient term and parity would measure luck, not arithmetic.
+        ref = OS.sgd_step(layers, params, x[:off[-1]], labels[:off[-1]], off, lr, store=OL.round_bf16,
+                          keep_acts=check_acts)
+        assert got["status"] == 0
+        worst = 0.0
+        if check_acts:
+            for li, lay in enumerate(layers):
+                if li + 1 < len(layers) and layers[li + 1]["op"] == "relu" and layers[li + 1]["src"] == li:
+                    continue   # stored after the folded ReLU; compared at the ReLU layer
+                ref_act = np.concatenate([ref.acts[k][li].reshape(off[k + 1] - off[k], -1) for k in range(K)])
+                dt = "f32" if li == len(layers) - 1 else "bf16"
+                a = run.omni.net_activation(run.net, run.ws, li, off[-1], dt).float().cpu().numpy()
+                e = assert_close(a, ref_act, tol, f"{tag} act[{li}] {lay['op']}")
+                worst = max(worst, e[0])
+        assert_close(got["loss_per_worker"], ref.loss_per_worker, tol, f"{tag} L_k")
+        assert abs(got["loss"] - ref.loss) <= tol * abs(ref.loss)
+        for name, s, e in param_tensor_slices(layers):
+            for k in range(K):
+                er = assert_close(got["worker_grads"][k, s:e], ref.worker_grads[k, s:e], tol, f"{tag} g_{k} {name}")
+                worst = max(worst, er[0])
+            upd = params[s:e].astype(np.float64) - got["params"][s:e].astype(np.float64)
+            if np.abs(ref.grad[s:e]).max() > 0:
+                assert_close(upd, lr * ref.grad[s:e], tol, f"{tag} update {name}")
+            assert_close(got["params"][s:e], ref.params[s:e], tol, f"{tag} theta' {name}")
+        print(f"   worst max-norm relative error {worst:.2e}", flush=True)
+    finally:
+        run.close()
+
+
+def test_small_cnn():
+    layers = synth.cnn3(num_classes=10, hw=16, chans=(3, 16, 32, 64))
+    rng = np.random.default_rng(7)
+    params = synth.he_normal_params(layers, 3, True)
+    x, y = synth.make_batch(11, 37, (16, 16, 3), 10, True)
+    _check_step(layers, (16, 16, 3), params, x, y, [0, 5, 6, 37], 0.1, "cnn3-16px")
+
+
+def test_cnn_with_biases_and_odd_batches():
+    layers = synth.cnn3(num_classes=10, hw=8, chans=(3, 8, 24, 40))
+    rng = np.random.default_rng(9)
+    params = synth.he_normal_params(layers, 4, True)
+    for sl in synth.param_slices(layers):
+        if "b" in sl:
+            s, e = sl["b"]
+            params[s:e] = synth.to_bf16_grid(rng.standard_normal(e - s).astype(np.float32) * 0.2)
+    x, y = synth.make_batch(12, 131, (8, 8, 3), 10, True)
+    _check_step(layers, (8, 8, 3), params, x, y, [0, 1, 2, 66, 131], 0.05, "cnn3-8px-bias")
+
+
+def test_config2_cnn3():
+    w = synth.workload(2)
+    b, off = controller_run(w.T, w.B)
+    assert sum(b) == 1024 and len(b) == 8
+    _check_step(w.layers, w.in_shape, w.params, w.x, w.labels, off, w.lr, "cnn3")
+
+
+def test_bf16_mlp_hidden_linear():
+    # fully connected layers through the same implicit-GEMM kernels (1x1 "convolution")
+    layers = synth.mlp([64, 96, 40, 10])
+    params = synth.he_normal_params(layers, 2, True)
+    x, y = synth.make_batch(5, 77, (1, 1, 64), 10, True)
+    _check_step(layers, (1, 1, 64), params, x, y, [0, 30, 31, 77], 0.1, "bf16-mlp")
+
+
+def test_cnn_determinism():
+    layers = synth.cnn3(num_classes=10, hw=16, chans=(3, 16, 32, 64))
+    params = synth.he_normal_params(layers, 3, True)
+    x, y = synth.make_batch(11, 200, (16, 16, 3), 10, True)
+    run = GpuRun(layers, (16, 16, 3), "bf16", 3, 200)
+    try:
+        a = run.step(params, x, y, [0, 50, 90, 200], 0.1)
+        c = run.step(params, x, y, [0, 50, 90, 200], 0.1)
+        assert np.array_equal(a["params"], c["params"]) and np.array_equal(a["worker_grads"], c["worker_grads"])
+    finally:
+        run.close()
