@@ -251,15 +251,14 @@ struct ChunkTable {
   int32_t first[OMNI_MAX_WORKERS + 1];   // first chunk index of every worker; first[K] = total
 };
 
-template <int TN>
+template <int TM, int TN>
 __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Segments seg, ChunkTable ct) {
-  constexpr int BN = 64 * TN;
+  constexpr int BM = 64 * TM, BN = 64 * TN;   // output tile: BM output channels x BN reduction columns
   constexpr int kRow = BK + 4;               // 72-byte rows: 8-byte accesses, 8 rows apart lands 16 banks apart
   constexpr int kA = BM * kRow, kB = BN * kRow;
-  constexpr int kTileFloats = 2 * TN * 16 * kThreads;
+  constexpr int kTileFloats = TM * TN * 16 * kThreads;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (kA + kB)];
   __shared__ int tab[kMaxPieces];
-  __shared__ uint32_t arrival;
   auto sA = [&](int s) { return lds + s * (kA + kB); };
   auto sB = [&](int s) { return lds + s * (kA + kB) + kA; };
 
@@ -270,7 +269,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
   const int tile = blockIdx.x;
   const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
   const int row0 = tile_m * BM, col0 = tile_n * BN;
-  const int wrow = (wave >> 1) * 64, wcol = (wave & 1) * 32 * TN;
+  const int wrow = (wave >> 1) * 32 * TM, wcol = (wave & 1) * 32 * TN;
 
   // which worker and which chunk of its positions
   int wk = 0;
@@ -284,14 +283,14 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
   build_tap_table(tab, g, tid);
   __syncthreads();
 
-  // Staging tasks.  Threads 0..127: 16 output-channel pieces x 8 groups of 4
-  // positions of dY.  Threads 128..: (BN/8) reduction pieces x 8 groups of the
-  // gathered input.
-  const bool is_a = tid < 128;
-  const int t2 = is_a ? tid : tid - 128;
-  const int npiece = is_a ? 16 : BN / 8;
+  // Staging tasks.  The first BM threads: (BM/8) output-channel pieces x 8
+  // groups of 4 positions of dY.  The next BN threads: (BN/8) reduction pieces x
+  // 8 groups of the gathered input.
+  const bool is_a = tid < BM;
+  const int t2 = is_a ? tid : tid - BM;
+  const int npiece = is_a ? BM / 8 : BN / 8;
   const int piece = t2 % npiece, mg = t2 / npiece;
-  const bool task = mg < 8;
+  const bool task = tid < BM + BN;   // (mg < 8 follows)
   int bu = 0, bv = 0, bci = 0;
   bool piece_ok;
   if (is_a) {
@@ -303,9 +302,9 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
     bu = t & 15; bv = (t >> 4) & 15; bci = t >> 8;
   }
 
-  v16f acc[2][TN];
+  v16f acc[TM][TN];
 #pragma unroll
-  for (int a = 0; a < 2; ++a)
+  for (int a = 0; a < TM; ++a)
 #pragma unroll
     for (int b = 0; b < TN; ++b)
 #pragma unroll
@@ -371,14 +370,14 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
     load_slab(s + 1 < nslab ? mbeg + (s + 1) * BK : mend);
 #pragma unroll
     for (int ks = 0; ks < BK / 16; ++ks) {
-      bf16x8 fa[2], fb[TN];
+      bf16x8 fa[TM], fb[TN];
       const int ko = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
-      for (int a = 0; a < 2; ++a) fa[a] = frag(sA(cur), wrow + a * 32 + (lane & 31), ko);
+      for (int a = 0; a < TM; ++a) fa[a] = frag(sA(cur), wrow + a * 32 + (lane & 31), ko);
 #pragma unroll
       for (int b = 0; b < TN; ++b) fb[b] = frag(sB(cur), wcol + b * 32 + (lane & 31), ko);
 #pragma unroll
-      for (int a = 0; a < 2; ++a)
+      for (int a = 0; a < TM; ++a)
 #pragma unroll
         for (int b = 0; b < TN; ++b)
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
@@ -395,52 +394,18 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
     }
   }
 
-  // ---- combine the chunks of this worker (fixed order), then write its gradient tile
-  bool finish = true;
+  // ---- a worker cut into several chunks: park the partial tile, a second kernel adds them up
   if (nchunks > 1) {
     float* mine = p.partial + ((size_t)tile * ct.first[seg.K] + blockIdx.y) * (kTileFloats + BM);
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
       for (int b = 0; b < TN; ++b)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-          __hip_atomic_store(mine + ((a * TN + b) * 16 + v) * kThreads + tid, acc[a][b][v], __ATOMIC_RELAXED,
-                             __HIP_MEMORY_SCOPE_AGENT);
-    if (want_bias && tid < BM)
-      __hip_atomic_store(mine + kTileFloats + tid, bsum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    uint32_t* ctr = p.counters + (size_t)tile * seg.K + wk;
-    if (tid == 0) arrival = __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    __syncthreads();
-    finish = (arrival == (uint32_t)nchunks - 1);
-    if (finish) {
-      const float* all = p.partial + ((size_t)tile * ct.first[seg.K] + ct.first[wk]) * (kTileFloats + BM);
-#pragma unroll
-      for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < TN; ++b)
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-      bsum = 0.f;
-      for (int c = 0; c < nchunks; ++c) {
-        const float* src = all + (size_t)c * (kTileFloats + BM);
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int b = 0; b < TN; ++b)
-#pragma unroll
-            for (int v = 0; v < 16; ++v)
-              acc[a][b][v] += __hip_atomic_load(src + ((a * TN + b) * 16 + v) * kThreads + tid, __ATOMIC_RELAXED,
-                                                __HIP_MEMORY_SCOPE_AGENT);
-        if (want_bias && tid < BM)
-          bsum += __hip_atomic_load(src + kTileFloats + tid, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      if (tid == 0) *ctr = 0u;
-    }
+        for (int v = 0; v < 16; ++v) mine[((a * TN + b) * 16 + v) * kThreads + tid] = acc[a][b][v];
+    if (tid < BM) mine[kTileFloats + tid] = bsum;
+    return;
   }
-  if (!finish) return;
 
   const int taps = g.ks * g.ks;
   float* gw = p.gw + (size_t)wk * p.worker_stride;
@@ -452,7 +417,7 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
     if (ci >= p.cin_real) continue;   // padding channels of the first layer
     const int colreal = tap * p.cin_real + ci;
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < TM; ++a)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int co = row0 + wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
@@ -462,9 +427,66 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
   if (want_bias && tid < BM && row0 + tid < p.Cout) p.gb[(size_t)wk * p.worker_stride + row0 + tid] = bsum;
 }
 
+// Second stage of a chunked wgrad: grid (tiles, workers, TM*TN*16 register slots).
+// Each thread owns the same (output channel, reduction column) as the thread of
+// the first stage that held this slot, and adds the worker's chunks in chunk
+// order (fixed order: results repeat bit for bit).
+template <int TM, int TN>
+__global__ __launch_bounds__(kThreads) void conv_wgrad_reduce_kernel(WgradParams p, Segments seg, ChunkTable ct) {
+  constexpr int BM = 64 * TM, BN = 64 * TN;
+  constexpr int kTileFloats = TM * TN * 16 * kThreads;
+  const int tile = blockIdx.x, wk = blockIdx.y, slot = blockIdx.z;
+  const int nchunks = ct.first[wk + 1] - ct.first[wk];
+  if (nchunks <= 1) return;   // written directly by the first stage
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const ConvGeom g = p.g;
+  const int tiles_n = (g.K + BN - 1) / BN;
+  const int tile_m = tile / tiles_n, tile_n = tile % tiles_n;
+  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  const int wrow = (wave >> 1) * 32 * TM, wcol = (wave & 1) * 32 * TN;
+  const float* all = p.partial + ((size_t)tile * ct.first[seg.K] + ct.first[wk]) * (kTileFloats + BM);
+  const size_t stride = kTileFloats + BM;
+
+  // Each wavefront adds a quarter of the chunks (16-byte loads, 8 in flight), then
+  // the four quarter sums are added in wavefront order.
+  __shared__ float red[4][kThreads];
+  {
+    const float* src = all + (size_t)slot * kThreads + lane * 4;
+    const int cbeg = wave * nchunks / 4, cend = (wave + 1) * nchunks / 4;
+    v4f acc4 = {0.f, 0.f, 0.f, 0.f};
+    int c = cbeg;
+    for (; c + 8 <= cend; c += 8) {
+      v4f t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = *reinterpret_cast<const v4f*>(src + (size_t)(c + u) * stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc4 += t[u];
+    }
+    for (; c < cend; ++c) acc4 += *reinterpret_cast<const v4f*>(src + (size_t)c * stride);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) red[wave][lane * 4 + e] = acc4[e];
+  }
+  __syncthreads();
+  const float s0 = (red[0][tid] + red[1][tid]) + (red[2][tid] + red[3][tid]);
+  const int a = slot / (TN * 16), b = (slot / 16) % TN, v = slot % 16;
+  const int kcol = col0 + wcol + b * 32 + (lane & 31);
+  const int co = row0 + wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+  const int taps = g.ks * g.ks;
+  if (kcol < g.K && co < p.Cout) {
+    const int tap = kcol / g.Cs, ci = kcol - tap * g.Cs;
+    if (ci < p.cin_real)
+      p.gw[(size_t)wk * p.worker_stride + (size_t)co * (taps * p.cin_real) + tap * p.cin_real + ci] = s0;
+  }
+  if (slot == 0 && p.gb != nullptr && tile_n == 0 && tid < BM && row0 + tid < p.Cout) {
+    float bs = 0.f;
+    for (int c = 0; c < nchunks; ++c) bs += all[(size_t)c * stride + kTileFloats + tid];
+    p.gb[(size_t)wk * p.worker_stride + row0 + tid] = bs;
+  }
+}
+
 }  // namespace
 
-size_t conv_wgrad_partial_floats() { return (size_t)kConvMaxPartialTiles * (2 * 2 * 16 * kThreads + BM); }
+size_t conv_wgrad_partial_floats() { return (size_t)kConvMaxPartialTiles * (2 * 2 * 16 * kThreads + 128); }
 
 bool conv_shape_supported(const ConvGeom& g, long positions) {
   return g.Cs % 8 == 0 && g.K <= kMaxPieces * 8 && g.ks >= 1 && g.ks <= 15 && positions < (1L << 24);
@@ -491,11 +513,12 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
   WgradParams p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
   p.Cout = Cout; p.cin_real = cin_real; p.g = g; p.partial = partial; p.counters = counters;
-  const int tn = g.K > 64 ? 2 : 1;
-  const int tiles = ((Cout + BM - 1) / BM) * ((g.K + 64 * tn - 1) / (64 * tn));
+  const int tm = Cout > 64 ? 2 : 1, tn = g.K > 64 ? 2 : 1;
+  const int tiles = ((Cout + 64 * tm - 1) / (64 * tm)) * ((g.K + 64 * tn - 1) / (64 * tn));
   const long hw = (long)g.Hp * g.Wp;
   const long total = (long)seg.off[seg.K] * hw;
-  // chunk length: aim at ~2048 workgroups, at least 8 slabs each, within the scratch and counter budgets
+  // Chunk length: about 2048 workgroups in all (the reduction is where the
+  // parallelism of a small filter bank lies), at least 8 slabs each, within the scratch budget.
   long want = std::max<long>(1, 2048 / tiles);
   long chunk = std::max<long>((total + want - 1) / want, 8 * BK);
   chunk = (chunk + BK - 1) / BK * BK;
@@ -507,16 +530,25 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
       acc += (int)(((long)(seg.off[k + 1] - seg.off[k]) * hw + chunk - 1) / chunk);
     }
     ct.first[seg.K] = acc;
-    // one chunk per worker needs neither scratch nor counters
-    if (acc == seg.K || ((long)tiles * acc <= kConvMaxPartialTiles && (long)tiles * seg.K <= kConvCounters)) break;
+    // one chunk per worker needs no scratch
+    if (acc == seg.K || (long)tiles * acc <= kConvMaxPartialTiles) break;
     chunk *= 2;
   }
   p.chunk = (int)chunk;
   dim3 grid(tiles, ct.first[seg.K]);
-  if (tn == 2)
-    hipLaunchKernelGGL(conv_wgrad_kernel<2>, grid, dim3(kThreads), 0, st, p, seg, ct);
-  else
-    hipLaunchKernelGGL(conv_wgrad_kernel<1>, grid, dim3(kThreads), 0, st, p, seg, ct);
+  const bool chunked = ct.first[seg.K] > seg.K;
+#define OMNI_WGRAD(TM, TN)                                                                                   \
+  {                                                                                                          \
+    hipLaunchKernelGGL((conv_wgrad_kernel<TM, TN>), grid, dim3(kThreads), 0, st, p, seg, ct);                \
+    if (chunked)                                                                                             \
+      hipLaunchKernelGGL((conv_wgrad_reduce_kernel<TM, TN>), dim3(tiles, seg.K, TM * TN * 16), dim3(kThreads), \
+                         0, st, p, seg, ct);                                                                 \
+  }
+  if (tm == 2 && tn == 2) OMNI_WGRAD(2, 2)
+  else if (tm == 2) OMNI_WGRAD(2, 1)
+  else if (tn == 2) OMNI_WGRAD(1, 2)
+  else OMNI_WGRAD(1, 1)
+#undef OMNI_WGRAD
 }
 
 }  // namespace omni
