@@ -82,6 +82,22 @@ void maxpool2_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, 
 void maxpool2_bwd_bf16(hipStream_t st, const bf16_t* in, const bf16_t* dout, bf16_t* din, int rows, int H, int W,
                        int C, bool relu_mask);
 
+// ---- per-worker batch norm, residual add, global average pool (bn.hip) ----
+constexpr int kBnMaxSplits = 64;   // position splits per worker in the statistics reductions
+// stats: [K][C][2] (mean, 1/sqrt(var+eps)); partial: [K][kBnMaxSplits][C][2] doubles of scratch.
+void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
+                     const Segments& seg, bool relu, float* stats, double* partial);
+// means: [K][C][2] scratch; g_gamma / g_beta: worker k's entries at + k*worker_stride.
+void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
+                      const Segments& seg, const float* stats, float* means, double* partial, float* g_gamma,
+                      float* g_beta, size_t worker_stride);
+void add_fwd_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, bf16_t* out, long elems, bool relu);
+// dst (+)= g, zeroed where mask <= 0 (mask may be null)
+void route_grad_bf16(hipStream_t st, const bf16_t* g, const bf16_t* mask, bf16_t* dst, long elems, bool accumulate);
+void gap_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, int hw, int C);
+void gap_bwd_bf16(hipStream_t st, const bf16_t* dout, const bf16_t* mask, bf16_t* din, int rows, int hw, int C,
+                  bool accumulate);
+
 // ---- loss and update (pointwise.hip) ----
 void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int C, const Segments& seg,
                       float* dz, float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status);

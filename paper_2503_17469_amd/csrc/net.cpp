@@ -43,6 +43,7 @@ struct Layer {
   size_t wsh_off = 0;           // bf16 weight copy [cout][taps][cin_pad], element offset into the shadow area
   size_t wt_off = 0;            // transposed copy [cin_pad][taps][cout] for dgrad
   bool need_dgrad = false;
+  size_t stat_off = 0;          // batch norm: float offset of [K_max][C][2] statistics (then as many for the backward means)
 };
 
 }  // namespace
@@ -56,6 +57,8 @@ struct omni_net {
   size_t ws_bytes = 0;
   size_t grads_off = 0, loss_rows_off = 0, status_off = 0, partial_off = 0, counters_off = 0;
   size_t shadow_off = 0, shadow_elems = 0, xpad_off = 0, conv_partial_off = 0, conv_counters_off = 0;
+  size_t bn_off = 0, bn_floats = 0, bn_partial_off = 0;
+  int bn_cmax = 0;
   int classes = 0;
   const void* ws_ready = nullptr;   // workspace whose arrival counters are known to be zero
   // optional event timing of one kernel class
@@ -121,7 +124,7 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
     return (int)net->tensors.size() - 1;
   };
 
-  size_t ppos = 0, shpos = 0;
+  size_t ppos = 0, shpos = 0, bnpos = 0;
   net->layers.resize(n);
   for (int i = 0; i < n; ++i) {
     Layer& L = net->layers[i];
@@ -171,7 +174,8 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
       case OMNI_OP_RELU: {
         if (L.in0 < 0) return bail(fail(OMNI_EINVAL, "layer %d: ReLU on the network input is not supported", i));
         const Layer& prod = net->layers[L.d.src];
-        const bool ok_prod = prod.d.op == OMNI_OP_LINEAR || prod.d.op == OMNI_OP_CONV;
+        const bool ok_prod = prod.d.op == OMNI_OP_LINEAR || prod.d.op == OMNI_OP_CONV || prod.d.op == OMNI_OP_BN ||
+                             prod.d.op == OMNI_OP_ADD;
         if (!ok_prod || prod.fused_away)
           return bail(fail(OMNI_EINVAL, "layer %d: ReLU after op %d is not supported", i, prod.d.op));
         if (net->tensors[L.in0].consumers != 0 || net->tensors[L.in0].relu)
@@ -188,6 +192,40 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
         L.out = new_tensor(h / 2, w / 2, c);
         break;
       }
+      case OMNI_OP_BN: {
+        if (!bf) return bail(fail(OMNI_EINVAL, "layer %d: batch norm is implemented for dtype bf16 only", i));
+        if (L.in0 < 0 || c % 8 || L.d.cin != c)
+          return bail(fail(OMNI_EINVAL, "layer %d: batch norm needs a layer input with channels %% 8 == 0 (got %d, declared %d)", i, c, L.d.cin));
+        if (net->tensors[L.in0].relu)
+          return bail(fail(OMNI_EINVAL, "layer %d: batch norm directly after a folded ReLU is not supported", i));
+        L.out = new_tensor(h, w, c);
+        L.w_off = ppos; ppos += (size_t)c;      // gamma
+        L.b_off = ppos; ppos += (size_t)c;      // beta
+        L.has_b = true;
+        L.stat_off = bnpos; bnpos += (size_t)K_max * c * 4;
+        if (c > net->bn_cmax) net->bn_cmax = c;
+        break;
+      }
+      case OMNI_OP_ADD: {
+        if (!bf) return bail(fail(OMNI_EINVAL, "layer %d: residual add is implemented for dtype bf16 only", i));
+        if (L.d.src2 < 0 || L.d.src2 >= i || L.in0 < 0)
+          return bail(fail(OMNI_EINVAL, "layer %d: add needs two layer inputs", i));
+        L.in1 = net->layers[L.d.src2].out;
+        if (!net->layers[L.d.src2].fused_away && net->tensors[L.in1].relu)
+          return bail(fail(OMNI_EINVAL, "layer %d: reads layer %d before its ReLU, which was folded into it", i, L.d.src2));
+        const Tensor& tb = net->tensors[L.in1];
+        if (tb.h != h || tb.w != w || tb.c != c || c % 8)
+          return bail(fail(OMNI_EINVAL, "layer %d: add operands differ in shape", i));
+        L.out = new_tensor(h, w, c);
+        net->tensors[L.in1].consumers++;
+        break;
+      }
+      case OMNI_OP_GAP: {
+        if (!bf) return bail(fail(OMNI_EINVAL, "layer %d: global average pooling is implemented for dtype bf16 only", i));
+        if (L.in0 < 0 || c % 8) return bail(fail(OMNI_EINVAL, "layer %d: pooling needs a layer input with channels %% 8 == 0", i));
+        L.out = new_tensor(1, 1, c);
+        break;
+      }
       default:
         return bail(fail(OMNI_EINVAL, "layer %d: op %d not supported", i, L.d.op));
     }
@@ -201,8 +239,9 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
     }
   }
   for (const Layer& L : net->layers)
-    if (L.d.op == OMNI_OP_MAXPOOL2 && net->tensors[L.in0].consumers != 1)
-      return bail(fail(OMNI_EINVAL, "the input of a max pooling layer must have no other consumer"));
+    if ((L.d.op == OMNI_OP_MAXPOOL2 || L.d.op == OMNI_OP_BN) && net->tensors[L.in0].consumers != 1)
+      return bail(fail(OMNI_EINVAL, "the input of a max pooling or batch norm layer must have no other consumer"));
+  net->bn_floats = bnpos;
   net->P = ppos;
   net->P_stride = align_up(ppos, 64);
   net->shadow_elems = shpos;
@@ -231,6 +270,10 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
     net->conv_partial_off = take(omni::conv_wgrad_partial_floats() * sizeof(float));
     net->shadow_off = take(net->shadow_elems * 2);
     if (in_c % 8 != 0) net->xpad_off = take((size_t)B_max * in_h * in_w * ((in_c + 7) / 8 * 8) * 2);
+    if (net->bn_floats) {
+      net->bn_off = take(net->bn_floats * sizeof(float));
+      net->bn_partial_off = take((size_t)K_max * omni::kBnMaxSplits * net->bn_cmax * 2 * sizeof(double));
+    }
   }
   for (Tensor& t : net->tensors) {
     const size_t bytes = (size_t)B_max * t.elems * t.esize;
@@ -405,6 +448,8 @@ void step_bf16(StepCtx& c) {
   };
   auto actw = [&](int t) { return reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].act_off); };
   auto grad = [&](int t) { return reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].grad_off); };
+  float* bn_area = reinterpret_cast<float*>(c.ws + net->bn_off);
+  double* bn_partial = reinterpret_cast<double*>(c.ws + net->bn_partial_off);
   float* conv_partial = reinterpret_cast<float*>(c.ws + net->conv_partial_off);
   uint32_t* conv_counters = reinterpret_cast<uint32_t*>(c.ws + net->conv_counters_off);
 
@@ -448,6 +493,14 @@ void step_bf16(StepCtx& c) {
                            L.has_b ? c.params + L.b_off : nullptr, nullptr, to.relu, false);
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
       omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
+    } else if (L.d.op == OMNI_OP_BN) {
+      omni::bn_forward_bf16(st, act(L.in0), actw(L.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
+                            c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial);
+    } else if (L.d.op == OMNI_OP_ADD) {
+      omni::add_fwd_bf16(st, act(L.in0), act(L.in1), actw(L.out), (long)rows * L.ih * L.iw * L.ic,
+                         net->tensors[L.out].relu);
+    } else if (L.d.op == OMNI_OP_GAP) {
+      omni::gap_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih * L.iw, L.ic);
     }
   }
 
@@ -499,6 +552,23 @@ void step_bf16(StepCtx& c) {
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
       omni::maxpool2_bwd_bf16(st, act(L.in0), grad(L.out), grad(L.in0), rows, L.ih, L.iw, L.ic,
                               net->tensors[L.in0].relu);
+      written[L.in0] = 1;
+    } else if (L.d.op == OMNI_OP_BN) {
+      float* stats = bn_area + L.stat_off;
+      omni::bn_backward_bf16(st, act(L.in0), grad(L.out), grad(L.in0), c.params + L.w_off, L.ic, L.ih * L.iw, c.seg,
+                             stats, stats + (size_t)net->K_max * L.ic * 2, bn_partial, c.G + L.w_off, c.G + L.b_off,
+                             net->P_stride);
+      written[L.in0] = 1;
+    } else if (L.d.op == OMNI_OP_ADD) {
+      const long elems = (long)rows * L.ih * L.iw * L.ic;
+      for (int t : {L.in0, L.in1}) {
+        omni::route_grad_bf16(st, grad(L.out), net->tensors[t].relu ? act(t) : nullptr, grad(t), elems,
+                              written[t] != 0);
+        written[t] = 1;
+      }
+    } else if (L.d.op == OMNI_OP_GAP) {
+      omni::gap_bwd_bf16(st, grad(L.out), net->tensors[L.in0].relu ? act(L.in0) : nullptr, grad(L.in0), rows,
+                         L.ih * L.iw, L.ic, written[L.in0] != 0);
       written[L.in0] = 1;
     }
   }
