@@ -21,16 +21,24 @@ if ROOT not in sys.path:
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 PEAK_HBM_GBS = 8000.0
 
-# kernel whose roofline is reported, per workload: (timing class, layer index, description)
+# kernel whose roofline is reported, per workload: (timing class, layer index)
 DOMINANT = {
     "tiny_mlp": ("linear_wgrad", 0),
     "mlp3072": ("linear_wgrad", 0),
+    "cnn3": ("conv_wgrad", 3),
+    "cnn3_dynamic": ("conv_wgrad", 3),
+    "resnet18": ("conv_fwd", 3),
 }
 
 
-def linear_layer_flops(layers, li, rows):
+def layer_flops(layers, in_shape, li, rows):
+    """Algorithmic flop of one forward / dgrad / wgrad launch of layer li over `rows` samples."""
+    import synth.nets as nets
     L = layers[li]
-    return 2.0 * rows * L["cin"] * L["cout"]
+    if L["op"] == "linear":
+        return 2.0 * rows * L["cin"] * L["cout"]
+    ho, wo, _ = nets.layer_shapes(layers, in_shape)[li]
+    return 2.0 * rows * ho * wo * L["cout"] * L["k"] * L["k"] * L["cin"]
 
 
 def cpu_baseline(w, off, budget_s=12.0):
@@ -42,10 +50,14 @@ def cpu_baseline(w, off, budget_s=12.0):
     except Exception:
         threads = os.cpu_count() or 1
     x = w.x
+    store = None
+    if w.dtype == "bf16":
+        from oracle import layers as oracle_layers
+        store = oracle_layers.round_bf16
     n = 0
     t0 = time.perf_counter()
     while True:
-        oracle_step.sgd_step(w.layers, w.params, x, w.labels, off, w.lr)
+        oracle_step.sgd_step(w.layers, w.params, x, w.labels, off, w.lr, store=store)
         n += 1
         el = time.perf_counter() - t0
         if el >= budget_s:
@@ -57,7 +69,7 @@ def cpu_baseline(w, off, budget_s=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--steps", type=int, default=2000, help="timed steps (use ~50 for resnet18)")
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="mlp3072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -97,6 +109,14 @@ def main():
         bb, oo = omni.ctl_run(ctl, w.K)
         omni.step(net, params, x, y, oo, bb, lr, ws, lpw, loss)
 
+    # One plain device-to-device copy of known size (256 MiB read + 256 MiB written): under
+    # `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its counters calibrate the traffic figures.
+    cal_src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    cal_dst = torch.empty_like(cal_src)
+    cal_dst.copy_(cal_src)
+    torch.cuda.synchronize()
+    del cal_src, cal_dst
+
     for _ in range(args.warmup):
         one_step()
     torch.cuda.synchronize()
@@ -117,8 +137,19 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = w.B * args.steps / dt
 
+    # the fused weighted-reduce + SGD kernel against the HBM roofline (separate short loop, same buffers)
+    n_upd = min(200, args.steps)
+    omni.net_timing_enable(net, "update", -1, n_upd)
+    for _ in range(n_upd):
+        one_step()
+    torch.cuda.synchronize()
+    u_ms, u_n = omni.net_timing_read(net)
+    omni.net_timing_enable(net, -1, -1, 1)
+    upd_bytes = (w.K + 2) * 4.0 * w.P
+    upd_gbs = upd_bytes / (u_ms / max(u_n, 1) * 1e-3) / 1e9
+
     kernel_s = k_ms / max(k_n, 1) * 1e-3
-    flops = linear_layer_flops(w.layers, klayer, w.B)
+    flops = layer_flops(w.layers, w.in_shape, klayer, w.B)
     achieved = flops / kernel_s / 1e12
     peak = PEAK_TFLOPS[w.dtype]
     roofline = {"bound": "mfma", "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
@@ -139,9 +170,13 @@ def main():
         "dtype": "f32" if w.dtype == "f32" else "bf16",
         "data": "synthetic",
         "config": {"workload": w.name, "K": w.K, "B": w.B, "b": b, "params": int(w.P),
-                   "net": "MLP 3072-1024-1024-10" if w.name == "mlp3072" else w.name,
+                   "net": "MLP 3072-1024-1024-10 fp32" if w.name == "mlp3072" else w.name,
                    "includes": "controller+offsets+fwd+loss+bwd+weighted reduce+SGD"},
         "roofline": roofline,
+        "roofline_update": {"bound": "hbm", "kernel": "weighted reduce + SGD", "achieved": upd_gbs,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "traffic": None,
+                            "bytes_per_launch": upd_bytes, "avg_launch_us": u_ms / max(u_n, 1) * 1e3,
+                            "note": "working set below 256 MB may be served from the Infinity Cache"},
         "final_loss": final_loss,
     }
     if not args.no_cpu_baseline:

@@ -111,34 +111,53 @@ __device__ inline uint16_t bf16_rne(float f) {
 // theta[j] -= lr * sum_k lambda_k G[k][j]  (equations bspweightedgrads and
 // bspvariableSGD fused: the K gradient rows and theta are each read once, theta
 // written once).  Rows of G are 256-byte aligned, so 16-byte loads throughout.
+// The gradient rows are read exactly once (streaming, non-temporal loads); two
+// 16-byte columns per thread are in flight together so that 2*(K+1) loads cover
+// the HBM latency.
 template <bool SHADOW>
 __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ params,
                                                            const float* __restrict__ grads, size_t stride,
                                                            size_t P, int K, Lambdas lam, float lr,
                                                            uint16_t* __restrict__ shadow) {
   const size_t n4 = P / 4;
-  const size_t step = (size_t)gridDim.x * blockDim.x;
-  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += step) {
-    v4f g = {0.f, 0.f, 0.f, 0.f};
+  const size_t nthreads = (size_t)gridDim.x * blockDim.x;
+  const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (size_t i0 = t; i0 < n4; i0 += 2 * nthreads) {
+    const size_t i1 = i0 + nthreads;
+    const bool has1 = i1 < n4;
+    const size_t j1 = has1 ? i1 : i0;          // the second column re-reads the first when past the end
+    v4f g0 = {0.f, 0.f, 0.f, 0.f}, g1 = {0.f, 0.f, 0.f, 0.f};
+    const v4f th0 = *reinterpret_cast<const v4f*>(params + 4 * i0);
+    const v4f th1 = *reinterpret_cast<const v4f*>(params + 4 * j1);
     int k = 0;
     for (; k + 4 <= K; k += 4) {
-      const v4f g0 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 0) * stride + 4 * i);
-      const v4f g1 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 1) * stride + 4 * i);
-      const v4f g2 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 2) * stride + 4 * i);
-      const v4f g3 = *reinterpret_cast<const v4f*>(grads + (size_t)(k + 3) * stride + 4 * i);
-      g += lam.v[k] * g0;
-      g += lam.v[k + 1] * g1;
-      g += lam.v[k + 2] * g2;
-      g += lam.v[k + 3] * g3;
+      v4f a[4], c[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        a[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)(k + u) * stride + 4 * i0));
+        c[u] = __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)(k + u) * stride + 4 * j1));
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        g0 += lam.v[k + u] * a[u];
+        g1 += lam.v[k + u] * c[u];
+      }
     }
-    for (; k < K; ++k) g += lam.v[k] * *reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * i);
-    v4f th = *reinterpret_cast<const v4f*>(params + 4 * i);
-    th -= lr * g;
-    *reinterpret_cast<v4f*>(params + 4 * i) = th;
+    for (; k < K; ++k) {
+      g0 += lam.v[k] * __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * i0));
+      g1 += lam.v[k] * __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * j1));
+    }
+    const v4f n0 = th0 - lr * g0, n1 = th1 - lr * g1;
+    *reinterpret_cast<v4f*>(params + 4 * i0) = n0;
+    if (has1) *reinterpret_cast<v4f*>(params + 4 * i1) = n1;
     if (SHADOW) {
       ushort4 s;
-      s.x = bf16_rne(th[0]); s.y = bf16_rne(th[1]); s.z = bf16_rne(th[2]); s.w = bf16_rne(th[3]);
-      *reinterpret_cast<ushort4*>(shadow + 4 * i) = s;
+      s.x = bf16_rne(n0[0]); s.y = bf16_rne(n0[1]); s.z = bf16_rne(n0[2]); s.w = bf16_rne(n0[3]);
+      *reinterpret_cast<ushort4*>(shadow + 4 * i0) = s;
+      if (has1) {
+        s.x = bf16_rne(n1[0]); s.y = bf16_rne(n1[1]); s.z = bf16_rne(n1[2]); s.w = bf16_rne(n1[3]);
+        *reinterpret_cast<ushort4*>(shadow + 4 * i1) = s;
+      }
     }
   }
   // tail (P not a multiple of 4)
@@ -173,8 +192,8 @@ void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t 
   const double B = (double)seg.off[seg.K];
   for (int k = 0; k < seg.K; ++k) lam.v[k] = (float)((double)(seg.off[k + 1] - seg.off[k]) / B);
   const size_t n4 = P / 4;
-  size_t blocks = (n4 + 255) / 256;
-  if (blocks > 4096) blocks = 4096;
+  size_t blocks = (n4 + 511) / 512;          // two columns per thread per trip
+  if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
   if (shadow_bf16)
     hipLaunchKernelGGL(weighted_sgd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, params, grads, stride,
