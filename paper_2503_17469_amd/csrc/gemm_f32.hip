@@ -54,15 +54,56 @@ struct Slab {
 
   // Loads never branch: an element outside the operand is fetched from the
   // operand's first element instead and zeroed when the slab is written to LDS
-  // (`ok` carries 4 validity bits per piece).  Branch-free loads let the compiler
-  // keep them in flight across the whole MFMA section of the current slab.
+  // (`ok` carries validity bits).  Branch-free loads let the compiler keep them
+  // in flight across the whole MFMA section of the current slab.
   // VEC requires the contiguous extent (kk for k-contiguous, rows for
   // row-contiguous operands) to be a multiple of 4 and 16-byte aligned rows, so a
-  // 4-element piece is either wholly inside or wholly outside.
+  // 4-element piece is either wholly inside or wholly outside (one bit per piece).
+  // Everything that does not change from slab to slab is worked out once per
+  // thread (`Pre`): the per-slab address is one 64-bit add per piece.  The vector
+  // ALU shares issue slots with the matrix pipe, so every instruction saved here
+  // is matrix time gained.
+  struct Pre {
+    int koff[kPerThread];     // reduction offset of the piece inside a slab
+    long cpart[kPerThread];   // element offset of the piece for slab start 0
+    uint32_t rowok;           // bit i: the piece's rows lie inside the operand
+  };
+  __device__ static inline Pre prepare(int ld, int row0, int rows, int tid) {
+    Pre pre;
+    pre.rowok = 0;
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) {
+      const int c = tid + kThreads * i;
+      if (!MC) {
+        const int r = row0 + c / (BK / 4), kc = (c % (BK / 4)) * 4;
+        pre.koff[i] = kc + 3;
+        pre.cpart[i] = (long)r * ld + kc;
+        pre.rowok |= (r < rows ? 1u : 0u) << i;
+      } else {
+        const int kk = c / (R / 4), r = row0 + (c % (R / 4)) * 4;
+        pre.koff[i] = kk;
+        pre.cpart[i] = (long)kk * ld + r;
+        pre.rowok |= (r + 3 < rows ? 1u : 0u) << i;
+      }
+    }
+    return pre;
+  }
+
   template <bool VEC>
   __device__ static inline void load(v4f (&reg)[kPerThread], uint32_t& ok, const float* __restrict__ base, int ld,
-                                     int row0, int rows, int k0, int kend, int tid) {
+                                     int row0, int rows, int k0, int kend, int tid, const Pre& pre) {
     ok = 0;
+    if (VEC) {
+      const long kbase = MC ? (long)k0 * ld : (long)k0;
+      const int klen = kend - k0;
+#pragma unroll
+      for (int i = 0; i < kPerThread; ++i) {
+        const bool in = ((pre.rowok >> i) & 1u) && pre.koff[i] < klen;
+        reg[i] = *reinterpret_cast<const v4f*>(base + (in ? pre.cpart[i] + kbase : 0));
+        ok |= (in ? 1u : 0u) << i;
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < kPerThread; ++i) {
       const int c = tid + kThreads * i;
@@ -74,40 +115,44 @@ struct Slab {
         gk = k0 + c / (R / 4);
         gr = row0 + (c % (R / 4)) * 4;
       }
-      if (VEC) {
-        const bool in = MC ? (gk < kend && gr + 3 < rows) : (gr < rows && gk + 3 < kend);
-        const size_t o = MC ? (size_t)gk * ld + gr : (size_t)gr * ld + gk;
-        reg[i] = *reinterpret_cast<const v4f*>(base + (in ? o : 0));
-        ok |= (in ? 0xFu : 0u) << (4 * i);
-      } else {
-        v4f v;
+      v4f v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const bool in = MC ? (gk < kend && gr + e < rows) : (gr < rows && gk + e < kend);
-          const size_t o = MC ? (size_t)gk * ld + gr + e : (size_t)gr * ld + gk + e;
-          v[e] = base[in ? o : 0];
-          ok |= (in ? 1u : 0u) << (4 * i + e);
-        }
-        reg[i] = v;
+      for (int e = 0; e < 4; ++e) {
+        const bool in = MC ? (gk < kend && gr + e < rows) : (gr < rows && gk + e < kend);
+        const size_t o = MC ? (size_t)gk * ld + gr + e : (size_t)gr * ld + gk + e;
+        v[e] = base[in ? o : 0];
+        ok |= (in ? 1u : 0u) << (4 * i + e);
       }
+      reg[i] = v;
     }
   }
 
-  __device__ static inline void store(const v4f (&reg)[kPerThread], uint32_t ok, float* lds, int tid) {
+  // piece i of the thread's share of the slab
+  template <bool VEC>
+  __device__ static inline void store_one(const v4f (&reg)[kPerThread], uint32_t ok, float* lds, int tid, int i) {
+    const int c = tid + kThreads * i;
+    v4f v = reg[i];
+    if (VEC) {
+      const bool in = (ok >> i) & 1u;
 #pragma unroll
-    for (int i = 0; i < kPerThread; ++i) {
-      const int c = tid + kThreads * i;
-      v4f v = reg[i];
+      for (int e = 0; e < 4; ++e) v[e] = in ? v[e] : 0.f;
+    } else {
 #pragma unroll
       for (int e = 0; e < 4; ++e) v[e] = ((ok >> (4 * i + e)) & 1u) ? v[e] : 0.f;
-      if (!MC) {
-        const int r = c / (BK / 4), kc = (c % (BK / 4)) * 4;
-        *reinterpret_cast<v4f*>(lds + r * kStride + kc) = v;
-      } else {
-        const int kk = c / (R / 4), rc = (c % (R / 4)) * 4;
-        *reinterpret_cast<v4f*>(lds + kk * kStride + rc) = v;
-      }
     }
+    if (!MC) {
+      const int r = c / (BK / 4), kc = (c % (BK / 4)) * 4;
+      *reinterpret_cast<v4f*>(lds + r * kStride + kc) = v;
+    } else {
+      const int kk = c / (R / 4), rc = (c % (R / 4)) * 4;
+      *reinterpret_cast<v4f*>(lds + kk * kStride + rc) = v;
+    }
+  }
+
+  template <bool VEC>
+  __device__ static inline void store(const v4f (&reg)[kPerThread], uint32_t ok, float* lds, int tid) {
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) store_one<VEC>(reg, ok, lds, tid, i);
   }
 
   // Operand registers for the 4 MFMA steps covering kk = ks*8 .. ks*8+7 of the
@@ -140,11 +185,14 @@ struct GemmParams {
   const float* mask;   // DGRAD: [M][ldc]; the value passes where mask > 0, may be null
   int relu;            // FWD
   int accumulate;      // DGRAD: C += result
-  int xcd_remap;       // FWD / DGRAD: 1 if the tile grid is re-ordered per XCD
+  int xcd_remap;       // FWD / DGRAD: 1 if the workgroups are re-ordered per XCD
+  int splits;          // FWD / DGRAD: reduction splits per tile
   float* partial;      // FWD / DGRAD split-K: [tiles][splits][16][256] floats
   uint32_t* counters;  // FWD / DGRAD split-K: one per tile, zero between launches
   size_t c_worker_stride;  // WGRAD: floats between consecutive workers' outputs
   float* bias_grad;        // WGRAD: per worker column sums of A (at + worker*c_worker_stride), may be null
+  int ngroups;             // WGRAD: consecutive workers are dealt to this many workgroups per tile (gridDim.y)
+  int gfirst[9];           // WGRAD: first worker of every group; gfirst[ngroups] = K
 };
 
 template <int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
@@ -159,15 +207,25 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segmen
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_n = (p.N + kTile - 1) / kTile;
-  int tile = blockIdx.x;
-  if (MODE != MODE_WGRAD && p.xcd_remap) {
-    // Workgroups are dealt to the 8 XCDs round-robin by index; give each XCD a
-    // contiguous run of tiles so that tiles sharing B rows meet in one L2.
-    const int per = gridDim.x >> 3;
-    tile = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+  const int tiles_m = (p.M + kTile - 1) / kTile;
+  int tile = blockIdx.x, split = 0;
+  const int splits = (MODE == MODE_WGRAD) ? 1 : p.splits;
+  if (MODE != MODE_WGRAD) {
+    // Forward / dgrad launch tiles*splits workgroups in one dimension.  They are
+    // dealt to the 8 XCDs round-robin by index; re-order them so that each XCD
+    // owns a contiguous run of (split, tile) pairs, split-major: an XCD then
+    // works on ONE slice of the reduction, and that slice of both operands
+    // (a few MB) stays in its own L2 while all its tiles sweep over it.
+    int g = blockIdx.x;
+    if (p.xcd_remap) {
+      const int per = gridDim.x >> 3;
+      g = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+    }
+    const int tiles = tiles_m * tiles_n;
+    split = g / tiles;
+    tile = g - split * tiles;
   }
   // tile_n major: consecutive tiles share the same rows of B
-  const int tiles_m = (p.M + kTile - 1) / kTile;
   const int tile_n = (MODE == MODE_WGRAD) ? tile % tiles_n : tile / tiles_m;
   const int tile_m = (MODE == MODE_WGRAD) ? tile / tiles_n : tile % tiles_m;
   const int row0 = tile_m * kTile, col0 = tile_n * kTile;
@@ -176,12 +234,12 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segmen
   // The reduction is a stream of slabs over one or more consecutive ranges
   // ("workers"); the accumulator is flushed whenever a range ends.  A slab is
   // (range index w, start k0, end of its range kend); w == nrange marks the end.
-  const int splits = gridDim.y, split = blockIdx.y;
-  const int nrange = (MODE == MODE_WGRAD) ? seg.K : 1;
+  const int nrange = (MODE == MODE_WGRAD) ? p.gfirst[blockIdx.y + 1] : 1;
   int w0 = 0, k00, kend0;
   if (MODE == MODE_WGRAD) {
-    k00 = seg.off[0];
-    kend0 = seg.off[1];
+    w0 = p.gfirst[blockIdx.y];
+    k00 = seg.off[w0];
+    kend0 = seg.off[w0 + 1];
   } else {
     const int slabs = (p.kred + BK - 1) / BK;
     const int per = (slabs + splits - 1) / splits;
@@ -212,19 +270,21 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segmen
 
   // Two register sets hold the slabs one and two steps ahead of the one being
   // multiplied, so every global load has two MFMA sections to arrive in.
+  const typename SA::Pre preA = SA::prepare(p.lda, row0, p.M, tid);
+  const typename SB::Pre preB = SB::prepare(p.ldb, col0, p.N, tid);
   v4f ra0[SA::kPerThread], rb0[SB::kPerThread], ra1[SA::kPerThread], rb1[SB::kPerThread];
   uint32_t oka0 = 0, okb0 = 0, oka1 = 0, okb1 = 0;
   OMNI_NEXT_SLAB(w0, k00, kend0, w1, k01, kend1)
-  SA::template load<VEC>(ra0, oka0, p.A, p.lda, row0, p.M, k00, kend0, tid);
-  SB::template load<VEC>(rb0, okb0, p.B, p.ldb, col0, p.N, k00, kend0, tid);
+  SA::template load<VEC>(ra0, oka0, p.A, p.lda, row0, p.M, k00, kend0, tid, preA);
+  SB::template load<VEC>(rb0, okb0, p.B, p.ldb, col0, p.N, k00, kend0, tid, preB);
   // Prefetches past the end of the stream are still issued (they re-read element
   // 0 and are discarded): a load that is issued on one path only would force
   // every later wait to assume it is not there and drain the whole queue.
   if (w1 >= nrange) kend1 = 0;
-  SA::template load<VEC>(ra1, oka1, p.A, p.lda, row0, p.M, k01, kend1, tid);
-  SB::template load<VEC>(rb1, okb1, p.B, p.ldb, col0, p.N, k01, kend1, tid);
-  SA::store(ra0, oka0, sA(0), tid);
-  SB::store(rb0, okb0, sB(0), tid);
+  SA::template load<VEC>(ra1, oka1, p.A, p.lda, row0, p.M, k01, kend1, tid, preA);
+  SB::template load<VEC>(rb1, okb1, p.B, p.ldb, col0, p.N, k01, kend1, tid, preB);
+  SA::template store<VEC>(ra0, oka0, sA(0), tid);
+  SB::template store<VEC>(rb0, okb0, sB(0), tid);
   __syncthreads();
 
   int cur = 0;
@@ -239,16 +299,30 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segmen
       w2 = tw; k02 = tk0; kend2 = tkend;                                                                \
     }                                                                                                   \
     if (w2 >= nrange) kend2 = 0;                                                                        \
-    SA::template load<VEC>(LA, LOKA, p.A, p.lda, row0, p.M, k02, kend2, tid);                           \
-    SB::template load<VEC>(LB, LOKB, p.B, p.ldb, col0, p.N, k02, kend2, tid);                           \
+    SA::template load<VEC>(LA, LOKA, p.A, p.lda, row0, p.M, k02, kend2, tid, preA);                      \
+    SB::template load<VEC>(LB, LOKB, p.B, p.ldb, col0, p.N, k02, kend2, tid, preB);                      \
     __builtin_amdgcn_sched_barrier(0); /* keep the fetches ahead of the MFMA section */                 \
-    _Pragma("unroll") for (int ks = 0; ks < BK / 8; ++ks) {                                             \
-      const v4f fa = SA::frag(sA(cur), wrow, ks, lane);                                                 \
-      const v4f fb = SB::frag(sB(cur), wcol, ks, lane);                                                 \
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[0], fb[0], acc, 0, 0, 0);                           \
-      acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[1], fb[1], acc2, 0, 0, 0);                         \
-      acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[2], fb[2], acc, 0, 0, 0);                           \
-      acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[3], fb[3], acc2, 0, 0, 0);                         \
+    /* The slab one step ahead has been in flight for a whole step: its pieces go to the other LDS */  \
+    /* stage in between the MFMA groups of this slab, and the operand fragments of the next group   */  \
+    /* are fetched before the current group is issued, so that the matrix pipe is not left waiting. */  \
+    {                                                                                                   \
+      v4f fa[2], fb[2];                                                                                 \
+      fa[0] = SA::frag(sA(cur), wrow, 0, lane);                                                         \
+      fb[0] = SB::frag(sB(cur), wcol, 0, lane);                                                         \
+      _Pragma("unroll") for (int ks = 0; ks < BK / 8; ++ks) {                                           \
+        if (ks + 1 < BK / 8) {                                                                          \
+          fa[(ks + 1) & 1] = SA::frag(sA(cur), wrow, ks + 1, lane);                                     \
+          fb[(ks + 1) & 1] = SB::frag(sB(cur), wcol, ks + 1, lane);                                     \
+        }                                                                                               \
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][0], fb[ks & 1][0], acc, 0, 0, 0);         \
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][1], fb[ks & 1][1], acc2, 0, 0, 0);       \
+        acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][2], fb[ks & 1][2], acc, 0, 0, 0);         \
+        acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][3], fb[ks & 1][3], acc2, 0, 0, 0);       \
+        if (ks < SA::kPerThread) SA::template store_one<VEC>(NA, NOKA, sA(cur ^ 1), tid, ks);                         \
+        else if (ks - SA::kPerThread < SB::kPerThread)                                                  \
+          SB::template store_one<VEC>(NB, NOKB, sB(cur ^ 1), tid, ks - SA::kPerThread);                               \
+        __builtin_amdgcn_sched_barrier(0);                                                              \
+      }                                                                                                 \
     }                                                                                                   \
     if (want_bias_grad && tid < kTile) {                                                                \
       /* A is the output-gradient slab [kk][row]: its column sums are the bias gradient. */             \
@@ -269,8 +343,6 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segmen
       _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[v] = acc2[v] = 0.f;                            \
     }                                                                                                   \
     if (w1 >= nrange) break;                                                                            \
-    SA::store(NA, NOKA, sA(cur ^ 1), tid);                                                              \
-    SB::store(NB, NOKB, sB(cur ^ 1), tid);                                                              \
     __syncthreads();                                                                                    \
     cur ^= 1;                                                                                           \
     w0 = w1; k00 = k01; kend0 = kend1;                                                                  \
@@ -288,19 +360,27 @@ __global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segmen
     for (int v = 0; v < 16; ++v) acc[v] += acc2[v];
     bool finish = true;
     if (splits > 1) {
-      // Park this split's partial tile; whoever arrives last adds them up.
-      // The tiles travel through device-scope (L2-bypassing) stores and loads,
-      // so no whole-cache write-back or invalidate is needed between the
-      // chiplets: each thread drains its own stores, the barrier collects
-      // the workgroup, then one thread bumps the tile's arrival counter.
+      // Park this split's partial tile; whoever arrives last adds them up.  The
+      // splits of a tile may run on different XCDs, whose L2s are not coherent
+      // with each other inside a kernel.  The partial tiles therefore travel
+      // through device-scope stores and loads (they bypass the XCD-private L2);
+      // every thread drains its own stores, the barrier collects the workgroup,
+      // and ONE wavefront then executes the device-scope release (an L2
+      // write-back: done by all four wavefronts, or paired with an acquire that
+      // invalidates the L2 under everybody else's feet, it cost 25 % of the
+      // step) before one thread bumps the tile's arrival counter.  Without that
+      // release the counter could overtake the data (seen as rare wrong tiles).
       float* mine = p.partial + ((size_t)tile * splits + split) * (16 * kThreads);
 #pragma unroll
       for (int v = 0; v < 16; ++v)
         __hip_atomic_store(mine + v * kThreads + tid, acc[v], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
       __syncthreads();
-      if (tid == 0)
-        arrival = __hip_atomic_fetch_add(&p.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (wave == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        if (tid == 0)
+          arrival = __hip_atomic_fetch_add(&p.counters[tile], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
       __syncthreads();
       finish = (arrival == (uint32_t)splits - 1);
       if (finish) {
@@ -342,8 +422,26 @@ inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 
 template <int BK, bool A_MC, bool B_MC, int MODE>
 void launch(hipStream_t st, GemmParams& p, const Segments& seg, int splits, bool vec) {
   const int tiles = ((p.M + kTile - 1) / kTile) * ((p.N + kTile - 1) / kTile);
-  p.xcd_remap = (MODE != MODE_WGRAD && tiles % 8 == 0) ? 1 : 0;
-  dim3 grid(tiles, splits, 1);
+  p.splits = splits;
+  p.xcd_remap = (MODE != MODE_WGRAD && (tiles * splits) % 8 == 0) ? 1 : 0;
+  dim3 grid(tiles * splits, 1, 1);
+  if (MODE == MODE_WGRAD) {
+    // With few tiles, the workers are dealt to several workgroups per tile: groups of
+    // consecutive workers with about equal row counts (each worker stays whole, so
+    // nothing is summed across workgroups).
+    int G = tiles >= 512 ? 1 : std::min(std::min(8, seg.K), (512 + tiles - 1) / tiles);
+    const int B = seg.off[seg.K];
+    p.gfirst[0] = 0;
+    int g = 1;
+    for (int w = 1; w < seg.K && g < G; ++w) {
+      // start group g at the first worker whose start reaches g/G of the rows (keeping every later group non-empty)
+      if ((long)seg.off[w] * G >= (long)g * B || seg.K - w <= G - g) p.gfirst[g++] = w;
+    }
+    G = g;
+    p.gfirst[G] = seg.K;
+    p.ngroups = G;
+    grid = dim3(tiles, G, 1);
+  }
   if (vec)
     hipLaunchKernelGGL((gemm_f32_kernel<BK, A_MC, B_MC, MODE, true>), grid, dim3(kThreads), 0, st, p, seg);
   else

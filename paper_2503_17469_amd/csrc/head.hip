@@ -223,12 +223,12 @@ __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
   for (int c = 0; c < 16; ++c) acc[c] = 0.f;
   if (j < cin) {
     int s = seg.off[wk] + rs;
-    for (; s + 48 < s_end; s += 64) {          // four rows per trip: their loads overlap
-      float av[4];
+    for (; s + 112 < s_end; s += 128) {        // eight rows per trip: their loads overlap
+      float av[8];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) av[u] = Piece<T>::get(x + (size_t)(s + 16 * u) * cin + j);
+      for (int u = 0; u < 8; ++u) av[u] = Piece<T>::get(x + (size_t)(s + 16 * u) * cin + j);
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
+      for (int u = 0; u < 8; ++u) {
         const float* d = dz + (size_t)(s + 16 * u) * C + c0;
 #pragma unroll
         for (int c = 0; c < 16; ++c) acc[c] += d[c < nc ? c : 0] * av[u];   // columns >= nc are never stored

@@ -61,6 +61,10 @@ struct omni_net {
   int bn_cmax = 0;
   int classes = 0;
   const void* ws_ready = nullptr;   // workspace whose arrival counters are known to be zero
+  // Side stream for parameter-gradient kernels: they only feed the final update,
+  // so they run beside the input-gradient chain instead of in front of it.
+  hipStream_t side = nullptr;
+  std::vector<hipEvent_t> sync_ev;  // fork / join points of one step (timing disabled)
   // optional event timing of one kernel class
   int time_class = -1, time_layer = -1;
   std::vector<hipEvent_t> ev;   // pairs: start, stop
@@ -68,6 +72,8 @@ struct omni_net {
 
   ~omni_net() {
     for (hipEvent_t e : ev) (void)hipEventDestroy(e);
+    for (hipEvent_t e : sync_ev) (void)hipEventDestroy(e);
+    if (side) (void)hipStreamDestroy(side);
   }
 };
 
@@ -346,6 +352,33 @@ namespace {
 struct StepCtx {
   omni_net* net;
   hipStream_t st;
+  hipStream_t side;      // equals st when no side stream could be made
+  size_t sync_used = 0;
+  // the side stream may start once everything enqueued on the main stream so far is done
+  void fork() {
+    if (side == st) return;
+    if (sync_used == net->sync_ev.size()) {
+      hipEvent_t e;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { side = st; return; }
+      net->sync_ev.push_back(e);
+    }
+    hipEvent_t e = net->sync_ev[sync_used++];
+    (void)hipEventRecord(e, st);
+    (void)hipStreamWaitEvent(side, e, 0);
+  }
+  // the main stream waits for everything enqueued on the side stream so far
+  void join() {
+    if (side == st || !forked) return;
+    if (sync_used == net->sync_ev.size()) {
+      hipEvent_t e;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { (void)hipStreamSynchronize(side); return; }
+      net->sync_ev.push_back(e);
+    }
+    hipEvent_t e = net->sync_ev[sync_used++];
+    (void)hipEventRecord(e, side);
+    (void)hipStreamWaitEvent(st, e, 0);
+  }
+  bool forked = false;
   char* ws;
   float* params;
   const void* x;
@@ -415,6 +448,8 @@ void step_f32(StepCtx& c) {
     const Layer& L = net->layers[i];
     if (L.fused_away || (fused_head && i == n_layers - 1)) continue;
     {
+      // (No side stream here: at this size a cross-stream fork and join each cost about 10 us of
+      // idle GPU, more than the overlap returns; measured.)
       TimedScope ts(net, st, OMNI_KERNEL_LINEAR_WGRAD, i);
       omni::linear_wgrad_f32(st, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
                              net->P_stride, c.seg, L.d.cin, L.d.cout);
@@ -517,7 +552,9 @@ void step_bf16(StepCtx& c) {
                               z, dz, c.loss_rows, need_dx && net->tensors[last.in0].relu,
                               need_dx ? grad(last.in0) : nullptr, false);
     if (need_dx) written[last.in0] = 1;
-    omni::head_wgrad_loss(st, true, dz, act(last.in0), c.labels, last.d.cin, last.d.cout, c.seg, c.G + last.w_off,
+    c.fork();
+    c.forked = true;
+    omni::head_wgrad_loss(c.side, true, dz, act(last.in0), c.labels, last.d.cin, last.d.cout, c.seg, c.G + last.w_off,
                           last.has_b ? c.G + last.b_off : nullptr, net->P_stride, c.loss_rows, c.loss_per_worker,
                           c.loss, c.status);
   }
@@ -531,8 +568,14 @@ void step_bf16(StepCtx& c) {
       const Tensor& to = net->tensors[L.out];
       const bool conv = L.d.op == OMNI_OP_CONV;
       {
-        TimedScope ts(net, st, conv ? OMNI_KERNEL_CONV_WGRAD : OMNI_KERNEL_LINEAR_WGRAD, i);
-        omni::conv_wgrad_bf16(st, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
+        // Parameter gradients run on the side stream beside the input-gradient chain.  ALL of
+        // them do, the first layer's included: they share one scratch area for chunk partials,
+        // so they must stay ordered among themselves.
+        c.fork();
+        c.forked = true;
+        hipStream_t ws_ = c.side;
+        TimedScope ts(net, ws_, conv ? OMNI_KERNEL_CONV_WGRAD : OMNI_KERNEL_LINEAR_WGRAD, i);
+        omni::conv_wgrad_bf16(ws_, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
                               net->P_stride, L.d.cout, L.d.cin, g, c.seg, conv_partial, conv_counters);
       }
       if (L.in0 >= 0) {
@@ -621,8 +664,12 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
     net->ws_ready = workspace;
   }
 
+  if (!net->side && hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess) net->side = nullptr;
+  c.side = net->side ? net->side : c.st;
+
   if (net->dtype == OMNI_F32) step_f32(c);
   else step_bf16(c);
+  c.join();
 
   // ---- weighted aggregation + update
   if (!(flags & OMNI_STEP_NO_UPDATE)) {
