@@ -13,8 +13,9 @@
 // Kernel A (forward / dgrad): 128 x (64*TN) output tile per workgroup, 4
 // wavefronts in a 2x2 grid, each 64 x (32*TN).  The left operand is gathered
 // on the fly (no im2col buffer): a 16-byte piece holds 8 consecutive channels of
-// one filter tap, so it is contiguous in memory.  Slabs of 32 reduction
+// one filter tap, so it is contiguous in memory.  Slabs of 64 reduction
 // elements go through LDS (double buffered, next slab prefetched to registers).
+// The output width must be a multiple of 8 (16-byte output pieces).
 //
 // Kernel B (wgrad): the reduction runs over positions m, which is the SLOW index
 // of both operands, while the matrix instruction wants 8 consecutive reduction
@@ -103,13 +104,28 @@ struct ConvParams {
   int relu, accumulate;
 };
 
-template <int TN>
-__global__ __launch_bounds__(kThreads) void conv_gemm_kernel(ConvParams p) {
+// Balance of kernel A: the vector ALU shares issue slots with the matrix pipe, and
+// a first version (32-element slabs, per-piece gather arithmetic, 2-byte stores)
+// spent three quarters of them away from the matrix pipe.  Hence
+//   * a slab is 64 reduction elements (16 MFMAs per wavefront per barrier);
+//   * FAST (channels a multiple of 64, filter <= 3x3, dgrad only for stride 1): a
+//     slab lies inside one filter tap, so the tap is wavefront-uniform; each
+//     thread keeps the pixel offset of its four rows and a 9-bit "tap inside the
+//     image" mask, and a piece address is two adds;
+//   * the output tile is staged through LDS as fp32 and leaves as 16-byte pieces
+//     (bias, ReLU, mask, accumulate applied there).
+constexpr int BK2 = 64;
+
+template <int TN, bool FAST>
+__global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
   constexpr int BN = 64 * TN;
-  constexpr int kRow = BK + 8;               // LDS row pitch in bf16 (80 bytes: 16-byte reads, rows 20 banks apart)
+  constexpr int NB = 2 * TN;                 // right-operand pieces per thread per slab
+  constexpr int kRow = BK2 + 8;              // 144-byte rows: 16-byte reads, rows 4 banks apart
   constexpr int kA = BM * kRow, kB = BN * kRow;
-  __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (kA + kB)];
-  __shared__ int tab[kMaxPieces];
+  constexpr int kOutPitch = BN + 4;          // fp32 staging of the output tile
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  bf16_t* lds = reinterpret_cast<bf16_t*>(smem);
+  int* tab = reinterpret_cast<int*>(smem + (size_t)2 * (kA + kB) * sizeof(bf16_t));
   auto sA = [&](int s) { return lds + s * (kA + kB); };
   auto sB = [&](int s) { return lds + s * (kA + kB) + kA; };
 
@@ -119,20 +135,47 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(ConvParams p) {
   const int row0 = tile_m * BM, col0 = tile_n * BN;
   const int wrow = (wave >> 1) * 64, wcol = (wave & 1) * 32 * TN;
   const ConvGeom g = p.g;
+  const int kc = tid & 7, rbase = tid >> 3;   // piece within a slab; rows rbase + 32*i
 
-  build_tap_table(tab, g, tid);
+  if (!FAST) build_tap_table(tab, g, tid);
 
-  // this thread's two left-operand rows (fixed for the whole reduction)
-  int an[2], ah[2], aw[2];
-  bool arow_ok[2];
+  // ---- per-thread invariants of the left operand
+  long rowbase[4];
+  uint32_t tapmask[4];
+  int an[4], ah[4], aw[4];
+  uint32_t arow_ok = 0;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int m = row0 + ((tid + kThreads * i) >> 2);
-    arow_ok[i] = m < p.M;
-    decode_pos(g, arow_ok[i] ? m : 0, an[i], ah[i], aw[i]);
+  for (int i = 0; i < 4; ++i) {
+    const int m = row0 + rbase + 32 * i;
+    const bool ok = m < p.M;
+    arow_ok |= (ok ? 1u : 0u) << i;
+    int n, h, w;
+    decode_pos(g, ok ? m : 0, n, h, w);
+    an[i] = n; ah[i] = h; aw[i] = w;
+    rowbase[i] = 0;
+    tapmask[i] = 0;
+    if (FAST) {
+      const int hb = g.transposed ? h + g.pad : h * g.stride - g.pad;
+      const int wb = g.transposed ? w + g.pad : w * g.stride - g.pad;
+      rowbase[i] = (((long)n * g.Hs + hb) * g.Ws + wb) * g.Cs + kc * 8;
+      for (int u = 0; u < g.ks; ++u)
+        for (int v = 0; v < g.ks; ++v) {
+          const int hs = g.transposed ? hb - u : hb + u, ws = g.transposed ? wb - v : wb + v;
+          const bool in = ok && hs >= 0 && hs < g.Hs && ws >= 0 && ws < g.Ws;
+          tapmask[i] |= (in ? 1u : 0u) << (u * g.ks + v);
+        }
+    }
   }
-  const int akc = tid & 3;   // piece within the slab (same for both rows: 256 % 4 == 0)
-  __syncthreads();           // tap table ready
+  // ---- and of the right operand
+  long brow[NB];
+  uint32_t brow_ok = 0;
+#pragma unroll
+  for (int i = 0; i < NB; ++i) {
+    const int r = col0 + rbase + 32 * i;
+    brow[i] = (long)r * g.K + kc * 8;
+    brow_ok |= (r < p.N ? 1u : 0u) << i;
+  }
+  if (!FAST) __syncthreads();   // tap table ready
 
   v16f acc[2][TN];
 #pragma unroll
@@ -142,55 +185,71 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(ConvParams p) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-  u32x4 ra[2], rb[TN];
-  uint32_t ok = 0;   // bit i: left piece i valid; bit 4+i: right piece i valid
-  auto load_slab = [&](int k0) {
+  u32x4 ra[4], rb[NB];
+  uint32_t ok = 0;   // bits 0..3 left pieces, 4.. right pieces
+  // FAST: (tap, channel base) of the slab advance uniformly
+  int tap = 0, cb = 0;
+  auto load_slab = [&](int k0, int tap_, int cb_) {
     ok = 0;
-    const int q = (k0 >> 3) + akc;
-    const bool kin = q * 8 < g.K;
-    const int t = tab[kin ? q : 0];
-    const int u = t & 15, v = (t >> 4) & 15, ci = t >> 8;
+    if (FAST) {
+      const int u = tap_ / g.ks, v = tap_ - u * g.ks;
+      const long tapoff = (g.transposed ? -1L : 1L) * ((long)u * g.Ws + v) * g.Cs + cb_;
+      const bool kin = k0 < g.K;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const long o = gather_offset(g, an[i], ah[i], aw[i], u, v, ci);
-      const bool in = kin && arow_ok[i] && o >= 0;
-      ra[i] = *reinterpret_cast<const u32x4*>(p.src + (in ? o : 0));
-      ok |= (in ? 1u : 0u) << i;
+      for (int i = 0; i < 4; ++i) {
+        const bool in = kin && ((tapmask[i] >> tap_) & 1u);
+        ra[i] = *reinterpret_cast<const u32x4*>(p.src + (in ? rowbase[i] + tapoff : 0));
+        ok |= (in ? 1u : 0u) << i;
+      }
+    } else {
+      const int q = (k0 >> 3) + kc;
+      const bool kin = q * 8 < g.K;
+      const int t = tab[kin ? q : 0];
+      const int u = t & 15, v = (t >> 4) & 15, ci = t >> 8;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const long o = gather_offset(g, an[i], ah[i], aw[i], u, v, ci);
+        const bool in = kin && ((arow_ok >> i) & 1u) && o >= 0;
+        ra[i] = *reinterpret_cast<const u32x4*>(p.src + (in ? o : 0));
+        ok |= (in ? 1u : 0u) << i;
+      }
     }
+    const bool bkin = k0 + kc * 8 < g.K;
 #pragma unroll
-    for (int i = 0; i < TN; ++i) {
-      const int c = tid + kThreads * i;
-      const int r = col0 + (c >> 2), k = k0 + (c & 3) * 8;
-      const bool in = r < p.N && k < g.K;
-      rb[i] = *reinterpret_cast<const u32x4*>(p.wgt + (in ? (size_t)r * g.K + k : 0));
+    for (int i = 0; i < NB; ++i) {
+      const bool in = bkin && ((brow_ok >> i) & 1u);
+      rb[i] = *reinterpret_cast<const u32x4*>(p.wgt + (in ? brow[i] + k0 : 0));
       ok |= (in ? 1u : 0u) << (4 + i);
     }
   };
-  auto store_slab = [&](int s) {
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = tid + kThreads * i;
-      *reinterpret_cast<u32x4*>(sA(s) + (c >> 2) * kRow + (c & 3) * 8) = ((ok >> i) & 1u) ? ra[i] : zero;
-    }
-#pragma unroll
-    for (int i = 0; i < TN; ++i) {
-      const int c = tid + kThreads * i;
-      *reinterpret_cast<u32x4*>(sB(s) + (c >> 2) * kRow + (c & 3) * 8) = ((ok >> (4 + i)) & 1u) ? rb[i] : zero;
-    }
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  auto store_a = [&](int s, int i) {
+    *reinterpret_cast<u32x4*>(sA(s) + (rbase + 32 * i) * kRow + kc * 8) = ((ok >> i) & 1u) ? ra[i] : zero;
+  };
+  auto store_b = [&](int s, int i) {
+    *reinterpret_cast<u32x4*>(sB(s) + (rbase + 32 * i) * kRow + kc * 8) = ((ok >> (4 + i)) & 1u) ? rb[i] : zero;
+  };
+  auto advance = [&]() {
+    cb += BK2;
+    if (cb >= g.Cs) { cb = 0; ++tap; }
   };
 
-  const int nslab = (g.K + BK - 1) / BK;
-  load_slab(0);
-  store_slab(0);
+  const int nslab = (g.K + BK2 - 1) / BK2;
+  load_slab(0, 0, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) store_a(0, i);
+#pragma unroll
+  for (int i = 0; i < NB; ++i) store_b(0, i);
   __syncthreads();
   for (int s = 0; s < nslab; ++s) {
     const int cur = s & 1;
+    if (FAST) advance();
     // always issued (past the end it re-reads element 0 and is dropped): a load
     // issued on one path only would make every later wait drain the queue
-    load_slab(s + 1 < nslab ? (s + 1) * BK : g.K);
+    load_slab(s + 1 < nslab ? (s + 1) * BK2 : g.K, s + 1 < nslab ? tap : 0, cb);
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
+    for (int ks = 0; ks < BK2 / 16; ++ks) {
       bf16x8 fa[2], fb[TN];
       const int ko = ks * 16 + (lane >> 5) * 8;
 #pragma unroll
@@ -206,31 +265,59 @@ __global__ __launch_bounds__(kThreads) void conv_gemm_kernel(ConvParams p) {
           acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
     }
     if (s + 1 < nslab) {
-      store_slab(cur ^ 1);
-      __syncthreads();
+#pragma unroll
+      for (int i = 0; i < 4; ++i) store_a(cur ^ 1, i);
+#pragma unroll
+      for (int i = 0; i < NB; ++i) store_b(cur ^ 1, i);
     }
+    __syncthreads();
   }
 
-  // accumulator layout of a 32x32 block: register v of lane l holds row
-  // 8*(v/4) + 4*(l/32) + v%4, column l%32
+  // ---- output tile -> LDS (fp32) -> 16-byte pieces.  Accumulator layout of a 32x32
+  // block: register v of lane l holds row 8*(v/4) + 4*(l/32) + v%4, column l%32.
+  float* so = reinterpret_cast<float*>(smem);
 #pragma unroll
   for (int b = 0; b < TN; ++b) {
-    const int j = col0 + wcol + b * 32 + (lane & 31);
-    if (j >= p.N) continue;
-    const float bj = p.bias ? p.bias[j] : 0.f;
+    const int jl = wcol + b * 32 + (lane & 31);
+    const int j = col0 + jl;
+    const float bj = (p.bias && j < p.N) ? p.bias[j] : 0.f;
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int i = row0 + wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
-        if (i >= p.M) continue;
-        const size_t idx = (size_t)i * p.N + j;
+        const int il = wrow + a * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
         float val = acc[a][b][v] + bj;
         if (p.relu) val = val > 0.f ? val : 0.f;
-        if (p.mask) val = bf16_to_f32(p.mask[idx]) > 0.f ? val : 0.f;
-        if (p.accumulate) val += bf16_to_f32(p.out[idx]);
-        p.out[idx] = f32_to_bf16(val);
+        so[il * kOutPitch + jl] = val;
       }
+  }
+  __syncthreads();
+  constexpr int kPiecesPerRow = BN / 8;
+#pragma unroll
+  for (int it = 0; it < BM * kPiecesPerRow / kThreads; ++it) {
+    const int c = tid + kThreads * it;
+    const int il = c / kPiecesPerRow, jl = (c % kPiecesPerRow) * 8;
+    const int i = row0 + il, j = col0 + jl;
+    if (i >= p.M || j >= p.N) continue;      // N is a multiple of 8: a piece is wholly inside or outside
+    float v[8];
+    const v4f lo = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl);
+    const v4f hi = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+    const size_t idx = (size_t)i * p.N + j;
+    if (p.mask) {
+      float mv[8];
+      Piece<bf16_t>::load(p.mask + idx, mv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = mv[e] > 0.f ? v[e] : 0.f;
+    }
+    if (p.accumulate) {
+      float ov[8];
+      Piece<bf16_t>::load(p.out + idx, ov);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += ov[e];
+    }
+    Piece<bf16_t>::store(p.out + idx, v);
   }
 }
 
@@ -492,18 +579,32 @@ bool conv_shape_supported(const ConvGeom& g, long positions) {
   return g.Cs % 8 == 0 && g.K <= kMaxPieces * 8 && g.ks >= 1 && g.ks <= 15 && positions < (1L << 24);
 }
 
+template <int TN, bool FAST>
+static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
+  constexpr int BN = 64 * TN;
+  constexpr size_t kBytes = (size_t)2 * (BM + BN) * (BK2 + 8) * sizeof(bf16_t) + (FAST ? 0 : kMaxPieces * sizeof(int));
+  static bool configured = false;   // raising the dynamic LDS limit is a per-function, one-time host call
+  if (!configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gemm2_kernel<TN, FAST>),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBytes);
+    configured = true;
+  }
+  hipLaunchKernelGGL((conv_gemm2_kernel<TN, FAST>), dim3(tiles), dim3(kThreads), kBytes, st, p);
+}
+
 void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
   const int tiles_m = (M + BM - 1) / BM;
+  const bool fast = g.Cs % BK2 == 0 && g.ks <= 3 && (!g.transposed || g.stride == 1);
   if (N > 64) {
-    dim3 grid(tiles_m * ((N + 127) / 128));
-    hipLaunchKernelGGL(conv_gemm_kernel<2>, grid, dim3(kThreads), 0, st, p);
+    const int tiles = tiles_m * ((N + 127) / 128);
+    if (fast) launch_gemm2<2, true>(st, p, tiles); else launch_gemm2<2, false>(st, p, tiles);
   } else {
-    dim3 grid(tiles_m * ((N + 63) / 64));
-    hipLaunchKernelGGL(conv_gemm_kernel<1>, grid, dim3(kThreads), 0, st, p);
+    const int tiles = tiles_m * ((N + 63) / 64);
+    if (fast) launch_gemm2<1, true>(st, p, tiles); else launch_gemm2<1, false>(st, p, tiles);
   }
 }
 
