@@ -66,6 +66,27 @@ def cpu_baseline(w, off, budget_s=12.0):
             "sample": f"{n} full steps of the same workload (B={w.B}), fp64 numpy, {el:.1f} s"}
 
 
+def measured_traffic(workload, key):
+    """HBM bytes per launch from the committed counter summary of this workload, or None.
+
+    The summary carries the hash of the kernel's source file at the time the counters were
+    taken; a figure for a kernel that has changed since is not reported."""
+    import hashlib
+    import re
+    root = os.path.dirname(os.path.abspath(__file__))
+    path = os.path.join(root, "profiles", f"step_{workload}_hbm_traffic.md")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        m = re.match(r"\s*traffic (.+?) bytes=(\S+) source=(\S+) sha256=([0-9a-f]{64})\s*$", line)
+        if not m or m.group(1) != key:
+            continue
+        src = os.path.join(root, m.group(3))
+        if os.path.exists(src) and hashlib.sha256(open(src, "rb").read()).hexdigest() == m.group(4):
+            return float(m.group(2))
+    return None
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,7 +174,8 @@ def main():
     achieved = flops / kernel_s / 1e12
     peak = PEAK_TFLOPS[w.dtype]
     roofline = {"bound": "mfma", "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
-                "unit": "TFLOP/s", "frac": achieved / peak, "traffic": None,
+                "unit": "TFLOP/s", "frac": achieved / peak,
+                "traffic": measured_traffic(w.name, f"{kcls}[layer {klayer}]"),
                 "avg_launch_us": kernel_s * 1e6, "launches": int(k_n)}
 
     out = {
@@ -174,7 +196,8 @@ def main():
                    "includes": "controller+offsets+fwd+loss+bwd+weighted reduce+SGD"},
         "roofline": roofline,
         "roofline_update": {"bound": "hbm", "kernel": "weighted reduce + SGD", "achieved": upd_gbs,
-                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS, "traffic": None,
+                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS,
+                            "traffic": measured_traffic(w.name, "update"),
                             "bytes_per_launch": upd_bytes, "avg_launch_us": u_ms / max(u_n, 1) * 1e3,
                             "note": "working set below 256 MB may be served from the Infinity Cache"},
         "final_loss": final_loss,
