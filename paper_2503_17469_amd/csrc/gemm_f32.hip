@@ -468,6 +468,7 @@ static int gemm_tiles(int rows, int cols) { return ((rows + kTile - 1) / kTile) 
 
 void linear_fwd_f32(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
                     int rows, int cin, int cout, bool relu, const SplitWorkspace& sw) {
+  if (linear_fwd_f32_direct(st, x, w, bias, y, rows, cin, cout, relu)) return;
   GemmParams p{};
   p.A = x; p.B = w; p.C = y; p.M = rows; p.N = cout; p.lda = cin; p.ldb = cin; p.ldc = cout;
   p.kred = cin; p.bias = bias; p.relu = relu ? 1 : 0;
@@ -479,6 +480,7 @@ void linear_fwd_f32(hipStream_t st, const float* x, const float* w, const float*
 
 void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
                       int rows, int cin, int cout, bool accumulate, const SplitWorkspace& sw) {
+  if (linear_dgrad_f32_direct(st, dy, w, mask, dx, rows, cin, cout, accumulate)) return;
   GemmParams p{};
   p.A = dy; p.B = w; p.C = dx; p.M = rows; p.N = cin; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.kred = cout; p.mask = mask; p.accumulate = accumulate ? 1 : 0;

@@ -163,6 +163,9 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
 
 // grid.x = K * ceil(cin/16) + 1, grid.y = ceil(C/16).  A workgroup is 16 input
 // columns x 16 row groups; each thread walks its share of the worker's rows.
+// The worker's dz rows (16 classes of them) are staged in LDS 256 rows at a time:
+// fetched per thread they would be 16 global loads per row, and the vector cache,
+// not the arithmetic, would set the pace.
 template <typename T>
 __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
     const float* __restrict__ dz, const T* __restrict__ x, const int32_t* __restrict__ labels, int cin, int C,
@@ -170,77 +173,94 @@ __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
     const float* __restrict__ loss_rows, float* __restrict__ loss_per_worker, float* __restrict__ loss,
     uint32_t* __restrict__ status) {
   __shared__ float red[16][16][17];
+  __shared__ __attribute__((aligned(16))) float dzs[256][16];
   const int tid = threadIdx.x;
   const int jchunks = (cin + 15) / 16;
 
   if ((int)blockIdx.x == seg.K * jchunks) {
-    // ---- the extra workgroup: losses and label check
+    // ---- the extra workgroup: losses and label check; one wavefront per worker
     if (blockIdx.y != 0) return;
-    float* r1 = &red[0][0][0];
+    float* part = &red[0][0][0];
+    const int lane = tid & 63, wv = tid >> 6;
     const int rows = seg.off[seg.K];
     const float invB = 1.0f / (float)rows;
-    float total = 0.f;
-    for (int k = 0; k < seg.K; ++k) {
+    for (int k = wv; k < seg.K; k += 4) {
       float a = 0.f;
-      for (int s = seg.off[k] + tid; s < seg.off[k + 1]; s += 256) a += loss_rows[s];
-      r1[tid] = a;
-      __syncthreads();
-      for (int h = 128; h > 0; h >>= 1) {
-        if (tid < h) r1[tid] += r1[tid + h];
-        __syncthreads();
-      }
-      if (tid == 0) {
+      for (int s = seg.off[k] + lane; s < seg.off[k + 1]; s += 64) a += loss_rows[s];
+      a = wave_sum(a);
+      if (lane == 0) {
         const float bk = (float)(seg.off[k + 1] - seg.off[k]);
-        const float Lk = r1[0] / bk;
+        const float Lk = a / bk;
         loss_per_worker[k] = Lk;
-        total += bk * invB * Lk;
+        part[k] = bk * invB * Lk;   // lambda_k L_k
       }
-      __syncthreads();
     }
-    uint32_t badl = 0;
-    for (int s = tid; s < rows; s += 256) badl |= (labels[s] < 0 || labels[s] >= C) ? 1u : 0u;
-    r1[tid] = (float)badl;
-    __syncthreads();
-    for (int h = 128; h > 0; h >>= 1) {
-      if (tid < h) r1[tid] = fmaxf(r1[tid], r1[tid + h]);
-      __syncthreads();
-    }
+    int badl = 0;
+    for (int s = tid; s < rows; s += 256) badl |= (labels[s] < 0 || labels[s] >= C) ? 1 : 0;
+    const int anybad = __syncthreads_or(badl);
     if (tid == 0) {
+      float total = 0.f;
+      for (int k = 0; k < seg.K; ++k) total += part[k];
       loss[0] = total;
-      status[0] = r1[0] > 0.f ? 1u : 0u;
+      status[0] = anybad ? 1u : 0u;
     }
     return;
   }
 
   const int wk = blockIdx.x / jchunks, jc = blockIdx.x % jchunks;
   const int jl = tid & 15, rs = tid >> 4;
-  const int j = jc * 16 + jl;
+  const int j = min(jc * 16 + jl, cin - 1);   // a column past the end shadows the last one and is not stored
   const int c0 = blockIdx.y * 16;
   const int nc = min(16, C - c0);
   const int s_end = seg.off[wk + 1];
+  const bool want_bias = jc == 0 && gb != nullptr;
   float acc[16];
 #pragma unroll
   for (int c = 0; c < 16; ++c) acc[c] = 0.f;
-  if (j < cin) {
-    int s = seg.off[wk] + rs;
-    for (; s + 112 < s_end; s += 128) {        // eight rows per trip: their loads overlap
+  float bsum = 0.f;   // class jl, rows rs, rs+16, ...
+
+  for (int base = seg.off[wk]; base < s_end; base += 256) {
+    const int n = min(256, s_end - base);
+    __syncthreads();   // the previous 256 rows have been consumed
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int f = tid + 256 * i, rr = f >> 4, c = f & 15;
+      const bool ok = rr < n && c < nc;
+      const float v = dz[(size_t)(base + (ok ? rr : 0)) * C + c0 + (ok ? c : 0)];
+      dzs[rr][c] = ok ? v : 0.f;
+    }
+    __syncthreads();
+    const T* xb = x + (size_t)base * cin + j;
+    int sl = rs;
+    for (; sl + 112 < n; sl += 128) {        // eight rows per trip: their loads overlap
       float av[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) av[u] = Piece<T>::get(x + (size_t)(s + 16 * u) * cin + j);
+      for (int u = 0; u < 8; ++u) av[u] = Piece<T>::get(xb + (size_t)(sl + 16 * u) * cin);
 #pragma unroll
       for (int u = 0; u < 8; ++u) {
-        const float* d = dz + (size_t)(s + 16 * u) * C + c0;
+        const v4f* d = reinterpret_cast<const v4f*>(&dzs[sl + 16 * u][0]);
 #pragma unroll
-        for (int c = 0; c < 16; ++c) acc[c] += d[c < nc ? c : 0] * av[u];   // columns >= nc are never stored
+        for (int q = 0; q < 4; ++q) {
+          const v4f dv = d[q];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) acc[4 * q + e] += dv[e] * av[u];
+        }
       }
     }
-    for (; s < s_end; s += 16) {
-      const float a = Piece<T>::get(x + (size_t)s * cin + j);
-      const float* d = dz + (size_t)s * C + c0;
+    for (; sl < n; sl += 16) {
+      const float a = Piece<T>::get(xb + (size_t)sl * cin);
+      const v4f* d = reinterpret_cast<const v4f*>(&dzs[sl][0]);
 #pragma unroll
-      for (int c = 0; c < 16; ++c) acc[c] += d[c < nc ? c : 0] * a;
+      for (int q = 0; q < 4; ++q) {
+        const v4f dv = d[q];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[4 * q + e] += dv[e] * a;
+      }
     }
+    if (want_bias)
+      for (int r2 = rs; r2 < n; r2 += 16) bsum += dzs[r2][jl];
   }
+
 #pragma unroll
   for (int c = 0; c < 16; ++c) red[rs][c][jl] = acc[c];
   __syncthreads();
@@ -252,15 +272,11 @@ __global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
     if (c < nc && jc * 16 + jj < cin)
       gw[(size_t)wk * worker_stride + (size_t)(c0 + c) * cin + jc * 16 + jj] = t;
   }
-  if (jc == 0 && gb != nullptr) {
+  if (want_bias) {
     // bias gradient: column sums of dz over the worker's rows, 16 row groups x 16 classes
     __syncthreads();
-    const int c = tid & 15, rg = tid >> 4;
-    float t = 0.f;
-    if (c < nc)
-      for (int s = seg.off[wk] + rg; s < s_end; s += 16) t += dz[(size_t)s * C + c0 + c];
     float* r2 = &red[0][0][0];
-    r2[rg * 16 + c] = t;
+    r2[rs * 16 + jl] = bsum;
     __syncthreads();
     if (tid < 16 && tid < nc) {
       float u = 0.f;

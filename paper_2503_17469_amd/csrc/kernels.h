@@ -26,6 +26,12 @@ void linear_fwd_f32(hipStream_t st, const float* x, const float* w, const float*
 // dx[rows][cin] (+)= dy[rows][cout] * w[cout][cin], zeroed where mask[rows][cin] <= 0 (mask may be null).
 void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
                       int rows, int cin, int cout, bool accumulate, const SplitWorkspace& sw);
+// Small-batch variants (gemm_f32_direct.hip): same results as the two above up to
+// summation order; return false without launching when the shape does not qualify.
+bool linear_fwd_f32_direct(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
+                           int rows, int cin, int cout, bool relu);
+bool linear_dgrad_f32_direct(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
+                             int rows, int cin, int cout, bool accumulate);
 // For every worker k: gw + k*worker_stride receives dy_k^T x_k ([cout][cin]) over rows
 // seg.off[k]..seg.off[k+1]-1, and gb + k*worker_stride the column sums of dy_k (gb may be null).
 void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw, float* gb,

@@ -61,6 +61,10 @@ def test_config1_mlp3072():
     ([132, 200, 96, 7], [0, 33, 34, 133, 197]),    # several tiles with ragged tails
     ([64, 64, 64], [0, 64, 128]),                  # exact tile multiples
     ([260, 10], [0, 5, 300]),                      # single layer, no ReLU
+    # reductions that are multiples of 32 with few output tiles take the small-batch kernels:
+    # ragged row tile (77 = 2*32 + 13), ragged column tile (200 = 3*64 + 8), uneven steps per wavefront (320/32 = 10)
+    ([256, 320, 200, 10], [0, 3, 40, 41, 77]),
+    ([288, 256, 30, 5], [0, 31, 32, 33]),          # one row tile, 30-column tile, 9 steps
 ])
 def test_ragged_shapes(dims, off):
     layers = synth.mlp(dims)
