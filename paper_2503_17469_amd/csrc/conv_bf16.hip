@@ -571,6 +571,275 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_reduce_kernel(WgradParams
   }
 }
 
+
+// ------------------------------------------------------------------ kernel C
+// Weight gradient of 3x3, stride-1, pad-1 convolutions (most of a residual net).
+// Kernel B treats the nine filter taps as nine independent column blocks: the
+// input is fetched and transposed nine times and dY once per column tile, and at
+// 64 channels that memory traffic, not the matrix pipe, sets the pace.  Here a
+// workgroup owns 64 output channels x 64 input channels x ALL nine taps and walks
+// through units of 128 output positions (a strip of rows of one image, or a few
+// whole small images):
+//   * dY^T [64 co][128 positions] and the input patch X^T [64 ci][rows+2][W+16]
+//     (with its zero halo) are transposed into LDS ONCE per unit;
+//   * the B operand of tap (u, v) is the patch shifted by (u-1) rows and (v-1)
+//     columns: the row shift is an address offset; the column shift of one
+//     element is made in registers from the aligned 16-byte read and its two
+//     neighbour words (v_alignbit), so one LDS read serves three taps;
+//   * each wavefront holds 32 co x 32 ci x 9 taps = nine accumulator blocks.
+// Units never straddle workers; a worker's units are cut into chunks, one
+// workgroup per (tile, chunk), partial tiles are added by a second kernel in
+// chunk order (bit-reproducible, no atomics).
+struct Wgrad3Params {
+  const bf16_t* dy;    // [rows*H*W][Cout]
+  const bf16_t* src;   // [rows][H][W][Cin]
+  float* gw;           // worker w: gw + w*worker_stride, [Cout][9][Cin]
+  float* gb;           // may be null
+  size_t worker_stride;
+  int Cout, Cin, H, W;
+  int R, nimg;         // a unit is nimg images x R rows; nimg * R * W = 128
+  int Wp, prows;       // patch row length W + 16 (data starts at column 8), patch rows nimg * (R + 2)
+  int SX;              // bytes between channels of X^T
+  int upc;             // units per chunk
+  float* partial;      // [(tile * total_chunks + chunk)][144][256] (+ 64 bias sums)
+};
+constexpr int kUnit = 128;
+constexpr int kSA = 2 * kUnit + 16;                 // bytes between channels of dY^T
+constexpr int kTile3Floats = 9 * 16 * kThreads;    // one partial tile
+constexpr int kTile3Stride = kTile3Floats + 64;
+
+// four positions x eight channels (c[q] = the 16-byte piece of position q) -> eight
+// channel rows of four positions each
+__device__ inline void transpose_store(const u32x4 c[4], unsigned char* dst, int row_bytes) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    u32x2 lo, hi;
+    lo[0] = (c[0][d] & 0xFFFFu) | (c[1][d] << 16);
+    lo[1] = (c[2][d] & 0xFFFFu) | (c[3][d] << 16);
+    hi[0] = (c[0][d] >> 16) | (c[1][d] & 0xFFFF0000u);
+    hi[1] = (c[2][d] >> 16) | (c[3][d] & 0xFFFF0000u);
+    *reinterpret_cast<u32x2*>(dst + (2 * d) * row_bytes) = lo;
+    *reinterpret_cast<u32x2*>(dst + (2 * d + 1) * row_bytes) = hi;
+  }
+}
+
+__global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p, Segments seg, ChunkTable ct) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem3[];
+  unsigned char* sA = smem3;                 // dY^T: 64 rows of kSA bytes
+  unsigned char* sX = smem3 + 64 * kSA;      // X^T: 64 rows of p.SX bytes
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 31, h = lane >> 5;
+  const int tiles_ci = (p.Cin + 63) / 64;
+  const int tile = blockIdx.x;
+  const int co0 = (tile / tiles_ci) * 64, ci0 = (tile % tiles_ci) * 64;
+  const int wco = (wave >> 1) * 32, wci = (wave & 1) * 32;
+  const int H = p.H, W = p.W, R = p.R;
+
+  int wk = 0;
+  while (wk + 1 < seg.K && (int)blockIdx.y >= ct.first[wk + 1]) ++wk;
+  const int chunk_idx = blockIdx.y - ct.first[wk];
+  const int nchunks = ct.first[wk + 1] - ct.first[wk];
+  const int bk = seg.off[wk + 1] - seg.off[wk];
+  const int upi = H / R;   // units per image when a unit is part of one image
+  const int units_k = p.nimg == 1 ? bk * upi : (bk + p.nimg - 1) / p.nimg;
+  const int ubeg = chunk_idx * p.upc, uend = min(units_k, ubeg + p.upc);
+
+  // the halo columns of the patch are never written again: they stay zero
+  for (int i = tid * 16; i < 64 * p.SX; i += kThreads * 16)
+    *reinterpret_cast<u32x4*>(sX + i) = u32x4{0u, 0u, 0u, 0u};
+
+  // ---- staging tasks (the same for every unit, relative to the unit's first image and row)
+  // dY: 8 channel octets x 32 groups of 4 positions
+  const int a_oct = tid & 7;
+  int a_rel, a_il;
+  {
+    const int p0 = 4 * (tid >> 3), rr = p0 / W, w = p0 - rr * W;
+    a_il = rr / R;
+    a_rel = (a_il * H + (rr - a_il * R)) * W + w;
+  }
+  const bool a_chan_ok = co0 + 8 * a_oct < p.Cout;
+  unsigned char* a_dst = sA + (8 * a_oct) * kSA + 8 * (tid >> 3);
+  // X: 8 octets x (W/4 groups of 4 columns) x patch rows, two tasks per thread
+  const int wq = W >> 2;
+  const int ntasks = p.prows * wq * 8;
+  int x_rel[2], x_il[2], x_rr[2], x_dst[2];
+  bool x_task[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int x = tid + t * kThreads;
+    x_task[t] = x < ntasks;
+    const int xx = x_task[t] ? x : 0;
+    const int oct = xx & 7, g = xx >> 3;
+    const int pr = g / wq, wg = g - pr * wq;
+    x_il[t] = pr / (R + 2);
+    x_rr[t] = pr - x_il[t] * (R + 2);                       // input row = first row + x_rr - 1
+    x_rel[t] = ((x_il[t] * H + x_rr[t] - 1) * W + 4 * wg) * p.Cin + 8 * oct;
+    x_dst[t] = (8 * oct) * p.SX + (pr * p.Wp + 4 * wg + 8) * 2;
+    x_task[t] = x_task[t] && ci0 + 8 * oct < p.Cin;
+  }
+
+  // ---- fragment addresses: k-step ks covers positions 16 ks .. 16 ks + 15, this lane the 8 at 16 ks + 8 h
+  int offB[kUnit / 16];
+#pragma unroll
+  for (int ks = 0; ks < kUnit / 16; ++ks) {
+    const int pos = (2 * ks + h) * 8, rr = pos / W, w0 = pos - rr * W;
+    const int il = rr / R;
+    offB[ks] = ((il * (R + 2) + (rr - il * R)) * p.Wp + w0 + 8) * 2;
+  }
+  const unsigned char* a_frag = sA + (wco + j) * kSA + h * 16;
+  const unsigned char* x_frag = sX + (wci + j) * p.SX;
+  const int row_shift = p.Wp * 2;
+
+  v16f acc[9];
+#pragma unroll
+  for (int t = 0; t < 9; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[t][v] = 0.f;
+  const bool want_bias = p.gb != nullptr && ci0 == 0;
+  float bsum = 0.f;
+
+  u32x4 ra[4], rx[2][4];
+  uint32_t ok = 0;   // bits 0-3: dY positions; bit 4, 5: the two X tasks
+  auto load_unit = [&](int u) {
+    int n0, r0, nvalid;
+    if (p.nimg == 1) {
+      const int img = u / upi;
+      n0 = seg.off[wk] + img; r0 = (u - img * upi) * R; nvalid = 1;
+    } else {
+      n0 = seg.off[wk] + u * p.nimg; r0 = 0; nvalid = min(p.nimg, seg.off[wk + 1] - n0);
+    }
+    ok = 0;
+    const long base_pos = ((long)n0 * H + r0) * W;
+    // Loads never branch (a guarded load makes the compiler wait for each group before the
+    // next): an invalid piece reads the tensor's first 16 bytes and is zeroed when stored.
+    {
+      const bool in = a_chan_ok && a_il < nvalid;
+      const long m = -(long)in;   // all ones or zero
+      const long o = ((base_pos + a_rel) * p.Cout + co0 + 8 * a_oct) & m;
+      const long st = (long)p.Cout & m;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) ra[q] = *reinterpret_cast<const u32x4*>(p.dy + o + q * st);
+      ok |= 0xFu & (uint32_t)m;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = r0 + x_rr[t] - 1;
+      const bool in = x_task[t] && x_il[t] < nvalid && row >= 0 && row < H;
+      const long m = -(long)in;
+      const long o = (base_pos * p.Cin + x_rel[t] + ci0) & m;
+      const long st = (long)p.Cin & m;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) rx[t][q] = *reinterpret_cast<const u32x4*>(p.src + o + q * st);
+      ok |= ((uint32_t)m & 1u) << (4 + t);
+    }
+  };
+  auto store_unit = [&]() {
+    const u32x4 zero = {0u, 0u, 0u, 0u};
+    u32x4 c[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) c[q] = (ok & 0xFu) ? ra[q] : zero;
+    transpose_store(c, a_dst, kSA);
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      if (tid + t * kThreads >= ntasks) continue;   // no such patch piece (not a matter of validity)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) c[q] = ((ok >> (4 + t)) & 1u) ? rx[t][q] : zero;
+      transpose_store(c, sX + x_dst[t], p.SX);
+    }
+  };
+
+  load_unit(min(ubeg, max(uend - 1, 0)));
+  for (int u = ubeg; u < uend; ++u) {
+    __syncthreads();   // the previous unit's fragments have been read (and, first time, the zero fill is done)
+    store_unit();
+    __syncthreads();
+    load_unit(min(u + 1, uend - 1));   // always issued: in flight during the MFMAs below
+#pragma unroll
+    for (int ks = 0; ks < kUnit / 16; ++ks) {
+      const bf16x8 fa = as_bf16x8(*reinterpret_cast<const u32x4*>(a_frag + ks * 32));
+#pragma unroll
+      for (int du = 0; du < 3; ++du) {
+        const unsigned char* xb = x_frag + offB[ks] + du * row_shift;
+        const u32x4 q = *reinterpret_cast<const u32x4*>(xb);
+        const uint32_t pl = *reinterpret_cast<const uint32_t*>(xb - 4);
+        const uint32_t pn = *reinterpret_cast<const uint32_t*>(xb + 16);
+        const uint32_t m01 = __builtin_amdgcn_alignbit(q[1], q[0], 16);
+        const uint32_t m12 = __builtin_amdgcn_alignbit(q[2], q[1], 16);
+        const uint32_t m23 = __builtin_amdgcn_alignbit(q[3], q[2], 16);
+        const u32x4 left = {__builtin_amdgcn_alignbit(q[0], pl, 16), m01, m12, m23};
+        const u32x4 right = {m01, m12, m23, __builtin_amdgcn_alignbit(pn, q[3], 16)};
+        acc[du * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(left), acc[du * 3 + 0], 0, 0, 0);
+        acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(q), acc[du * 3 + 1], 0, 0, 0);
+        acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
+      }
+    }
+    if (want_bias && tid < 64) {
+      // rows of dY^T are output channels: their sums over positions are the bias gradient
+      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA + tid * kSA);
+#pragma unroll 16
+      for (int d = 0; d < kUnit / 2; ++d) bsum += bf16_lo(rowp[d]) + bf16_hi(rowp[d]);
+    }
+  }
+
+  if (nchunks > 1) {
+    float* mine = p.partial + ((size_t)tile * ct.first[seg.K] + blockIdx.y) * kTile3Stride;
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) mine[(t * 16 + v) * kThreads + tid] = acc[t][v];
+    if (tid < 64) mine[kTile3Floats + tid] = bsum;
+    return;
+  }
+  float* gw = p.gw + (size_t)wk * p.worker_stride;
+  const int ci = ci0 + wci + j;
+  if (ci < p.Cin) {
+#pragma unroll
+    for (int t = 0; t < 9; ++t)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int co = co0 + wco + 8 * (v / 4) + 4 * h + (v % 4);
+        if (co < p.Cout) gw[((size_t)co * 9 + t) * p.Cin + ci] = acc[t][v];
+      }
+  }
+  if (want_bias && tid < 64 && co0 + tid < p.Cout) p.gb[(size_t)wk * p.worker_stride + co0 + tid] = bsum;
+}
+
+// Second stage: grid (tiles, workers, 9 taps x 4 register quarters).  Each thread owns
+// the (output channel, input channel) pairs the same thread of the first stage held
+// and adds the worker's chunks in chunk order.
+__global__ __launch_bounds__(kThreads) void conv3_wgrad_reduce_kernel(Wgrad3Params p, Segments seg, ChunkTable ct) {
+  const int tile = blockIdx.x, wk = blockIdx.y, tap = blockIdx.z >> 2, vq = blockIdx.z & 3;
+  const int nchunks = ct.first[wk + 1] - ct.first[wk];
+  if (nchunks <= 1) return;   // written directly by the first stage
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 31, h = lane >> 5;
+  const int tiles_ci = (p.Cin + 63) / 64;
+  const int co0 = (tile / tiles_ci) * 64, ci0 = (tile % tiles_ci) * 64;
+  const int wco = (wave >> 1) * 32, wci = (wave & 1) * 32;
+  const float* all = p.partial + ((size_t)tile * ct.first[seg.K] + ct.first[wk]) * kTile3Stride;
+  const float* mine = all + (size_t)(tap * 16 + vq * 4) * kThreads + tid;
+  float s[4] = {0.f, 0.f, 0.f, 0.f};
+  for (int c = 0; c < nchunks; ++c) {
+    const float* q = mine + (size_t)c * kTile3Stride;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) s[e] += q[e * kThreads];
+  }
+  const int ci = ci0 + wci + j;
+  if (ci < p.Cin) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int v = vq * 4 + e;
+      const int co = co0 + wco + 8 * (v / 4) + 4 * h + (v % 4);
+      if (co < p.Cout) p.gw[(size_t)wk * p.worker_stride + ((size_t)co * 9 + tap) * p.Cin + ci] = s[e];
+    }
+  }
+  if (blockIdx.z == 0 && p.gb != nullptr && ci0 == 0 && tid < 64 && co0 + tid < p.Cout) {
+    float bs = 0.f;
+    for (int c = 0; c < nchunks; ++c) bs += all[(size_t)c * kTile3Stride + kTile3Floats + tid];
+    p.gb[(size_t)wk * p.worker_stride + co0 + tid] = bs;
+  }
+}
+
 }  // namespace
 
 size_t conv_wgrad_partial_floats() { return (size_t)kConvMaxPartialTiles * (2 * 2 * 16 * kThreads + 128); }
@@ -608,9 +877,74 @@ void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
   }
 }
 
+// 3x3 / stride 1 / pad 1 with at least 32 stored channels and a map whose rows
+// tile into units of 128 positions: kernel C.  Returns false if the shape does not qualify.
+static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
+                        size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
+                        float* partial) {
+  const int H = g.Hs, W = g.Ws;
+  if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.transposed || g.Hp != H || g.Wp != W) return false;
+  if (cin_real != g.Cs || g.Cs < 32 || g.Cs % 8 != 0 || Cout % 8 != 0) return false;
+  if (W % 8 != 0 || W > kUnit || kUnit % W != 0) return false;
+  const int R = std::min(H, kUnit / W);
+  if (H % R != 0 || kUnit % (R * W) != 0) return false;
+  const int nimg = kUnit / (R * W);
+  if (nimg > 1 && R != H) return false;
+  Wgrad3Params p{};
+  p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
+  p.Cout = Cout; p.Cin = g.Cs; p.H = H; p.W = W; p.R = R; p.nimg = nimg;
+  p.Wp = W + 16; p.prows = nimg * (R + 2);
+  // channel stride of X^T in 4-byte words must be 4 mod 8: 16 lanes x 16 bytes then cover all 64 banks
+  int words = p.prows * p.Wp / 2;
+  words += (4 - words % 8 + 8) % 8;
+  p.SX = words * 4;
+  p.partial = partial;
+  const size_t lds = (size_t)64 * kSA + (size_t)64 * p.SX;
+  if (lds > 80 * 1024) return false;
+  const int tiles = ((Cout + 63) / 64) * ((g.Cs + 63) / 64);
+  const size_t max_slots = conv_wgrad_partial_floats() / kTile3Stride;
+  // units per worker, and a chunk length that gives about two workgroups per compute unit
+  long total_units = 0;
+  int units[OMNI_MAX_WORKERS];
+  for (int k = 0; k < seg.K; ++k) {
+    const int bk = seg.off[k + 1] - seg.off[k];
+    units[k] = nimg == 1 ? bk * (H / R) : (bk + nimg - 1) / nimg;
+    total_units += units[k];
+  }
+  long want = std::max<long>(1, 512 / tiles);
+  long upc = std::max<long>((total_units + want - 1) / want, 4);
+  ChunkTable ct{};
+  for (;;) {
+    int acc = 0;
+    for (int k = 0; k < seg.K; ++k) {
+      ct.first[k] = acc;
+      acc += (int)((units[k] + upc - 1) / upc);
+    }
+    ct.first[seg.K] = acc;
+    if (acc == 0) return true;   // no rows at all
+    // all workgroups resident at once (two per compute unit): a few extra ones would run as a second round
+    if ((size_t)tiles * acc <= max_slots && ((long)tiles * acc <= 512 || acc == seg.K)) break;
+    upc += std::max<long>(1, upc / 16);
+  }
+  p.upc = (int)upc;
+  static size_t configured = 0;   // raising the dynamic LDS limit is a per-function host call
+  if (lds > configured) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_wgrad_kernel),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured = lds;
+  }
+  hipLaunchKernelGGL(conv3_wgrad_kernel, dim3(tiles, ct.first[seg.K]), dim3(kThreads), lds, st, p, seg, ct);
+  bool chunked = false;
+  for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
+  if (chunked)
+    hipLaunchKernelGGL(conv3_wgrad_reduce_kernel, dim3(tiles, seg.K, 36), dim3(kThreads), 0, st, p, seg, ct);
+  return true;
+}
+
 void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                      float* partial, uint32_t* counters) {
+  if (conv3_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
   WgradParams p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
   p.Cout = Cout; p.cin_real = cin_real; p.g = g; p.partial = partial; p.counters = counters;
