@@ -12,6 +12,8 @@
 //           dx = gamma*invstd_k * (dy - mean_k(dy) - xhat * mean_k(dy*xhat))
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "bf16.h"
 #include "common.h"
 #include "kernels.h"
@@ -31,18 +33,35 @@ __device__ inline int owner_of_row(const Segments& seg, int n) {
   return lo;
 }
 
+// Work is dealt to workgroups in proportion to the workers' sizes: worker k owns the
+// splits / chunks first[k] .. first[k+1]-1, each covering an equal share of ITS positions,
+// so ragged b_k do not leave most of the chip waiting for the largest worker.
+struct ShareTable { int32_t first[OMNI_MAX_WORKERS + 1]; };
+
+__device__ inline int share_owner(const ShareTable& tb, int K, int id) {
+  int lo = 0, hi = K - 1;
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (id >= tb.first[mid]) lo = mid; else hi = mid - 1;
+  }
+  return lo;
+}
+
 // Partial sums of (a) x and x^2, or (b) dy and dy*xhat, over one split of one worker's positions.
-// grid (splits, K, ceil(C/64)); block = 8 channel pieces x 32 position lanes.
+// grid (total splits, ceil(C/64)); block = 8 channel pieces x 32 position lanes; four
+// positions per lane in flight.
 template <bool BWD>
 __global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                          const float* __restrict__ stats, int C, int hw,
-                                                         Segments seg, double* __restrict__ partial) {
+                                                         Segments seg, ShareTable tb, double* __restrict__ partial) {
   __shared__ double red[32][8][17];
   const int tid = threadIdx.x;
   const int c8 = tid & 7, pl = tid >> 3;
-  const int wk = blockIdx.y, split = blockIdx.x, nsplit = gridDim.x;
-  const int c0 = blockIdx.z * 64 + c8 * 8;
+  const int wk = share_owner(tb, seg.K, blockIdx.x);
+  const int split = blockIdx.x - tb.first[wk], nsplit = tb.first[wk + 1] - tb.first[wk];
+  const int c0 = blockIdx.y * 64 + c8 * 8;
   const bool cok = c0 < C;
+  const int cl = cok ? c0 : 0;   // a piece past the last channel shadows piece 0 and is not stored
   const long pbeg = (long)seg.off[wk] * hw, pend = (long)seg.off[wk + 1] * hw;
   const long per = (pend - pbeg + nsplit - 1) / nsplit;
   const long sbeg = pbeg + split * per, send = min(pend, sbeg + per);
@@ -53,25 +72,36 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* __restric
   float mu[8], is[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) { s1[e] = 0.0; s2[e] = 0.0; mu[e] = 0.f; is[e] = 1.f; }
-  if (BWD && cok) {
+  if (BWD) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-      mu[e] = stats[((size_t)wk * C + c0 + e) * 2];
-      is[e] = stats[((size_t)wk * C + c0 + e) * 2 + 1];
+      mu[e] = stats[((size_t)wk * C + cl + e) * 2];
+      is[e] = stats[((size_t)wk * C + cl + e) * 2 + 1];
     }
   }
-  if (cok) {
-    for (long p = sbeg + pl; p < send; p += 32) {
-      float xv[8];
-      Piece<bf16_t>::load(x + p * C + c0, xv);
-      if (!BWD) {
+  for (long p = sbeg + pl; p < send; p += 128) {
+    // loads are unconditional (a position past the end re-reads the last one and adds zero)
+    float xv[4][8], dv[4][8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { s1[e] += (double)xv[e]; s2[e] += (double)xv[e] * (double)xv[e]; }
-      } else {
-        float dv[8];
-        Piece<bf16_t>::load(dy + p * C + c0, dv);
+    for (int u = 0; u < 4; ++u) {
+      const long q = min(p + 32 * u, send - 1);
+      Piece<bf16_t>::load(x + q * C + cl, xv[u]);
+      if (BWD) Piece<bf16_t>::load(dy + q * C + cl, dv[u]);
+    }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) { s1[e] += (double)dv[e]; s2[e] += (double)(dv[e] * ((xv[e] - mu[e]) * is[e])); }
+    for (int u = 0; u < 4; ++u) {
+      const float live = p + 32 * u < send ? 1.f : 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (!BWD) {
+          const float v = xv[u][e] * live;
+          s1[e] += (double)v;
+          s2[e] += (double)v * (double)v;
+        } else {
+          const float d = dv[u][e] * live;
+          s1[e] += (double)d;
+          s2[e] += (double)(d * ((xv[u][e] - mu[e]) * is[e]));
+        }
       }
     }
   }
@@ -83,22 +113,47 @@ __global__ __launch_bounds__(256) void bn_partial_kernel(const bf16_t* __restric
     double t = 0.0;
 #pragma unroll
     for (int r = 0; r < 32; ++r) t += red[r][cc >> 3][which * 8 + (cc & 7)];
-    const int c = blockIdx.z * 64 + cc;
-    if (c < C) partial[(((size_t)wk * nsplit + split) * C + c) * 2 + which] = t;
+    const int c = blockIdx.y * 64 + cc;
+    if (c < C) partial[((size_t)blockIdx.x * C + c) * 2 + which] = t;
   }
 }
 
-// Forward: mean and 1/sqrt(var + eps) per (worker, channel).
-__global__ __launch_bounds__(256) void bn_finalize_fwd_kernel(const double* __restrict__ partial, int C, int hw,
-                                                              int nsplit, Segments seg, float* __restrict__ stats) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= seg.K * C) return;
-  const int wk = i / C, c = i - wk * C;
-  double a = 0.0, b = 0.0;
-  for (int s = 0; s < nsplit; ++s) {
-    a += partial[(((size_t)wk * nsplit + s) * C + c) * 2];
-    b += partial[(((size_t)wk * nsplit + s) * C + c) * 2 + 1];
+// Sum of worker wk's split partials for 64 channels: 4 lanes per channel walk the splits
+// (stride 4, fixed order), then the 4 lane sums are added in lane order.
+__device__ inline void bn_sum_splits(const double* __restrict__ partial, int C, const ShareTable& tb, int wk,
+                                     int c, int sg, double (*red)[64][2], double& a, double& b) {
+  a = 0.0; b = 0.0;
+  if (c < C) {
+    int s = tb.first[wk] + sg;
+    const int s_end = tb.first[wk + 1];
+    for (; s + 28 < s_end; s += 32) {   // eight loads in flight; the additions keep their order
+      double2 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *reinterpret_cast<const double2*>(partial + ((size_t)(s + 4 * u) * C + c) * 2);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { a += v[u].x; b += v[u].y; }
+    }
+    for (; s < s_end; s += 4) {
+      const double2 v = *reinterpret_cast<const double2*>(partial + ((size_t)s * C + c) * 2);
+      a += v.x; b += v.y;
+    }
   }
+  red[sg][threadIdx.x & 63][0] = a;
+  red[sg][threadIdx.x & 63][1] = b;
+  __syncthreads();
+  const int cc = threadIdx.x & 63;
+  a = (red[0][cc][0] + red[1][cc][0]) + (red[2][cc][0] + red[3][cc][0]);
+  b = (red[0][cc][1] + red[1][cc][1]) + (red[2][cc][1] + red[3][cc][1]);
+}
+
+// Forward: mean and 1/sqrt(var + eps) per (worker, channel).  grid (K, ceil(C/64)).
+__global__ __launch_bounds__(256) void bn_finalize_fwd_kernel(const double* __restrict__ partial, int C, int hw,
+                                                              Segments seg, ShareTable tb, float* __restrict__ stats) {
+  __shared__ double red[4][64][2];
+  const int wk = blockIdx.x, c = blockIdx.y * 64 + (threadIdx.x & 63), sg = threadIdx.x >> 6;
+  double a, b;
+  bn_sum_splits(partial, C, tb, wk, c, sg, red, a, b);
+  if (sg != 0 || c >= C) return;
   const double n = (double)(seg.off[wk + 1] - seg.off[wk]) * hw;
   const double mean = a / n;
   double var = b / n - mean * mean;
@@ -109,17 +164,14 @@ __global__ __launch_bounds__(256) void bn_finalize_fwd_kernel(const double* __re
 
 // Backward: dbeta, dgamma into worker k's gradient row, and the two means used by dx.
 __global__ __launch_bounds__(256) void bn_finalize_bwd_kernel(const double* __restrict__ partial, int C, int hw,
-                                                              int nsplit, Segments seg, float* __restrict__ means,
+                                                              Segments seg, ShareTable tb, float* __restrict__ means,
                                                               float* __restrict__ g_gamma, float* __restrict__ g_beta,
                                                               size_t worker_stride) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= seg.K * C) return;
-  const int wk = i / C, c = i - wk * C;
-  double a = 0.0, b = 0.0;
-  for (int s = 0; s < nsplit; ++s) {
-    a += partial[(((size_t)wk * nsplit + s) * C + c) * 2];
-    b += partial[(((size_t)wk * nsplit + s) * C + c) * 2 + 1];
-  }
+  __shared__ double red[4][64][2];
+  const int wk = blockIdx.x, c = blockIdx.y * 64 + (threadIdx.x & 63), sg = threadIdx.x >> 6;
+  double a, b;
+  bn_sum_splits(partial, C, tb, wk, c, sg, red, a, b);
+  if (sg != 0 || c >= C) return;
   const double n = (double)(seg.off[wk + 1] - seg.off[wk]) * hw;
   g_beta[(size_t)wk * worker_stride + c] = (float)a;
   g_gamma[(size_t)wk * worker_stride + c] = (float)b;
@@ -127,40 +179,68 @@ __global__ __launch_bounds__(256) void bn_finalize_bwd_kernel(const double* __re
   means[((size_t)wk * C + c) * 2 + 1] = (float)(b / n);
 }
 
-// One thread = 8 channels of one position.
+// Normalise (forward) or input gradient (backward).  grid (total chunks); a workgroup
+// walks one chunk of ONE worker's positions, so each thread keeps the statistics and
+// the affine parameters of its 8 channels in registers; C/8 threads cover a position,
+// floor(256 / (C/8)) positions are in flight per trip, four trips unrolled.
 template <bool BWD>
 __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16_t* __restrict__ x, const bf16_t* __restrict__ dy,
                                                        const float* __restrict__ stats, const float* __restrict__ means,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
-                                                       int C, int hw, long pieces, Segments seg, int relu,
+                                                       int C, int hw, Segments seg, ShareTable tb, int relu,
                                                        bf16_t* __restrict__ out) {
-  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= pieces) return;
   const int c8n = C / 8;
-  const int c0 = (int)(i % c8n) * 8;
-  const long p = i / c8n;
-  const int wk = owner_of_row(seg, (int)(p / hw));
-  float xv[8], o[8];
-  Piece<bf16_t>::load(x + p * C + c0, xv);
-  const float* st = stats + ((size_t)wk * C + c0) * 2;
-  if (!BWD) {
+  const int ppar = 256 / c8n;                   // positions per trip
+  const int tid = threadIdx.x;
+  const int pc = tid % c8n, lp = tid / c8n;
+  if (lp >= ppar) return;
+  const int wk = share_owner(tb, seg.K, blockIdx.x);
+  const int chunk = blockIdx.x - tb.first[wk], nchunk = tb.first[wk + 1] - tb.first[wk];
+  const long pbeg = (long)seg.off[wk] * hw, pend = (long)seg.off[wk + 1] * hw;
+  const long per = (pend - pbeg + nchunk - 1) / nchunk;
+  const long cbeg = pbeg + chunk * per, cend = min(pend, cbeg + per);
+  const int c0 = pc * 8;
+  float mu[8], is[8], gm[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float y = gamma[c0 + e] * ((xv[e] - st[2 * e]) * st[2 * e + 1]) + beta[c0 + e];
-      if (relu) y = y > 0.f ? y : 0.f;
-      o[e] = y;
+  for (int e = 0; e < 8; ++e) {
+    mu[e] = stats[((size_t)wk * C + c0 + e) * 2];
+    is[e] = stats[((size_t)wk * C + c0 + e) * 2 + 1];
+    gm[e] = gamma[c0 + e];
+  }
+  float bt[8], mn1[8], mn2[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    bt[e] = BWD ? 0.f : beta[c0 + e];
+    mn1[e] = BWD ? means[((size_t)wk * C + c0 + e) * 2] : 0.f;
+    mn2[e] = BWD ? means[((size_t)wk * C + c0 + e) * 2 + 1] : 0.f;
+  }
+  for (long p = cbeg + lp; p < cend; p += 4 * ppar) {
+    float xv[4][8], dv[4][8];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const long q = min(p + (long)u * ppar, cend - 1);
+      Piece<bf16_t>::load(x + q * C + c0, xv[u]);
+      if (BWD) Piece<bf16_t>::load(dy + q * C + c0, dv[u]);
     }
-  } else {
-    float dv[8];
-    Piece<bf16_t>::load(dy + p * C + c0, dv);
-    const float* mn = means + ((size_t)wk * C + c0) * 2;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const float xh = (xv[e] - st[2 * e]) * st[2 * e + 1];
-      o[e] = gamma[c0 + e] * st[2 * e + 1] * (dv[e] - mn[2 * e] - xh * mn[2 * e + 1]);
+    for (int u = 0; u < 4; ++u) {
+      const long q = p + (long)u * ppar;
+      if (q >= cend) break;
+      float o[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float xh = (xv[u][e] - mu[e]) * is[e];
+        if (!BWD) {
+          float y = gm[e] * xh + bt[e];
+          if (relu) y = y > 0.f ? y : 0.f;
+          o[e] = y;
+        } else {
+          o[e] = gm[e] * is[e] * (dv[u][e] - mn1[e] - xh * mn2[e]);
+        }
+      }
+      Piece<bf16_t>::store(out + q * C + c0, o);
     }
   }
-  Piece<bf16_t>::store(out + p * C + c0, o);
 }
 
 // out = a + b (optionally ReLU)
@@ -256,38 +336,64 @@ __global__ __launch_bounds__(256) void gap_bwd_kernel(const bf16_t* __restrict__
 
 inline unsigned blocks_for(long n) { return (unsigned)((n + 255) / 256); }
 
-int pick_bn_splits(const Segments& seg, int C) {
+// Deal `total` shares to the workers in proportion to their rows (at least one each).
+ShareTable deal_shares(const Segments& seg, long total) {
+  ShareTable tb{};
+  const long B = std::max(1, seg.off[seg.K]);
+  int acc = 0;
+  for (int k = 0; k < seg.K; ++k) {
+    tb.first[k] = acc;
+    const long bk = seg.off[k + 1] - seg.off[k];
+    acc += (int)std::max<long>(1, (total * bk + B / 2) / B);
+  }
+  tb.first[seg.K] = acc;
+  return tb;
+}
+
+ShareTable bn_splits(const Segments& seg, int C) {
   const int groups = (C + 63) / 64;
-  int s = 2048 / (seg.K * groups);
-  s = s < 1 ? 1 : s;
-  return s > kBnMaxSplits ? kBnMaxSplits : s;
+  // about 2048 workgroups, never more splits than the scratch holds (K * kBnMaxSplits in all)
+  long total = std::max<long>(seg.K, 2048 / groups);
+  total = std::min<long>(total, (long)seg.K * (kBnMaxSplits - 2));
+  return deal_shares(seg, total);
+}
+
+ShareTable bn_chunks(const Segments& seg, int C, int hw) {
+  const long positions = (long)seg.off[seg.K] * hw;
+  const int ppar = 256 / (C / 8);
+  // about 4096 workgroups, at least 8 trips each
+  long total = std::min<long>(4096, std::max<long>(seg.K, positions / (32L * ppar)));
+  return deal_shares(seg, total);
 }
 
 }  // namespace
 
+bool bn_shape_supported(int C) { return C % 8 == 0 && C >= 8 && C <= 2048; }
+
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
                      const Segments& seg, bool relu, float* stats, double* partial) {
-  const int ns = pick_bn_splits(seg, C);
-  hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(ns, seg.K, (C + 63) / 64), dim3(256), 0, st, x, nullptr, nullptr,
-                     C, hw, seg, partial);
-  hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3(blocks_for((long)seg.K * C)), dim3(256), 0, st, partial, C, hw, ns,
-                     seg, stats);
-  const long pieces = (long)seg.off[seg.K] * hw * (C / 8);
-  hipLaunchKernelGGL(bn_apply_kernel<false>, dim3(blocks_for(pieces)), dim3(256), 0, st, x, nullptr, stats, nullptr,
-                     gamma, beta, C, hw, pieces, seg, relu ? 1 : 0, y);
+  const ShareTable sp = bn_splits(seg, C);
+  const int groups = (C + 63) / 64;
+  hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(sp.first[seg.K], groups), dim3(256), 0, st, x, nullptr, nullptr,
+                     C, hw, seg, sp, partial);
+  hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3(seg.K, groups), dim3(256), 0, st, partial, C, hw, seg, sp, stats);
+  const ShareTable ch = bn_chunks(seg, C, hw);
+  hipLaunchKernelGGL(bn_apply_kernel<false>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, nullptr, stats, nullptr,
+                     gamma, beta, C, hw, seg, ch, relu ? 1 : 0, y);
 }
 
 void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
                       const Segments& seg, const float* stats, float* means, double* partial, float* g_gamma,
                       float* g_beta, size_t worker_stride) {
-  const int ns = pick_bn_splits(seg, C);
-  hipLaunchKernelGGL(bn_partial_kernel<true>, dim3(ns, seg.K, (C + 63) / 64), dim3(256), 0, st, x, dy, stats, C, hw,
-                     seg, partial);
-  hipLaunchKernelGGL(bn_finalize_bwd_kernel, dim3(blocks_for((long)seg.K * C)), dim3(256), 0, st, partial, C, hw, ns,
-                     seg, means, g_gamma, g_beta, worker_stride);
-  const long pieces = (long)seg.off[seg.K] * hw * (C / 8);
-  hipLaunchKernelGGL(bn_apply_kernel<true>, dim3(blocks_for(pieces)), dim3(256), 0, st, x, dy, stats, means, gamma,
-                     nullptr, C, hw, pieces, seg, 0, dx);
+  const ShareTable sp = bn_splits(seg, C);
+  const int groups = (C + 63) / 64;
+  hipLaunchKernelGGL(bn_partial_kernel<true>, dim3(sp.first[seg.K], groups), dim3(256), 0, st, x, dy, stats, C, hw,
+                     seg, sp, partial);
+  hipLaunchKernelGGL(bn_finalize_bwd_kernel, dim3(seg.K, groups), dim3(256), 0, st, partial, C, hw, seg, sp, means,
+                     g_gamma, g_beta, worker_stride);
+  const ShareTable ch = bn_chunks(seg, C, hw);
+  hipLaunchKernelGGL(bn_apply_kernel<true>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, dy, stats, means, gamma,
+                     nullptr, C, hw, seg, ch, 0, dx);
 }
 
 void add_fwd_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, bf16_t* out, long elems, bool relu) {

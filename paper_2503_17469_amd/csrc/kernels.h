@@ -89,8 +89,10 @@ void maxpool2_bwd_bf16(hipStream_t st, const bf16_t* in, const bf16_t* dout, bf1
                        int C, bool relu_mask);
 
 // ---- per-worker batch norm, residual add, global average pool (bn.hip) ----
-constexpr int kBnMaxSplits = 64;   // position splits per worker in the statistics reductions
-// stats: [K][C][2] (mean, 1/sqrt(var+eps)); partial: [K][kBnMaxSplits][C][2] doubles of scratch.
+constexpr int kBnMaxSplits = 256;  // statistics scratch holds K * kBnMaxSplits position splits in all
+// stats: [K][C][2] (mean, 1/sqrt(var+eps)); partial: [K * kBnMaxSplits][C][2] doubles of scratch.
+// Channel counts the batch-norm kernels handle: a multiple of 8, at most 2048.
+bool bn_shape_supported(int C);
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
                      const Segments& seg, bool relu, float* stats, double* partial);
 // means: [K][C][2] scratch; g_gamma / g_beta: worker k's entries at + k*worker_stride.

@@ -200,8 +200,8 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
       }
       case OMNI_OP_BN: {
         if (!bf) return bail(fail(OMNI_EINVAL, "layer %d: batch norm is implemented for dtype bf16 only", i));
-        if (L.in0 < 0 || c % 8 || L.d.cin != c)
-          return bail(fail(OMNI_EINVAL, "layer %d: batch norm needs a layer input with channels %% 8 == 0 (got %d, declared %d)", i, c, L.d.cin));
+        if (L.in0 < 0 || !omni::bn_shape_supported(c) || L.d.cin != c)
+          return bail(fail(OMNI_EINVAL, "layer %d: batch norm needs a layer input with channels %% 8 == 0, at most 2048 (got %d, declared %d)", i, c, L.d.cin));
         if (net->tensors[L.in0].relu)
           return bail(fail(OMNI_EINVAL, "layer %d: batch norm directly after a folded ReLU is not supported", i));
         L.out = new_tensor(h, w, c);
