@@ -92,6 +92,18 @@ __device__ inline void decode_pos(const ConvGeom& g, int m, int& n, int& h, int&
   w = r - h * g.Wp;
 }
 
+// the same with explicit extents: m -> (n, h, w) over planes of hw positions, rows of wd
+__device__ inline void decode_pos2(int hw, int wd, int m, int& n, int& h, int& w) {
+  n = (int)((float)m * (1.0f / (float)hw));
+  if (n * hw > m) --n;
+  if ((n + 1) * hw <= m) ++n;
+  const int r = m - n * hw;
+  h = (int)((float)r * (1.0f / (float)wd));
+  if (h * wd > r) --h;
+  if ((h + 1) * wd <= r) ++h;
+  w = r - h * wd;
+}
+
 // ------------------------------------------------------------------ kernel A
 struct ConvParams {
   const bf16_t* src;   // gathered tensor [rows][Hs][Ws][Cs]
@@ -114,10 +126,17 @@ struct ConvParams {
 //     image" mask, and a piece address is two adds;
 //   * the output tile is staged through LDS as fp32 and leaves as 16-byte pieces
 //     (bias, ReLU, mask, accumulate applied there).
+//   * PHASED (dgrad of a stride-2 convolution, channels a multiple of 64): an input
+//     position (h, w) only meets the filter taps whose parity matches (h+pad-u and
+//     w+pad-v even), a quarter of a 3x3 filter on average.  Rows are enumerated
+//     parity class by parity class (each class padded to whole tiles), so the set
+//     of live taps is uniform over a workgroup and dead taps are never multiplied.
 constexpr int BK2 = 64;
+enum { GEN = 0, FASTM = 1, PHASED = 2 };
 
-template <int TN, bool FAST>
+template <int TN, int MODE>
 __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
+  constexpr bool FAST = MODE != GEN;
   constexpr int BN = 64 * TN;
   constexpr int NB = 2 * TN;                 // right-operand pieces per thread per slab
   constexpr int kRow = BK2 + 8;              // 144-byte rows: 16-byte reads, rows 4 banks apart
@@ -129,13 +148,39 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
   auto sA = [&](int s) { return lds + s * (kA + kB); };
   auto sB = [&](int s) { return lds + s * (kA + kB) + kA; };
 
+  __shared__ int outrow[BM];   // PHASED: output row of every tile row (-1: none)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_n = (p.N + BN - 1) / BN;
   const int tile_m = blockIdx.x / tiles_n, tile_n = blockIdx.x % tiles_n;
-  const int row0 = tile_m * BM, col0 = tile_n * BN;
+  const int col0 = tile_n * BN;
   const int wrow = (wave >> 1) * 64, wcol = (wave & 1) * 32 * TN;
   const ConvGeom g = p.g;
   const int kc = tid & 7, rbase = tid >> 3;   // piece within a slab; rows rbase + 32*i
+
+  // PHASED: this tile's parity class, its rows within the class, its live taps
+  int row0 = tile_m * BM;
+  int cls_size = 0, ph = 0, pw = 0, H2 = 1, W2 = 1;
+  int u0 = 0, v0 = 0, nv = 1, nlive = 0;   // live taps: u = u0 + 2i, v = v0 + 2j, enumerated i-major
+  if (MODE == PHASED) {
+    H2 = g.Hp >> 1; W2 = g.Wp >> 1;
+    cls_size = g.rows * H2 * W2;
+    const int tiles_per_class = (cls_size + BM - 1) / BM;
+    const int cls = tile_m / tiles_per_class;
+    row0 = (tile_m - cls * tiles_per_class) * BM;   // first row within the class
+    ph = cls >> 1; pw = cls & 1;
+    u0 = (ph + g.pad) & 1; v0 = (pw + g.pad) & 1;
+    const int nu = u0 < g.ks ? (g.ks - u0 + 1) >> 1 : 0;
+    nv = v0 < g.ks ? (g.ks - v0 + 1) >> 1 : 0;
+    nlive = nu * nv;
+    if (nv == 0) nv = 1;
+  }
+  // t-th live tap -> filter tap (u, v) and source displacement (du, dv) in the half-resolution grid
+  auto live_tap = [&](int t, int& u, int& v, int& du, int& dv) {
+    const int i = t / nv, j = t - i * nv;
+    u = u0 + 2 * i; v = v0 + 2 * j;
+    du = (ph + g.pad - u) >> 1;   // arithmetic shift: -2 -> -1
+    dv = (pw + g.pad - v) >> 1;
+  };
 
   if (!FAST) build_tap_table(tab, g, tid);
 
@@ -147,14 +192,25 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
     const int m = row0 + rbase + 32 * i;
-    const bool ok = m < p.M;
+    const bool ok = MODE == PHASED ? m < cls_size : m < p.M;
     arow_ok |= (ok ? 1u : 0u) << i;
     int n, h, w;
-    decode_pos(g, ok ? m : 0, n, h, w);
+    if (MODE == PHASED) decode_pos2(H2 * W2, W2, ok ? m : 0, n, h, w);
+    else decode_pos(g, ok ? m : 0, n, h, w);
     an[i] = n; ah[i] = h; aw[i] = w;
     rowbase[i] = 0;
     tapmask[i] = 0;
-    if (FAST) {
+    if (MODE == PHASED) {
+      // (h, w) are the half-resolution coordinates: the output position is (2h+ph, 2w+pw)
+      rowbase[i] = (((long)n * g.Hs + h) * g.Ws + w) * g.Cs + kc * 8;
+      for (int t = 0; t < nlive; ++t) {
+        int u, v, du, dv;
+        live_tap(t, u, v, du, dv);
+        const int hs = h + du, ws = w + dv;
+        const bool in = ok && hs >= 0 && hs < g.Hs && ws >= 0 && ws < g.Ws;
+        tapmask[i] |= (in ? 1u : 0u) << t;
+      }
+    } else if (FAST) {
       const int hb = g.transposed ? h + g.pad : h * g.stride - g.pad;
       const int wb = g.transposed ? w + g.pad : w * g.stride - g.pad;
       rowbase[i] = (((long)n * g.Hs + hb) * g.Ws + wb) * g.Cs + kc * 8;
@@ -175,7 +231,13 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
     brow[i] = (long)r * g.K + kc * 8;
     brow_ok |= (r < p.N ? 1u : 0u) << i;
   }
-  if (!FAST) __syncthreads();   // tap table ready
+  if (MODE == PHASED && tid < BM) {
+    const int m = row0 + tid;
+    int n, h, w;
+    decode_pos2(H2 * W2, W2, m < cls_size ? m : 0, n, h, w);
+    outrow[tid] = m < cls_size ? (n * g.Hp + 2 * h + ph) * g.Wp + 2 * w + pw : -1;
+  }
+  if (!FAST || MODE == PHASED) __syncthreads();   // tap table / row map ready
 
   v16f acc[2][TN];
 #pragma unroll
@@ -192,8 +254,15 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
   auto load_slab = [&](int k0, int tap_, int cb_) {
     ok = 0;
     if (FAST) {
-      const int u = tap_ / g.ks, v = tap_ - u * g.ks;
-      const long tapoff = (g.transposed ? -1L : 1L) * ((long)u * g.Ws + v) * g.Cs + cb_;
+      long tapoff;
+      if (MODE == PHASED) {
+        int u, v, du, dv;
+        live_tap(tap_, u, v, du, dv);   // tap_ counts the live taps
+        tapoff = ((long)du * g.Ws + dv) * g.Cs + cb_;
+      } else {
+        const int u = tap_ / g.ks, v = tap_ - u * g.ks;
+        tapoff = (g.transposed ? -1L : 1L) * ((long)u * g.Ws + v) * g.Cs + cb_;
+      }
       const bool kin = k0 < g.K;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
@@ -234,8 +303,16 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
     if (cb >= g.Cs) { cb = 0; ++tap; }
   };
 
-  const int nslab = (g.K + BK2 - 1) / BK2;
-  load_slab(0, 0, 0);
+  const int nslab = MODE == PHASED ? nlive * (g.Cs / BK2) : (g.K + BK2 - 1) / BK2;
+  // first reduction element of a slab (the right operand's column); g.K = none
+  auto slab_k0 = [&](int s_, int tap_, int cb_) {
+    if (s_ >= nslab) return g.K;
+    if (MODE != PHASED) return s_ * BK2;
+    int u, v, du, dv;
+    live_tap(tap_, u, v, du, dv);
+    return (u * g.ks + v) * g.Cs + cb_;
+  };
+  load_slab(slab_k0(0, 0, 0), 0, 0);
 #pragma unroll
   for (int i = 0; i < 4; ++i) store_a(0, i);
 #pragma unroll
@@ -246,7 +323,7 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
     if (FAST) advance();
     // always issued (past the end it re-reads element 0 and is dropped): a load
     // issued on one path only would make every later wait drain the queue
-    load_slab(s + 1 < nslab ? (s + 1) * BK2 : g.K, s + 1 < nslab ? tap : 0, cb);
+    load_slab(slab_k0(s + 1, tap, cb), s + 1 < nslab ? tap : 0, cb);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < BK2 / 16; ++ks) {
@@ -297,8 +374,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
   for (int it = 0; it < BM * kPiecesPerRow / kThreads; ++it) {
     const int c = tid + kThreads * it;
     const int il = c / kPiecesPerRow, jl = (c % kPiecesPerRow) * 8;
-    const int i = row0 + il, j = col0 + jl;
-    if (i >= p.M || j >= p.N) continue;      // N is a multiple of 8: a piece is wholly inside or outside
+    const int i = MODE == PHASED ? outrow[il] : row0 + il, j = col0 + jl;
+    if (i < 0 || i >= p.M || j >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
     float v[8];
     const v4f lo = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl);
     const v4f hi = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl + 4);
@@ -848,17 +925,18 @@ bool conv_shape_supported(const ConvGeom& g, long positions) {
   return g.Cs % 8 == 0 && g.K <= kMaxPieces * 8 && g.ks >= 1 && g.ks <= 15 && positions < (1L << 24);
 }
 
-template <int TN, bool FAST>
+template <int TN, int MODE>
 static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
   constexpr int BN = 64 * TN;
-  constexpr size_t kBytes = (size_t)2 * (BM + BN) * (BK2 + 8) * sizeof(bf16_t) + (FAST ? 0 : kMaxPieces * sizeof(int));
+  constexpr size_t kBytes =
+      (size_t)2 * (BM + BN) * (BK2 + 8) * sizeof(bf16_t) + (MODE != GEN ? 0 : kMaxPieces * sizeof(int));
   static bool configured = false;   // raising the dynamic LDS limit is a per-function, one-time host call
   if (!configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gemm2_kernel<TN, FAST>),
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv_gemm2_kernel<TN, MODE>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBytes);
     configured = true;
   }
-  hipLaunchKernelGGL((conv_gemm2_kernel<TN, FAST>), dim3(tiles), dim3(kThreads), kBytes, st, p);
+  hipLaunchKernelGGL((conv_gemm2_kernel<TN, MODE>), dim3(tiles), dim3(kThreads), kBytes, st, p);
 }
 
 void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
@@ -866,15 +944,26 @@ void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
-  const int tiles_m = (M + BM - 1) / BM;
-  const bool fast = g.Cs % BK2 == 0 && g.ks <= 3 && (!g.transposed || g.stride == 1);
-  if (N > 64) {
-    const int tiles = tiles_m * ((N + 127) / 128);
-    if (fast) launch_gemm2<2, true>(st, p, tiles); else launch_gemm2<2, false>(st, p, tiles);
-  } else {
-    const int tiles = tiles_m * ((N + 63) / 64);
-    if (fast) launch_gemm2<1, true>(st, p, tiles); else launch_gemm2<1, false>(st, p, tiles);
+  int tiles_m = (M + BM - 1) / BM;
+  const bool chan_ok = g.Cs % BK2 == 0 && g.ks <= 3;
+  const bool fast = chan_ok && (!g.transposed || g.stride == 1);
+  // dgrad of a stride-2 convolution: the gathered tensor is the half-resolution output gradient
+  const bool phased = chan_ok && g.transposed && g.stride == 2 && g.Hp % 2 == 0 && g.Wp % 2 == 0 &&
+                      g.Hs == g.Hp / 2 && g.Ws == g.Wp / 2 && (long)g.rows * g.Hp * g.Wp == M;
+  if (phased) {
+    const long cls = (long)g.rows * (g.Hp / 2) * (g.Wp / 2);
+    tiles_m = 4 * (int)((cls + BM - 1) / BM);   // every parity class is padded to whole tiles
   }
+  const int mode = phased ? PHASED : fast ? FASTM : GEN;
+  const int tiles = tiles_m * (N > 64 ? (N + 127) / 128 : (N + 63) / 64);
+#define OMNI_GEMM2(TN)                                           \
+  {                                                              \
+    if (mode == PHASED) launch_gemm2<TN, PHASED>(st, p, tiles);  \
+    else if (mode == FASTM) launch_gemm2<TN, FASTM>(st, p, tiles); \
+    else launch_gemm2<TN, GEN>(st, p, tiles);                    \
+  }
+  if (N > 64) OMNI_GEMM2(2) else OMNI_GEMM2(1)
+#undef OMNI_GEMM2
 }
 
 // 3x3 / stride 1 / pad 1 with at least 32 stored channels and a map whose rows
