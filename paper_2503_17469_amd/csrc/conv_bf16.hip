@@ -398,6 +398,228 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
   }
 }
 
+// ------------------------------------------------------------------ kernel D
+// Forward and stride-1 dgrad of 3x3 / pad-1 convolutions with a channel count that
+// is a multiple of 64 (most of a residual net).  Kernel A gathers the left operand
+// once per filter tap: nine global loads, nine LDS stores of every input element.
+// Here a workgroup owns 256 output positions (a strip of rows of one image, or a few
+// whole small images) x 64 output channels:
+//   * the input patch of those positions, halo included, is staged in LDS once per
+//     64-channel slice ([patch position][64 channels], 144-byte rows);
+//   * the left operand of tap (u, v) is that patch read at a row offset: no data
+//     moves between taps, only the 8 KB weight slab of the tap streams through LDS
+//     (double buffered, prefetched to registers);
+//   * each wavefront owns 64 positions x 64 channels (2 x 2 accumulator blocks).
+// For dgrad the gathered tensor is dY, the weights are the transposed copy and the
+// taps are mirrored (dX(p) meets tap (u, v) at p + (1-u, 1-v)).
+struct Conv3Params {
+  const bf16_t* src;   // [rows][H][W][Cs]
+  const bf16_t* wgt;   // [N][9][Cs]
+  bf16_t* out;         // [rows*H*W][N]
+  int rows, H, W, Cs, N;
+  int R, nimg;         // a unit is nimg images x R rows; nimg * R * W = 256
+  int flip;            // 1: dgrad (mirrored taps)
+  const float* bias;
+  const bf16_t* mask;
+  int relu, accumulate;
+};
+constexpr int kUnitD = 256;
+constexpr int kRowD = 64 + 8;   // elements per LDS row (144 bytes): 16-byte reads land 4 banks apart
+constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread (up to 416 patch positions)
+
+// MULTI: more than one 64-channel slice (the patch is re-staged per slice).
+template <bool MULTI>
+__global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smemD[];
+  const int W = p.W, H = p.H, R = p.R;
+  const int PW = W + 2, PR = R + 2;
+  const int npatch = p.nimg * PR * PW;                    // patch positions
+  bf16_t* sP = reinterpret_cast<bf16_t*>(smemD);          // [npatch][kRowD]
+  bf16_t* sW = sP + (size_t)npatch * kRowD;               // 2 x [64][kRowD]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 31, h = lane >> 5;
+  const int tiles_n = (p.N + 63) / 64;
+  const int unit = blockIdx.x / tiles_n, tile_n = blockIdx.x - unit * tiles_n;
+  const int col0 = tile_n * 64;
+  const int K = 9 * p.Cs;
+
+  // ---- the unit: first image, first row, images present
+  int n0, r0, nvalid;
+  if (p.nimg == 1) {
+    const int upi = H / R, img = unit / upi;
+    n0 = img; r0 = (unit - img * upi) * R; nvalid = 1;
+  } else {
+    n0 = unit * p.nimg; r0 = 0; nvalid = min(p.nimg, p.rows - n0);
+  }
+  const long out_base = ((long)n0 * H + r0) * W;           // the unit's positions are contiguous rows of `out`
+  const int npos = nvalid * R * W;                         // live positions of this unit
+
+  // ---- patch staging tasks: piece x = tid + 256 t -> patch position x / 8, channel octet x % 8
+  int poff[kMaxPatchPieces];   // element offsets (the host checks the tensor has fewer than 2^31)
+  uint32_t pvalid = 0;
+  const int npieces = npatch * 8;
+#pragma unroll
+  for (int t = 0; t < kMaxPatchPieces; ++t) {
+    const int x = tid + t * kThreads;
+    const int pp = min(x, npieces - 1) >> 3, oct = x & 7;
+    const int il = pp / (PR * PW), rem = pp - il * (PR * PW);
+    const int pr = rem / PW, pc = rem - pr * PW;
+    const int row = r0 + pr - 1, col = pc - 1;
+    const bool in = x < npieces && il < nvalid && row >= 0 && row < H && col >= 0 && col < W;
+    poff[t] = in ? ((((n0 + il) * H + row) * W + col) * p.Cs + oct * 8) : 0;
+    pvalid |= (in ? 1u : 0u) << t;
+  }
+  // ---- weight staging: rows tid/8 and tid/8 + 32 of the 64-channel tile, octet tid % 8
+  const int wr = tid >> 3, woct = tid & 7;
+  long woff[2];
+  uint32_t wvalid = 0;
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = col0 + wr + 32 * i;
+    const bool in = r < p.N;
+    woff[i] = in ? (long)r * K + woct * 8 : 0;
+    wvalid |= (in ? 1u : 0u) << i;
+  }
+  // ---- fragment addresses: this wavefront's positions wave*64 + a*32 + j
+  int pbase[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int pos = wave * 64 + a * 32 + j;
+    const int rr = pos / W, w = pos - rr * W;
+    const int il = rr / R, r = rr - il * R;
+    pbase[a] = ((il * PR + r) * PW + w) * kRowD + h * 8;   // patch origin is (-1, -1): tap (u, v) adds u*PW + v
+  }
+  const int bfrag = j * kRowD + h * 8;
+
+  v16f acc[2][2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  const u32x4 zero = {0u, 0u, 0u, 0u};
+  u32x4 rp[kMaxPatchPieces], rw[2];
+  // loads are unconditional: an absent piece re-reads element 0 and is zeroed when stored
+  auto load_patch = [&](int cs) {
+#pragma unroll
+    for (int t = 0; t < kMaxPatchPieces; ++t) {
+      const int m = -(int)((pvalid >> t) & 1u);
+      rp[t] = *reinterpret_cast<const u32x4*>(p.src + ((poff[t] + cs * 64) & m));
+    }
+  };
+  auto store_patch = [&]() {
+#pragma unroll
+    for (int t = 0; t < kMaxPatchPieces; ++t) {
+      const int x = tid + t * kThreads;
+      if (x < npieces)
+        *reinterpret_cast<u32x4*>(sP + (x >> 3) * kRowD + (x & 7) * 8) = ((pvalid >> t) & 1u) ? rp[t] : zero;
+    }
+  };
+  auto load_w = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const long m = -(long)((wvalid >> i) & 1u);
+      rw[i] = *reinterpret_cast<const u32x4*>(p.wgt + ((woff[i] + k0) & m));
+    }
+  };
+  auto store_w = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+      *reinterpret_cast<u32x4*>(sW + buf * 64 * kRowD + (wr + 32 * i) * kRowD + woct * 8) =
+          ((wvalid >> i) & 1u) ? rw[i] : zero;
+  };
+
+  const int nslice = MULTI ? p.Cs / 64 : 1;
+  load_patch(0);
+  load_w(0);
+  store_patch();
+  store_w(0);
+  __syncthreads();
+  for (int cs = 0; cs < nslice; ++cs) {
+#pragma unroll
+    for (int tap = 0; tap < 9; ++tap) {
+      const int cur = tap & 1 ? 1 - (cs & 1) : (cs & 1);   // step cs*9 + tap, odd/even (9 taps per slice)
+      const int u = tap / 3, v = tap - u * 3;
+      // next step's weights (always issued; past the end it re-reads the last slab)
+      if (tap < 8) load_w((tap + 1) * p.Cs + cs * 64);
+      else load_w(min(cs + 1, nslice - 1) * 64);
+      // the next slice's patch starts its way to registers a few taps before it is needed
+      if (MULTI && tap == 4) load_patch(min(cs + 1, nslice - 1));
+      const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRowD;
+      const bf16_t* wb = sW + cur * 64 * kRowD + bfrag;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        bf16x8 fa[2], fb[2];
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+          fa[a] = as_bf16x8(*reinterpret_cast<const u32x4*>(sP + pbase[a] + toff + kk * 16));
+#pragma unroll
+        for (int b = 0; b < 2; ++b)
+          fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(wb + b * 32 * kRowD + kk * 16));
+#pragma unroll
+        for (int a = 0; a < 2; ++a)
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+      }
+      store_w(cur ^ 1);
+      __syncthreads();
+      if (MULTI && tap == 8) {
+        store_patch();       // every wavefront is past its last read of the old slice
+        __syncthreads();
+      }
+    }
+  }
+
+  // ---- output tile -> LDS (fp32) -> 16-byte pieces (the staging area is free: the loop ended with a barrier)
+  constexpr int kOutPitch = 64 + 4;
+  float* so = reinterpret_cast<float*>(smemD);
+#pragma unroll
+  for (int b = 0; b < 2; ++b) {
+    const int jl = b * 32 + j;
+    const int c = col0 + jl;
+    const float bj = (p.bias && c < p.N) ? p.bias[c] : 0.f;
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int il = wave * 64 + a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+        float val = acc[a][b][v] + bj;
+        if (p.relu) val = val > 0.f ? val : 0.f;
+        so[il * kOutPitch + jl] = val;
+      }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int it = 0; it < kUnitD * 8 / kThreads; ++it) {
+    const int c = tid + kThreads * it;
+    const int il = c >> 3, jl = (c & 7) * 8;
+    const int jg = col0 + jl;
+    if (il >= npos || jg >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
+    float v[8];
+    const v4f lo = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl);
+    const v4f hi = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl + 4);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+    const size_t idx = (size_t)(out_base + il) * p.N + jg;
+    if (p.mask) {
+      float mv[8];
+      Piece<bf16_t>::load(p.mask + idx, mv);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] = mv[e] > 0.f ? v[e] : 0.f;
+    }
+    if (p.accumulate) {
+      float ov[8];
+      Piece<bf16_t>::load(p.out + idx, ov);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += ov[e];
+    }
+    Piece<bf16_t>::store(p.out + idx, v);
+  }
+}
+
 // ------------------------------------------------------------------ kernel B
 struct WgradParams {
   const bf16_t* dy;    // [positions][Cout]
@@ -939,8 +1161,47 @@ static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
   hipLaunchKernelGGL((conv_gemm2_kernel<TN, MODE>), dim3(tiles), dim3(kThreads), kBytes, st, p);
 }
 
+// 3x3 / pad 1 / stride 1 (forward, or dgrad of such a layer) with channels a multiple of 64 and a
+// map whose rows tile into units of 256 positions: kernel D.  Returns false if the shape does not qualify.
+static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                       const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
+  const int H = g.Hs, W = g.Ws;
+  if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
+  if (g.Cs % 64 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
+  if ((long)M * g.Cs >= (1L << 31)) return false;   // 32-bit element offsets in the kernel
+  if (W < 8 || W > kUnitD || kUnitD % W != 0) return false;
+  const int R = std::min(H, kUnitD / W);
+  if (H % R != 0 || kUnitD % (R * W) != 0) return false;
+  const int nimg = kUnitD / (R * W);
+  if (nimg > 1 && R != H) return false;
+  const int npatch = nimg * (R + 2) * (W + 2);
+  if (npatch * 8 > kMaxPatchPieces * kThreads) return false;
+  Conv3Params p{};
+  p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
+  p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0;
+  p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
+  const size_t stage = ((size_t)npatch + 2 * 64) * kRowD * sizeof(bf16_t);
+  const size_t outt = (size_t)kUnitD * (64 + 4) * sizeof(float);
+  const size_t lds = std::max(stage, outt);
+  if (lds > 80 * 1024) return false;
+  static size_t configured[2] = {0, 0};
+  const int multi = g.Cs > 64 ? 1 : 0;
+  if (lds > configured[multi]) {
+    const void* fn = multi ? reinterpret_cast<const void*>(&conv3_gemm_kernel<true>)
+                           : reinterpret_cast<const void*>(&conv3_gemm_kernel<false>);
+    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured[multi] = lds;
+  }
+  const int units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
+  const dim3 grid(units * ((N + 63) / 64));
+  if (multi) hipLaunchKernelGGL(conv3_gemm_kernel<true>, grid, dim3(kThreads), lds, st, p);
+  else hipLaunchKernelGGL(conv3_gemm_kernel<false>, grid, dim3(kThreads), lds, st, p);
+  return true;
+}
+
 void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
+  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate)) return;
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
