@@ -909,6 +909,19 @@ constexpr int kTile3Stride = kTile3Floats + 64;
 
 // four positions x eight channels (c[q] = the 16-byte piece of position q) -> eight
 // channel rows of four positions each
+// the same for a destination that is only 4-byte aligned
+__device__ inline void transpose_store32(const u32x4 c[4], unsigned char* dst, int row_bytes) {
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    uint32_t* lo = reinterpret_cast<uint32_t*>(dst + (2 * d) * row_bytes);
+    uint32_t* hi = reinterpret_cast<uint32_t*>(dst + (2 * d + 1) * row_bytes);
+    lo[0] = (c[0][d] & 0xFFFFu) | (c[1][d] << 16);
+    lo[1] = (c[2][d] & 0xFFFFu) | (c[3][d] << 16);
+    hi[0] = (c[0][d] >> 16) | (c[1][d] & 0xFFFF0000u);
+    hi[1] = (c[2][d] >> 16) | (c[3][d] & 0xFFFF0000u);
+  }
+}
+
 __device__ inline void transpose_store(const u32x4 c[4], unsigned char* dst, int row_bytes) {
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
@@ -922,6 +935,9 @@ __device__ inline void transpose_store(const u32x4 c[4], unsigned char* dst, int
   }
 }
 
+// W4: maps four columns wide (a patch row is 8 elements = one 16-byte read, data in columns 2-5;
+// a group of 8 reduction positions is two image rows).
+template <bool W4>
 __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p, Segments seg, ChunkTable ct) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem3[];
   unsigned char* sA = smem3;                 // dY^T: 64 rows of kSA bytes
@@ -973,7 +989,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     x_il[t] = pr / (R + 2);
     x_rr[t] = pr - x_il[t] * (R + 2);                       // input row = first row + x_rr - 1
     x_rel[t] = ((x_il[t] * H + x_rr[t] - 1) * W + 4 * wg) * p.Cin + 8 * oct;
-    x_dst[t] = (8 * oct) * p.SX + (pr * p.Wp + 4 * wg + 8) * 2;
+    x_dst[t] = (8 * oct) * p.SX + (pr * p.Wp + 4 * wg + (W4 ? 2 : 8)) * 2;
     x_task[t] = x_task[t] && ci0 + 8 * oct < p.Cin;
   }
 
@@ -983,7 +999,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
   for (int ks = 0; ks < kUnit / 16; ++ks) {
     const int pos = (2 * ks + h) * 8, rr = pos / W, w0 = pos - rr * W;
     const int il = rr / R;
-    offB[ks] = ((il * (R + 2) + (rr - il * R)) * p.Wp + w0 + 8) * 2;
+    offB[ks] = ((il * (R + 2) + (rr - il * R)) * p.Wp + (W4 ? 0 : w0 + 8)) * 2;
   }
   const unsigned char* a_frag = sA + (wco + j) * kSA + h * 16;
   const unsigned char* x_frag = sX + (wci + j) * p.SX;
@@ -1043,7 +1059,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
       if (tid + t * kThreads >= ntasks) continue;   // no such patch piece (not a matter of validity)
 #pragma unroll
       for (int q = 0; q < 4; ++q) c[q] = ((ok >> (4 + t)) & 1u) ? rx[t][q] : zero;
-      transpose_store(c, sX + x_dst[t], p.SX);
+      if (W4) transpose_store32(c, sX + x_dst[t], p.SX);
+      else transpose_store(c, sX + x_dst[t], p.SX);
     }
   };
 
@@ -1056,6 +1073,28 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
 #pragma unroll
     for (int ks = 0; ks < kUnit / 16; ++ks) {
       const bf16x8 fa = as_bf16x8(*reinterpret_cast<const u32x4*>(a_frag + ks * 32));
+      if constexpr (W4) {
+        // patch rows r .. r+3 of this lane's image (16 bytes each) serve all nine taps
+        u32x4 row[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) row[i] = *reinterpret_cast<const u32x4*>(x_frag + offB[ks] + i * row_shift);
+        uint32_t lf[4][2], rt[4][2];   // columns 1-4 and 3-6 of every row
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const uint32_t m21 = __builtin_amdgcn_alignbit(row[i][2], row[i][1], 16);
+          lf[i][0] = __builtin_amdgcn_alignbit(row[i][1], row[i][0], 16); lf[i][1] = m21;
+          rt[i][0] = m21; rt[i][1] = __builtin_amdgcn_alignbit(row[i][3], row[i][2], 16);
+        }
+#pragma unroll
+        for (int du = 0; du < 3; ++du) {
+          const u32x4 left = {lf[du][0], lf[du][1], lf[du + 1][0], lf[du + 1][1]};
+          const u32x4 mid = {row[du][1], row[du][2], row[du + 1][1], row[du + 1][2]};
+          const u32x4 right = {rt[du][0], rt[du][1], rt[du + 1][0], rt[du + 1][1]};
+          acc[du * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(left), acc[du * 3 + 0], 0, 0, 0);
+          acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(mid), acc[du * 3 + 1], 0, 0, 0);
+          acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
+        }
+      } else {
 #pragma unroll
       for (int du = 0; du < 3; ++du) {
         const unsigned char* xb = x_frag + offB[ks] + du * row_shift;
@@ -1070,6 +1109,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
         acc[du * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(left), acc[du * 3 + 0], 0, 0, 0);
         acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(q), acc[du * 3 + 1], 0, 0, 0);
         acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
+      }
       }
     }
     if (want_bias && tid < 64) {
@@ -1235,7 +1275,8 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   const int H = g.Hs, W = g.Ws;
   if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.transposed || g.Hp != H || g.Wp != W) return false;
   if (cin_real != g.Cs || g.Cs < 32 || g.Cs % 8 != 0 || Cout % 8 != 0) return false;
-  if (W % 8 != 0 || W > kUnit || kUnit % W != 0) return false;
+  const bool w4 = W == 4 && H == 4;
+  if (!w4 && (W % 8 != 0 || W > kUnit || kUnit % W != 0)) return false;
   const int R = std::min(H, kUnit / W);
   if (H % R != 0 || kUnit % (R * W) != 0) return false;
   const int nimg = kUnit / (R * W);
@@ -1243,7 +1284,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   Wgrad3Params p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
   p.Cout = Cout; p.Cin = g.Cs; p.H = H; p.W = W; p.R = R; p.nimg = nimg;
-  p.Wp = W + 16; p.prows = nimg * (R + 2);
+  p.Wp = w4 ? 8 : W + 16; p.prows = nimg * (R + 2);
   // channel stride of X^T in 4-byte words must be 4 mod 8: 16 lanes x 16 bytes then cover all 64 banks
   int words = p.prows * p.Wp / 2;
   words += (4 - words % 8 + 8) % 8;
@@ -1277,13 +1318,16 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
     upc += std::max<long>(1, upc / 16);
   }
   p.upc = (int)upc;
-  static size_t configured = 0;   // raising the dynamic LDS limit is a per-function host call
-  if (lds > configured) {
-    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_wgrad_kernel),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured = lds;
+  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
+  if (lds > configured[w4]) {
+    const void* fn = w4 ? reinterpret_cast<const void*>(&conv3_wgrad_kernel<true>)
+                        : reinterpret_cast<const void*>(&conv3_wgrad_kernel<false>);
+    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured[w4] = lds;
   }
-  hipLaunchKernelGGL(conv3_wgrad_kernel, dim3(tiles, ct.first[seg.K]), dim3(kThreads), lds, st, p, seg, ct);
+  const dim3 grid(tiles, ct.first[seg.K]);
+  if (w4) hipLaunchKernelGGL(conv3_wgrad_kernel<true>, grid, dim3(kThreads), lds, st, p, seg, ct);
+  else hipLaunchKernelGGL(conv3_wgrad_kernel<false>, grid, dim3(kThreads), lds, st, p, seg, ct);
   bool chunked = false;
   for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
   if (chunked)
