@@ -418,6 +418,7 @@ struct Conv3Params {
   bf16_t* out;         // [rows*H*W][N]
   int rows, H, W, Cs, N;
   int R, nimg;         // a unit is nimg images x R rows; nimg * R * W = 256
+  int units, upw;      // units in all, units per workgroup
   int flip;            // 1: dgrad (mirrored taps)
   const float* bias;
   const bf16_t* mask;
@@ -428,7 +429,10 @@ constexpr int kRowD = 64 + 8;   // elements per LDS row (144 bytes): 16-byte rea
 constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread (up to 416 patch positions)
 
 // MULTI: more than one 64-channel slice (the patch is re-staged per slice).
-template <bool MULTI>
+// A workgroup walks `upw` consecutive units of one channel tile: the next unit's patch
+// and first weight slab travel to registers during the last taps of the current one,
+// so only the first unit of a workgroup waits for memory before it can multiply.
+template <bool MULTI, int NP>   // NP: 16-byte patch pieces per thread
 __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smemD[];
   const int W = p.W, H = p.H, R = p.R;
@@ -439,35 +443,28 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 31, h = lane >> 5;
   const int tiles_n = (p.N + 63) / 64;
-  const int unit = blockIdx.x / tiles_n, tile_n = blockIdx.x - unit * tiles_n;
+  const int group = blockIdx.x / tiles_n, tile_n = blockIdx.x - group * tiles_n;
   const int col0 = tile_n * 64;
   const int K = 9 * p.Cs;
+  const int ubeg = group * p.upw, uend = min(p.units, ubeg + p.upw);
 
-  // ---- the unit: first image, first row, images present
-  int n0, r0, nvalid;
-  if (p.nimg == 1) {
-    const int upi = H / R, img = unit / upi;
-    n0 = img; r0 = (unit - img * upi) * R; nvalid = 1;
-  } else {
-    n0 = unit * p.nimg; r0 = 0; nvalid = min(p.nimg, p.rows - n0);
-  }
-  const long out_base = ((long)n0 * H + r0) * W;           // the unit's positions are contiguous rows of `out`
-  const int npos = nvalid * R * W;                         // live positions of this unit
-
-  // ---- patch staging tasks: piece x = tid + 256 t -> patch position x / 8, channel octet x % 8
-  int poff[kMaxPatchPieces];   // element offsets (the host checks the tensor has fewer than 2^31)
-  uint32_t pvalid = 0;
+  // ---- patch staging tasks: piece x = tid + 256 t -> patch position x / 8, channel octet x % 8.
+  // Relative to the unit's first image and row; which pieces exist depends on the unit.
+  int prel[NP];                // element offset relative to the unit (the host checks the tensor has fewer than 2^31)
+  uint32_t col_ok = 0, top = 0, bottom = 0;   // piece t: inside the image's columns / in the first / last patch row
+  uint64_t img4 = 0;                           // piece t: image within the unit, 4 bits each
   const int npieces = npatch * 8;
 #pragma unroll
-  for (int t = 0; t < kMaxPatchPieces; ++t) {
+  for (int t = 0; t < NP; ++t) {
     const int x = tid + t * kThreads;
     const int pp = min(x, npieces - 1) >> 3, oct = x & 7;
     const int il = pp / (PR * PW), rem = pp - il * (PR * PW);
     const int pr = rem / PW, pc = rem - pr * PW;
-    const int row = r0 + pr - 1, col = pc - 1;
-    const bool in = x < npieces && il < nvalid && row >= 0 && row < H && col >= 0 && col < W;
-    poff[t] = in ? ((((n0 + il) * H + row) * W + col) * p.Cs + oct * 8) : 0;
-    pvalid |= (in ? 1u : 0u) << t;
+    prel[t] = ((il * H + pr - 1) * W + pc - 1) * p.Cs + oct * 8;
+    col_ok |= (x < npieces && pc >= 1 && pc <= W ? 1u : 0u) << t;
+    top |= (pr == 0 ? 1u : 0u) << t;
+    bottom |= (pr == PR - 1 ? 1u : 0u) << t;
+    img4 |= (uint64_t)il << (4 * t);
   }
   // ---- weight staging: rows tid/8 and tid/8 + 32 of the 64-channel tile, octet tid % 8
   const int wr = tid >> 3, woct = tid & 7;
@@ -491,27 +488,36 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   }
   const int bfrag = j * kRowD + h * 8;
 
-  v16f acc[2][2];
-#pragma unroll
-  for (int a = 0; a < 2; ++a)
-#pragma unroll
-    for (int b = 0; b < 2; ++b)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
-
   const u32x4 zero = {0u, 0u, 0u, 0u};
-  u32x4 rp[kMaxPatchPieces], rw[2];
+  u32x4 rp[NP], rw[2];
+  uint32_t pvalid = 0;
+  // unit -> first image, first row, images present
+  auto unit_geom = [&](int unit, int& n0, int& r0, int& nvalid) {
+    if (p.nimg == 1) {
+      const int upi = H / R, img = unit / upi;
+      n0 = img; r0 = (unit - img * upi) * R; nvalid = 1;
+    } else {
+      n0 = unit * p.nimg; r0 = 0; nvalid = min(p.nimg, p.rows - n0);
+    }
+  };
   // loads are unconditional: an absent piece re-reads element 0 and is zeroed when stored
-  auto load_patch = [&](int cs) {
+  auto load_patch = [&](int unit, int cs) {
+    int n0, r0, nvalid;
+    unit_geom(unit, n0, r0, nvalid);
+    const int ubase = (n0 * H + r0) * W * p.Cs + cs * 64;
+    // the first / last patch row lies outside the image when the unit touches its top / bottom edge
+    pvalid = col_ok & ~(r0 == 0 ? top : 0u) & ~(r0 + R == H ? bottom : 0u);
 #pragma unroll
-    for (int t = 0; t < kMaxPatchPieces; ++t) {
+    for (int t = 0; t < NP; ++t) {
+      const int il = (int)(img4 >> (4 * t)) & 15;
+      if (il >= nvalid) pvalid &= ~(1u << t);
       const int m = -(int)((pvalid >> t) & 1u);
-      rp[t] = *reinterpret_cast<const u32x4*>(p.src + ((poff[t] + cs * 64) & m));
+      rp[t] = *reinterpret_cast<const u32x4*>(p.src + ((ubase + prel[t]) & m));
     }
   };
   auto store_patch = [&]() {
 #pragma unroll
-    for (int t = 0; t < kMaxPatchPieces; ++t) {
+    for (int t = 0; t < NP; ++t) {
       const int x = tid + t * kThreads;
       if (x < npieces)
         *reinterpret_cast<u32x4*>(sP + (x >> 3) * kRowD + (x & 7) * 8) = ((pvalid >> t) & 1u) ? rp[t] : zero;
@@ -532,91 +538,108 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   };
 
   const int nslice = MULTI ? p.Cs / 64 : 1;
-  load_patch(0);
+  load_patch(min(ubeg, p.units - 1), 0);
   load_w(0);
-  store_patch();
-  store_w(0);
-  __syncthreads();
-  for (int cs = 0; cs < nslice; ++cs) {
-#pragma unroll
-    for (int tap = 0; tap < 9; ++tap) {
-      const int cur = tap & 1 ? 1 - (cs & 1) : (cs & 1);   // step cs*9 + tap, odd/even (9 taps per slice)
-      const int u = tap / 3, v = tap - u * 3;
-      // next step's weights (always issued; past the end it re-reads the last slab)
-      if (tap < 8) load_w((tap + 1) * p.Cs + cs * 64);
-      else load_w(min(cs + 1, nslice - 1) * 64);
-      // the next slice's patch starts its way to registers a few taps before it is needed
-      if (MULTI && tap == 4) load_patch(min(cs + 1, nslice - 1));
-      const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRowD;
-      const bf16_t* wb = sW + cur * 64 * kRowD + bfrag;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        bf16x8 fa[2], fb[2];
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-          fa[a] = as_bf16x8(*reinterpret_cast<const u32x4*>(sP + pbase[a] + toff + kk * 16));
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-          fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(wb + b * 32 * kRowD + kk * 16));
-#pragma unroll
-        for (int a = 0; a < 2; ++a)
-#pragma unroll
-          for (int b = 0; b < 2; ++b)
-            acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
-      }
-      store_w(cur ^ 1);
-      __syncthreads();
-      if (MULTI && tap == 8) {
-        store_patch();       // every wavefront is past its last read of the old slice
-        __syncthreads();
-      }
-    }
-  }
-
-  // ---- output tile -> LDS (fp32) -> 16-byte pieces (the staging area is free: the loop ended with a barrier)
-  constexpr int kOutPitch = 64 + 4;
-  float* so = reinterpret_cast<float*>(smemD);
-#pragma unroll
-  for (int b = 0; b < 2; ++b) {
-    const int jl = b * 32 + j;
-    const int c = col0 + jl;
-    const float bj = (p.bias && c < p.N) ? p.bias[c] : 0.f;
+  for (int unit = ubeg; unit < uend; ++unit) {
+    // the unit's first patch slice and first weight slab are in registers
+    store_patch();
+    store_w(0);
+    __syncthreads();
+    v16f acc[2][2];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int il = wave * 64 + a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
-        float val = acc[a][b][v] + bj;
-        if (p.relu) val = val > 0.f ? val : 0.f;
-        so[il * kOutPitch + jl] = val;
+      for (int b = 0; b < 2; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+    for (int cs = 0; cs < nslice; ++cs) {
+      const bool last_slice = cs + 1 == nslice;
+#pragma unroll
+      for (int tap = 0; tap < 9; ++tap) {
+        const int cur = tap & 1 ? 1 - (cs & 1) : (cs & 1);   // step cs*9 + tap, odd/even (9 taps per slice)
+        const int u = tap / 3, v = tap - u * 3;
+        // next step's weights (always issued): next tap, next slice, or the next unit's first slab
+        if (tap < 8) load_w((tap + 1) * p.Cs + cs * 64);
+        else load_w(last_slice ? 0 : (cs + 1) * 64);
+        // the next slice's patch (or the next unit's first) starts its way to registers a few taps early
+        if (tap == 4) load_patch(last_slice ? min(unit + 1, uend - 1) : unit, last_slice ? 0 : cs + 1);
+        const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRowD;
+        const bf16_t* wb = sW + cur * 64 * kRowD + bfrag;
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          bf16x8 fa[2], fb[2];
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+            fa[a] = as_bf16x8(*reinterpret_cast<const u32x4*>(sP + pbase[a] + toff + kk * 16));
+#pragma unroll
+          for (int b = 0; b < 2; ++b)
+            fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(wb + b * 32 * kRowD + kk * 16));
+#pragma unroll
+          for (int a = 0; a < 2; ++a)
+#pragma unroll
+            for (int b = 0; b < 2; ++b)
+              acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+        }
+        if (tap < 8 || !last_slice) store_w(cur ^ 1);
+        __syncthreads();
+        if (MULTI && tap == 8 && !last_slice) {
+          store_patch();       // every wavefront is past its last read of the old slice
+          __syncthreads();
+        }
       }
-  }
-  __syncthreads();
-#pragma unroll
-  for (int it = 0; it < kUnitD * 8 / kThreads; ++it) {
-    const int c = tid + kThreads * it;
-    const int il = c >> 3, jl = (c & 7) * 8;
-    const int jg = col0 + jl;
-    if (il >= npos || jg >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
-    float v[8];
-    const v4f lo = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl);
-    const v4f hi = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl + 4);
-#pragma unroll
-    for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
-    const size_t idx = (size_t)(out_base + il) * p.N + jg;
-    if (p.mask) {
-      float mv[8];
-      Piece<bf16_t>::load(p.mask + idx, mv);
-#pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] = mv[e] > 0.f ? v[e] : 0.f;
     }
-    if (p.accumulate) {
-      float ov[8];
-      Piece<bf16_t>::load(p.out + idx, ov);
+
+    // ---- output tile -> LDS (fp32) -> 16-byte pieces (the staging area is free: the taps ended with a barrier)
+    int n0, r0, nvalid;
+    unit_geom(unit, n0, r0, nvalid);
+    const long out_base = ((long)n0 * H + r0) * W;   // the unit's positions are contiguous rows of `out`
+    const int npos = nvalid * R * W;                 // live positions of this unit
+    constexpr int kOutPitch = 64 + 4;
+    float* so = reinterpret_cast<float*>(smemD);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) v[e] += ov[e];
+    for (int b = 0; b < 2; ++b) {
+      const int jl = b * 32 + j;
+      const int c = col0 + jl;
+      const float bj = (p.bias && c < p.N) ? p.bias[c] : 0.f;
+#pragma unroll
+      for (int a = 0; a < 2; ++a)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int il = wave * 64 + a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+          float val = acc[a][b][v] + bj;
+          if (p.relu) val = val > 0.f ? val : 0.f;
+          so[il * kOutPitch + jl] = val;
+        }
     }
-    Piece<bf16_t>::store(p.out + idx, v);
+    __syncthreads();
+#pragma unroll
+    for (int it = 0; it < kUnitD * 8 / kThreads; ++it) {
+      const int c = tid + kThreads * it;
+      const int il = c >> 3, jl = (c & 7) * 8;
+      const int jg = col0 + jl;
+      if (il >= npos || jg >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
+      float v[8];
+      const v4f lo = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl);
+      const v4f hi = *reinterpret_cast<const v4f*>(so + il * kOutPitch + jl + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
+      const size_t idx = (size_t)(out_base + il) * p.N + jg;
+      if (p.mask) {
+        float mv[8];
+        Piece<bf16_t>::load(p.mask + idx, mv);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = mv[e] > 0.f ? v[e] : 0.f;
+      }
+      if (p.accumulate) {
+        float ov[8];
+        Piece<bf16_t>::load(p.out + idx, ov);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += ov[e];
+      }
+      Piece<bf16_t>::store(p.out + idx, v);
+    }
+    __syncthreads();   // the staging area is about to be refilled
   }
 }
 
@@ -1224,18 +1247,29 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   const size_t outt = (size_t)kUnitD * (64 + 4) * sizeof(float);
   const size_t lds = std::max(stage, outt);
   if (lds > 80 * 1024) return false;
-  static size_t configured[2] = {0, 0};
-  const int multi = g.Cs > 64 ? 1 : 0;
-  if (lds > configured[multi]) {
-    const void* fn = multi ? reinterpret_cast<const void*>(&conv3_gemm_kernel<true>)
-                           : reinterpret_cast<const void*>(&conv3_gemm_kernel<false>);
-    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured[multi] = lds;
-  }
+  const int multi = 1, big = npatch * 8 > 11 * kThreads ? 1 : 0;   // (a single-slice instantiation spilled registers)
   const int units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
-  const dim3 grid(units * ((N + 63) / 64));
-  if (multi) hipLaunchKernelGGL(conv3_gemm_kernel<true>, grid, dim3(kThreads), lds, st, p);
-  else hipLaunchKernelGGL(conv3_gemm_kernel<false>, grid, dim3(kThreads), lds, st, p);
+  const int tiles_n = (N + 63) / 64;
+  // several units per workgroup once there are enough workgroups to fill the chip a few times over
+  int upw = 1;
+  while (upw < 4 && (long)units * tiles_n / (upw * 2) >= 2048) upw *= 2;
+  p.units = units; p.upw = upw;
+  const dim3 grid(((units + upw - 1) / upw) * tiles_n);
+  static size_t configured[4] = {0, 0, 0, 0};
+#define OMNI_CONV3(MULTI_, NP_)                                                                        \
+  {                                                                                                    \
+    if (lds > configured[multi * 2 + big]) {                                                           \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<MULTI_, NP_>),        \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
+      configured[multi * 2 + big] = lds;                                                               \
+    }                                                                                                  \
+    hipLaunchKernelGGL((conv3_gemm_kernel<MULTI_, NP_>), grid, dim3(kThreads), lds, st, p);            \
+  }
+  if (multi && big) OMNI_CONV3(true, 13)
+  else if (multi) OMNI_CONV3(true, 11)
+  else if (big) OMNI_CONV3(false, 13)
+  else OMNI_CONV3(false, 11)
+#undef OMNI_CONV3
   return true;
 }
 
