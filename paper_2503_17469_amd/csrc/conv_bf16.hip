@@ -723,26 +723,26 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
 
   u32x4 r[4];
   uint32_t ok = 0;
+  // Loads never branch and their base pointer is chosen once (a guarded load, or a pointer
+  // re-selected per load, makes the compiler wait for every load before issuing the next):
+  // an absent piece re-reads the tensor's first 16 bytes and is zeroed when stored.
+  const bf16_t* const base = is_a ? p.dy : p.src;
   auto load_slab = [&](int m0) {
     ok = 0;
     const int mfirst = m0 + mg * 4;
     int n = 0, h = 0, w = 0;
-    if (!is_a) decode_pos(g, min(mfirst, max(mend - 1, 0)), n, h, w);
+    decode_pos(g, min(mfirst, max(mend - 1, 0)), n, h, w);
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
       const int m = mfirst + q;
-      bool in = task && piece_ok && m < mend;
-      long o;
-      if (is_a) {
-        o = (long)m * p.Cout + row0 + piece * 8;
-      } else {
-        o = gather_offset(g, n, h, w, bu, bv, bci);
-        in = in && o >= 0;
-        if (++w == g.Wp) { w = 0; if (++h == g.Hp) { h = 0; ++n; } }
-      }
-      const bf16_t* base = is_a ? p.dy : p.src;
-      r[q] = *reinterpret_cast<const u32x4*>(base + (in ? o : 0));
-      ok |= (in ? 1u : 0u) << q;
+      const long oa = (long)m * p.Cout + row0 + piece * 8;
+      const long ob = gather_offset(g, n, h, w, bu, bv, bci);
+      const long o = is_a ? oa : ob;
+      const bool in = task && piece_ok && m < mend && o >= 0;
+      if (++w == g.Wp) { w = 0; if (++h == g.Hp) { h = 0; ++n; } }
+      const long msk = -(long)in;
+      r[q] = *reinterpret_cast<const u32x4*>(base + (o & msk));
+      ok |= ((uint32_t)msk & 1u) << q;
     }
   };
   auto store_slab = [&](int s) {
@@ -1380,9 +1380,10 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
   const int tiles = ((Cout + 64 * tm - 1) / (64 * tm)) * ((g.K + 64 * tn - 1) / (64 * tn));
   const long hw = (long)g.Hp * g.Wp;
   const long total = (long)seg.off[seg.K] * hw;
-  // Chunk length: about 2048 workgroups in all (the reduction is where the
-  // parallelism of a small filter bank lies), at least 8 slabs each, within the scratch budget.
-  long want = std::max<long>(1, 2048 / tiles);
+  // Chunk length: about 512 workgroups in all, two per compute unit (the reduction is where the
+  // parallelism of a small filter bank lies; every extra chunk is a partial tile written and
+  // read back), at least 8 slabs each, within the scratch budget.
+  long want = std::max<long>(1, 512 / tiles);
   long chunk = std::max<long>((total + want - 1) / want, 8 * BK);
   chunk = (chunk + BK - 1) / BK * BK;
   ChunkTable ct{};
@@ -1393,9 +1394,11 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
       acc += (int)(((long)(seg.off[k + 1] - seg.off[k]) * hw + chunk - 1) / chunk);
     }
     ct.first[seg.K] = acc;
-    // one chunk per worker needs no scratch
-    if (acc == seg.K || (long)tiles * acc <= kConvMaxPartialTiles) break;
-    chunk *= 2;
+    // one chunk per worker needs no scratch; otherwise all workgroups should be resident at once
+    // (two per compute unit): a few extra ones would run as a second round
+    if (acc == seg.K || ((long)tiles * acc <= kConvMaxPartialTiles && (long)tiles * acc <= std::max(512, tiles * seg.K)))
+      break;
+    chunk += std::max<long>(BK, chunk / 16 / BK * BK);
   }
   p.chunk = (int)chunk;
   dim3 grid(tiles, ct.first[seg.K]);
