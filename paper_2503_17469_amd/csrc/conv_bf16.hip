@@ -59,24 +59,15 @@ __device__ inline void build_tap_table(int* tab, const ConvGeom& g, int tid) {
 
 // Source element offset of (sample n, position h,w, tap u,v, channel ci); -1 if it falls in the padding.
 __device__ inline long gather_offset(const ConvGeom& g, int n, int h, int w, int u, int v, int ci) {
-  int hs, ws;
-  bool ok;
-  if (!g.transposed) {
-    hs = h * g.stride + u - g.pad;
-    ws = w * g.stride + v - g.pad;
-    ok = hs >= 0 && hs < g.Hs && ws >= 0 && ws < g.Ws;
-  } else {
-    const int th = h + g.pad - u, tw = w + g.pad - v;
-    ok = th >= 0 && tw >= 0;
-    if (g.stride == 1) {
-      hs = th; ws = tw;
-    } else {
-      ok = ok && (th % g.stride == 0) && (tw % g.stride == 0);
-      hs = th / g.stride; ws = tw / g.stride;
-    }
-    ok = ok && hs < g.Hs && ws < g.Ws;
-  }
-  return ok ? (((long)n * g.Hs + hs) * g.Ws + ws) * g.Cs + ci : -1;
+  // written without early exits: the callers' loads must not sit behind divergent branches
+  const int th = g.transposed ? h + g.pad - u : h * g.stride + u - g.pad;
+  const int tw = g.transposed ? w + g.pad - v : w * g.stride + v - g.pad;
+  const bool strided = g.transposed && g.stride > 1;
+  const int hs = strided ? th / g.stride : th, ws = strided ? tw / g.stride : tw;
+  bool ok = th >= 0 && tw >= 0 && hs < g.Hs && ws < g.Ws;
+  ok = ok && (!strided || (hs * g.stride == th && ws * g.stride == tw));
+  const long o = (((long)n * g.Hs + hs) * g.Ws + ws) * g.Cs + ci;
+  return ok ? o : -1;
 }
 
 // position index m -> (n, h, w); m < 2^24 so the float quotient is exact after one correction
@@ -210,6 +201,13 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
         const bool in = ok && hs >= 0 && hs < g.Hs && ws >= 0 && ws < g.Ws;
         tapmask[i] |= (in ? 1u : 0u) << t;
       }
+    } else if (MODE == GEN) {
+      // (unless the source is strided: then ah/aw stay the position and gather_offset divides)
+      if (!(g.transposed && g.stride > 1)) {
+        ah[i] = g.transposed ? h + g.pad : h * g.stride - g.pad;
+        aw[i] = g.transposed ? w + g.pad : w * g.stride - g.pad;
+        rowbase[i] = (((long)n * g.Hs + ah[i]) * g.Ws + aw[i]) * g.Cs;
+      }
     } else if (FAST) {
       const int hb = g.transposed ? h + g.pad : h * g.stride - g.pad;
       const int wb = g.transposed ? w + g.pad : w * g.stride - g.pad;
@@ -266,29 +264,43 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
       const bool kin = k0 < g.K;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const bool in = kin && ((tapmask[i] >> tap_) & 1u);
-        ra[i] = *reinterpret_cast<const u32x4*>(p.src + (in ? rowbase[i] + tapoff : 0));
-        ok |= (in ? 1u : 0u) << i;
+        const long msk = -(long)(kin && ((tapmask[i] >> tap_) & 1u));
+        ra[i] = *reinterpret_cast<const u32x4*>(p.src + ((rowbase[i] + tapoff) & msk));
+        ok |= ((uint32_t)msk & 1u) << i;
       }
     } else {
       const int q = (k0 >> 3) + kc;
       const bool kin = q * 8 < g.K;
       const int t = tab[kin ? q : 0];
       const int u = t & 15, v = (t >> 4) & 15, ci = t >> 8;
+      if (g.transposed && g.stride > 1) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const long o = gather_offset(g, an[i], ah[i], aw[i], u, v, ci);
-        const bool in = kin && ((arow_ok >> i) & 1u) && o >= 0;
-        ra[i] = *reinterpret_cast<const u32x4*>(p.src + (in ? o : 0));
-        ok |= (in ? 1u : 0u) << i;
+        for (int i = 0; i < 4; ++i) {
+          const long o = gather_offset(g, an[i], ah[i], aw[i], u, v, ci);
+          const long msk = -(long)(kin && ((arow_ok >> i) & 1u) && o >= 0);
+          ra[i] = *reinterpret_cast<const u32x4*>(p.src + (o & msk));
+          ok |= ((uint32_t)msk & 1u) << i;
+        }
+      } else {
+        // ah/aw hold the source coordinates of tap (0, 0); a tap is a displacement
+        const int su = g.transposed ? -u : u, sv = g.transposed ? -v : v;
+        const long tapoff = ((long)su * g.Ws + sv) * g.Cs + ci;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const bool in = kin && ((arow_ok >> i) & 1u) && (unsigned)(ah[i] + su) < (unsigned)g.Hs &&
+                          (unsigned)(aw[i] + sv) < (unsigned)g.Ws;
+          const long msk = -(long)in;
+          ra[i] = *reinterpret_cast<const u32x4*>(p.src + ((rowbase[i] + tapoff) & msk));
+          ok |= ((uint32_t)msk & 1u) << i;
+        }
       }
     }
     const bool bkin = k0 + kc * 8 < g.K;
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const bool in = bkin && ((brow_ok >> i) & 1u);
-      rb[i] = *reinterpret_cast<const u32x4*>(p.wgt + (in ? brow[i] + k0 : 0));
-      ok |= (in ? 1u : 0u) << (4 + i);
+      const long msk = -(long)(bkin && ((brow_ok >> i) & 1u));
+      rb[i] = *reinterpret_cast<const u32x4*>(p.wgt + ((brow[i] + k0) & msk));
+      ok |= ((uint32_t)msk & 1u) << (4 + i);
     }
   };
   const u32x4 zero = {0u, 0u, 0u, 0u};
@@ -1348,7 +1360,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
     ct.first[seg.K] = acc;
     if (acc == 0) return true;   // no rows at all
     // all workgroups resident at once (two per compute unit): a few extra ones would run as a second round
-    if ((size_t)tiles * acc <= max_slots && ((long)tiles * acc <= 512 || acc == seg.K)) break;
+    if ((size_t)tiles * acc <= max_slots && ((long)tiles * acc <= std::max(512, 2 * tiles * seg.K) || acc == seg.K)) break;
     upc += std::max<long>(1, upc / 16);
   }
   p.upc = (int)upc;
@@ -1396,7 +1408,7 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
     ct.first[seg.K] = acc;
     // one chunk per worker needs no scratch; otherwise all workgroups should be resident at once
     // (two per compute unit): a few extra ones would run as a second round
-    if (acc == seg.K || ((long)tiles * acc <= kConvMaxPartialTiles && (long)tiles * acc <= std::max(512, tiles * seg.K)))
+    if (acc == seg.K || ((long)tiles * acc <= kConvMaxPartialTiles && (long)tiles * acc <= std::max(512, 2 * tiles * seg.K)))
       break;
     chunk += std::max<long>(BK, chunk / 16 / BK * BK);
   }
