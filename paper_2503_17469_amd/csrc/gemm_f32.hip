@@ -195,8 +195,12 @@ struct GemmParams {
   int gfirst[9];           // WGRAD: first worker of every group; gfirst[ngroups] = K
 };
 
+// (The second launch bound caps the kernel at 256 registers: the compiler then issues the MFMAs on
+// ordinary vector registers.  With accumulation registers it copied all 32 accumulator registers in
+// and out around the MFMAs of every step, 64 extra vector instructions per 16 MFMAs, because the
+// per-worker flush inside the loop reads and zeroes them.)
 template <int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
-__global__ __launch_bounds__(kThreads) void gemm_f32_kernel(GemmParams p, Segments seg) {
+__global__ __launch_bounds__(kThreads, 2) void gemm_f32_kernel(GemmParams p, Segments seg) {
   using SA = Slab<kTile, BK, A_MC>;
   using SB = Slab<kTile, BK, B_MC>;
   constexpr int kStage = SA::kFloats + SB::kFloats;
