@@ -576,6 +576,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
         else load_w(last_slice ? 0 : (cs + 1) * 64);
         // the next slice's patch (or the next unit's first) starts its way to registers a few taps early
         if (tap == 4) load_patch(last_slice ? min(unit + 1, uend - 1) : unit, last_slice ? 0 : cs + 1);
+        __builtin_amdgcn_sched_barrier(0);   // the loads stay here, a whole tap ahead of their use
         const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRowD;
         const bf16_t* wb = sW + cur * 64 * kRowD + bfrag;
 #pragma unroll
@@ -593,6 +594,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
             for (int b = 0; b < 2; ++b)
               acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
+        __builtin_amdgcn_sched_barrier(0);   // nothing that touches the loaded registers moves above the MFMAs
         if (tap < 8 || !last_slice) store_w(cur ^ 1);
         __syncthreads();
         if (MULTI && tap == 8 && !last_slice) {
@@ -1105,6 +1107,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     store_unit();
     __syncthreads();
     load_unit(min(u + 1, uend - 1));   // always issued: in flight during the MFMAs below
+    __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int ks = 0; ks < kUnit / 16; ++ks) {
       const bf16x8 fa = as_bf16x8(*reinterpret_cast<const u32x4*>(a_frag + ks * 32));
