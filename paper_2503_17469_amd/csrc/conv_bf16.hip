@@ -24,7 +24,17 @@
 // words before writing LDS.  Each worker's position range is cut into equal
 // chunks, one workgroup per (tile, chunk): every workgroup does the same amount
 // of work however ragged the b_k are.  Chunks of one worker park partial tiles;
-// the last to arrive adds them in chunk order (bit-reproducible).
+// a second kernel adds them in chunk order (bit-reproducible, no atomics).
+//
+// 3x3 / pad-1 / stride-1 layers (most of a residual net) have kernels of their own
+// that keep the input patch of a block of positions resident in LDS, so the nine
+// taps cost no extra global loads, transposes or LDS stores:
+//   kernel C (wgrad, 32 channels and more): 64 x 64 channels x all nine taps per
+//     workgroup; column shifts of the patch are made in registers;
+//   kernel D (forward and dgrad, channels a multiple of 64): 256 positions x 64
+//     channels per workgroup; taps are row offsets into the patch.
+// Kernel A also has a mode for the dgrad of stride-2 layers that multiplies only
+// the filter taps an input position can meet (a quarter of a 3x3 filter).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -440,11 +450,10 @@ constexpr int kUnitD = 256;
 constexpr int kRowD = 64 + 8;   // elements per LDS row (144 bytes): 16-byte reads land 4 banks apart
 constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread (up to 416 patch positions)
 
-// MULTI: more than one 64-channel slice (the patch is re-staged per slice).
 // A workgroup walks `upw` consecutive units of one channel tile: the next unit's patch
 // and first weight slab travel to registers during the last taps of the current one,
 // so only the first unit of a workgroup waits for memory before it can multiply.
-template <bool MULTI, int NP>   // NP: 16-byte patch pieces per thread
+template <int NP>   // NP: 16-byte patch pieces per thread
 __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smemD[];
   const int W = p.W, H = p.H, R = p.R;
@@ -549,7 +558,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
           ((wvalid >> i) & 1u) ? rw[i] : zero;
   };
 
-  const int nslice = MULTI ? p.Cs / 64 : 1;
+  const int nslice = p.Cs / 64;   // the patch is re-staged per 64-channel slice
   load_patch(min(ubeg, p.units - 1), 0);
   load_w(0);
   for (int unit = ubeg; unit < uend; ++unit) {
@@ -597,7 +606,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
         __builtin_amdgcn_sched_barrier(0);   // nothing that touches the loaded registers moves above the MFMAs
         if (tap < 8 || !last_slice) store_w(cur ^ 1);
         __syncthreads();
-        if (MULTI && tap == 8 && !last_slice) {
+        if (tap == 8 && !last_slice) {
           store_patch();       // every wavefront is past its last read of the old slice
           __syncthreads();
         }
@@ -1262,7 +1271,7 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   const size_t outt = (size_t)kUnitD * (64 + 4) * sizeof(float);
   const size_t lds = std::max(stage, outt);
   if (lds > 80 * 1024) return false;
-  const int multi = 1, big = npatch * 8 > 11 * kThreads ? 1 : 0;   // (a single-slice instantiation spilled registers)
+  const int big = npatch * 8 > 11 * kThreads ? 1 : 0;
   const int units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
   const int tiles_n = (N + 63) / 64;
   // several units per workgroup once there are enough workgroups to fill the chip a few times over
@@ -1270,20 +1279,17 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   while (upw < 4 && (long)units * tiles_n / (upw * 2) >= 2048) upw *= 2;
   p.units = units; p.upw = upw;
   const dim3 grid(((units + upw - 1) / upw) * tiles_n);
-  static size_t configured[4] = {0, 0, 0, 0};
-#define OMNI_CONV3(MULTI_, NP_)                                                                        \
-  {                                                                                                    \
-    if (lds > configured[multi * 2 + big]) {                                                           \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<MULTI_, NP_>),        \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                 \
-      configured[multi * 2 + big] = lds;                                                               \
-    }                                                                                                  \
-    hipLaunchKernelGGL((conv3_gemm_kernel<MULTI_, NP_>), grid, dim3(kThreads), lds, st, p);            \
+  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
+#define OMNI_CONV3(NP_)                                                                         \
+  {                                                                                             \
+    if (lds > configured[big]) {                                                                \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_>),         \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
+      configured[big] = lds;                                                                    \
+    }                                                                                           \
+    hipLaunchKernelGGL((conv3_gemm_kernel<NP_>), grid, dim3(kThreads), lds, st, p);             \
   }
-  if (multi && big) OMNI_CONV3(true, 13)
-  else if (multi) OMNI_CONV3(true, 11)
-  else if (big) OMNI_CONV3(false, 13)
-  else OMNI_CONV3(false, 11)
+  if (big) OMNI_CONV3(13) else OMNI_CONV3(11)
 #undef OMNI_CONV3
   return true;
 }

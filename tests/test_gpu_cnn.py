@@ -73,6 +73,26 @@ def test_cnn_with_biases_and_odd_batches():
     _check_step(layers, (8, 8, 3), params, x, y, [0, 1, 2, 66, 131], 0.05, "cnn3-8px-bias")
 
 
+@pytest.mark.parametrize("hw,chans,B,cuts", [
+    # 3x3 patch kernels with biases, channel tiles that are not full, units that are not full:
+    # conv2 64->96 on 8x8 maps (two-image / four-image units, second channel tile half empty),
+    # conv3 96->64 on 4x4 maps (96 stored channels: two input-channel tiles, the second half empty)
+    (16, (3, 64, 96, 64), 21, [0, 1, 8, 21]),
+    # conv2 64->64 on 16x16 maps (one image per forward unit, two units per image for wgrad), conv3 on 8x8
+    (32, (3, 64, 64, 128), 9, [0, 2, 9]),
+])
+def test_cnn_patch_kernels(hw, chans, B, cuts):
+    layers = synth.cnn3(num_classes=10, hw=hw, chans=chans)
+    rng = np.random.default_rng(hw + B)
+    params = synth.he_normal_params(layers, 6, True)
+    for sl in synth.param_slices(layers):
+        if "b" in sl:
+            s, e = sl["b"]
+            params[s:e] = synth.to_bf16_grid(rng.standard_normal(e - s).astype(np.float32) * 0.2)
+    x, y = synth.make_batch(13 + hw, B, (hw, hw, 3), 10, True)
+    _check_step(layers, (hw, hw, 3), params, x, y, cuts, 0.05, f"cnn3-{hw}px-{chans}")
+
+
 def test_config2_cnn3():
     w = synth.workload(2)
     b, off = controller_run(w.T, w.B)
