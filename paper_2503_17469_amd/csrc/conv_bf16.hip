@@ -135,8 +135,10 @@ struct ConvParams {
 constexpr int BK2 = 64;
 enum { GEN = 0, FASTM = 1, PHASED = 2 };
 
+// (Launch bounds cap the kernels at 256 registers: the compiler then issues the MFMAs on ordinary
+// registers; with accumulation registers it copied every accumulator in around the MFMAs of each slab.)
 template <int TN, int MODE>
-__global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
+__global__ __launch_bounds__(kThreads, 2) void conv_gemm2_kernel(ConvParams p) {
   constexpr bool FAST = MODE != GEN;
   constexpr int BN = 64 * TN;
   constexpr int NB = 2 * TN;                 // right-operand pieces per thread per slab
@@ -256,11 +258,12 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
       for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
   u32x4 ra[4], rb[NB];
-  uint32_t ok = 0;   // bits 0..3 left pieces, 4.. right pieces
+  // Loads of absent pieces (padding, ragged tile edges) are pointed at a page of zeros: one pointer
+  // select instead of a select per loaded register, and the load itself stays unconditional.
+  const bf16_t* const zp = static_cast<const bf16_t*>(g.zero);
   // FAST: (tap, channel base) of the slab advance uniformly
   int tap = 0, cb = 0;
   auto load_slab = [&](int k0, int tap_, int cb_) {
-    ok = 0;
     if (FAST) {
       long tapoff;
       if (MODE == PHASED) {
@@ -274,9 +277,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
       const bool kin = k0 < g.K;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        const long msk = -(long)(kin && ((tapmask[i] >> tap_) & 1u));
-        ra[i] = *reinterpret_cast<const u32x4*>(p.src + ((rowbase[i] + tapoff) & msk));
-        ok |= ((uint32_t)msk & 1u) << i;
+        const bool in = kin && ((tapmask[i] >> tap_) & 1u);
+        ra[i] = *reinterpret_cast<const u32x4*>(in ? p.src + (rowbase[i] + tapoff) : zp);
       }
     } else {
       const int q = (k0 >> 3) + kc;
@@ -287,9 +289,8 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
           const long o = gather_offset(g, an[i], ah[i], aw[i], u, v, ci);
-          const long msk = -(long)(kin && ((arow_ok >> i) & 1u) && o >= 0);
-          ra[i] = *reinterpret_cast<const u32x4*>(p.src + (o & msk));
-          ok |= ((uint32_t)msk & 1u) << i;
+          const bool in = kin && ((arow_ok >> i) & 1u) && o >= 0;
+          ra[i] = *reinterpret_cast<const u32x4*>(in ? p.src + o : zp);
         }
       } else {
         // ah/aw hold the source coordinates of tap (0, 0); a tap is a displacement
@@ -299,26 +300,22 @@ __global__ __launch_bounds__(kThreads) void conv_gemm2_kernel(ConvParams p) {
         for (int i = 0; i < 4; ++i) {
           const bool in = kin && ((arow_ok >> i) & 1u) && (unsigned)(ah[i] + su) < (unsigned)g.Hs &&
                           (unsigned)(aw[i] + sv) < (unsigned)g.Ws;
-          const long msk = -(long)in;
-          ra[i] = *reinterpret_cast<const u32x4*>(p.src + ((rowbase[i] + tapoff) & msk));
-          ok |= ((uint32_t)msk & 1u) << i;
+          ra[i] = *reinterpret_cast<const u32x4*>(in ? p.src + (rowbase[i] + tapoff) : zp);
         }
       }
     }
     const bool bkin = k0 + kc * 8 < g.K;
 #pragma unroll
     for (int i = 0; i < NB; ++i) {
-      const long msk = -(long)(bkin && ((brow_ok >> i) & 1u));
-      rb[i] = *reinterpret_cast<const u32x4*>(p.wgt + ((brow[i] + k0) & msk));
-      ok |= ((uint32_t)msk & 1u) << (4 + i);
+      const bool in = bkin && ((brow_ok >> i) & 1u);
+      rb[i] = *reinterpret_cast<const u32x4*>(in ? p.wgt + (brow[i] + k0) : zp);
     }
   };
-  const u32x4 zero = {0u, 0u, 0u, 0u};
   auto store_a = [&](int s, int i) {
-    *reinterpret_cast<u32x4*>(sA(s) + (rbase + 32 * i) * kRow + kc * 8) = ((ok >> i) & 1u) ? ra[i] : zero;
+    *reinterpret_cast<u32x4*>(sA(s) + (rbase + 32 * i) * kRow + kc * 8) = ra[i];
   };
   auto store_b = [&](int s, int i) {
-    *reinterpret_cast<u32x4*>(sB(s) + (rbase + 32 * i) * kRow + kc * 8) = ((ok >> (4 + i)) & 1u) ? rb[i] : zero;
+    *reinterpret_cast<u32x4*>(sB(s) + (rbase + 32 * i) * kRow + kc * 8) = rb[i];
   };
   auto advance = [&]() {
     cb += BK2;
@@ -442,6 +439,7 @@ struct Conv3Params {
   int R, nimg;         // a unit is nimg images x R rows; nimg * R * W = 256
   int units, upw;      // units in all, units per workgroup
   int flip;            // 1: dgrad (mirrored taps)
+  const void* zero;    // page of zeros for absent pieces
   const float* bias;
   const bf16_t* mask;
   int relu, accumulate;
@@ -509,7 +507,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   }
   const int bfrag = j * kRowD + h * 8;
 
-  const u32x4 zero = {0u, 0u, 0u, 0u};
+  const bf16_t* const zp = static_cast<const bf16_t*>(p.zero);   // absent pieces are read from a page of zeros
   u32x4 rp[NP], rw[2];
   uint32_t pvalid = 0;
   // unit -> first image, first row, images present
@@ -521,7 +519,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
       n0 = unit * p.nimg; r0 = 0; nvalid = min(p.nimg, p.rows - n0);
     }
   };
-  // loads are unconditional: an absent piece re-reads element 0 and is zeroed when stored
+  // loads are unconditional
   auto load_patch = [&](int unit, int cs) {
     int n0, r0, nvalid;
     unit_geom(unit, n0, r0, nvalid);
@@ -532,8 +530,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     for (int t = 0; t < NP; ++t) {
       const int il = (int)(img4 >> (4 * t)) & 15;
       if (il >= nvalid) pvalid &= ~(1u << t);
-      const int m = -(int)((pvalid >> t) & 1u);
-      rp[t] = *reinterpret_cast<const u32x4*>(p.src + ((ubase + prel[t]) & m));
+      rp[t] = *reinterpret_cast<const u32x4*>(((pvalid >> t) & 1u) ? p.src + (ubase + prel[t]) : zp);
     }
   };
   auto store_patch = [&]() {
@@ -541,21 +538,19 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     for (int t = 0; t < NP; ++t) {
       const int x = tid + t * kThreads;
       if (x < npieces)
-        *reinterpret_cast<u32x4*>(sP + (x >> 3) * kRowD + (x & 7) * 8) = ((pvalid >> t) & 1u) ? rp[t] : zero;
+        *reinterpret_cast<u32x4*>(sP + (x >> 3) * kRowD + (x & 7) * 8) = rp[t];
     }
   };
   auto load_w = [&](int k0) {
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
-      const long m = -(long)((wvalid >> i) & 1u);
-      rw[i] = *reinterpret_cast<const u32x4*>(p.wgt + ((woff[i] + k0) & m));
+      rw[i] = *reinterpret_cast<const u32x4*>(((wvalid >> i) & 1u) ? p.wgt + (woff[i] + k0) : zp);
     }
   };
   auto store_w = [&](int buf) {
 #pragma unroll
     for (int i = 0; i < 2; ++i)
-      *reinterpret_cast<u32x4*>(sW + buf * 64 * kRowD + (wr + 32 * i) * kRowD + woct * 8) =
-          ((wvalid >> i) & 1u) ? rw[i] : zero;
+      *reinterpret_cast<u32x4*>(sW + buf * 64 * kRowD + (wr + 32 * i) * kRowD + woct * 8) = rw[i];
   };
 
   const int nslice = p.Cs / 64;   // the patch is re-staged per 64-channel slice
@@ -684,7 +679,7 @@ struct ChunkTable {
 };
 
 template <int TM, int TN>
-__global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Segments seg, ChunkTable ct) {
+__global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, Segments seg, ChunkTable ct) {
   constexpr int BM = 64 * TM, BN = 64 * TN;   // output tile: BM output channels x BN reduction columns
   constexpr int kRow = BK + 4;               // 72-byte rows: 8-byte accesses, 8 rows apart lands 16 banks apart
   constexpr int kA = BM * kRow, kB = BN * kRow;
@@ -745,13 +740,12 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
   float bsum = 0.f;
 
   u32x4 r[4];
-  uint32_t ok = 0;
   // Loads never branch and their base pointer is chosen once (a guarded load, or a pointer
   // re-selected per load, makes the compiler wait for every load before issuing the next):
-  // an absent piece re-reads the tensor's first 16 bytes and is zeroed when stored.
+  // an absent piece is read from a page of zeros.
   const bf16_t* const base = is_a ? p.dy : p.src;
+  const bf16_t* const zp = static_cast<const bf16_t*>(g.zero);
   auto load_slab = [&](int m0) {
-    ok = 0;
     const int mfirst = m0 + mg * 4;
     int n = 0, h = 0, w = 0;
     decode_pos(g, min(mfirst, max(mend - 1, 0)), n, h, w);
@@ -763,17 +757,12 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_kernel(WgradParams p, Seg
       const long o = is_a ? oa : ob;
       const bool in = task && piece_ok && m < mend && o >= 0;
       if (++w == g.Wp) { w = 0; if (++h == g.Hp) { h = 0; ++n; } }
-      const long msk = -(long)in;
-      r[q] = *reinterpret_cast<const u32x4*>(base + (o & msk));
-      ok |= ((uint32_t)msk & 1u) << q;
+      r[q] = *reinterpret_cast<const u32x4*>(in ? base + o : zp);
     }
   };
   auto store_slab = [&](int s) {
     if (!task) return;
-    u32x4 c[4];
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int q = 0; q < 4; ++q) c[q] = ((ok >> q) & 1u) ? r[q] : zero;
+    const u32x4* c = r;
     bf16_t* dst = (is_a ? sA(s) : sB(s)) + (piece * 8) * kRow + mg * 4;
     // word d of piece q holds channels 2d (low half) and 2d+1 (high half) of position q
 #pragma unroll
@@ -947,6 +936,7 @@ struct Wgrad3Params {
   int SX;              // bytes between channels of X^T
   int upc;             // units per chunk
   float* partial;      // [(tile * total_chunks + chunk)][144][256] (+ 64 bias sums)
+  const void* zero;    // page of zeros for absent pieces
 };
 constexpr int kUnit = 128;
 constexpr int kSA = 2 * kUnit + 16;                 // bytes between channels of dY^T
@@ -1060,7 +1050,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
   float bsum = 0.f;
 
   u32x4 ra[4], rx[2][4];
-  uint32_t ok = 0;   // bits 0-3: dY positions; bit 4, 5: the two X tasks
+  const bf16_t* const zp = static_cast<const bf16_t*>(p.zero);
   auto load_unit = [&](int u) {
     int n0, r0, nvalid;
     if (p.nimg == 1) {
@@ -1069,44 +1059,33 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     } else {
       n0 = seg.off[wk] + u * p.nimg; r0 = 0; nvalid = min(p.nimg, seg.off[wk + 1] - n0);
     }
-    ok = 0;
     const long base_pos = ((long)n0 * H + r0) * W;
     // Loads never branch (a guarded load makes the compiler wait for each group before the
-    // next): an invalid piece reads the tensor's first 16 bytes and is zeroed when stored.
+    // next): an absent piece is read from a page of zeros.
     {
       const bool in = a_chan_ok && a_il < nvalid;
-      const long m = -(long)in;   // all ones or zero
-      const long o = ((base_pos + a_rel) * p.Cout + co0 + 8 * a_oct) & m;
-      const long st = (long)p.Cout & m;
+      const bf16_t* src = in ? p.dy + ((base_pos + a_rel) * p.Cout + co0 + 8 * a_oct) : zp;
+      const int st = in ? p.Cout : 0;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) ra[q] = *reinterpret_cast<const u32x4*>(p.dy + o + q * st);
-      ok |= 0xFu & (uint32_t)m;
+      for (int q = 0; q < 4; ++q) ra[q] = *reinterpret_cast<const u32x4*>(src + q * st);
     }
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int row = r0 + x_rr[t] - 1;
       const bool in = x_task[t] && x_il[t] < nvalid && row >= 0 && row < H;
-      const long m = -(long)in;
-      const long o = (base_pos * p.Cin + x_rel[t] + ci0) & m;
-      const long st = (long)p.Cin & m;
+      const bf16_t* src = in ? p.src + (base_pos * p.Cin + x_rel[t] + ci0) : zp;
+      const int st = in ? p.Cin : 0;
 #pragma unroll
-      for (int q = 0; q < 4; ++q) rx[t][q] = *reinterpret_cast<const u32x4*>(p.src + o + q * st);
-      ok |= ((uint32_t)m & 1u) << (4 + t);
+      for (int q = 0; q < 4; ++q) rx[t][q] = *reinterpret_cast<const u32x4*>(src + q * st);
     }
   };
   auto store_unit = [&]() {
-    const u32x4 zero = {0u, 0u, 0u, 0u};
-    u32x4 c[4];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) c[q] = (ok & 0xFu) ? ra[q] : zero;
-    transpose_store(c, a_dst, kSA);
+    transpose_store(ra, a_dst, kSA);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       if (tid + t * kThreads >= ntasks) continue;   // no such patch piece (not a matter of validity)
-#pragma unroll
-      for (int q = 0; q < 4; ++q) c[q] = ((ok >> (4 + t)) & 1u) ? rx[t][q] : zero;
-      if (W4) transpose_store32(c, sX + x_dst[t], p.SX);
-      else transpose_store(c, sX + x_dst[t], p.SX);
+      if (W4) transpose_store32(rx[t], sX + x_dst[t], p.SX);
+      else transpose_store(rx[t], sX + x_dst[t], p.SX);
     }
   };
 
@@ -1265,7 +1244,7 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   if (npatch * 8 > kMaxPatchPieces * kThreads) return false;
   Conv3Params p{};
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
-  p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0;
+  p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0; p.zero = g.zero;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
   const size_t stage = ((size_t)npatch + 2 * 64) * kRowD * sizeof(bf16_t);
   const size_t outt = (size_t)kUnitD * (64 + 4) * sizeof(float);
@@ -1345,6 +1324,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   words += (4 - words % 8 + 8) % 8;
   p.SX = words * 4;
   p.partial = partial;
+  p.zero = g.zero;
   const size_t lds = (size_t)64 * kSA + (size_t)64 * p.SX;
   if (lds > 80 * 1024) return false;
   const int tiles = ((Cout + 63) / 64) * ((g.Cs + 63) / 64);

@@ -63,9 +63,10 @@ struct ConvGeom {
   int ks, stride, pad;  // filter size, stride, zero padding of the forward convolution
   int transposed;       // 0: source = h*stride + u - pad.  1 (dgrad): t = h + pad - u, source = t/stride if divisible
   int K;                // ks*ks*Cs
+  const void* zero;     // at least 16 bytes of zeros in device memory: where loads of absent pieces are pointed
 };
 constexpr int kConvMaxPartialTiles = 2048;   // (tile, chunk) slots of wgrad scratch
-constexpr int kConvCounters = 16384;         // (tile, worker) arrival counters
+constexpr int kConvCounters = 16384;         // words of scratch that stay zero for the life of a workspace (the zero page)
 size_t conv_wgrad_partial_floats();
 bool conv_shape_supported(const ConvGeom& g, long positions);
 // out[M][N] = gather(src)[M][K] * wgt[N][K]^T (+bias) (ReLU) (masked where mask <= 0) (+= out)

@@ -504,6 +504,7 @@ void step_bf16(StepCtx& c) {
     }
     g.transposed = 0;
     g.K = g.ks * g.ks * g.Cs;
+    g.zero = conv_counters;   // zeroed once per workspace, never written
     return g;
   };
 
