@@ -25,8 +25,8 @@ PEAK_HBM_GBS = 8000.0
 DOMINANT = {
     "tiny_mlp": ("linear_wgrad", 0),
     "mlp3072": ("linear_wgrad", 0),
-    "cnn3": ("conv_wgrad", 3),
-    "cnn3_dynamic": ("conv_wgrad", 3),
+    "cnn3": ("conv_wgrad", 0),
+    "cnn3_dynamic": ("conv_wgrad", 0),
     "resnet18": ("conv_fwd", 3),
 }
 

@@ -930,7 +930,8 @@ struct Wgrad3Params {
   float* gw;           // worker w: gw + w*worker_stride, [Cout][9][Cin]
   float* gb;           // may be null
   size_t worker_stride;
-  int Cout, Cin, H, W;
+  int Cout, Cin, H, W;  // Cin: stored channels (a multiple of 8)
+  int cin_real;        // channels of the gradient tensor (the first layer stores 3 channels padded to 8)
   int R, nimg;         // a unit is nimg images x R rows; nimg * R * W = 128
   int Wp, prows;       // patch row length W + 16 (data starts at column 8), patch rows nimg * (R + 2)
   int SX;              // bytes between channels of X^T
@@ -995,9 +996,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
   const int units_k = p.nimg == 1 ? bk * upi : (bk + p.nimg - 1) / p.nimg;
   const int ubeg = chunk_idx * p.upc, uend = min(units_k, ubeg + p.upc);
 
-  // the halo columns of the patch are never written again: they stay zero
-  for (int i = tid * 16; i < 64 * p.SX; i += kThreads * 16)
-    *reinterpret_cast<u32x4*>(sX + i) = u32x4{0u, 0u, 0u, 0u};
+  // The halo columns of the patch are never written again: they stay zero.  So do the rows of
+  // channels past the end of the tensor (their staging tasks are skipped altogether).
+  for (int i = tid * 16; i < 64 * kSA + 64 * p.SX; i += kThreads * 16)
+    *reinterpret_cast<u32x4*>(smem3 + i) = u32x4{0u, 0u, 0u, 0u};
 
   // ---- staging tasks (the same for every unit, relative to the unit's first image and row)
   // dY: 8 channel octets x 32 groups of 4 positions
@@ -1026,7 +1028,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     x_rr[t] = pr - x_il[t] * (R + 2);                       // input row = first row + x_rr - 1
     x_rel[t] = ((x_il[t] * H + x_rr[t] - 1) * W + 4 * wg) * p.Cin + 8 * oct;
     x_dst[t] = (8 * oct) * p.SX + (pr * p.Wp + 4 * wg + (W4 ? 2 : 8)) * 2;
-    x_task[t] = x_task[t] && ci0 + 8 * oct < p.Cin;
+    x_task[t] = x_task[t] && ci0 + 8 * oct < p.Cin;   // false: no such piece, or a channel octet past the end
   }
 
   // ---- fragment addresses: k-step ks covers positions 16 ks .. 16 ks + 15, this lane the 8 at 16 ks + 8 h
@@ -1080,10 +1082,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     }
   };
   auto store_unit = [&]() {
-    transpose_store(ra, a_dst, kSA);
+    if (a_chan_ok) transpose_store(ra, a_dst, kSA);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
-      if (tid + t * kThreads >= ntasks) continue;   // no such patch piece (not a matter of validity)
+      if (!x_task[t]) continue;   // no such patch piece, or channels that stay zero
       if (W4) transpose_store32(rx[t], sX + x_dst[t], p.SX);
       else transpose_store(rx[t], sX + x_dst[t], p.SX);
     }
@@ -1146,24 +1148,26 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     }
   }
 
+  const int ci = ci0 + wci + j;
   if (nchunks > 1) {
     float* mine = p.partial + ((size_t)tile * ct.first[seg.K] + blockIdx.y) * kTile3Stride;
+    if (ci < p.cin_real) {   // the second stage reads the same lanes only
 #pragma unroll
-    for (int t = 0; t < 9; ++t)
+      for (int t = 0; t < 9; ++t)
 #pragma unroll
-      for (int v = 0; v < 16; ++v) mine[(t * 16 + v) * kThreads + tid] = acc[t][v];
+        for (int v = 0; v < 16; ++v) mine[(t * 16 + v) * kThreads + tid] = acc[t][v];
+    }
     if (tid < 64) mine[kTile3Floats + tid] = bsum;
     return;
   }
   float* gw = p.gw + (size_t)wk * p.worker_stride;
-  const int ci = ci0 + wci + j;
-  if (ci < p.Cin) {
+  if (ci < p.cin_real) {
 #pragma unroll
     for (int t = 0; t < 9; ++t)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int co = co0 + wco + 8 * (v / 4) + 4 * h + (v % 4);
-        if (co < p.Cout) gw[((size_t)co * 9 + t) * p.Cin + ci] = acc[t][v];
+        if (co < p.Cout) gw[((size_t)co * 9 + t) * p.cin_real + ci] = acc[t][v];
       }
   }
   if (want_bias && tid < 64 && co0 + tid < p.Cout) p.gb[(size_t)wk * p.worker_stride + co0 + tid] = bsum;
@@ -1184,18 +1188,32 @@ __global__ __launch_bounds__(kThreads) void conv3_wgrad_reduce_kernel(Wgrad3Para
   const float* all = p.partial + ((size_t)tile * ct.first[seg.K] + ct.first[wk]) * kTile3Stride;
   const float* mine = all + (size_t)(tap * 16 + vq * 4) * kThreads + tid;
   float s[4] = {0.f, 0.f, 0.f, 0.f};
-  for (int c = 0; c < nchunks; ++c) {
-    const float* q = mine + (size_t)c * kTile3Stride;
-#pragma unroll
-    for (int e = 0; e < 4; ++e) s[e] += q[e * kThreads];
-  }
   const int ci = ci0 + wci + j;
-  if (ci < p.Cin) {
+  if (ci < p.cin_real) {
+    int c = 0;
+    for (; c + 8 <= nchunks; c += 8) {   // eight chunks in flight; the additions keep chunk order
+      float t[8][4];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) t[u][e] = mine[(size_t)(c + u) * kTile3Stride + e * kThreads];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) s[e] += t[u][e];
+    }
+    for (; c < nchunks; ++c) {
+      const float* q = mine + (size_t)c * kTile3Stride;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) s[e] += q[e * kThreads];
+    }
+  }
+  if (ci < p.cin_real) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       const int v = vq * 4 + e;
       const int co = co0 + wco + 8 * (v / 4) + 4 * h + (v % 4);
-      if (co < p.Cout) p.gw[(size_t)wk * p.worker_stride + ((size_t)co * 9 + tap) * p.Cin + ci] = s[e];
+      if (co < p.Cout) p.gw[(size_t)wk * p.worker_stride + ((size_t)co * 9 + tap) * p.cin_real + ci] = s[e];
     }
   }
   if (blockIdx.z == 0 && p.gb != nullptr && ci0 == 0 && tid < 64 && co0 + tid < p.Cout) {
@@ -1301,14 +1319,15 @@ void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
 #undef OMNI_GEMM2
 }
 
-// 3x3 / stride 1 / pad 1 with at least 32 stored channels and a map whose rows
-// tile into units of 128 positions: kernel C.  Returns false if the shape does not qualify.
+// 3x3 / stride 1 / pad 1 and a map whose rows tile into units of 128 positions: kernel C.  (Also
+// for the first layer's 8 stored channels: most of its 64-channel tile is empty, but the matrix
+// pipe is not what that layer waits for.)  Returns false if the shape does not qualify.
 static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                         size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                         float* partial) {
   const int H = g.Hs, W = g.Ws;
   if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.transposed || g.Hp != H || g.Wp != W) return false;
-  if (cin_real != g.Cs || g.Cs < 32 || g.Cs % 8 != 0 || Cout % 8 != 0) return false;
+  if (cin_real > g.Cs || g.Cs % 8 != 0 || Cout % 8 != 0) return false;
   const bool w4 = W == 4 && H == 4;
   if (!w4 && (W % 8 != 0 || W > kUnit || kUnit % W != 0)) return false;
   const int R = std::min(H, kUnit / W);
@@ -1317,7 +1336,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   if (nimg > 1 && R != H) return false;
   Wgrad3Params p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
-  p.Cout = Cout; p.Cin = g.Cs; p.H = H; p.W = W; p.R = R; p.nimg = nimg;
+  p.Cout = Cout; p.Cin = g.Cs; p.cin_real = cin_real; p.H = H; p.W = W; p.R = R; p.nimg = nimg;
   p.Wp = w4 ? 8 : W + 16; p.prows = nimg * (R + 2);
   // channel stride of X^T in 4-byte words must be 4 mod 8: 16 lanes x 16 bytes then cover all 64 banks
   int words = p.prows * p.Wp / 2;
