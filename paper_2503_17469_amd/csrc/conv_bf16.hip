@@ -661,6 +661,161 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   }
 }
 
+// ------------------------------------------------------------------ kernel F
+// Forward of the FIRST layer: 3x3 / pad 1 / stride 1 on 8 stored channels (3 real ones), at most
+// 64 output channels.  The reduction is 9 taps x 8 channels = 72: one 16-byte piece per tap, so a
+// k-step of 16 is two taps, and the lane halves of an MFMA operand simply read the patch at two
+// different tap offsets.  All weights (at most 64 x 80 values) live in registers for the whole
+// kernel; per unit of 256 positions the patch is 5 KB of LDS and the work is 10-20 MFMAs per
+// wavefront: the kernel is bound by reading the input and writing the output once.
+struct Conv1Params {
+  const bf16_t* src;   // [rows][H][W][8]
+  const bf16_t* wgt;   // [N][9][8]
+  bf16_t* out;         // [rows*H*W][N]
+  int rows, H, W, N;
+  int R, nimg;         // a unit is nimg images x R rows; nimg * R * W = 256
+  int units, upw;
+  const float* bias;
+  int relu;
+  const void* zero;
+};
+
+template <int NBLK>   // 32-channel blocks of output channels: 1 or 2
+__global__ __launch_bounds__(kThreads, 2) void conv1_fwd_kernel(Conv1Params p) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smemF[];
+  constexpr int NT = 32 * NBLK;
+  constexpr int kPitch = NT + 8;   // bf16 elements per staged output row
+  const int W = p.W, H = p.H, R = p.R;
+  const int PW = W + 2, PR = R + 2;
+  const int npatch = p.nimg * PR * PW;
+  u32x4* sP = reinterpret_cast<u32x4*>(smemF);                                  // [npatch] pieces of 8 channels
+  bf16_t* so = reinterpret_cast<bf16_t*>(smemF + (size_t)((npatch + 3) & ~3) * 16);   // [256][kPitch]
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int j = lane & 31, h = lane >> 5;
+  const bf16_t* const zp = static_cast<const bf16_t*>(p.zero);
+
+  // ---- weights: B fragment of k-step ks = taps 2ks (lanes 0-31) and 2ks+1 (lanes 32-63) of channel j
+  bf16x8 wf[NBLK][5];
+#pragma unroll
+  for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+    for (int ks = 0; ks < 5; ++ks) {
+      const int tap = 2 * ks + h, co = 32 * b + j;
+      const bool in = tap < 9 && co < p.N;
+      wf[b][ks] = as_bf16x8(*reinterpret_cast<const u32x4*>(in ? p.wgt + ((size_t)co * 9 + tap) * 8 : zp));
+    }
+  float bj[NBLK];
+#pragma unroll
+  for (int b = 0; b < NBLK; ++b) bj[b] = (p.bias && 32 * b + j < p.N) ? p.bias[32 * b + j] : 0.f;
+
+  // ---- patch staging: piece x = tid + 256 t is patch position x (two per thread)
+  int prel[2], pil[2], ppr[2];
+  bool pcol[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    const int x = min(tid + t * kThreads, npatch - 1);
+    const int il = x / (PR * PW), rem = x - il * (PR * PW);
+    const int pr = rem / PW, pc = rem - pr * PW;
+    pil[t] = il; ppr[t] = pr;
+    pcol[t] = tid + t * kThreads < npatch && pc >= 1 && pc <= W;
+    prel[t] = ((il * H + pr - 1) * W + pc - 1) * 8;
+  }
+  // ---- fragment addresses: positions wave*64 + a*32 + j, tap offset by lane half
+  int pbase[2];
+#pragma unroll
+  for (int a = 0; a < 2; ++a) {
+    const int pos = wave * 64 + a * 32 + j;
+    const int rr = pos / W, w = pos - rr * W;
+    const int il = rr / R, r = rr - il * R;
+    pbase[a] = (il * PR + r) * PW + w;
+  }
+  int toff[5];
+#pragma unroll
+  for (int ks = 0; ks < 5; ++ks) {
+    const int tap = min(2 * ks + h, 8);   // the tenth "tap" does not exist: its weights are zero, its data are zeroed below
+    toff[ks] = (tap / 3) * PW + tap % 3;
+  }
+
+  auto unit_geom = [&](int unit, int& n0, int& r0, int& nvalid) {
+    if (p.nimg == 1) {
+      const int upi = H / R, img = unit / upi;
+      n0 = img; r0 = (unit - img * upi) * R; nvalid = 1;
+    } else {
+      n0 = unit * p.nimg; r0 = 0; nvalid = min(p.nimg, p.rows - n0);
+    }
+  };
+  u32x4 rp[2];
+  auto load_patch = [&](int unit) {
+    int n0, r0, nvalid;
+    unit_geom(unit, n0, r0, nvalid);
+    const long ubase = ((long)n0 * H + r0) * W * 8;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+      const int row = r0 + ppr[t] - 1;
+      const bool in = pcol[t] && pil[t] < nvalid && row >= 0 && row < H;
+      rp[t] = *reinterpret_cast<const u32x4*>(in ? p.src + (ubase + prel[t]) : zp);
+    }
+  };
+
+  const int ubeg = blockIdx.x * p.upw, uend = min(p.units, ubeg + p.upw);
+  load_patch(min(ubeg, p.units - 1));
+  for (int unit = ubeg; unit < uend; ++unit) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+      if (tid + t * kThreads < npatch) sP[tid + t * kThreads] = rp[t];
+    __syncthreads();
+    load_patch(min(unit + 1, uend - 1));
+    __builtin_amdgcn_sched_barrier(0);
+
+    v16f acc[2][NBLK];
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 5; ++ks) {
+#pragma unroll
+      for (int a = 0; a < 2; ++a) {
+        u32x4 q = sP[pbase[a] + toff[ks]];
+        if (ks == 4 && h == 1) q = u32x4{0u, 0u, 0u, 0u};
+        const bf16x8 fa = as_bf16x8(q);
+#pragma unroll
+        for (int b = 0; b < NBLK; ++b)
+          acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, wf[b][ks], acc[a][b], 0, 0, 0);
+      }
+    }
+    // bias, ReLU, round to bf16, stage so that rows leave as 16-byte pieces
+#pragma unroll
+    for (int a = 0; a < 2; ++a)
+#pragma unroll
+      for (int b = 0; b < NBLK; ++b)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int il = wave * 64 + a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+          float val = acc[a][b][v] + bj[b];
+          if (p.relu) val = val > 0.f ? val : 0.f;
+          so[il * kPitch + 32 * b + j] = f32_to_bf16(val);
+        }
+    __syncthreads();
+    int n0, r0, nvalid;
+    unit_geom(unit, n0, r0, nvalid);
+    const long out_base = ((long)n0 * H + r0) * W;
+    const int npos = nvalid * R * W;
+    constexpr int kPieces = NT / 8;
+#pragma unroll
+    for (int it = 0; it < kUnitD * kPieces / kThreads; ++it) {
+      const int c = tid + kThreads * it;
+      const int il = c / kPieces, jl = (c % kPieces) * 8;
+      if (il < npos && jl < p.N)   // N is a multiple of 8
+        *reinterpret_cast<u32x4*>(p.out + (size_t)(out_base + il) * p.N + jl) =
+            *reinterpret_cast<const u32x4*>(so + il * kPitch + jl);
+    }
+    // (the next iteration's patch store touches sP only; `so` is rewritten after the next barrier)
+  }
+}
+
 // ------------------------------------------------------------------ kernel B
 struct WgradParams {
   const bf16_t* dy;    // [positions][Cout]
@@ -1291,9 +1446,37 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   return true;
 }
 
+// First layer forward (8 stored channels, 3x3 / pad 1 / stride 1, at most 64 outputs): kernel F.
+static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
+  const int H = g.Hs, W = g.Ws;
+  if (g.transposed || mask || accumulate || g.Cs != 8 || g.ks != 3 || g.stride != 1 || g.pad != 1) return false;
+  if (g.Hp != H || g.Wp != W || N % 8 != 0 || N > 64 || (long)g.rows * H * W != M) return false;
+  if (W < 8 || W > kUnitD || kUnitD % W != 0) return false;
+  const int R = std::min(H, kUnitD / W);
+  if (H % R != 0 || kUnitD % (R * W) != 0) return false;
+  const int nimg = kUnitD / (R * W);
+  if (nimg > 1 && R != H) return false;
+  const int npatch = nimg * (R + 2) * (W + 2);
+  if (npatch > 2 * kThreads) return false;
+  Conv1Params p{};
+  p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.N = N; p.R = R; p.nimg = nimg;
+  p.bias = bias; p.relu = relu ? 1 : 0; p.zero = g.zero;
+  p.units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
+  p.upw = 1;
+  while (p.upw < 8 && p.units / (p.upw * 2) >= 1024) p.upw *= 2;
+  const int nblk = N > 32 ? 2 : 1;
+  const size_t lds = (size_t)((npatch + 3) & ~3) * 16 + (size_t)kUnitD * (32 * nblk + 8) * sizeof(bf16_t);
+  const dim3 grid((p.units + p.upw - 1) / p.upw);
+  if (nblk == 2) hipLaunchKernelGGL(conv1_fwd_kernel<2>, grid, dim3(kThreads), lds, st, p);
+  else hipLaunchKernelGGL(conv1_fwd_kernel<1>, grid, dim3(kThreads), lds, st, p);
+  return true;
+}
+
 void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
   if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate)) return;
+  if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate)) return;
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
