@@ -22,12 +22,14 @@ PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 PEAK_HBM_GBS = 8000.0
 
 # kernel whose roofline is reported, per workload: (timing class, layer index)
+# dominant kernel of every workload: (timing class, layer, roofline that bounds it)
 DOMINANT = {
-    "tiny_mlp": ("linear_wgrad", 0),
-    "mlp3072": ("linear_wgrad", 0),
-    "cnn3": ("conv_wgrad", 0),
-    "cnn3_dynamic": ("conv_wgrad", 0),
-    "resnet18": ("conv_fwd", 3),
+    "tiny_mlp": ("linear_wgrad", 0, "mfma"),
+    "mlp3072": ("linear_wgrad", 0, "mfma"),
+    # first conv layer, 3 input channels: 0.3 kflop per byte, far below the chip's ridge point
+    "cnn3": ("conv_wgrad", 0, "hbm"),
+    "cnn3_dynamic": ("conv_wgrad", 0, "hbm"),
+    "resnet18": ("conv_fwd", 3, "mfma"),
 }
 
 
@@ -39,6 +41,18 @@ def layer_flops(layers, in_shape, li, rows):
         return 2.0 * rows * L["cin"] * L["cout"]
     ho, wo, _ = nets.layer_shapes(layers, in_shape)[li]
     return 2.0 * rows * ho * wo * L["cout"] * L["k"] * L["k"] * L["cin"]
+
+
+def wgrad_bytes(layers, in_shape, li, rows, K):
+    """Algorithmic HBM bytes of one conv weight-gradient launch of layer li: the output gradient and
+    the (channel-padded, bf16) layer input read once, K per-worker fp32 gradients written."""
+    import synth.nets as nets
+    L = layers[li]
+    shapes = nets.layer_shapes(layers, in_shape)
+    ho, wo, _ = shapes[li]
+    hi, wi, ci = in_shape if L["src"] < 0 else shapes[L["src"]]
+    ci_pad = (ci + 7) // 8 * 8
+    return 2.0 * rows * (ho * wo * L["cout"] + hi * wi * ci_pad) + 4.0 * K * L["cout"] * L["k"] * L["k"] * L["cin"]
 
 
 def cpu_baseline(w, off, budget_s=12.0):
@@ -142,7 +156,7 @@ def main():
         one_step()
     torch.cuda.synchronize()
 
-    kcls, klayer = DOMINANT[w.name]
+    kcls, klayer, kbound = DOMINANT[w.name]
     omni.net_timing_enable(net, kcls, klayer, args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -170,11 +184,15 @@ def main():
     upd_gbs = upd_bytes / (u_ms / max(u_n, 1) * 1e-3) / 1e9
 
     kernel_s = k_ms / max(k_n, 1) * 1e-3
-    flops = layer_flops(w.layers, w.in_shape, klayer, w.B)
-    achieved = flops / kernel_s / 1e12
-    peak = PEAK_TFLOPS[w.dtype]
-    roofline = {"bound": "mfma", "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
-                "unit": "TFLOP/s", "frac": achieved / peak,
+    if kbound == "mfma":
+        flops = layer_flops(w.layers, w.in_shape, klayer, w.B)
+        achieved = flops / kernel_s / 1e12
+        peak, unit = PEAK_TFLOPS[w.dtype], "TFLOP/s"
+    else:
+        achieved = wgrad_bytes(w.layers, w.in_shape, klayer, w.B, w.K) / kernel_s / 1e9
+        peak, unit = PEAK_HBM_GBS, "GB/s"
+    roofline = {"bound": kbound, "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
+                "unit": unit, "frac": achieved / peak,
                 "traffic": measured_traffic(w.name, f"{kcls}[layer {klayer}]"),
                 "avg_launch_us": kernel_s * 1e6, "launches": int(k_n)}
 
