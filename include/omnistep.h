@@ -219,6 +219,32 @@ void omni_net_destroy(omni_net* net);
 int omni_weighted_sgd(void* stream, float* params, const float* grads, size_t stride,
                       size_t P, const int32_t* b, int32_t K, float lr, void* shadow_bf16);
 
+/* The optimiser of the paper's experiments (Section "Evaluation", model hyperparameters:
+ * "SGD with momentum 0.9 and weight decay 5e-4"), fused with the aggregation of equation
+ * bspweightedgrads.  The paper prints no formula; this is the update of the framework it
+ * names (no dampening, no Nesterov look-ahead, L2 penalty folded into the gradient):
+ *   g = sum_k (b[k] / sum_i b[i]) * grads[k*stride + j]
+ *   d = g + weight_decay * params[j];  velocity[j] = momentum * velocity[j] + d
+ *   params[j] -= lr * velocity[j]
+ *   velocity dev [P] fp32 in/out, 16-byte aligned, owned by the caller, all zeros before
+ *   the first step; the other arguments as omni_weighted_sgd.  momentum in [0, 1),
+ *   weight_decay >= 0, all finite; anything else is OMNI_EINVAL and nothing is launched. */
+int omni_weighted_sgd_momentum(void* stream, float* params, float* velocity, const float* grads,
+                               size_t stride, size_t P, const int32_t* b, int32_t K, float lr,
+                               float momentum, float weight_decay, void* shadow_bf16);
+
+/* Make omni_step apply that update instead of plain SGD (velocity as above, P =
+ * omni_net_param_count floats); velocity == NULL returns to plain SGD.  Host call, takes
+ * effect from the next omni_step. */
+int omni_net_set_momentum(omni_net* net, float* velocity, float momentum, float weight_decay);
+
+/* Stepwise learning-rate schedule of the same hyperparameter list ("initial LR 0.1 that
+ * decays by a factor of 10 after 15, 30 and 45 epochs"): *lr_out = lr0 * gamma^m with m
+ * the number of milestones <= epoch (epochs counted from 0).  Host only, double
+ * arithmetic; milestones host [n], may be NULL when n == 0. */
+int omni_lr_step_decay(double lr0, double gamma, const int32_t* milestones, int32_t n,
+                       int32_t epoch, double* lr_out);
+
 /* Softmax cross-entropy over a ragged batch: for row s of worker k,
  * loss_rows[s] = -log softmax(z_s)[y_s] and dz_s = (softmax(z_s) - e_{y_s}) / b_k
  * (the 1/|b_k| of equation bspweightedgrads), then L_k and sum_k lambda_k L_k.

@@ -27,6 +27,7 @@ EXPORTS = [
     "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
+    "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
 ]
 KERNEL_CLASSES = {"linear_fwd": 0, "linear_dgrad": 1, "linear_wgrad": 2, "loss": 3, "update": 4,
                   "conv_fwd": 5, "conv_dgrad": 6, "conv_wgrad": 7}
@@ -79,6 +80,9 @@ def _load():
     lib.omni_net_timing_read.argtypes = [vp, P(C.c_double), P(C.c_int64)]
     lib.omni_weighted_sgd.argtypes = [vp, vp, vp, sz, sz, P(i32), i32, f32, vp]
     lib.omni_softmax_xent.argtypes = [vp, vp, vp, i32, P(i32), i32, vp, vp, vp, vp, vp]
+    lib.omni_weighted_sgd_momentum.argtypes = [vp, vp, vp, vp, sz, sz, P(i32), i32, f32, f32, f32, vp]
+    lib.omni_net_set_momentum.argtypes = [vp, vp, f32, f32]
+    lib.omni_lr_step_decay.argtypes = [C.c_double, C.c_double, P(i32), i32, i32, P(C.c_double)]
     return lib
 
 
@@ -220,6 +224,28 @@ def weighted_sgd(params, grads, b, lr, shadow_bf16=None, P=None, stream=None):
     P = params.numel() if P is None else P
     _check(lib.omni_weighted_sgd(stream if stream is not None else _stream(), _ptr(params), _ptr(grads), stride, P,
                                  _i32(b), K, float(lr), _ptr(shadow_bf16)))
+
+
+def weighted_sgd_momentum(params, velocity, grads, b, lr, momentum, weight_decay, shadow_bf16=None, P=None,
+                          stream=None):
+    K = len(b)
+    stride = grads.stride(0)
+    P = params.numel() if P is None else P
+    _check(lib.omni_weighted_sgd_momentum(stream if stream is not None else _stream(), _ptr(params), _ptr(velocity),
+                                          _ptr(grads), stride, P, _i32(b), K, float(lr), float(momentum),
+                                          float(weight_decay), _ptr(shadow_bf16)))
+
+
+def net_set_momentum(net, velocity, momentum, weight_decay):
+    _check(lib.omni_net_set_momentum(net, _ptr(velocity), float(momentum), float(weight_decay)))
+
+
+def lr_step_decay(lr0, gamma, milestones, epoch):
+    out = C.c_double(0.0)
+    n = len(milestones)
+    arr = _i32(milestones) if n else None
+    _check(lib.omni_lr_step_decay(float(lr0), float(gamma), arr, n, int(epoch), C.byref(out)))
+    return out.value
 
 
 def softmax_xent(z, labels, off, dz, loss_rows, loss_per_worker, loss, status, stream=None):

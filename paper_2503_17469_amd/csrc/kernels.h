@@ -111,8 +111,11 @@ void gap_bwd_bf16(hipStream_t st, const bf16_t* dout, const bf16_t* mask, bf16_t
 void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int C, const Segments& seg,
                       float* dz, float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status);
 // params[j] -= lr * sum_k lambda[k] * grads[k*stride + j]; optional bf16 copy of the result.
+// velocity == nullptr: plain SGD.  Otherwise d = g + weight_decay*theta, velocity = momentum*velocity + d,
+// theta -= lr*velocity (velocity [P], read and written).
 void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
-                      const Segments& seg, float lr, uint16_t* shadow_bf16);
+                      const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity = nullptr,
+                      float momentum = 0.f, float weight_decay = 0.f);
 void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v);
 
 }  // namespace omni

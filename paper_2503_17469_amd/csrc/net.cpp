@@ -61,6 +61,9 @@ struct omni_net {
   int bn_cmax = 0;
   int classes = 0;
   const void* ws_ready = nullptr;   // workspace whose arrival counters are known to be zero
+  // optimiser: velocity == nullptr is plain SGD
+  float* velocity = nullptr;
+  float momentum = 0.f, weight_decay = 0.f;
   // Side stream for parameter-gradient kernels: they only feed the final update,
   // so they run beside the input-gradient chain instead of in front of it.
   hipStream_t side = nullptr;
@@ -675,7 +678,8 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   // ---- weighted aggregation + update
   if (!(flags & OMNI_STEP_NO_UPDATE)) {
     TimedScope ts(net, c.st, OMNI_KERNEL_UPDATE, -1);
-    omni::weighted_sgd_f32(c.st, params, c.G, net->P_stride, net->P, c.seg, lr, nullptr);
+    omni::weighted_sgd_f32(c.st, params, c.G, net->P_stride, net->P, c.seg, lr, nullptr, net->velocity,
+                           net->momentum, net->weight_decay);
   }
 
   hipError_t e = hipGetLastError();
@@ -705,6 +709,67 @@ int omni_weighted_sgd(void* stream, float* params, const float* grads, size_t st
                          static_cast<uint16_t*>(shadow_bf16));
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(OMNI_EHIP, "omni_weighted_sgd: launch failed: %s", hipGetErrorString(e));
+  return OMNI_OK;
+}
+
+static int check_momentum(const char* who, float momentum, float weight_decay) {
+  if (!std::isfinite(momentum) || momentum < 0.f || momentum >= 1.f)
+    return fail(OMNI_EINVAL, "%s: momentum must lie in [0, 1)", who);
+  if (!std::isfinite(weight_decay) || weight_decay < 0.f)
+    return fail(OMNI_EINVAL, "%s: weight_decay must be finite and >= 0", who);
+  return OMNI_OK;
+}
+
+int omni_weighted_sgd_momentum(void* stream, float* params, float* velocity, const float* grads, size_t stride,
+                               size_t P, const int32_t* b, int32_t K, float lr, float momentum, float weight_decay,
+                               void* shadow_bf16) {
+  if (!params || !velocity || !grads || !b) return fail(OMNI_EINVAL, "omni_weighted_sgd_momentum: NULL argument");
+  if (K < 1 || K > OMNI_MAX_WORKERS)
+    return fail(K < 1 ? OMNI_EINVAL : OMNI_ECAPACITY, "omni_weighted_sgd_momentum: K=%d", K);
+  if (P < 1 || stride < P || (stride & 3u))
+    return fail(OMNI_EINVAL, "omni_weighted_sgd_momentum: need P >= 1 and stride >= P, stride %% 4 == 0");
+  if ((reinterpret_cast<uintptr_t>(params) & 15u) || (reinterpret_cast<uintptr_t>(grads) & 15u) ||
+      (reinterpret_cast<uintptr_t>(velocity) & 15u) || (reinterpret_cast<uintptr_t>(shadow_bf16) & 7u))
+    return fail(OMNI_EINVAL, "omni_weighted_sgd_momentum: params/velocity/grads must be 16-byte aligned");
+  if (!std::isfinite(lr)) return fail(OMNI_EINVAL, "omni_weighted_sgd_momentum: lr is not finite");
+  if (int rc = check_momentum("omni_weighted_sgd_momentum", momentum, weight_decay)) return rc;
+  omni::Segments seg{};
+  seg.K = K;
+  int64_t acc = 0;
+  for (int k = 0; k < K; ++k) {
+    if (b[k] < 1) return fail(OMNI_EINVAL, "omni_weighted_sgd_momentum: b[%d]=%d must be at least 1", k, b[k]);
+    acc += b[k];
+    if (acc > INT32_MAX) return fail(OMNI_EOVERFLOW, "omni_weighted_sgd_momentum: sum of b overflows");
+    seg.off[k + 1] = (int32_t)acc;
+  }
+  omni::weighted_sgd_f32(static_cast<hipStream_t>(stream), params, grads, stride, P, seg, lr,
+                         static_cast<uint16_t*>(shadow_bf16), velocity, momentum, weight_decay);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(OMNI_EHIP, "omni_weighted_sgd_momentum: launch failed: %s", hipGetErrorString(e));
+  return OMNI_OK;
+}
+
+int omni_net_set_momentum(omni_net* net, float* velocity, float momentum, float weight_decay) {
+  if (!net) return fail(OMNI_EINVAL, "omni_net_set_momentum: NULL net");
+  if (!velocity) {
+    net->velocity = nullptr; net->momentum = 0.f; net->weight_decay = 0.f;
+    return OMNI_OK;
+  }
+  if (reinterpret_cast<uintptr_t>(velocity) & 15u)
+    return fail(OMNI_EINVAL, "omni_net_set_momentum: velocity must be 16-byte aligned");
+  if (int rc = check_momentum("omni_net_set_momentum", momentum, weight_decay)) return rc;
+  net->velocity = velocity; net->momentum = momentum; net->weight_decay = weight_decay;
+  return OMNI_OK;
+}
+
+int omni_lr_step_decay(double lr0, double gamma, const int32_t* milestones, int32_t n, int32_t epoch,
+                       double* lr_out) {
+  if (!lr_out || n < 0 || (n > 0 && !milestones)) return fail(OMNI_EINVAL, "omni_lr_step_decay: bad argument");
+  if (!std::isfinite(lr0) || !std::isfinite(gamma)) return fail(OMNI_EINVAL, "omni_lr_step_decay: lr0/gamma not finite");
+  double lr = lr0;
+  for (int i = 0; i < n; ++i)
+    if (epoch >= milestones[i]) lr *= gamma;
+  *lr_out = lr;
   return OMNI_OK;
 }
 

@@ -114,10 +114,28 @@ __device__ inline uint16_t bf16_rne(float f) {
 // The gradient rows are read exactly once (streaming, non-temporal loads); two
 // 16-byte columns per thread are in flight together so that 2*(K+1) loads cover
 // the HBM latency.
-template <bool SHADOW>
-__global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ params,
+// MOM: the momentum / weight-decay update of the paper's experiments (velocity is read and
+// written beside the parameters: (K+4)*4 bytes per parameter instead of (K+2)*4):
+//   d = g + wd*theta;  v = mu*v + d;  theta -= lr*v.
+struct Optim {
+  float lr, momentum, weight_decay;
+};
+
+template <bool MOM>
+__device__ inline void apply_update(v4f& th, v4f& v, const v4f& g, const Optim& o) {
+  if (MOM) {
+    const v4f d = g + o.weight_decay * th;
+    v = o.momentum * v + d;
+    th = th - o.lr * v;
+  } else {
+    th = th - o.lr * g;
+  }
+}
+
+template <bool SHADOW, bool MOM>
+__global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ params, float* __restrict__ velocity,
                                                            const float* __restrict__ grads, size_t stride,
-                                                           size_t P, int K, Lambdas lam, float lr,
+                                                           size_t P, int K, Lambdas lam, Optim opt,
                                                            uint16_t* __restrict__ shadow) {
   const size_t n4 = P / 4;
   const size_t nthreads = (size_t)gridDim.x * blockDim.x;
@@ -127,8 +145,13 @@ __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ p
     const bool has1 = i1 < n4;
     const size_t j1 = has1 ? i1 : i0;          // the second column re-reads the first when past the end
     v4f g0 = {0.f, 0.f, 0.f, 0.f}, g1 = {0.f, 0.f, 0.f, 0.f};
-    const v4f th0 = *reinterpret_cast<const v4f*>(params + 4 * i0);
-    const v4f th1 = *reinterpret_cast<const v4f*>(params + 4 * j1);
+    v4f th0 = *reinterpret_cast<const v4f*>(params + 4 * i0);
+    v4f th1 = *reinterpret_cast<const v4f*>(params + 4 * j1);
+    v4f v0 = {0.f, 0.f, 0.f, 0.f}, v1 = {0.f, 0.f, 0.f, 0.f};
+    if (MOM) {
+      v0 = *reinterpret_cast<const v4f*>(velocity + 4 * i0);
+      v1 = *reinterpret_cast<const v4f*>(velocity + 4 * j1);
+    }
     int k = 0;
     for (; k + 4 <= K; k += 4) {
       v4f a[4], c[4];
@@ -147,15 +170,20 @@ __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ p
       g0 += lam.v[k] * __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * i0));
       g1 += lam.v[k] * __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * j1));
     }
-    const v4f n0 = th0 - lr * g0, n1 = th1 - lr * g1;
-    *reinterpret_cast<v4f*>(params + 4 * i0) = n0;
-    if (has1) *reinterpret_cast<v4f*>(params + 4 * i1) = n1;
+    apply_update<MOM>(th0, v0, g0, opt);
+    apply_update<MOM>(th1, v1, g1, opt);
+    *reinterpret_cast<v4f*>(params + 4 * i0) = th0;
+    if (has1) *reinterpret_cast<v4f*>(params + 4 * i1) = th1;
+    if (MOM) {
+      *reinterpret_cast<v4f*>(velocity + 4 * i0) = v0;
+      if (has1) *reinterpret_cast<v4f*>(velocity + 4 * i1) = v1;
+    }
     if (SHADOW) {
       ushort4 s;
-      s.x = bf16_rne(n0[0]); s.y = bf16_rne(n0[1]); s.z = bf16_rne(n0[2]); s.w = bf16_rne(n0[3]);
+      s.x = bf16_rne(th0[0]); s.y = bf16_rne(th0[1]); s.z = bf16_rne(th0[2]); s.w = bf16_rne(th0[3]);
       *reinterpret_cast<ushort4*>(shadow + 4 * i0) = s;
       if (has1) {
-        s.x = bf16_rne(n1[0]); s.y = bf16_rne(n1[1]); s.z = bf16_rne(n1[2]); s.w = bf16_rne(n1[3]);
+        s.x = bf16_rne(th1[0]); s.y = bf16_rne(th1[1]); s.z = bf16_rne(th1[2]); s.w = bf16_rne(th1[3]);
         *reinterpret_cast<ushort4*>(shadow + 4 * i1) = s;
       }
     }
@@ -165,7 +193,15 @@ __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ p
     const size_t j = n4 * 4 + threadIdx.x;
     float g = 0.f;
     for (int k = 0; k < K; ++k) g += lam.v[k] * grads[(size_t)k * stride + j];
-    const float th = params[j] - lr * g;
+    float th = params[j];
+    if (MOM) {
+      const float d = g + opt.weight_decay * th;
+      const float v = opt.momentum * velocity[j] + d;
+      velocity[j] = v;
+      th = th - opt.lr * v;
+    } else {
+      th = th - opt.lr * g;
+    }
     params[j] = th;
     if (SHADOW) shadow[j] = bf16_rne(th);
   }
@@ -187,20 +223,26 @@ void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int
 }
 
 void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
-                      const Segments& seg, float lr, uint16_t* shadow_bf16) {
+                      const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity, float momentum,
+                      float weight_decay) {
   Lambdas lam{};
   const double B = (double)seg.off[seg.K];
   for (int k = 0; k < seg.K; ++k) lam.v[k] = (float)((double)(seg.off[k + 1] - seg.off[k]) / B);
+  const Optim opt{lr, momentum, weight_decay};
   const size_t n4 = P / 4;
   size_t blocks = (n4 + 511) / 512;          // two columns per thread per trip
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
-  if (shadow_bf16)
-    hipLaunchKernelGGL(weighted_sgd_kernel<true>, dim3((unsigned)blocks), dim3(256), 0, st, params, grads, stride,
-                       P, seg.K, lam, lr, shadow_bf16);
-  else
-    hipLaunchKernelGGL(weighted_sgd_kernel<false>, dim3((unsigned)blocks), dim3(256), 0, st, params, grads, stride,
-                       P, seg.K, lam, lr, shadow_bf16);
+  const dim3 grid((unsigned)blocks), block(256);
+#define OMNI_UPD(SH, MO)                                                                                         \
+  hipLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, params, velocity, grads, stride, P, seg.K, \
+                     lam, opt, shadow_bf16)
+  if (velocity) {
+    if (shadow_bf16) OMNI_UPD(true, true); else OMNI_UPD(false, true);
+  } else {
+    if (shadow_bf16) OMNI_UPD(true, false); else OMNI_UPD(false, false);
+  }
+#undef OMNI_UPD
 }
 
 void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v) {

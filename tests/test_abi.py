@@ -118,3 +118,19 @@ def test_net_create_validation_needs_no_gpu():
         omni.net_create(bad, (1, 1, 8), "f32", 1, 4)
     with pytest.raises(omni.OmniError):
         omni.net_create(w.layers, w.in_shape, "f32", 65, 480)
+
+
+def test_lr_step_decay_matches_oracle():
+    from oracle import optim as OO
+    import random
+    rnd = random.Random(3)
+    for _ in range(200):
+        n = rnd.randint(0, 5)
+        ms = sorted(rnd.sample(range(1, 200), n))
+        lr0, gamma, e = rnd.choice([0.1, 0.01, 0.5]), rnd.choice([0.1, 0.2, 0.5]), rnd.randint(0, 220)
+        # (repeated multiplication in the library, a power in the oracle: a few ulp apart)
+        assert omni.lr_step_decay(lr0, gamma, ms, e) == pytest.approx(OO.lr_step_decay(lr0, gamma, ms, e), rel=1e-13)
+    # the schedule of the paper's ResNet18 run: 0.1 divided by 10 after 15, 30 and 45 epochs
+    assert [round(omni.lr_step_decay(0.1, 0.1, [15, 30, 45], e), 10) for e in (0, 15, 30, 45)] == [0.1, 0.01, 0.001, 0.0001]
+    with pytest.raises(omni.OmniError):
+        omni.lr_step_decay(float("inf"), 0.1, [1], 0)

@@ -96,3 +96,57 @@ def test_softmax_xent(C, off):
         assert abs(loss.item() - L) <= 1e-5 * abs(L)
     else:
         assert np.abs(dzd.cpu().numpy()).max() == 0 and abs(loss.item()) == 0
+
+
+@pytest.mark.parametrize("P,K,mu,wd", [(9610, 2, 0.9, 5e-4), (4206602, 4, 0.9, 5e-4), (1027, 5, 0.5, 0.0),
+                                       (3, 1, 0.9, 1e-4), (113738, 16, 0.0, 5e-4)])
+def test_weighted_sgd_momentum(P, K, mu, wd):
+    """Four consecutive updates with the velocity carried along, against the fp64 oracle
+    free-running from the same start (fp32 rounding of four steps stays far inside 1e-4)."""
+    import torch
+    import paper_2503_17469_amd as omni
+    from oracle import optim as OO
+    print(f"case weighted_sgd_momentum P={P} K={K} mu={mu} wd={wd}", flush=True)
+    rng = np.random.default_rng(P * 7 + K)
+    stride = (P + 63) // 64 * 64
+    theta = rng.standard_normal(P).astype(np.float32)
+    b = [int(v) for v in rng.integers(1, 300, K)]
+    lr = 0.05
+    th = torch.from_numpy(theta).cuda()
+    vel = torch.zeros(P, device="cuda")
+    shadow = torch.zeros(P, dtype=torch.bfloat16, device="cuda")
+    ref_t, ref_v = theta.astype(np.float64), np.zeros(P)
+    for s in range(4):
+        G = np.zeros((K, stride), dtype=np.float32)
+        G[:, :P] = rng.standard_normal((K, P)).astype(np.float32)
+        omni.weighted_sgd_momentum(th, vel, torch.from_numpy(G).cuda(), b, lr, mu, wd, shadow_bf16=shadow)
+        ref_t, ref_v, _ = OO.weighted_momentum_step(ref_t, ref_v, G[:, :P], b, lr, mu, wd)
+    torch.cuda.synchronize()
+    got_t, got_v = th.cpu().numpy(), vel.cpu().numpy()
+    assert_close(got_t, ref_t, 1e-4, "theta after 4 steps")
+    assert_close(got_v, ref_v, 1e-4, "velocity after 4 steps")
+    assert np.array_equal(shadow.float().cpu().numpy().astype(np.float64), OL.round_bf16(got_t))
+
+
+def test_weighted_sgd_momentum_degenerate_and_rejects():
+    import torch
+    import paper_2503_17469_amd as omni
+    rng = np.random.default_rng(5)
+    P, K = 1000, 3
+    theta = rng.standard_normal(P).astype(np.float32)
+    G = torch.from_numpy(rng.standard_normal((K, 1024)).astype(np.float32)).cuda()
+    b = [3, 1, 9]
+    # momentum 0, weight decay 0: the plain update, bit for bit; velocity receives the aggregate
+    t1, t2 = torch.from_numpy(theta).cuda(), torch.from_numpy(theta).cuda()
+    vel = torch.zeros(P, device="cuda")
+    omni.weighted_sgd(t1, G, b, 0.1, P=P)
+    omni.weighted_sgd_momentum(t2, vel, G, b, 0.1, 0.0, 0.0, P=P)
+    torch.cuda.synchronize()
+    assert torch.equal(t1, t2)
+    for bad in (dict(momentum=1.0), dict(momentum=-0.1), dict(weight_decay=-1e-3), dict(momentum=float("nan"))):
+        kw = dict(momentum=0.9, weight_decay=5e-4)
+        kw.update(bad)
+        with pytest.raises(omni.OmniError):
+            omni.weighted_sgd_momentum(t2, vel, G, b, 0.1, kw["momentum"], kw["weight_decay"], P=P)
+    with pytest.raises(omni.OmniError):
+        omni.weighted_sgd_momentum(t2, None, G, b, 0.1, 0.9, 0.0, P=P)

@@ -135,3 +135,47 @@ def test_bad_label_sets_status():
         assert np.all(np.isfinite(got["params"]))
     finally:
         run.close()
+
+
+def test_step_with_momentum_and_weight_decay():
+    """Three steps of omni_step with the momentum update selected, against the oracle chain
+    (per-step fp64 gradients from the oracle's own parameters, then the momentum oracle)."""
+    import torch
+    import paper_2503_17469_amd as omni
+    from oracle import optim as OO
+    dims, off = [96, 64, 32, 10], [0, 5, 6, 29, 40]
+    layers = synth.mlp(dims)
+    rng = np.random.default_rng(17)
+    params = synth.he_normal_params(layers, 9, False)
+    B, K = off[-1], len(off) - 1
+    b = [off[k + 1] - off[k] for k in range(K)]
+    lr, mu, wd = 0.05, 0.9, 5e-4
+    run = GpuRun(layers, (1, 1, dims[0]), "f32", K, B)
+    try:
+        th = torch.from_numpy(params).cuda()
+        vel = torch.zeros_like(th)
+        omni.net_set_momentum(run.net, vel, mu, wd)
+        lpw, loss = torch.zeros(K, device="cuda"), torch.zeros(1, device="cuda")
+        ref_t, ref_v = params.astype(np.float64), np.zeros(params.size)
+        for s in range(3):
+            x = rng.standard_normal((B, dims[0])).astype(np.float32)
+            y = rng.integers(0, dims[-1], B).astype(np.int32)
+            omni.step(run.net, th, torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), off, b, lr, run.ws, lpw, loss)
+            ref = OS.sgd_step(layers, ref_t, x, y, off, lr)
+            ref_t, ref_v, _ = OO.weighted_momentum_step(ref_t, ref_v, ref.worker_grads, b, lr, mu, wd)
+            torch.cuda.synchronize()
+            assert abs(float(loss.item()) - ref.loss) <= 1e-4 * abs(ref.loss), f"step {s} loss"
+        assert_close(th.cpu().numpy(), ref_t, 1e-4, "theta after 3 momentum steps")
+        assert_close(vel.cpu().numpy(), ref_v, 1e-4, "velocity after 3 momentum steps")
+        # back to plain SGD: one more step changes theta by exactly -lr * g (velocity untouched)
+        omni.net_set_momentum(run.net, None, 0.0, 0.0)
+        v_before = vel.clone()
+        x = rng.standard_normal((B, dims[0])).astype(np.float32)
+        y = rng.integers(0, dims[-1], B).astype(np.int32)
+        omni.step(run.net, th, torch.from_numpy(x).cuda(), torch.from_numpy(y).cuda(), off, b, lr, run.ws, lpw, loss)
+        torch.cuda.synchronize()
+        assert torch.equal(vel, v_before)
+        ref = OS.sgd_step(layers, ref_t, x, y, off, lr)
+        assert_close(th.cpu().numpy(), ref.params, 1e-4, "theta after returning to plain SGD")
+    finally:
+        run.close()
