@@ -90,6 +90,38 @@ int omni_ctl_run(omni_ctl* ctl, int32_t* b_out, int32_t* off_out);
 
 void omni_ctl_destroy(omni_ctl* ctl);
 
+/* ------------------------------------------------------------------ measured-time controller
+ * Procedure getBsz of Algorithm 1 with the stability kit of section "Control Stability
+ * for Dynamic-Batching": workers report the time one iteration took (omni_dyn_observe);
+ * the controller smooths it (newest-sample weight alpha; the average restarts after
+ * every adjustment) and, at the end of an epoch (omni_dyn_adjust), proposes
+ * b* = b - T (t - t_avg), T = b / t (equations itrtimeerror, dynbszadjust), accepts it
+ * only if |b* - b| / b* >= deadband (equation omnibszdeadbandlimit), and applies the
+ * bounds and the global-batch rule:
+ *   OMNI_RULE_NONE            each worker decides for itself; accepted b* is clamped to
+ *                             [b_min, b_max] and rounded to nearest (ties to even); the
+ *                             global batch may drift;
+ *   OMNI_RULE_MULTIPLICATIVE  all workers move if any ratio reaches the dead-band; the
+ *                             b* are rescaled to sum B ("proportionately", the text after
+ *                             equation dynbszGlobalBFixed) and made integer inside the
+ *                             bounds by largest remainder;
+ *   OMNI_RULE_ADDITIVE        equation dynbszGlobalBFixed as printed: every b* loses
+ *                             (sum b* - B) / K, is clamped and rounded (the sum is B only
+ *                             up to rounding and while no clamp fires).
+ * Host only, IEEE double arithmetic in a fixed operation order (results repeat bit for
+ * bit).  b_init host [K] or NULL for Algorithm 1's uniform start B / K; b_max = 0 means
+ * B; times host [K], positive and finite, any common unit.  b_out [K], off_out [K+1],
+ * changed_out may each be NULL.  omni_dyn_adjust without an observation since the last
+ * adjustment is OMNI_EINVAL; infeasible bounds are OMNI_EINFEASIBLE. */
+typedef struct omni_dyn omni_dyn;
+enum { OMNI_RULE_NONE = 0, OMNI_RULE_MULTIPLICATIVE = 1, OMNI_RULE_ADDITIVE = 2 };
+int omni_dyn_create(int32_t K, int32_t B, int32_t b_min, int32_t b_max, double deadband,
+                    double ewma_alpha, int32_t global_rule, const int32_t* b_init, omni_dyn** out);
+int omni_dyn_observe(omni_dyn* ctl, const double* t);
+int omni_dyn_adjust(omni_dyn* ctl, int32_t* b_out, int32_t* off_out, int32_t* changed_out);
+int omni_dyn_get(const omni_dyn* ctl, int32_t* b_out, int32_t* off_out);
+void omni_dyn_destroy(omni_dyn* ctl);
+
 /* ------------------------------------------------------------------ network
  * A network is a list of layers over channels-last activations [rows, H, W, C].
  * `src` / `src2` name the producing layer (-1 = the network input); src2 is

@@ -28,7 +28,9 @@ EXPORTS = [
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
     "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
+    "omni_dyn_create", "omni_dyn_observe", "omni_dyn_adjust", "omni_dyn_get", "omni_dyn_destroy",
 ]
+RULES = {"none": 0, "multiplicative": 1, "additive": 2}
 KERNEL_CLASSES = {"linear_fwd": 0, "linear_dgrad": 1, "linear_wgrad": 2, "loss": 3, "update": 4,
                   "conv_fwd": 5, "conv_dgrad": 6, "conv_wgrad": 7}
 
@@ -83,6 +85,12 @@ def _load():
     lib.omni_weighted_sgd_momentum.argtypes = [vp, vp, vp, vp, sz, sz, P(i32), i32, f32, f32, f32, vp]
     lib.omni_net_set_momentum.argtypes = [vp, vp, f32, f32]
     lib.omni_lr_step_decay.argtypes = [C.c_double, C.c_double, P(i32), i32, i32, P(C.c_double)]
+    lib.omni_dyn_create.argtypes = [i32, i32, i32, i32, C.c_double, C.c_double, i32, P(i32), P(vp)]
+    lib.omni_dyn_observe.argtypes = [vp, P(C.c_double)]
+    lib.omni_dyn_adjust.argtypes = [vp, P(i32), P(i32), P(i32)]
+    lib.omni_dyn_get.argtypes = [vp, P(i32), P(i32)]
+    lib.omni_dyn_destroy.argtypes = [vp]
+    lib.omni_dyn_destroy.restype = None
     return lib
 
 
@@ -246,6 +254,37 @@ def lr_step_decay(lr0, gamma, milestones, epoch):
     arr = _i32(milestones) if n else None
     _check(lib.omni_lr_step_decay(float(lr0), float(gamma), arr, n, int(epoch), C.byref(out)))
     return out.value
+
+
+def dyn_create(K, B, b_min=1, b_max=0, deadband=0.0, alpha=1.0, rule="multiplicative", b_init=None):
+    h = C.c_void_p()
+    init = _i32(b_init) if b_init is not None else None
+    _check(lib.omni_dyn_create(K, B, b_min, b_max, float(deadband), float(alpha), RULES[rule], init, C.byref(h)))
+    return h
+
+
+def dyn_observe(ctl, t):
+    arr = (C.c_double * len(t))(*[float(x) for x in t])
+    _check(lib.omni_dyn_observe(ctl, arr))
+
+
+def dyn_adjust(ctl, K):
+    b = (C.c_int32 * K)()
+    off = (C.c_int32 * (K + 1))()
+    changed = C.c_int32(0)
+    _check(lib.omni_dyn_adjust(ctl, b, off, C.byref(changed)))
+    return list(b), list(off), bool(changed.value)
+
+
+def dyn_get(ctl, K):
+    b = (C.c_int32 * K)()
+    off = (C.c_int32 * (K + 1))()
+    _check(lib.omni_dyn_get(ctl, b, off))
+    return list(b), list(off)
+
+
+def dyn_destroy(ctl):
+    lib.omni_dyn_destroy(ctl)
 
 
 def softmax_xent(z, labels, off, dz, loss_rows, loss_per_worker, loss, status, stream=None):

@@ -30,7 +30,8 @@ def build(verbose: bool = False, jobs: int = 8) -> str:
         if src.endswith(".hip"):
             cmd[1:1] = DEVICE_FLAGS
         else:
-            cmd[1:1] = ["-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include"]
+            # host code: no fused multiply-adds (the measured-time controller's doubles must repeat bit for bit)
+            cmd[1:1] = ["-x", "c++", "-D__HIP_PLATFORM_AMD__", "-I/opt/rocm/include", "-ffp-contract=off"]
             cmd[0] = os.environ.get("CXX", "g++")
         r = subprocess.run(cmd, capture_output=True, text=True)
         if verbose or r.returncode != 0:

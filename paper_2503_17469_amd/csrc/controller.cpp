@@ -59,6 +59,53 @@ void largest_remainder(const uint64_t* T, const int* ids, int n, int64_t total, 
 
 }  // namespace
 
+namespace omni {
+
+// Integer batch sizes proportional to the weights T with sum B inside [b_min, b_max]: largest
+// remainder; if a share falls outside the bounds, the side with the larger total violation is
+// clamped, those workers leave the pool with their units, and the rest is apportioned again.
+int apportion_bounded(const uint64_t* T, int K, int64_t B, int64_t b_min, int64_t b_max, int64_t* b,
+                      const char* who) {
+  int ids[OMNI_MAX_WORKERS];
+  int64_t share[OMNI_MAX_WORKERS];
+  int n = K;
+  for (int k = 0; k < K; ++k) ids[k] = k;
+  int64_t remaining = B;
+  for (;;) {
+    if (n == 0) {
+      if (remaining != 0) return fail(OMNI_EINFEASIBLE, "%s: clamping left %lld units", who, (long long)remaining);
+      break;
+    }
+    if (remaining < 0) return fail(OMNI_EINFEASIBLE, "%s: clamping over-assigned", who);
+    largest_remainder(T, ids, n, remaining, share);
+    int64_t deficit = 0, excess = 0;
+    int n_low = 0, n_high = 0;
+    for (int i = 0; i < n; ++i) {
+      if (share[i] < b_min) { deficit += b_min - share[i]; ++n_low; }
+      if (share[i] > b_max) { excess += share[i] - b_max; ++n_high; }
+    }
+    if (!n_low && !n_high) {
+      for (int i = 0; i < n; ++i) b[ids[i]] = share[i];
+      break;
+    }
+    const bool clamp_high = n_high && excess >= deficit;
+    int m = 0;
+    for (int i = 0; i < n; ++i) {
+      const bool hit = clamp_high ? share[i] > b_max : share[i] < b_min;
+      if (hit) {
+        b[ids[i]] = clamp_high ? b_max : b_min;
+        remaining -= b[ids[i]];
+      } else {
+        ids[m++] = ids[i];
+      }
+    }
+    n = m;
+  }
+  return OMNI_OK;
+}
+
+}  // namespace omni
+
 extern "C" {
 
 const char* omni_last_error(void) { return omni::g_err; }
@@ -92,46 +139,11 @@ int omni_ctl_set_throughputs(omni_ctl* ctl, const uint64_t* T) {
 int omni_ctl_run(omni_ctl* ctl, int32_t* b_out, int32_t* off_out) {
   if (!ctl || !b_out || !off_out) return omni::fail(OMNI_EINVAL, "omni_ctl_run: NULL argument");
   if (!ctl->have_T) return omni::fail(OMNI_EINVAL, "omni_ctl_run: throughputs not set");
-  const int K = ctl->K;
-  int ids[OMNI_MAX_WORKERS];
-  int64_t share[OMNI_MAX_WORKERS];
   int64_t b[OMNI_MAX_WORKERS];
-  int n = K;
-  for (int k = 0; k < K; ++k) ids[k] = k;
-  int64_t remaining = ctl->B;
-  for (;;) {
-    if (n == 0) {
-      if (remaining != 0) return omni::fail(OMNI_EINFEASIBLE, "omni_ctl_run: clamping left %lld units", (long long)remaining);
-      break;
-    }
-    if (remaining < 0) return omni::fail(OMNI_EINFEASIBLE, "omni_ctl_run: clamping over-assigned");
-    largest_remainder(ctl->T, ids, n, remaining, share);
-    int64_t deficit = 0, excess = 0;
-    int n_low = 0, n_high = 0;
-    for (int i = 0; i < n; ++i) {
-      if (share[i] < ctl->b_min) { deficit += ctl->b_min - share[i]; ++n_low; }
-      if (share[i] > ctl->b_max) { excess += share[i] - ctl->b_max; ++n_high; }
-    }
-    if (!n_low && !n_high) {
-      for (int i = 0; i < n; ++i) b[ids[i]] = share[i];
-      break;
-    }
-    const bool clamp_high = n_high && excess >= deficit;
-    int m = 0;
-    for (int i = 0; i < n; ++i) {
-      const bool hit = clamp_high ? share[i] > ctl->b_max : share[i] < ctl->b_min;
-      if (hit) {
-        b[ids[i]] = clamp_high ? ctl->b_max : ctl->b_min;
-        remaining -= b[ids[i]];
-      } else {
-        ids[m++] = ids[i];
-      }
-    }
-    n = m;
-  }
+  if (int rc = omni::apportion_bounded(ctl->T, ctl->K, ctl->B, ctl->b_min, ctl->b_max, b, "omni_ctl_run")) return rc;
   int64_t acc = 0;
   off_out[0] = 0;
-  for (int k = 0; k < K; ++k) {
+  for (int k = 0; k < ctl->K; ++k) {
     b_out[k] = (int32_t)b[k];
     acc += b[k];
     off_out[k + 1] = (int32_t)acc;

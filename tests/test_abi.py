@@ -134,3 +134,61 @@ def test_lr_step_decay_matches_oracle():
     assert [round(omni.lr_step_decay(0.1, 0.1, [15, 30, 45], e), 10) for e in (0, 15, 30, 45)] == [0.1, 0.01, 0.001, 0.0001]
     with pytest.raises(omni.OmniError):
         omni.lr_step_decay(float("inf"), 0.1, [1], 0)
+
+
+def test_measured_time_controller_matches_oracle_bit_for_bit():
+    """Random heterogeneity walks with noisy times: the library and the oracle must agree on every
+    integer at every adjustment, in all three global-batch modes."""
+    from oracle import dyncontrol as OD
+    import random
+    rnd = random.Random(11)
+    for trial in range(300):
+        K = rnd.randint(1, 16)
+        B = rnd.randint(K, 64 * K)
+        b_min = rnd.choice([1, 1, 2, 4])
+        b_max = rnd.choice([0, 0, max(b_min, (2 * B) // K), max(b_min, (3 * B + K - 1) // K)])
+        if K * b_min > B or (b_max and K * b_max < B):
+            continue
+        rule = rnd.choice(["none", "multiplicative", "additive"])
+        dead = rnd.choice([0.0, 0.05, 0.1, 0.15])
+        alpha = rnd.choice([1.0, 0.5, 0.25, 0.9])
+        ref = OD.DynController(K, B, b_min, b_max or None, dead, alpha, omni.binding.RULES[rule])
+        ctl = omni.dyn_create(K, B, b_min, b_max, dead, alpha, rule)
+        try:
+            assert omni.dyn_get(ctl, K) == (ref.b, OD.offsets(ref.b))
+            T = [rnd.uniform(1.0, 8.0) for _ in range(K)]
+            for epoch in range(6):
+                if rnd.random() < 0.3:
+                    T = [rnd.uniform(1.0, 8.0) for _ in range(K)]
+                for it in range(rnd.randint(1, 4)):
+                    t = [ref.b[k] / T[k] * rnd.uniform(0.9, 1.1) for k in range(K)]
+                    ref.observe(t)
+                    omni.dyn_observe(ctl, t)
+                want = ref.adjust()
+                got = omni.dyn_adjust(ctl, K)
+                assert got == want, (trial, epoch, rule, got, want)
+                if rule == "multiplicative":
+                    assert sum(got[0]) == B
+        finally:
+            omni.dyn_destroy(ctl)
+
+
+def test_measured_time_controller_errors():
+    with pytest.raises(omni.OmniError):
+        omni.dyn_create(4, 3)                      # fewer samples than workers
+    with pytest.raises(omni.OmniError):
+        omni.dyn_create(4, 128, deadband=1.0)
+    with pytest.raises(omni.OmniError):
+        omni.dyn_create(4, 128, alpha=0.0)
+    ctl = omni.dyn_create(4, 128, 12, 96, 0.15, 1.0, "none")
+    try:
+        with pytest.raises(omni.OmniError):
+            omni.dyn_adjust(ctl, 4)                # nothing observed yet
+        with pytest.raises(omni.OmniError):
+            omni.dyn_observe(ctl, [1.0, 0.0, 1.0, 1.0])
+        # the paper's static experiment: HL8 cores (6, 6, 4, 32), initial batch 32, bounds (12, 96), 15 % dead-band
+        omni.dyn_observe(ctl, [32 / 6, 32 / 6, 32 / 4, 32 / 32])
+        b, off, changed = omni.dyn_adjust(ctl, 4)
+        assert changed and b[3] == 96 and min(b) >= 12 and off[-1] == sum(b)
+    finally:
+        omni.dyn_destroy(ctl)
