@@ -237,7 +237,8 @@ def main():
                             "note": "working set below 256 MB may be served from the Infinity Cache"},
         "roofline_update_momentum": {"bound": "hbm", "kernel": "weighted reduce + momentum SGD with weight decay",
                                      "achieved": mom_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                     "frac": mom_gbs / PEAK_HBM_GBS, "traffic": None, "bytes_per_launch": mom_bytes,
+                                     "frac": mom_gbs / PEAK_HBM_GBS,
+                                     "traffic": measured_traffic(w.name, "update_momentum"), "bytes_per_launch": mom_bytes,
                                      "avg_launch_us": m_ms / max(m_n, 1) * 1e3},
         "final_loss": final_loss,
     }
