@@ -277,6 +277,49 @@ int omni_net_set_momentum(omni_net* net, float* velocity, float momentum, float 
 int omni_lr_step_decay(double lr0, double gamma, const int32_t* milestones, int32_t n,
                        int32_t epoch, double* lr_out);
 
+/* ------------------------------------------------------------------ asynchronous training
+ * Algorithm 2 ("Asynchronous training in OmniLearn") and equations aspweightedgrads /
+ * aspvariableSGD on simulated workers.  Worker k repeats: pull the server model, compute
+ * the mean gradient g_k of its own b_k samples at the pulled model (omni_step with one
+ * worker and OMNI_STEP_NO_UPDATE; the gradient stays in that call's workspace, so give
+ * every simulated worker a workspace of its own), local SGD step with its own learning
+ * rate eta_k = eta * b_k / B, push.
+ *
+ * omni_asp_schedule (host only, exact integers): an iteration of worker k takes b[k] / T[k]
+ * time units; pushes are processed in order of their finishing time, simultaneous ones
+ * lower worker index first, and a worker pulls again right after its own push.  Writes the
+ * worker of each of the first n_events pushes and the server version (number of pushes
+ * before the pull) its gradient was computed on; the staleness of push e is
+ * e - pulled_version_out[e].  T host [K] >= 1, b host [K] >= 1, outputs host [n_events]. */
+int omni_asp_schedule(int32_t K, const uint64_t* T, const int32_t* b, int32_t n_events,
+                      int32_t* worker_out, int32_t* pulled_version_out);
+
+/* What a push does to the server model: dst[j] = base[j] - eta_k * grad[j], with
+ * eta_k = lr * b_k / B (lr_scaling != 0, the linear scaling rule of equation
+ * aspvariableSGD) or lr.  dst == base == server model: the server adds the worker's local
+ * change to its current model (an update computed on an older model lands on the newer
+ * one).  base == the model the worker pulled, dst == server model: the server model is
+ * replaced by the worker's local model, as pushToPS is printed.  dst, base, grad dev [P]
+ * fp32, 16-byte aligned; dst and base equal or disjoint.  Enqueued on `stream`, no
+ * synchronisation.  OMNI_EINVAL on NULL / misaligned / partially overlapping buffers,
+ * b_k < 1, B < b_k or a non-finite lr. */
+int omni_asp_update(void* stream, float* dst, const float* base, const float* grad, size_t P,
+                    float lr, int32_t b_k, int32_t B, int32_t lr_scaling);
+
+/* The server's batch-size bookkeeping, procedure evalBsz of Algorithm 2 (host only).  A
+ * worker reports (k, the batch size it used, its smoothed compute time per iteration);
+ * both are stored; once every worker has reported at least once, each report re-evaluates
+ * getBsz (Algorithm 1: b* = b - (b / t)(t - mean t); accepted if |b* - b| / b* >= deadband;
+ * clamped to [b_min, b_max]; rounded half to even) for all workers from the stored values,
+ * and the caller gets its own new size; before that it keeps its size.  The global batch
+ * is not re-normalised (Algorithm 2 has no such step).  Double arithmetic, bit-reproducible.
+ * omni_asp_ps_sizes copies the stored sizes (0 for a worker that has not reported). */
+typedef struct omni_asp_ps omni_asp_ps;
+int omni_asp_ps_create(int32_t K, int32_t b_min, int32_t b_max, double deadband, omni_asp_ps** out);
+int omni_asp_ps_eval_bsz(omni_asp_ps* ps, int32_t k, int32_t b, double t, int32_t* b_out);
+int omni_asp_ps_sizes(const omni_asp_ps* ps, int32_t* b_out);
+void omni_asp_ps_destroy(omni_asp_ps* ps);
+
 /* Softmax cross-entropy over a ragged batch: for row s of worker k,
  * loss_rows[s] = -log softmax(z_s)[y_s] and dz_s = (softmax(z_s) - e_{y_s}) / b_k
  * (the 1/|b_k| of equation bspweightedgrads), then L_k and sum_k lambda_k L_k.

@@ -29,6 +29,8 @@ EXPORTS = [
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
     "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
     "omni_dyn_create", "omni_dyn_observe", "omni_dyn_adjust", "omni_dyn_get", "omni_dyn_destroy",
+    "omni_asp_schedule", "omni_asp_update",
+    "omni_asp_ps_create", "omni_asp_ps_eval_bsz", "omni_asp_ps_sizes", "omni_asp_ps_destroy",
 ]
 RULES = {"none": 0, "multiplicative": 1, "additive": 2}
 KERNEL_CLASSES = {"linear_fwd": 0, "linear_dgrad": 1, "linear_wgrad": 2, "loss": 3, "update": 4,
@@ -91,6 +93,13 @@ def _load():
     lib.omni_dyn_get.argtypes = [vp, P(i32), P(i32)]
     lib.omni_dyn_destroy.argtypes = [vp]
     lib.omni_dyn_destroy.restype = None
+    lib.omni_asp_schedule.argtypes = [i32, P(u64), P(i32), i32, P(i32), P(i32)]
+    lib.omni_asp_update.argtypes = [vp, vp, vp, vp, sz, f32, i32, i32, i32]
+    lib.omni_asp_ps_create.argtypes = [i32, i32, i32, C.c_double, P(vp)]
+    lib.omni_asp_ps_eval_bsz.argtypes = [vp, i32, i32, C.c_double, P(i32)]
+    lib.omni_asp_ps_sizes.argtypes = [vp, P(i32)]
+    lib.omni_asp_ps_destroy.argtypes = [vp]
+    lib.omni_asp_ps_destroy.restype = None
     return lib
 
 
@@ -285,6 +294,44 @@ def dyn_get(ctl, K):
 
 def dyn_destroy(ctl):
     lib.omni_dyn_destroy(ctl)
+
+
+def asp_schedule(T, b, n_events):
+    K = len(T)
+    worker = (C.c_int32 * max(n_events, 1))()
+    version = (C.c_int32 * max(n_events, 1))()
+    _check(lib.omni_asp_schedule(K, (C.c_uint64 * K)(*[int(v) for v in T]), _i32(b), n_events, worker, version))
+    return list(worker)[:n_events], list(version)[:n_events]
+
+
+def asp_update(dst, base, grad, lr, b_k, B, lr_scaling=True, P=None, stream=None):
+    """grad: a device tensor, or a raw device address (int) such as net_worker_grads returns."""
+    P = dst.numel() if P is None else P
+    g = C.c_void_p(grad) if isinstance(grad, int) else _ptr(grad)
+    _check(lib.omni_asp_update(stream if stream is not None else _stream(), _ptr(dst), _ptr(base), g, P, float(lr),
+                               int(b_k), int(B), 1 if lr_scaling else 0))
+
+
+def asp_ps_create(K, b_min, b_max, deadband):
+    h = C.c_void_p()
+    _check(lib.omni_asp_ps_create(K, b_min, b_max, float(deadband), C.byref(h)))
+    return h
+
+
+def asp_ps_eval_bsz(ps, k, b, t):
+    out = C.c_int32(0)
+    _check(lib.omni_asp_ps_eval_bsz(ps, int(k), int(b), float(t), C.byref(out)))
+    return out.value
+
+
+def asp_ps_sizes(ps, K):
+    out = (C.c_int32 * K)()
+    _check(lib.omni_asp_ps_sizes(ps, out))
+    return list(out)
+
+
+def asp_ps_destroy(ps):
+    lib.omni_asp_ps_destroy(ps)
 
 
 def softmax_xent(z, labels, off, dz, loss_rows, loss_per_worker, loss, status, stream=None):

@@ -192,3 +192,69 @@ def test_measured_time_controller_errors():
         assert changed and b[3] == 96 and min(b) >= 12 and off[-1] == sum(b)
     finally:
         omni.dyn_destroy(ctl)
+
+
+def test_asp_schedule_matches_oracle():
+    """Push order and pulled versions are integers: the library must agree exactly."""
+    from oracle import asp as OA
+    import random
+    rnd = random.Random(21)
+    for trial in range(300):
+        K = rnd.randint(1, 12)
+        T = [rnd.randint(1, 50) for _ in range(K)]
+        b = [rnd.randint(1, 50) for _ in range(K)]
+        n = rnd.randint(0, 120)
+        assert omni.asp_schedule(T, b, n) == OA.schedule(T, b, n), (T, b, n)
+    # values near the ends of the integer ranges (128-bit cross products)
+    T = [2 ** 64 - 1, 2 ** 64 - 3, 2 ** 63 + 5, 1]
+    b = [2 ** 31 - 1, 2 ** 31 - 2, 2 ** 30, 1]
+    assert omni.asp_schedule(T, b, 500) == OA.schedule(T, b, 500)
+    # the benchmark's split: equal iteration times, round-robin, every update K - 1 pushes stale
+    w, v = omni.asp_schedule([1000, 2000, 4000, 8000], [32, 64, 128, 256], 12)
+    assert w == [0, 1, 2, 3] * 3 and [e - x for e, x in enumerate(v)][4:] == [3] * 8
+
+
+def test_asp_schedule_errors():
+    with pytest.raises(omni.OmniError):
+        omni.asp_schedule([1, 0], [1, 1], 3)
+    with pytest.raises(omni.OmniError):
+        omni.asp_schedule([1, 1], [1, 0], 3)
+    with pytest.raises(omni.OmniError):
+        omni.asp_schedule([1] * 65, [1] * 65, 3)
+    assert omni.asp_schedule([3], [2], 0) == ([], [])
+
+
+def test_asp_eval_bsz_matches_oracle_bit_for_bit():
+    from oracle import asp as OA
+    import random
+    rnd = random.Random(22)
+    for trial in range(200):
+        K = rnd.randint(1, 10)
+        b_min = rnd.choice([1, 4, 12])
+        b_max = rnd.choice([96, 256, 4096])
+        dead = rnd.choice([0.0, 0.05, 0.15])
+        ref = OA.ParameterServer(K, b_min, b_max, dead)
+        ps = omni.asp_ps_create(K, b_min, b_max, dead)
+        try:
+            b = [rnd.randint(b_min, b_max) for _ in range(K)]
+            speed = [rnd.uniform(1.0, 8.0) for _ in range(K)]
+            for call in range(6 * K):
+                k = rnd.randrange(K)
+                t = b[k] / speed[k] * rnd.uniform(0.9, 1.1)
+                want = ref.eval_bsz(k, b[k], t)
+                got = omni.asp_ps_eval_bsz(ps, k, b[k], t)
+                assert got == want, (trial, call)
+                b[k] = got
+                assert omni.asp_ps_sizes(ps, K) == [ref.wrk_b.get(j, 0) for j in range(K)]
+        finally:
+            omni.asp_ps_destroy(ps)
+    with pytest.raises(omni.OmniError):
+        omni.asp_ps_create(4, 8, 4, 0.1)
+    ps = omni.asp_ps_create(2, 1, 64, 0.0)
+    try:
+        with pytest.raises(omni.OmniError):
+            omni.asp_ps_eval_bsz(ps, 2, 8, 1.0)
+        with pytest.raises(omni.OmniError):
+            omni.asp_ps_eval_bsz(ps, 0, 8, float("inf"))
+    finally:
+        omni.asp_ps_destroy(ps)
