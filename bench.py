@@ -101,6 +101,62 @@ def measured_traffic(workload, key):
     return None
 
 
+def asp_variant(omni, torch, net, w, b, off, params, x, y, lr, rounds=50):
+    """The asynchronous variant (Algorithm 2) on the same network, data and batch split: simulated
+    workers whose speed matches their batch size push in turn; every push is one launch of the push
+    kernel followed by that worker's next gradient (forward + backward over its own rows, one worker,
+    no update) at the model it has just pulled.  Reports samples/s over all pushes and the push kernel
+    against the HBM roofline (model read, gradient read, model written: 12 bytes per parameter)."""
+    K, B = w.K, w.B
+    server = params.clone()
+    nbytes = omni.net_workspace_bytes(net)
+    wss = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(K)]
+    lpw = torch.zeros(1, device="cuda")
+    loss = torch.zeros(1, device="cuda")
+    xs = [x[off[k]:off[k + 1]] for k in range(K)]
+    ys = [y[off[k]:off[k + 1]] for k in range(K)]
+    grads = [omni.net_worker_grads(net, wss[k], 1)[0] for k in range(K)]
+    n_events = rounds * K
+    worker, version = omni.asp_schedule(w.T, b, n_events)
+
+    def compute(k):
+        omni.step(net, server, xs[k], ys[k], [0, b[k]], [b[k]], 0.0, wss[k], lpw, loss, 1)
+
+    def run(events):
+        for k in events:
+            omni.asp_update(server, server, grads[k], lr, b[k], B, True)
+            compute(k)
+
+    for k in range(K):
+        compute(k)
+    run(worker[:2 * K])
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(worker)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    samples = sum(b[k] for k in worker)
+    # the push kernel alone, bracketed by events on the stream it is launched on
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_push = 200
+    e0.record()
+    for i in range(n_push):
+        omni.asp_update(server, server, grads[i % K], lr, b[i % K], B, True)
+    e1.record()
+    torch.cuda.synchronize()
+    push_s = e0.elapsed_time(e1) * 1e-3 / n_push
+    push_bytes = 12.0 * w.P
+    gbs = push_bytes / push_s / 1e9
+    stale = [e - v for e, v in enumerate(version)][K:]
+    return {"value": samples / dt, "unit": "samples/s", "pushes": n_events, "us_per_push": dt / n_events * 1e6,
+            "mean_staleness": sum(stale) / max(len(stale), 1), "final_loss": float(loss.item()),
+            "roofline_push": {"bound": "hbm", "kernel": "push (server model -= eta_k * g_k)", "achieved": gbs,
+                              "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": gbs / PEAK_HBM_GBS, "traffic": None,
+                              "bytes_per_launch": push_bytes, "avg_launch_us": push_s * 1e6,
+                              "note": "back-to-back launches; working set below 256 MB may be served from the "
+                                      "Infinity Cache"}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -108,6 +164,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--workload", default="mlp3072")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-asp", action="store_true", help="skip the asynchronous-variant measurement")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives or sharding exist here)")
@@ -200,6 +257,8 @@ def main():
     mom_bytes = (w.K + 4) * 4.0 * w.P
     mom_gbs = mom_bytes / (m_ms / max(m_n, 1) * 1e-3) / 1e9
 
+    asp = None if args.no_asp else asp_variant(omni, torch, net, w, b, off, params, x, y, lr)
+
     kernel_s = k_ms / max(k_n, 1) * 1e-3
     if kbound == "mfma":
         flops = layer_flops(w.layers, w.in_shape, klayer, w.B)
@@ -242,6 +301,8 @@ def main():
                                      "avg_launch_us": m_ms / max(m_n, 1) * 1e3},
         "final_loss": final_loss,
     }
+    if asp is not None:
+        out["asp_variant"] = asp
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, off)
     omni.net_destroy(net)
