@@ -277,6 +277,50 @@ int omni_net_set_momentum(omni_net* net, float* velocity, float momentum, float 
 int omni_lr_step_decay(double lr0, double gamma, const int32_t* milestones, int32_t n,
                        int32_t epoch, double* lr_out);
 
+/* ------------------------------------------------------------------ static variable batching
+ * Equation varbszBSP (section "Variable Batching"): b_k = c_k / sum(c) * B from the compute
+ * resource c_k of each worker (cores, FLOP/s, any common unit), made integer exactly like
+ * omni_ctl_run (largest remainder, ties to the lowest index, bounds by clamping and
+ * re-apportioning).  Host only.  c host [K] >= 1; b_out host [K]; off_out host [K+1] or NULL;
+ * b_max = 0 means B.  Errors as omni_ctl_create / omni_ctl_run. */
+int omni_static_batches(int32_t K, const uint64_t* c, int32_t B, int32_t b_min, int32_t b_max,
+                        int32_t* b_out, int32_t* off_out);
+
+/* Equation hlevel: heterogeneity level = largest / smallest resource.  Any of the outputs
+ * may be NULL. */
+int omni_heterogeneity_level(int32_t K, const uint64_t* c, uint64_t* max_out, uint64_t* min_out,
+                             double* hl_out);
+
+/* Memory model of section "Heterogeneous memory across workers", equation hetmemeqn:
+ *   M_total(b) = (2 + opt_copies) * P * bytes_per_param            model, gradients, optimiser
+ *              + act_per_sample * b                                activations
+ *              + batch_slope * b + batch_intercept                 batch (data loader) memory
+ * omni_mem_fit_linear: least-squares line through n measured (batch size, bytes) points
+ * (the paper fits the batch term this way); integer sums are exact, 2 <= n <= 4096,
+ * 0 <= b <= 2^24, 0 <= bytes <= 2^48, at least two distinct b.
+ * omni_mem_total evaluates the model; omni_mem_max_batch returns the largest b in
+ * [0, limit] whose total is <= mem_avail (0: only the fixed part fits, -1: not even that).
+ * Host only, doubles, bit-reproducible. */
+int omni_mem_fit_linear(int32_t n, const int64_t* b, const int64_t* bytes, double* slope_out,
+                        double* intercept_out);
+int omni_mem_total(int64_t b, int64_t P, int32_t bytes_per_param, int32_t opt_copies,
+                   double act_per_sample, double batch_slope, double batch_intercept,
+                   double* total_out);
+int omni_mem_max_batch(double mem_avail, int64_t P, int32_t bytes_per_param, int32_t opt_copies,
+                       double act_per_sample, double batch_slope, double batch_intercept,
+                       int64_t limit, int64_t* b_max_out);
+
+/* The same question for this library's own training state, answered exactly rather than
+ * by a fitted model: the largest batch capacity B_max (>= K_max) for which
+ *   omni_net_workspace_bytes + (1 + opt_copies) * 4 * P + B_max * (input row + label)
+ * stays within budget_bytes of device memory (opt_copies = 1 with a velocity buffer).
+ * Host only (plans are built and discarded; no device memory is touched).  bytes_out
+ * (may be NULL) receives the total at B_max.  OMNI_EINFEASIBLE if even B_max = K_max does
+ * not fit; layer-list errors as omni_net_create. */
+int omni_net_max_batch(const omni_layer_desc* layers, int32_t n_layers, int32_t in_h, int32_t in_w,
+                       int32_t in_c, int32_t dtype, int32_t K_max, int32_t opt_copies,
+                       uint64_t budget_bytes, int32_t* B_max_out, uint64_t* bytes_out);
+
 /* ------------------------------------------------------------------ asynchronous training
  * Algorithm 2 ("Asynchronous training in OmniLearn") and equations aspweightedgrads /
  * aspvariableSGD on simulated workers.  Worker k repeats: pull the server model, compute

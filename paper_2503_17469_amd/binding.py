@@ -31,6 +31,8 @@ EXPORTS = [
     "omni_dyn_create", "omni_dyn_observe", "omni_dyn_adjust", "omni_dyn_get", "omni_dyn_destroy",
     "omni_asp_schedule", "omni_asp_update",
     "omni_asp_ps_create", "omni_asp_ps_eval_bsz", "omni_asp_ps_sizes", "omni_asp_ps_destroy",
+    "omni_static_batches", "omni_heterogeneity_level", "omni_mem_fit_linear", "omni_mem_total",
+    "omni_mem_max_batch", "omni_net_max_batch",
 ]
 RULES = {"none": 0, "multiplicative": 1, "additive": 2}
 KERNEL_CLASSES = {"linear_fwd": 0, "linear_dgrad": 1, "linear_wgrad": 2, "loss": 3, "update": 4,
@@ -100,6 +102,13 @@ def _load():
     lib.omni_asp_ps_sizes.argtypes = [vp, P(i32)]
     lib.omni_asp_ps_destroy.argtypes = [vp]
     lib.omni_asp_ps_destroy.restype = None
+    f64, i64 = C.c_double, C.c_int64
+    lib.omni_static_batches.argtypes = [i32, P(u64), i32, i32, i32, P(i32), P(i32)]
+    lib.omni_heterogeneity_level.argtypes = [i32, P(u64), P(u64), P(u64), P(f64)]
+    lib.omni_mem_fit_linear.argtypes = [i32, P(i64), P(i64), P(f64), P(f64)]
+    lib.omni_mem_total.argtypes = [i64, i64, i32, i32, f64, f64, f64, P(f64)]
+    lib.omni_mem_max_batch.argtypes = [f64, i64, i32, i32, f64, f64, f64, i64, P(i64)]
+    lib.omni_net_max_batch.argtypes = [P(LayerDesc), i32, i32, i32, i32, i32, i32, i32, u64, P(i32), P(u64)]
     return lib
 
 
@@ -152,7 +161,7 @@ def ctl_destroy(ctl):
 
 
 # ------------------------------------------------------------------ network
-def net_create(layers, in_shape, dtype: str, K_max: int, B_max: int):
+def _layer_descs(layers):
     descs = (LayerDesc * len(layers))()
     for d, L in zip(descs, layers):
         d.op = OPS[L["op"]]
@@ -164,6 +173,11 @@ def net_create(layers, in_shape, dtype: str, K_max: int, B_max: int):
         d.stride = L.get("stride", 1)
         d.pad = L.get("pad", 0)
         d.bias = 1 if L.get("bias", False) else 0
+    return descs
+
+
+def net_create(layers, in_shape, dtype: str, K_max: int, B_max: int):
+    descs = _layer_descs(layers)
     h = C.c_void_p()
     _check(lib.omni_net_create(descs, len(layers), in_shape[0], in_shape[1], in_shape[2],
                                {"f32": F32, "bf16": BF16}[dtype], K_max, B_max, C.byref(h)))
@@ -294,6 +308,54 @@ def dyn_get(ctl, K):
 
 def dyn_destroy(ctl):
     lib.omni_dyn_destroy(ctl)
+
+
+def static_batches(c, B, b_min=1, b_max=0):
+    K = len(c)
+    b = (C.c_int32 * K)()
+    off = (C.c_int32 * (K + 1))()
+    _check(lib.omni_static_batches(K, (C.c_uint64 * K)(*[int(v) for v in c]), B, b_min, b_max, b, off))
+    return list(b), list(off)
+
+
+def heterogeneity_level(c):
+    K = len(c)
+    hi, lo, hl = C.c_uint64(0), C.c_uint64(0), C.c_double(0.0)
+    _check(lib.omni_heterogeneity_level(K, (C.c_uint64 * K)(*[int(v) for v in c]), C.byref(hi), C.byref(lo),
+                                        C.byref(hl)))
+    return hi.value, lo.value, hl.value
+
+
+def mem_fit_linear(b, nbytes):
+    n = len(b)
+    slope, icpt = C.c_double(0.0), C.c_double(0.0)
+    _check(lib.omni_mem_fit_linear(n, (C.c_int64 * n)(*[int(v) for v in b]), (C.c_int64 * n)(*[int(v) for v in nbytes]),
+                                   C.byref(slope), C.byref(icpt)))
+    return slope.value, icpt.value
+
+
+def mem_total(b, P, bytes_per_param, opt_copies, act_per_sample, batch_slope, batch_intercept):
+    out = C.c_double(0.0)
+    _check(lib.omni_mem_total(int(b), int(P), bytes_per_param, opt_copies, float(act_per_sample), float(batch_slope),
+                              float(batch_intercept), C.byref(out)))
+    return out.value
+
+
+def mem_max_batch(mem_avail, P, bytes_per_param, opt_copies, act_per_sample, batch_slope, batch_intercept,
+                  limit=1 << 30):
+    out = C.c_int64(0)
+    _check(lib.omni_mem_max_batch(float(mem_avail), int(P), bytes_per_param, opt_copies, float(act_per_sample),
+                                  float(batch_slope), float(batch_intercept), int(limit), C.byref(out)))
+    return out.value
+
+
+def net_max_batch(layers, in_shape, dtype: str, K_max: int, opt_copies: int, budget_bytes: int):
+    descs = _layer_descs(layers)
+    B, total = C.c_int32(0), C.c_uint64(0)
+    _check(lib.omni_net_max_batch(descs, len(layers), in_shape[0], in_shape[1], in_shape[2],
+                                  {"f32": F32, "bf16": BF16}[dtype], K_max, opt_copies, int(budget_bytes),
+                                  C.byref(B), C.byref(total)))
+    return B.value, total.value
 
 
 def asp_schedule(T, b, n_events):

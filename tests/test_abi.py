@@ -10,6 +10,7 @@ import pytest
 import paper_2503_17469_amd as omni
 from paper_2503_17469_amd import binding
 from oracle import controller as OC
+import synth
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -258,3 +259,81 @@ def test_asp_eval_bsz_matches_oracle_bit_for_bit():
             omni.asp_ps_eval_bsz(ps, 0, 8, float("inf"))
     finally:
         omni.asp_ps_destroy(ps)
+
+
+def test_static_batches_and_level_match_oracle():
+    from oracle import static as OS
+    import random
+    rnd = random.Random(31)
+    for c, want in [((12, 12, 8, 16), [32, 32, 21, 43]), ((6, 6, 4, 32), [16, 16, 11, 85])]:
+        assert omni.static_batches(c, 128)[0] == want          # the paper's core table, B = 4 x 32
+    assert omni.static_batches([6, 6, 4, 32], 128, 12, 96)[0] == [16, 16, 12, 84]
+    for trial in range(500):
+        K = rnd.randint(1, 16)
+        c = [rnd.randint(1, 64) for _ in range(K)]
+        B = rnd.randint(K, 100 * K)
+        assert omni.static_batches(c, B) == OS.static_batches(c, B)
+        hi, lo, hl = omni.heterogeneity_level(c)
+        assert (hi, lo) == (max(c), min(c)) and hl == float(OS.heterogeneity_level(c))
+    assert omni.heterogeneity_level([4, 4, 4, 28])[2] == 7.0
+    with pytest.raises(omni.OmniError):
+        omni.static_batches([1, 0], 8)
+    with pytest.raises(omni.OmniError):
+        omni.static_batches([1, 1, 1], 2)
+    with pytest.raises(omni.OmniError) as ei:
+        omni.static_batches([1, 1], 100, 1, 10)
+    assert ei.value.code == -2
+
+
+def test_memory_model_matches_oracle():
+    from oracle import static as OS
+    import random
+    rnd = random.Random(32)
+    bs = [1, 32, 64, 128, 512, 1024]
+    for trial in range(100):
+        a, c0 = rnd.randint(10_000, 400_000), rnd.randint(0, 10 ** 9)
+        m = [max(0, int(a * x + c0 + rnd.gauss(0, 1e5))) for x in bs]
+        slope, icpt = omni.mem_fit_linear(bs, m)
+        rs, ri = OS.fit_linear(bs, m)
+        assert slope == pytest.approx(float(rs), rel=1e-14)
+        assert icpt == pytest.approx(float(ri), rel=1e-12, abs=1e-6)
+    assert omni.mem_fit_linear(bs, [3 * x + 7 for x in bs]) == (3.0, 7.0)
+    with pytest.raises(omni.OmniError):
+        omni.mem_fit_linear([4, 4], [1, 2])
+    for trial in range(500):
+        P = rnd.randint(1, 10 ** 8)
+        bpp, opt = rnd.choice([2, 4]), rnd.randint(0, 2)
+        act, slope, icpt = rnd.uniform(0, 1e7), rnd.uniform(0, 1e6), rnd.uniform(0, 1e9)
+        b = rnd.randint(0, 4096)
+        assert omni.mem_total(b, P, bpp, opt, act, slope, icpt) == OS.memory_total(b, P, bpp, opt, act, slope, icpt)
+        mem = rnd.uniform(0, 64e9)
+        assert omni.mem_max_batch(mem, P, bpp, opt, act, slope, icpt, 1 << 20) == \
+            OS.max_batch(mem, P, bpp, opt, act, slope, icpt, 1 << 20)
+    assert omni.mem_max_batch(float(1 << 30), 1_000_000, 4, 1, float(2 << 20), float(1 << 19), float(100 << 20)) == 365
+    with pytest.raises(omni.OmniError):
+        omni.mem_total(1, 0, 4, 0, 1.0, 1.0, 0.0)
+
+
+def test_net_max_batch_is_the_exact_boundary():
+    """The largest capacity whose training state fits the budget: the plan's own byte counts decide."""
+    for layers, shp, dt, K in [(synth.mlp([3072, 1024, 1024, 10]), (1, 1, 3072), "f32", 4),
+                               (synth.cnn3(), (32, 32, 3), "bf16", 8)]:
+        def need(B, opt):
+            net = omni.net_create(layers, shp, dt, K, B)
+            try:
+                P = omni.net_param_count(net)
+                return omni.net_workspace_bytes(net) + (1 + opt) * 4 * P + B * (shp[0] * shp[1] * shp[2] * (4 if dt == "f32" else 2) + 4)
+            finally:
+                omni.net_destroy(net)
+        for budget, opt in [(1 << 30, 0), (3 << 30, 1), (need(K, 0), 0), (need(777, 1), 1)]:
+            B, total = omni.net_max_batch(layers, shp, dt, K, opt, budget)
+            assert total == need(B, opt) <= budget
+            try:
+                over = need(B + 1, opt)
+            except omni.OmniError:
+                over = None                                  # the library's own capacity limit comes first
+            assert over is None or over > budget
+        assert omni.net_max_batch(layers, shp, dt, K, 1, need(777, 1))[0] >= 777
+        with pytest.raises(omni.OmniError) as ei:
+            omni.net_max_batch(layers, shp, dt, K, 0, 1000)
+        assert ei.value.code == -2
