@@ -193,3 +193,48 @@ def test_resnet18_full_size_properties():
         assert np.array_equal(again["worker_grads"], got["worker_grads"])
     finally:
         run.close()
+
+
+def test_resnet18_full_size_sampled_worker():
+    """Config-4 shape at full size, in the launch configuration the benchmark times, checked against
+    the oracle on the outputs the oracle can afford: with per-worker batch norm a worker's forward
+    and backward pass depend on its own rows only, so the smallest worker (62 of the 2048 rows) is
+    computed by the oracle alone and compared with what the full-size GPU step holds for it, by the
+    same criteria as the reduced-batch test."""
+    from gpu_util import rel_err
+    w = synth.workload(3)
+    b, off = controller_run(w.T, w.B)
+    K = len(b)
+    k = int(np.argmin(b))
+    s0, s1 = off[k], off[k + 1]
+    print(f"case resnet18-full-size: K={K} off={off}, oracle on worker {k} ({b[k]} rows)", flush=True)
+    params = _params(w.layers, 9)
+    xs, ys = w.x[s0:s1], w.labels[s0:s1]
+    ref = OS.sgd_step(w.layers, params, xs, ys, [0, b[k]], 0.0, store=OL.round_bf16, keep_acts=True)
+    rng = np.random.default_rng(0)
+    ref2 = OS.sgd_step(w.layers, params, xs, ys, [0, b[k]], 0.0,
+                       store=lambda a: OL.round_bf16(a * (1.0 + 1e-6 * rng.standard_normal(a.shape))))
+    run = GpuRun(w.layers, w.in_shape, "bf16", K, w.B)
+    try:
+        got = run.step(params, w.x, w.labels, off, 0.0, flags=1)
+        assert got["status"] == 0
+        folded = {L["src"] for L in w.layers if L["op"] == "relu"}
+        for li in range(12):
+            if li in folded:
+                continue
+            a = run.omni.net_activation(run.net, run.ws, li, off[-1], "bf16").float().cpu().numpy()[s0:s1]
+            assert_close(a, ref.acts[0][li].reshape(b[k], -1), TOL, f"act[{li}] rows of worker {k}")
+        assert abs(got["loss_per_worker"][k] - ref.loss_per_worker[0]) <= TOL * abs(ref.loss_per_worker[0])
+        sl = param_tensor_slices(w.layers)
+        for name, s, e in sl[-2:]:
+            assert_close(got["worker_grads"][k, s:e], ref.worker_grads[0, s:e], TOL, f"g_{k} {name}")
+        worst_ratio = 0.0
+        for name, s, e in sl[:-2]:
+            own = rel_err(ref2.worker_grads[0, s:e], ref.worker_grads[0, s:e])[1]
+            mine = rel_err(got["worker_grads"][k, s:e], ref.worker_grads[0, s:e])[1]
+            assert mine <= 1.5 * own + TOL, f"g_{k} {name}: GPU {mine:.2e} vs oracle self-sensitivity {own:.2e}"
+            worst_ratio = max(worst_ratio, mine / own)
+        print(f"   deep gradients of worker {k}: GPU-to-oracle distance at most {worst_ratio:.2f}x the oracle's own "
+              f"1e-6 sensitivity", flush=True)
+    finally:
+        run.close()
