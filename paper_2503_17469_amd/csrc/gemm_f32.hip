@@ -77,12 +77,12 @@ struct Slab {
       if (!MC) {
         const int r = row0 + c / (BK / 4), kc = (c % (BK / 4)) * 4;
         pre.koff[i] = kc + 3;
-        pre.cpart[i] = (long)r * ld + kc;
+        pre.cpart[i] = r < rows ? (long)r * ld + kc : (long)kc;      // absent row: row 0 stands in
         pre.rowok |= (r < rows ? 1u : 0u) << i;
       } else {
         const int kk = c / (R / 4), r = row0 + (c % (R / 4)) * 4;
         pre.koff[i] = kk;
-        pre.cpart[i] = (long)kk * ld + r;
+        pre.cpart[i] = r + 3 < rows ? (long)kk * ld + r : (long)kk * ld;   // absent rows: rows 0..3 stand in
         pre.rowok |= (r + 3 < rows ? 1u : 0u) << i;
       }
     }
@@ -124,6 +124,39 @@ struct Slab {
         ok |= (in ? 1u : 0u) << (4 * i + e);
       }
       reg[i] = v;
+    }
+  }
+
+  // The mask-free form used with VEC.  A slab whose BK reduction steps all lie inside the
+  // range is loaded as it is.  A slab that would run past the end of its range is moved
+  // back so that it ENDS at the end of the range (start ks = max(kend - BK, 0): the caller
+  // guarantees at least BK reduction steps in the operand, so this stays in bounds); the
+  // steps of the slab outside [k0, kend) are zeroed in LDS afterwards (zero_outside), which
+  // happens once per range.  Rows outside the operand are not zeroed at all: they only
+  // feed outputs that are never stored.  The loop over full slabs then has no validity
+  // bits, no selects and one address add per piece.
+  __device__ static inline void load_fast(v4f (&reg)[kPerThread], const float* __restrict__ base, int ld, int ks,
+                                          const Pre& pre) {
+    const float* sbase = base + (MC ? (long)ks * ld : (long)ks);
+#pragma unroll
+    for (int i = 0; i < kPerThread; ++i) reg[i] = *reinterpret_cast<const v4f*>(sbase + pre.cpart[i]);
+  }
+  __device__ static inline void store_fast(const v4f (&reg)[kPerThread], float* lds, int tid, int i) {
+    const int c = tid + kThreads * i;
+    if (!MC) {
+      const int r = c / (BK / 4), kc = (c % (BK / 4)) * 4;
+      *reinterpret_cast<v4f*>(lds + r * kStride + kc) = reg[i];
+    } else {
+      const int kk = c / (R / 4), rc = (c % (R / 4)) * 4;
+      *reinterpret_cast<v4f*>(lds + kk * kStride + rc) = reg[i];
+    }
+  }
+  // zero the reduction steps of a staged slab outside [lo, hi)
+  __device__ static inline void zero_outside(float* lds, int lo, int hi, int tid) {
+    for (int idx = tid; idx < R * BK; idx += kThreads) {
+      const int kk = MC ? idx / R : idx % BK;
+      const int r = MC ? idx % R : idx / BK;
+      if (kk < lo || kk >= hi) lds[MC ? kk * kStride + r : r * kStride + kk] = 0.f;
     }
   }
 
@@ -279,58 +312,96 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_f32_kernel(GemmParams p, Seg
   v4f ra0[SA::kPerThread], rb0[SB::kPerThread], ra1[SA::kPerThread], rb1[SB::kPerThread];
   uint32_t oka0 = 0, okb0 = 0, oka1 = 0, okb1 = 0;
   OMNI_NEXT_SLAB(w0, k00, kend0, w1, k01, kend1)
-  SA::template load<VEC>(ra0, oka0, p.A, p.lda, row0, p.M, k00, kend0, tid, preA);
-  SB::template load<VEC>(rb0, okb0, p.B, p.ldb, col0, p.N, k00, kend0, tid, preB);
-  // Prefetches past the end of the stream are still issued (they re-read element
-  // 0 and are discarded): a load that is issued on one path only would force
+  // start of the slab as it is fetched (see Slab::load_fast)
+#define OMNI_KSTART(K0, KEND) ((K0) + BK <= (KEND) ? (K0) : max((KEND) - BK, 0))
+  // Prefetches past the end of the stream are still issued (they re-read the
+  // first slab and are discarded): a load that is issued on one path only would force
   // every later wait to assume it is not there and drain the whole queue.
-  if (w1 >= nrange) kend1 = 0;
-  SA::template load<VEC>(ra1, oka1, p.A, p.lda, row0, p.M, k01, kend1, tid, preA);
-  SB::template load<VEC>(rb1, okb1, p.B, p.ldb, col0, p.N, k01, kend1, tid, preB);
-  SA::template store<VEC>(ra0, oka0, sA(0), tid);
-  SB::template store<VEC>(rb0, okb0, sB(0), tid);
+  if (w1 >= nrange) { k01 = 0; kend1 = 0; }
+  if (VEC) {
+    SA::load_fast(ra0, p.A, p.lda, OMNI_KSTART(k00, kend0), preA);
+    SB::load_fast(rb0, p.B, p.ldb, OMNI_KSTART(k00, kend0), preB);
+    SA::load_fast(ra1, p.A, p.lda, OMNI_KSTART(k01, kend1), preA);
+    SB::load_fast(rb1, p.B, p.ldb, OMNI_KSTART(k01, kend1), preB);
+#pragma unroll
+    for (int i = 0; i < SA::kPerThread; ++i) SA::store_fast(ra0, sA(0), tid, i);
+#pragma unroll
+    for (int i = 0; i < SB::kPerThread; ++i) SB::store_fast(rb0, sB(0), tid, i);
+    if (k00 + BK > kend0) {
+      const int ks = OMNI_KSTART(k00, kend0);
+      __syncthreads();
+      SA::zero_outside(sA(0), k00 - ks, kend0 - ks, tid);
+      SB::zero_outside(sB(0), k00 - ks, kend0 - ks, tid);
+    }
+  } else {
+    SA::template load<VEC>(ra0, oka0, p.A, p.lda, row0, p.M, k00, kend0, tid, preA);
+    SB::template load<VEC>(rb0, okb0, p.B, p.ldb, col0, p.N, k00, kend0, tid, preB);
+    SA::template load<VEC>(ra1, oka1, p.A, p.lda, row0, p.M, k01, kend1, tid, preA);
+    SB::template load<VEC>(rb1, okb1, p.B, p.ldb, col0, p.N, k01, kend1, tid, preB);
+    SA::template store<VEC>(ra0, oka0, sA(0), tid);
+    SB::template store<VEC>(rb0, okb0, sB(0), tid);
+  }
   __syncthreads();
 
-  int cur = 0;
-  // One pipeline step: multiply slab 0 (already in LDS stage `cur`), fetch the
+  // One pipeline step: multiply slab 0 (already in LDS stage CUR, a constant of each of the two
+  // copies of the step, so that every LDS address is an immediate offset), fetch the
   // slab two ahead into the free register set (LA/LB), then move the slab one
   // ahead from its register set (NA/NB) into the other LDS stage.
-#define OMNI_STEP(LA, LB, LOKA, LOKB, NA, NB, NOKA, NOKB)                                               \
+#define OMNI_STEP(CUR, LA, LB, LOKA, LOKB, NA, NB, NOKA, NOKB)                                               \
   {                                                                                                     \
     int w2 = nrange, k02 = 0, kend2 = 0;                                                                \
     if (w1 < nrange) {                                                                                  \
       OMNI_NEXT_SLAB(w1, k01, kend1, tw, tk0, tkend)                                                    \
       w2 = tw; k02 = tk0; kend2 = tkend;                                                                \
     }                                                                                                   \
-    if (w2 >= nrange) kend2 = 0;                                                                        \
-    SA::template load<VEC>(LA, LOKA, p.A, p.lda, row0, p.M, k02, kend2, tid, preA);                      \
-    SB::template load<VEC>(LB, LOKB, p.B, p.ldb, col0, p.N, k02, kend2, tid, preB);                      \
+    if (w2 >= nrange) { k02 = 0; kend2 = 0; }                                                           \
+    if (VEC) {                                                                                          \
+      const int ks2 = OMNI_KSTART(k02, kend2);                                                          \
+      SA::load_fast(LA, p.A, p.lda, ks2, preA);                                                         \
+      SB::load_fast(LB, p.B, p.ldb, ks2, preB);                                                         \
+    } else {                                                                                            \
+      SA::template load<VEC>(LA, LOKA, p.A, p.lda, row0, p.M, k02, kend2, tid, preA);                    \
+      SB::template load<VEC>(LB, LOKB, p.B, p.ldb, col0, p.N, k02, kend2, tid, preB);                    \
+    }                                                                                                   \
     __builtin_amdgcn_sched_barrier(0); /* keep the fetches ahead of the MFMA section */                 \
     /* The slab one step ahead has been in flight for a whole step: its pieces go to the other LDS */  \
     /* stage in between the MFMA groups of this slab, and the operand fragments of the next group   */  \
     /* are fetched before the current group is issued, so that the matrix pipe is not left waiting. */  \
     {                                                                                                   \
       v4f fa[2], fb[2];                                                                                 \
-      fa[0] = SA::frag(sA(cur), wrow, 0, lane);                                                         \
-      fb[0] = SB::frag(sB(cur), wcol, 0, lane);                                                         \
+      fa[0] = SA::frag(sA(CUR), wrow, 0, lane);                                                         \
+      fb[0] = SB::frag(sB(CUR), wcol, 0, lane);                                                         \
       _Pragma("unroll") for (int ks = 0; ks < BK / 8; ++ks) {                                           \
         if (ks + 1 < BK / 8) {                                                                          \
-          fa[(ks + 1) & 1] = SA::frag(sA(cur), wrow, ks + 1, lane);                                     \
-          fb[(ks + 1) & 1] = SB::frag(sB(cur), wcol, ks + 1, lane);                                     \
+          fa[(ks + 1) & 1] = SA::frag(sA(CUR), wrow, ks + 1, lane);                                     \
+          fb[(ks + 1) & 1] = SB::frag(sB(CUR), wcol, ks + 1, lane);                                     \
         }                                                                                               \
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][0], fb[ks & 1][0], acc, 0, 0, 0);         \
         acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][1], fb[ks & 1][1], acc2, 0, 0, 0);       \
         acc = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][2], fb[ks & 1][2], acc, 0, 0, 0);         \
         acc2 = __builtin_amdgcn_mfma_f32_32x32x2f32(fa[ks & 1][3], fb[ks & 1][3], acc2, 0, 0, 0);       \
-        if (ks < SA::kPerThread) SA::template store_one<VEC>(NA, NOKA, sA(cur ^ 1), tid, ks);                         \
-        else if (ks - SA::kPerThread < SB::kPerThread)                                                  \
-          SB::template store_one<VEC>(NB, NOKB, sB(cur ^ 1), tid, ks - SA::kPerThread);                               \
+        if (VEC) {                                                                                      \
+          if (ks < SA::kPerThread) SA::store_fast(NA, sA(1 - CUR), tid, ks);                            \
+          else if (ks - SA::kPerThread < SB::kPerThread) SB::store_fast(NB, sB(1 - CUR), tid, ks - SA::kPerThread); \
+        } else {                                                                                        \
+          if (ks < SA::kPerThread) SA::template store_one<VEC>(NA, NOKA, sA(1 - CUR), tid, ks);         \
+          else if (ks - SA::kPerThread < SB::kPerThread)                                                \
+            SB::template store_one<VEC>(NB, NOKB, sB(1 - CUR), tid, ks - SA::kPerThread);               \
+        }                                                                                               \
         __builtin_amdgcn_sched_barrier(0);                                                              \
       }                                                                                                 \
     }                                                                                                   \
+    if (VEC && w1 < nrange && k01 + BK > kend1) {                                                       \
+      /* the slab just staged runs past the end of its range: it was fetched moved back; clear the */  \
+      /* reduction steps that are not its own (once per range; all its pieces must have landed)     */  \
+      const int ks1 = OMNI_KSTART(k01, kend1);                                                          \
+      __syncthreads();                                                                                  \
+      SA::zero_outside(sA(1 - CUR), k01 - ks1, kend1 - ks1, tid);                                       \
+      SB::zero_outside(sB(1 - CUR), k01 - ks1, kend1 - ks1, tid);                                       \
+    }                                                                                                   \
     if (want_bias_grad && tid < kTile) {                                                                \
       /* A is the output-gradient slab [kk][row]: its column sums are the bias gradient. */             \
-      _Pragma("unroll 8") for (int kk = 0; kk < BK; ++kk) bsum += sA(cur)[kk * SA::kStride + tid];      \
+      _Pragma("unroll 8") for (int kk = 0; kk < BK; ++kk) bsum += sA(CUR)[kk * SA::kStride + tid];      \
     }                                                                                                   \
     if (MODE == MODE_WGRAD && w1 != w0) {                                                               \
       /* this worker's rows are done: its tile goes out (stores only; the prefetch stays in flight) */ \
@@ -348,16 +419,16 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_f32_kernel(GemmParams p, Seg
     }                                                                                                   \
     if (w1 >= nrange) break;                                                                            \
     __syncthreads();                                                                                    \
-    cur ^= 1;                                                                                           \
     w0 = w1; k00 = k01; kend0 = kend1;                                                                  \
     w1 = w2; k01 = k02; kend1 = kend2;                                                                  \
   }
   for (;;) {
-    OMNI_STEP(ra0, rb0, oka0, okb0, ra1, rb1, oka1, okb1)
-    OMNI_STEP(ra1, rb1, oka1, okb1, ra0, rb0, oka0, okb0)
+    OMNI_STEP(0, ra0, rb0, oka0, okb0, ra1, rb1, oka1, okb1)
+    OMNI_STEP(1, ra1, rb1, oka1, okb1, ra0, rb0, oka0, okb0)
   }
 #undef OMNI_STEP
 #undef OMNI_NEXT_SLAB
+#undef OMNI_KSTART
 
   if (MODE != MODE_WGRAD) {
 #pragma unroll
@@ -478,7 +549,8 @@ void linear_fwd_f32(hipStream_t st, const float* x, const float* w, const float*
   p.kred = cin; p.bias = bias; p.relu = relu ? 1 : 0;
   p.partial = sw.partial; p.counters = sw.counters;
   Segments seg{};
-  const bool vec = aligned16(x) && aligned16(w) && (cin % 4 == 0);   // both operands k-contiguous
+  // both operands k-contiguous; the mask-free loads need at least one whole slab of reduction steps
+  const bool vec = aligned16(x) && aligned16(w) && (cin % 4 == 0) && cin >= 32;
   launch<32, false, false, MODE_FWD>(st, p, seg, pick_splits(gemm_tiles(rows, cout), cin, 32, sw), vec);
 }
 
@@ -490,7 +562,7 @@ void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const flo
   p.kred = cout; p.mask = mask; p.accumulate = accumulate ? 1 : 0;
   p.partial = sw.partial; p.counters = sw.counters;
   Segments seg{};
-  const bool vec = aligned16(dy) && aligned16(w) && (cout % 4 == 0) && (cin % 4 == 0);
+  const bool vec = aligned16(dy) && aligned16(w) && (cout % 4 == 0) && (cin % 4 == 0) && cout >= 32;
   launch<32, false, true, MODE_DGRAD>(st, p, seg, pick_splits(gemm_tiles(rows, cin), cout, 32, sw), vec);
 }
 
@@ -499,7 +571,7 @@ void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw
   GemmParams p{};
   p.A = dy; p.B = x; p.C = gw; p.M = cout; p.N = cin; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.c_worker_stride = worker_stride; p.bias_grad = gb;
-  const bool vec = aligned16(dy) && aligned16(x) && (cout % 4 == 0) && (cin % 4 == 0);
+  const bool vec = aligned16(dy) && aligned16(x) && (cout % 4 == 0) && (cin % 4 == 0) && seg.off[seg.K] >= 32;
   launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, vec);
 }
 
