@@ -22,15 +22,32 @@ namespace {
 
 constexpr int kMaxClasses = 128;
 
+// Wavefront-wide reductions on the vector ALU's data-parallel primitives: two quad
+// permutes and two row mirrors leave every lane with the result of its row of 16, four
+// lane reads combine the rows.  (A butterfly of __shfl_xor goes through the LDS crossbar:
+// six dependent round trips of ~170 cycles each per reduction; with one wavefront per SIMD
+// nothing hides them, and the ten per-class sums of the classifier were most of this
+// kernel's time.)
+template <int CTRL>
+__device__ inline float dpp_move(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+__device__ inline float lane_value(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
 __device__ inline float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+  v += dpp_move<0x141>(v);   // row_half_mirror
+  v += dpp_move<0x140>(v);   // row_mirror
+  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
 }
 __device__ inline float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
+  v = fmaxf(v, dpp_move<0xB1>(v));
+  v = fmaxf(v, dpp_move<0x4E>(v));
+  v = fmaxf(v, dpp_move<0x141>(v));
+  v = fmaxf(v, dpp_move<0x140>(v));
+  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
 }
 __device__ inline int owner(const Segments& seg, int s) {
   int k = 0;
@@ -43,7 +60,12 @@ __device__ inline float dot4(v4f a, v4f b) { return a[0] * b[0] + a[1] * b[1] + 
 // (fp32, or bf16 with fp32 arithmetic).  NV = 16-byte pieces of the input row
 // each lane keeps in registers; one piece per lane covers 64 * EL consecutive
 // inputs across the wavefront, so cin <= 64 * EL * NV.
-template <typename T, int NV>
+// WLDS: the whole weight matrix (at most 48 KB) is copied into LDS once per workgroup, while
+// the input rows are on their way, and both passes over it (logits, input gradient) read it
+// there.  A wavefront then waits for memory once instead of once per group of classes in each
+// pass; with one row per wavefront and two wavefronts per compute unit that chain of round
+// trips, not bandwidth, is what the kernel's time consists of.
+template <typename T, int NV, bool WLDS>
 __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
     const T* __restrict__ x, const T* __restrict__ w, const float* __restrict__ bias,
     const int32_t* __restrict__ labels, int cin, int C, Segments seg, float* __restrict__ z,
@@ -51,6 +73,8 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
   constexpr int EL = Piece<T>::EL;
   constexpr int CH = NV * EL <= 16 ? 8 : 4;   // classes whose weight rows are in flight together
   __shared__ float zbuf[4][kMaxClasses];
+  extern __shared__ __attribute__((aligned(16))) unsigned char wl_raw[];
+  const T* wp = WLDS ? reinterpret_cast<const T*>(wl_raw) : w;
   const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int rows = seg.off[seg.K];
   const int row_raw = blockIdx.x * 4 + wv;
@@ -69,6 +93,21 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
     kk[i] = k < cin ? k : 0;
     Piece<T>::load(xr + kk[i], a[i]);
   }
+  if (WLDS) {
+    const int npieces = C * cin / EL;          // 16-byte pieces; cin is a multiple of EL
+    const u32x4* src = reinterpret_cast<const u32x4*>(w);
+    u32x4* dst = reinterpret_cast<u32x4*>(wl_raw);
+    // eight pieces per thread in flight at a time (a piece past the end re-reads the last one)
+    for (int q0 = threadIdx.x; q0 < npieces; q0 += 256 * 8) {
+      u32x4 t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = src[min(q0 + 256 * u, npieces - 1)];
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (q0 + 256 * u < npieces) dst[q0 + 256 * u] = t[u];
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int i = 0; i < NV; ++i)
     if ((lane + 64 * i) * EL >= cin) {
@@ -84,7 +123,7 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         float wv_[EL];
-        Piece<T>::load(w + (size_t)c * cin + kk[i], wv_);
+        Piece<T>::load(wp + (size_t)c * cin + kk[i], wv_);
 #pragma unroll
         for (int e = 0; e < EL; ++e) acc[j] += a[i][e] * wv_[e];
       }
@@ -136,7 +175,7 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         float wv_[EL];
-        Piece<T>::load(w + (size_t)c * cin + kk[i], wv_);
+        Piece<T>::load(wp + (size_t)c * cin + kk[i], wv_);
 #pragma unroll
         for (int e = 0; e < EL; ++e) g[i][e] += d * wv_[e];
       }
@@ -302,9 +341,17 @@ static void launch_head_fwd(hipStream_t st, const T* x, const T* w, const float*
   const int nv = (cin + 64 * Piece<T>::EL - 1) / (64 * Piece<T>::EL);
   const dim3 grid((rows + 3) / 4), block(256);
   const int acc = accumulate ? 1 : 0, um = use_mask ? 1 : 0;
-#define OMNI_HEAD(NV)                                                                                    \
-  hipLaunchKernelGGL((head_fwd_loss_dgrad_kernel<T, NV>), grid, block, 0, st, x, w, bias, labels, cin, classes, seg, \
-                     z, dz, loss_rows, um, dx, acc)
+  const size_t wbytes = (size_t)classes * cin * sizeof(T);
+  const bool wlds = wbytes <= 48 * 1024;
+#define OMNI_HEAD(NV)                                                                                              \
+  do {                                                                                                             \
+    if (wlds)                                                                                                      \
+      hipLaunchKernelGGL((head_fwd_loss_dgrad_kernel<T, NV, true>), grid, block, wbytes, st, x, w, bias, labels,   \
+                         cin, classes, seg, z, dz, loss_rows, um, dx, acc);                                        \
+    else                                                                                                           \
+      hipLaunchKernelGGL((head_fwd_loss_dgrad_kernel<T, NV, false>), grid, block, 0, st, x, w, bias, labels, cin,  \
+                         classes, seg, z, dz, loss_rows, um, dx, acc);                                             \
+  } while (0)
   if (nv <= 1) OMNI_HEAD(1);
   else if (nv <= 2) OMNI_HEAD(2);
   else if (nv <= 4) OMNI_HEAD(4);
