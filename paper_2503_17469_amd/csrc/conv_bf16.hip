@@ -1550,8 +1550,11 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
     }
     ct.first[seg.K] = acc;
     if (acc == 0) return true;   // no rows at all
-    // all workgroups resident at once (two per compute unit): a few extra ones would run as a second round
-    if ((size_t)tiles * acc <= max_slots && ((long)tiles * acc <= std::max(512, 2 * tiles * seg.K) || acc == seg.K)) break;
+    // one chunk per worker needs no scratch (every workgroup writes its worker's gradient itself);
+    // otherwise the partial tiles must fit the scratch and all workgroups should be resident at once
+    // (two per compute unit): a few extra ones would run as a second round
+    if (acc == seg.K) break;
+    if ((size_t)tiles * acc <= max_slots && (long)tiles * acc <= std::max(512, 2 * tiles * seg.K)) break;
     upc += std::max<long>(1, upc / 16);
   }
   p.upc = (int)upc;

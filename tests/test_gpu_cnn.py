@@ -119,3 +119,14 @@ def test_cnn_determinism():
         assert np.array_equal(a["params"], c["params"]) and np.array_equal(a["worker_grads"], c["worker_grads"])
     finally:
         run.close()
+
+
+def test_cnn_max_workers():
+    """K = 64 workers of 1 to 3 images each through every bf16 kernel family of the small CNN."""
+    rng = np.random.default_rng(65)
+    b = [int(v) for v in rng.integers(1, 4, size=64)]
+    off = [int(v) for v in [0] + list(np.cumsum(b))]
+    layers = synth.cnn3(num_classes=10, hw=8, chans=(3, 8, 16, 32))
+    params = synth.he_normal_params(layers, 6, True)
+    x, y = synth.make_batch(650, off[-1], (8, 8, 3), 10, True)
+    _check_step(layers, (8, 8, 3), params, x, y, off, 0.05, "cnn3-64-workers")

@@ -179,3 +179,16 @@ def test_step_with_momentum_and_weight_decay():
         assert_close(th.cpu().numpy(), ref.params, 1e-4, "theta after returning to plain SGD")
     finally:
         run.close()
+
+
+def test_max_workers():
+    """K = 64, the largest worker count the library takes, with batches of 1 to 5 rows."""
+    rng = np.random.default_rng(64)
+    b = [int(v) for v in rng.integers(1, 6, size=64)]
+    off = [0] + list(np.cumsum(b))
+    off = [int(v) for v in off]
+    dims = [96, 64, 10]
+    layers = synth.mlp(dims)
+    params = synth.he_normal_params(layers, 64, False)
+    x, labels = synth.make_batch(640, off[-1], (1, 1, dims[0]), dims[-1], False)
+    _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag="mlp-64-workers")
