@@ -1054,8 +1054,17 @@ __global__ __launch_bounds__(kThreads) void conv_wgrad_reduce_kernel(WgradParams
       p.gw[(size_t)wk * p.worker_stride + (size_t)co * (taps * p.cin_real) + tap * p.cin_real + ci] = s0;
   }
   if (slot == 0 && p.gb != nullptr && tile_n == 0 && tid < BM && row0 + tid < p.Cout) {
-    float bs = 0.f;
-    for (int c = 0; c < nchunks; ++c) bs += all[(size_t)c * stride + kTileFloats + tid];
+    float bs = 0.f;                      // eight loads in flight, additions in chunk order
+    const float* bsrc = all + kTileFloats + tid;
+    int c = 0;
+    for (; c + 8 <= nchunks; c += 8) {
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = bsrc[(size_t)(c + u) * stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) bs += t[u];
+    }
+    for (; c < nchunks; ++c) bs += bsrc[(size_t)c * stride];
     p.gb[(size_t)wk * p.worker_stride + row0 + tid] = bs;
   }
 }
@@ -1372,10 +1381,242 @@ __global__ __launch_bounds__(kThreads) void conv3_wgrad_reduce_kernel(Wgrad3Para
     }
   }
   if (blockIdx.z == 0 && p.gb != nullptr && ci0 == 0 && tid < 64 && co0 + tid < p.Cout) {
+    // eight loads in flight (one dependent round trip per chunk made this the kernel's long pole);
+    // the additions keep chunk order
     float bs = 0.f;
-    for (int c = 0; c < nchunks; ++c) bs += all[(size_t)c * kTile3Stride + kTile3Floats + tid];
+    const float* bsrc = all + kTile3Floats + tid;
+    int c = 0;
+    for (; c + 8 <= nchunks; c += 8) {
+      float t[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) t[u] = bsrc[(size_t)(c + u) * kTile3Stride];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) bs += t[u];
+    }
+    for (; c < nchunks; ++c) bs += bsrc[(size_t)c * kTile3Stride];
     p.gb[(size_t)wk * p.worker_stride + co0 + tid] = bs;
   }
+}
+
+
+// ---------------------------------------------------------------------------------------------
+// Kernel G: weight gradient of the first layer -- 3 input channels stored as 8, 3x3 / stride 1 /
+// pad 1, maps 32 wide, at most 64 output channels.
+//
+//   G_k[co][u][v][ci] = sum over the positions of worker k of dY[pos][co] * X[pos + (u-1, v-1)][ci]
+//
+// As a matrix product the output is tiny (Cout x 27) and the reduction (all positions) is
+// everything, so the layer is bound by reading dY and X once: what kernel C spends on a 64 x 64
+// channel tile that is 15/16 empty, and on parking and re-reading such tiles, is avoided by giving
+// the product its own shape: rows = output channels (32 per block), columns = (tap, channel)
+// pairs, 9 x 4 = 36 of them, column 36 = a channel of ones (its product is the bias gradient),
+// reduction = positions, 16 per v_mfma_f32_32x32x16_bf16.  Both operands have the reduction as
+// their SLOW index in memory ([pos][channel]); they are staged in LDS as they arrive (16-byte
+// pieces) and the transposition happens in the fragment reads: eight 2-byte reads per lane and
+// fragment, at immediate offsets.  A workgroup walks units of 4 image rows (128 positions) of one
+// worker; its four wavefronts split the positions of a unit and keep whole accumulators, which are
+// added through LDS at the end.  Chunks of one worker are added by a second small kernel in chunk
+// order (fixed summation order; no atomics).
+struct Wgrad1Params {
+  const bf16_t* dy;     // [rows][H][32][Cout]
+  const bf16_t* src;    // [rows][H][32][8]
+  float* gw;            // worker k at gw + k * worker_stride, layout [Cout][3][3][cin_real]
+  float* gb;            // may be null
+  size_t worker_stride;
+  int Cout, cin_real, H;
+  int upc;              // units per chunk
+  float* partial;       // [chunk][MB * 2 * 16 * 64] accumulator images
+};
+constexpr int kG_W = 32, kG_R = 4, kG_Unit = kG_W * kG_R;        // 128 positions
+constexpr int kG_PatchCols = kG_W + 2, kG_PatchRows = kG_R + 2;
+constexpr int kG_XBytes = kG_PatchRows * kG_PatchCols * 16;
+
+// (co, column) of accumulator register v of lane l in block (mb, nb) -> where it goes in G
+__device__ inline void wgrad1_emit(const Wgrad1Params& p, float* gw, float* gb, int mb, int nb, int v, int lane,
+                                   float val) {
+  const int co = mb * 32 + 8 * (v / 4) + 4 * (lane >> 5) + (v % 4);
+  const int col = nb * 32 + (lane & 31);
+  if (co >= p.Cout) return;
+  if (col < 36) {
+    const int tap = col >> 2, ci = col & 3;
+    if (ci < p.cin_real) gw[((size_t)co * 9 + tap) * p.cin_real + ci] = val;
+  } else if (col == 36 && gb != nullptr) {
+    gb[co] = val;
+  }
+}
+
+template <int MB>
+__global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p, Segments seg, ChunkTable ct) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smemg[];
+  const int SY = p.Cout * 2 + 8;                         // bytes per position of the staged dY strip
+  const int stage_bytes = (kG_Unit * SY + kG_XBytes + 15) & ~15;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+  int wk = 0;
+  while (wk + 1 < seg.K && (int)blockIdx.x >= ct.first[wk + 1]) ++wk;
+  const int chunk_idx = blockIdx.x - ct.first[wk];
+  const int nchunks = ct.first[wk + 1] - ct.first[wk];
+  const int upi = p.H / kG_R;                              // units per image
+  const int units = (seg.off[wk + 1] - seg.off[wk]) * upi;
+  const int ubeg = chunk_idx * p.upc, uend = min(units, ubeg + p.upc);
+
+  // zero both stages once (halo columns of the patch are never written again)
+  for (int i = tid * 16; i < 2 * stage_bytes; i += kThreads * 16) *reinterpret_cast<u32x4*>(smemg + i) = u32x4{0, 0, 0, 0};
+  __syncthreads();
+
+  // staging tasks of this thread: dY pieces (16 bytes = 8 channels of one position), one patch piece
+  const int ppp = p.Cout / 8;                              // pieces per position
+  const int ny = kG_Unit * ppp;                            // pieces per unit: 128 ... 1024
+  constexpr int kYMax = 4;                                 // Cout <= 64
+  u32x4 ry[kYMax], rx;
+  const bool has_x = tid < kG_PatchRows * kG_W;
+  const int xr = tid / kG_W, xc = tid % kG_W;              // patch row 0..5 (image row strip*4 - 1 + xr), column
+  auto fetch = [&](int u) {
+    const int img = seg.off[wk] + u / upi, row0 = (u % upi) * kG_R;
+    const bf16_t* ybase = p.dy + ((size_t)(img * p.H + row0) * kG_W) * p.Cout;
+#pragma unroll
+    for (int i = 0; i < kYMax; ++i) {
+      const int q = min(tid + kThreads * i, ny - 1);       // surplus slots re-read the last piece
+      ry[i] = *reinterpret_cast<const u32x4*>(ybase + (size_t)q * 8);
+    }
+    const int grow = row0 - 1 + xr;
+    const bool in = has_x && grow >= 0 && grow < p.H;
+    const bf16_t* xp = p.src + ((size_t)(img * p.H + (in ? grow : 0)) * kG_W + xc) * 8;
+    rx = *reinterpret_cast<const u32x4*>(has_x ? xp : p.src);
+    if (!in) rx = u32x4{0, 0, 0, 0};
+    rx[2] = (rx[2] & 0xFFFF0000u) | 0x3F80u;               // channel 4 := 1.0 (the bias column reads it)
+  };
+  auto stash = [&](int stage) {
+    unsigned char* sY = smemg + stage * stage_bytes;
+    unsigned char* sX = sY + kG_Unit * SY;
+#pragma unroll
+    for (int i = 0; i < kYMax; ++i) {
+      const int q = tid + kThreads * i;
+      if (q < ny) {
+        unsigned char* d = sY + (q / ppp) * SY + (q % ppp) * 16;    // 8-byte aligned (SY is 8 mod 16)
+        *reinterpret_cast<u32x2*>(d) = u32x2{ry[i][0], ry[i][1]};
+        *reinterpret_cast<u32x2*>(d + 8) = u32x2{ry[i][2], ry[i][3]};
+      }
+    }
+    if (has_x) *reinterpret_cast<u32x4*>(sX + (xr * kG_PatchCols + xc + 1) * 16) = rx;
+  };
+
+  // fragment addressing.  A: lane supplies output channel lane%32 of block mb, positions
+  // 16*kb + 8*(lane/32) + i.  B: lane supplies column lane%32 of block nb.
+  const int kg = lane >> 5, jl = lane & 31;
+  int bbase[2];
+#pragma unroll
+  for (int nb = 0; nb < 2; ++nb) {
+    const int col = nb * 32 + jl;
+    int u = 1, v = 1, ci = 5;                              // unused columns read a zero channel
+    if (col < 36) { u = (col >> 2) / 3; v = (col >> 2) % 3; ci = col & 3; }
+    else if (col == 36) ci = 4;
+    bbase[nb] = (u * kG_PatchCols + v + 8 * kg) * 16 + ci * 2;
+  }
+  const int abase = 8 * kg * SY + jl * 2;
+
+  v16f acc[MB][2];
+#pragma unroll
+  for (int a = 0; a < MB; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
+
+  if (ubeg < uend) {
+    fetch(ubeg);
+    stash(0);
+    __syncthreads();
+    int stage = 0;
+    for (int u = ubeg; u < uend; ++u) {
+      if (u + 1 < uend) fetch(u + 1);
+      const unsigned char* sY = smemg + stage * stage_bytes;
+      const unsigned char* sX = sY + kG_Unit * SY;
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int kb = wave + 4 * h;                        // 16 positions: image row kb/2, columns (kb%2)*16 ...
+        const unsigned char* ya = sY + kb * 16 * SY + abase;
+        const unsigned char* xb = sX + ((kb >> 1) * kG_PatchCols + (kb & 1) * 16) * 16;
+        bf16x8 fa[MB], fb[2];
+#pragma unroll
+        for (int a = 0; a < MB; ++a) {
+          u32x4 w;
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = *reinterpret_cast<const uint16_t*>(ya + a * 64 + (2 * d) * SY);
+            const uint32_t hi = *reinterpret_cast<const uint16_t*>(ya + a * 64 + (2 * d + 1) * SY);
+            w[d] = lo | (hi << 16);
+          }
+          fa[a] = as_bf16x8(w);
+        }
+#pragma unroll
+        for (int b = 0; b < 2; ++b) {
+          u32x4 w;
+#pragma unroll
+          for (int d = 0; d < 4; ++d) {
+            const uint32_t lo = *reinterpret_cast<const uint16_t*>(xb + bbase[b] + (2 * d) * 16);
+            const uint32_t hi = *reinterpret_cast<const uint16_t*>(xb + bbase[b] + (2 * d + 1) * 16);
+            w[d] = lo | (hi << 16);
+          }
+          fb[b] = as_bf16x8(w);
+        }
+#pragma unroll
+        for (int a = 0; a < MB; ++a)
+#pragma unroll
+          for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
+      }
+      if (u + 1 < uend) stash(stage ^ 1);
+      __syncthreads();
+      stage ^= 1;
+    }
+  }
+
+  // add the four wavefronts' accumulators (wavefront order) and write the chunk's result
+  float* red = reinterpret_cast<float*>(smemg);            // [4][MB*2*16][64] floats = 32 KB at MB = 2
+  constexpr int kImg = MB * 2 * 16 * 64;
+#pragma unroll
+  for (int a = 0; a < MB; ++a)
+#pragma unroll
+    for (int b = 0; b < 2; ++b)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) red[wave * kImg + ((a * 2 + b) * 16 + v) * 64 + lane] = acc[a][b][v];
+  __syncthreads();
+  float* gw = p.gw + (size_t)wk * p.worker_stride;
+  float* gb = p.gb ? p.gb + (size_t)wk * p.worker_stride : nullptr;
+  for (int e = tid; e < kImg; e += kThreads) {
+    const float val = ((red[e] + red[kImg + e]) + red[2 * kImg + e]) + red[3 * kImg + e];
+    if (nchunks > 1) {
+      p.partial[(size_t)blockIdx.x * kImg + e] = val;
+    } else {
+      const int blk = e / (16 * 64), v = (e / 64) % 16, l = e % 64;
+      wgrad1_emit(p, gw, gb, blk / 2, blk % 2, v, l, val);
+    }
+  }
+}
+
+// grid (K, MB * 8): one accumulator element per thread, the worker's chunks added in chunk order
+template <int MB>
+__global__ __launch_bounds__(kThreads) void conv1_wgrad_reduce_kernel(Wgrad1Params p, Segments seg, ChunkTable ct) {
+  constexpr int kImg = MB * 2 * 16 * 64;
+  const int wk = blockIdx.x;
+  const int nchunks = ct.first[wk + 1] - ct.first[wk];
+  if (nchunks <= 1) return;                                 // written by the first kernel
+  const int e = blockIdx.y * kThreads + threadIdx.x;
+  const float* src = p.partial + (size_t)ct.first[wk] * kImg + e;
+  float s = 0.f;
+  int c = 0;
+  for (; c + 8 <= nchunks; c += 8) {
+    float t[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) t[u] = src[(size_t)(c + u) * kImg];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += t[u];
+  }
+  for (; c < nchunks; ++c) s += src[(size_t)c * kImg];
+  float* gw = p.gw + (size_t)wk * p.worker_stride;
+  float* gb = p.gb ? p.gb + (size_t)wk * p.worker_stride : nullptr;
+  const int blk = e / (16 * 64), v = (e / 64) % 16, l = e % 64;
+  wgrad1_emit(p, gw, gb, blk / 2, blk % 2, v, l, s);
 }
 
 }  // namespace
@@ -1575,9 +1816,67 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   return true;
 }
 
+// The first layer (3 channels stored as 8) on 32-wide maps: kernel G.  Returns false if the shape
+// does not qualify.
+static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
+                        size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
+                        float* partial) {
+  const int H = g.Hs, W = g.Ws;
+  if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.transposed || g.Hp != H || g.Wp != W) return false;
+  if (g.Cs != 8 || cin_real > 4 || cin_real < 1 || W != kG_W || H % kG_R != 0) return false;
+  if (Cout % 8 != 0 || Cout < 8 || Cout > 64) return false;
+  const int mb = Cout > 32 ? 2 : 1;
+  const size_t img_floats = (size_t)mb * 2 * 16 * 64;
+  Wgrad1Params p{};
+  p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
+  p.Cout = Cout; p.cin_real = cin_real; p.H = H; p.partial = partial;
+  const int upi = H / kG_R;
+  long total_units = 0;
+  for (int k = 0; k < seg.K; ++k) total_units += (long)(seg.off[k + 1] - seg.off[k]) * upi;
+  if (total_units == 0) return true;
+  // about two workgroups per compute unit, at least 4 units each
+  // (every worker's last chunk may be short: aim K below 512 so the total stays within it)
+  const long want = std::max(64, 512 - seg.K);
+  long upc = std::max<long>((total_units + want - 1) / want, 4);
+  ChunkTable ct{};
+  for (;;) {
+    int acc = 0;
+    for (int k = 0; k < seg.K; ++k) {
+      ct.first[k] = acc;
+      acc += (int)(((long)(seg.off[k + 1] - seg.off[k]) * upi + upc - 1) / upc);
+    }
+    ct.first[seg.K] = acc;
+    if (acc == seg.K || (size_t)acc * img_floats <= conv_wgrad_partial_floats()) break;
+    upc += std::max<long>(1, upc / 8);
+  }
+  p.upc = (int)upc;
+  const int SY = Cout * 2 + 8;
+  const size_t stage = ((size_t)kG_Unit * SY + kG_XBytes + 15) & ~(size_t)15;
+  const size_t lds = std::max(2 * stage, 4 * img_floats * sizeof(float));
+  const dim3 grid(ct.first[seg.K]);
+  bool chunked = false;
+  for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
+  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
+  if (lds > configured[mb - 1]) {
+    const void* fn = mb == 1 ? reinterpret_cast<const void*>(&conv1_wgrad_kernel<1>)
+                             : reinterpret_cast<const void*>(&conv1_wgrad_kernel<2>);
+    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured[mb - 1] = lds;
+  }
+  if (mb == 1) {
+    hipLaunchKernelGGL(conv1_wgrad_kernel<1>, grid, dim3(kThreads), lds, st, p, seg, ct);
+    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<1>, dim3(seg.K, 8), dim3(kThreads), 0, st, p, seg, ct);
+  } else {
+    hipLaunchKernelGGL(conv1_wgrad_kernel<2>, grid, dim3(kThreads), lds, st, p, seg, ct);
+    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<2>, dim3(seg.K, 16), dim3(kThreads), 0, st, p, seg, ct);
+  }
+  return true;
+}
+
 void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                      float* partial, uint32_t* counters) {
+  if (conv1_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
   if (conv3_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
   WgradParams p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;

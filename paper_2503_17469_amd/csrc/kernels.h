@@ -80,8 +80,19 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
 // ---- bf16 pointwise kernels (pointwise_bf16.hip) ----
 // fp32 weights [cout][taps][cin_real] -> bf16 [cout][taps][cin_pad] (zero padded) and,
 // if w_t is not null, the transposed copy [cin_pad][taps][cout] used by dgrad.
-void cast_weights_bf16(hipStream_t st, const float* w, bf16_t* w_fwd, bf16_t* w_t, int cout, int taps,
-                       int cin_real, int cin_pad);
+// One layer's weight copy: fp32 [cout][taps][cin_real] at params + src -> bf16 [cout][taps][cin_pad] at
+// shadow + dst_fwd and, if dst_t >= 0, the transposed [cin_pad][taps][cout] at shadow + dst_t (offsets in elements).
+struct CastEntry {
+  long src, dst_fwd, dst_t;
+  int cout, taps, cin_real, cin_pad;
+  int first_block;   // filled by the launcher
+};
+constexpr int kCastMaxEntries = 64;
+struct CastTable {
+  int n;
+  CastEntry e[kCastMaxEntries];
+};
+void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, const CastEntry* entries, int n);
 void pad_channels_bf16(hipStream_t st, const bf16_t* x, bf16_t* xp, long pixels, int c_real, int c_pad);
 void maxpool2_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, int H, int W, int C);
 // din = dout routed to the first maximum of each 2x2 window (scan order), zero elsewhere;

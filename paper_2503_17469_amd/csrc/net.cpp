@@ -512,12 +512,19 @@ void step_bf16(StepCtx& c) {
   };
 
   // ---- bf16 copies of the weights (forward layout, and transposed for dgrad)
-  for (const Layer& L : net->layers) {
-    if (!is_param_op(L.d.op)) continue;
-    const int taps = L.d.op == OMNI_OP_CONV ? L.d.ksize * L.d.ksize : 1;
-    const int cin_real = L.d.op == OMNI_OP_CONV ? L.d.cin : L.cin_pad;
-    omni::cast_weights_bf16(st, c.params + L.w_off, shadow + L.wsh_off, L.need_dgrad ? shadow + L.wt_off : nullptr,
-                            L.d.cout, taps, cin_real, L.cin_pad);
+  {
+    std::vector<omni::CastEntry> casts;
+    for (const Layer& L : net->layers) {
+      if (!is_param_op(L.d.op)) continue;
+      omni::CastEntry e{};
+      e.src = (long)L.w_off; e.dst_fwd = (long)L.wsh_off; e.dst_t = L.need_dgrad ? (long)L.wt_off : -1;
+      e.cout = L.d.cout;
+      e.taps = L.d.op == OMNI_OP_CONV ? L.d.ksize * L.d.ksize : 1;
+      e.cin_real = L.d.op == OMNI_OP_CONV ? L.d.cin : L.cin_pad;
+      e.cin_pad = L.cin_pad;
+      casts.push_back(e);
+    }
+    omni::cast_weights_bf16(st, c.params, shadow, casts.data(), (int)casts.size());
   }
 
   // ---- forward over the concatenated batch

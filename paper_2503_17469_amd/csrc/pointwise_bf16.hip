@@ -2,6 +2,8 @@
 // padding of the network input, 2x2 max pooling forward and backward.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "bf16.h"
 #include "common.h"
 #include "kernels.h"
@@ -10,19 +12,24 @@ namespace omni {
 
 namespace {
 
-__global__ __launch_bounds__(256) void cast_weights_kernel(const float* __restrict__ w, bf16_t* __restrict__ w_fwd,
-                                                           bf16_t* __restrict__ w_t, int cout, int taps, int cin_real,
-                                                           int cin_pad) {
-  const long n = (long)cout * taps * cin_pad;
-  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+// All layers' weight copies in one launch: with a few thousand weights per layer a launch per
+// layer is pure launch latency (4 x 4.6 us at the three-layer CNN).  The table travels in the
+// kernel arguments.
+__global__ __launch_bounds__(256) void cast_weights_kernel(CastTable tab, const float* __restrict__ params,
+                                                           bf16_t* __restrict__ shadow) {
+  int e = 0;
+  while (e + 1 < tab.n && (int)blockIdx.x >= tab.e[e + 1].first_block) ++e;
+  const CastEntry t = tab.e[e];
+  const long n = (long)t.cout * t.taps * t.cin_pad;
+  const long i = (long)(blockIdx.x - t.first_block) * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  const int ci = (int)(i % cin_pad);
-  const long r = i / cin_pad;
-  const int tap = (int)(r % taps), co = (int)(r / taps);
-  const float v = ci < cin_real ? w[((long)co * taps + tap) * cin_real + ci] : 0.f;
+  const int ci = (int)(i % t.cin_pad);
+  const long r = i / t.cin_pad;
+  const int tap = (int)(r % t.taps), co = (int)(r / t.taps);
+  const float v = ci < t.cin_real ? params[t.src + ((long)co * t.taps + tap) * t.cin_real + ci] : 0.f;
   const bf16_t h = f32_to_bf16(v);
-  w_fwd[i] = h;
-  if (w_t) w_t[((long)ci * taps + tap) * cout + co] = h;
+  shadow[t.dst_fwd + i] = h;
+  if (t.dst_t >= 0) shadow[t.dst_t + ((long)ci * t.taps + tap) * t.cout + co] = h;
 }
 
 __global__ __launch_bounds__(256) void pad_channels_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ xp,
@@ -32,6 +39,20 @@ __global__ __launch_bounds__(256) void pad_channels_kernel(const bf16_t* __restr
   const int c = (int)(i % c_pad);
   const long px = i / c_pad;
   xp[i] = c < c_real ? x[px * c_real + c] : (bf16_t)0;
+}
+
+// 3 -> 8 channels, four pixels per thread: 24 bytes in (three 8-byte loads), four 16-byte pieces out
+__global__ __launch_bounds__(256) void pad_3to8_kernel(const bf16_t* __restrict__ x, bf16_t* __restrict__ xp,
+                                                       long quads) {
+  const long q = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (q >= quads) return;
+  const u32x2* src = reinterpret_cast<const u32x2*>(x + q * 12);
+  const u32x2 a = src[0], b = src[1], c = src[2];        // 12 values: a0 a1 | a2 b0 || b1 b2 | c0 c1 || c2 d0 | d1 d2
+  u32x4* dst = reinterpret_cast<u32x4*>(xp + q * 32);
+  dst[0] = u32x4{a[0], a[1] & 0xFFFFu, 0u, 0u};
+  dst[1] = u32x4{(a[1] >> 16) | (b[0] << 16), b[0] >> 16, 0u, 0u};
+  dst[2] = u32x4{b[1], c[0] & 0xFFFFu, 0u, 0u};
+  dst[3] = u32x4{(c[0] >> 16) | (c[1] << 16), c[1] >> 16, 0u, 0u};
 }
 
 // one thread = 8 channels of one output position
@@ -93,14 +114,26 @@ inline unsigned blocks_for(long n) { return (unsigned)((n + 255) / 256); }
 
 }  // namespace
 
-void cast_weights_bf16(hipStream_t st, const float* w, bf16_t* w_fwd, bf16_t* w_t, int cout, int taps,
-                       int cin_real, int cin_pad) {
-  const long n = (long)cout * taps * cin_pad;
-  hipLaunchKernelGGL(cast_weights_kernel, dim3(blocks_for(n)), dim3(256), 0, st, w, w_fwd, w_t, cout, taps, cin_real,
-                     cin_pad);
+void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, const CastEntry* entries, int n) {
+  for (int base = 0; base < n; base += kCastMaxEntries) {
+    CastTable tab{};
+    tab.n = std::min(n - base, kCastMaxEntries);
+    int blocks = 0;
+    for (int i = 0; i < tab.n; ++i) {
+      tab.e[i] = entries[base + i];
+      tab.e[i].first_block = blocks;
+      blocks += (int)blocks_for((long)tab.e[i].cout * tab.e[i].taps * tab.e[i].cin_pad);
+    }
+    if (blocks > 0) hipLaunchKernelGGL(cast_weights_kernel, dim3(blocks), dim3(256), 0, st, tab, params, shadow);
+  }
 }
 
 void pad_channels_bf16(hipStream_t st, const bf16_t* x, bf16_t* xp, long pixels, int c_real, int c_pad) {
+  if (c_real == 3 && c_pad == 8 && pixels % 4 == 0 && (reinterpret_cast<uintptr_t>(x) & 7u) == 0 &&
+      (reinterpret_cast<uintptr_t>(xp) & 15u) == 0) {
+    hipLaunchKernelGGL(pad_3to8_kernel, dim3(blocks_for(pixels / 4)), dim3(256), 0, st, x, xp, pixels / 4);
+    return;
+  }
   hipLaunchKernelGGL(pad_channels_kernel, dim3(blocks_for(pixels * c_pad)), dim3(256), 0, st, x, xp, pixels, c_real,
                      c_pad);
 }

@@ -130,3 +130,24 @@ def test_cnn_max_workers():
     params = synth.he_normal_params(layers, 6, True)
     x, y = synth.make_batch(650, off[-1], (8, 8, 3), 10, True)
     _check_step(layers, (8, 8, 3), params, x, y, off, 0.05, "cnn3-64-workers")
+
+
+@pytest.mark.parametrize("c1,B,cuts", [
+    (8, 21, [0, 1, 8, 21]),        # one block of output channels, mostly empty
+    (24, 21, [0, 5, 6, 21]),
+    (32, 40, [0, 13, 40]),
+    (40, 21, [0, 1, 8, 21]),       # two blocks, the second a quarter full
+    (64, 300, [0, 7, 150, 300]),   # two full blocks; enough strips that workers are cut into chunks
+])
+def test_first_layer_weight_gradient_kernel(c1, B, cuts):
+    """32 x 32 inputs with 3 channels: the first layer's weight gradient takes its own kernel
+    (positions as the reduction, (tap, channel) pairs as columns, bias gradient as a column of ones)."""
+    layers = synth.cnn3(num_classes=10, hw=32, chans=(3, c1, 16, 32))
+    rng = np.random.default_rng(c1)
+    params = synth.he_normal_params(layers, 10 + c1, True)
+    for sl in synth.param_slices(layers):
+        if "b" in sl:
+            s, e = sl["b"]
+            params[s:e] = synth.to_bf16_grid(rng.standard_normal(e - s).astype(np.float32) * 0.2)
+    x, y = synth.make_batch(900 + c1, B, (32, 32, 3), 10, True)
+    _check_step(layers, (32, 32, 3), params, x, y, cuts, 0.05, f"cnn3-32px-c{c1}", check_acts=(B <= 64))
