@@ -1337,25 +1337,31 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
   if (want_bias && tid < 64 && co0 + tid < p.Cout) p.gb[(size_t)wk * p.worker_stride + co0 + tid] = bsum;
 }
 
-// Second stage: grid (tiles, workers, 9 taps x 4 register quarters).  Each thread owns
-// the (output channel, input channel) pairs the same thread of the first stage held
-// and adds the worker's chunks in chunk order.
+// Second stage: grid (tiles, workers, 9 taps x 4 register quarters x 4 tile quadrants).  A workgroup
+// owns the (output channel, input channel) pairs one wavefront of the first stage held; each of its
+// four wavefronts adds a quarter of the worker's chunks (chunk order, eight chunks in flight), the
+// quarters are then added in order through LDS: a fixed summation order with four times the loads in
+// flight of one wavefront walking all chunks.
 __global__ __launch_bounds__(kThreads) void conv3_wgrad_reduce_kernel(Wgrad3Params p, Segments seg, ChunkTable ct) {
-  const int tile = blockIdx.x, wk = blockIdx.y, tap = blockIdx.z >> 2, vq = blockIdx.z & 3;
+  __shared__ float part[4][4][64];
+  const int tile = blockIdx.x, wk = blockIdx.y;
+  const int quad = blockIdx.z & 3, vq = (blockIdx.z >> 2) & 3, tap = blockIdx.z >> 4;
   const int nchunks = ct.first[wk + 1] - ct.first[wk];
   if (nchunks <= 1) return;   // written directly by the first stage
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, sub = tid >> 6;
   const int j = lane & 31, h = lane >> 5;
   const int tiles_ci = (p.Cin + 63) / 64;
   const int co0 = (tile / tiles_ci) * 64, ci0 = (tile % tiles_ci) * 64;
-  const int wco = (wave >> 1) * 32, wci = (wave & 1) * 32;
+  const int wco = (quad >> 1) * 32, wci = (quad & 1) * 32;
   const float* all = p.partial + ((size_t)tile * ct.first[seg.K] + ct.first[wk]) * kTile3Stride;
-  const float* mine = all + (size_t)(tap * 16 + vq * 4) * kThreads + tid;
+  const float* mine = all + (size_t)(tap * 16 + vq * 4) * kThreads + quad * 64 + lane;
+  const int per = (nchunks + 3) / 4;
+  const int c0 = min(sub * per, nchunks), c1 = min(c0 + per, nchunks);
   float s[4] = {0.f, 0.f, 0.f, 0.f};
   const int ci = ci0 + wci + j;
   if (ci < p.cin_real) {
-    int c = 0;
-    for (; c + 8 <= nchunks; c += 8) {   // eight chunks in flight; the additions keep chunk order
+    int c = c0;
+    for (; c + 8 <= c1; c += 8) {
       float t[8][4];
 #pragma unroll
       for (int u = 0; u < 8; ++u)
@@ -1366,18 +1372,22 @@ __global__ __launch_bounds__(kThreads) void conv3_wgrad_reduce_kernel(Wgrad3Para
 #pragma unroll
         for (int e = 0; e < 4; ++e) s[e] += t[u][e];
     }
-    for (; c < nchunks; ++c) {
+    for (; c < c1; ++c) {
       const float* q = mine + (size_t)c * kTile3Stride;
 #pragma unroll
       for (int e = 0; e < 4; ++e) s[e] += q[e * kThreads];
     }
   }
-  if (ci < p.cin_real) {
+#pragma unroll
+  for (int e = 0; e < 4; ++e) part[sub][e][lane] = s[e];
+  __syncthreads();
+  if (sub == 0 && ci < p.cin_real) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
+      const float tot = ((part[0][e][lane] + part[1][e][lane]) + part[2][e][lane]) + part[3][e][lane];
       const int v = vq * 4 + e;
       const int co = co0 + wco + 8 * (v / 4) + 4 * h + (v % 4);
-      if (co < p.Cout) p.gw[(size_t)wk * p.worker_stride + ((size_t)co * 9 + tap) * p.cin_real + ci] = s[e];
+      if (co < p.Cout) p.gw[(size_t)wk * p.worker_stride + ((size_t)co * 9 + tap) * p.cin_real + ci] = tot;
     }
   }
   if (blockIdx.z == 0 && p.gb != nullptr && ci0 == 0 && tid < 64 && co0 + tid < p.Cout) {
@@ -1594,25 +1604,35 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
   }
 }
 
-// grid (K, MB * 8): one accumulator element per thread, the worker's chunks added in chunk order
+// grid (K, MB * 32): 64 accumulator elements per workgroup; each of the four wavefronts adds a
+// quarter of the worker's chunks (in chunk order, eight loads in flight), the quarters are then
+// added in order through LDS: a fixed summation order with four times the loads in flight.
 template <int MB>
 __global__ __launch_bounds__(kThreads) void conv1_wgrad_reduce_kernel(Wgrad1Params p, Segments seg, ChunkTable ct) {
   constexpr int kImg = MB * 2 * 16 * 64;
+  __shared__ float part[4][64];
   const int wk = blockIdx.x;
   const int nchunks = ct.first[wk + 1] - ct.first[wk];
   if (nchunks <= 1) return;                                 // written by the first kernel
-  const int e = blockIdx.y * kThreads + threadIdx.x;
+  const int lane = threadIdx.x & 63, sub = threadIdx.x >> 6;
+  const int e = blockIdx.y * 64 + lane;
+  const int per = (nchunks + 3) / 4;
+  const int c0 = min(sub * per, nchunks), c1 = min(c0 + per, nchunks);
   const float* src = p.partial + (size_t)ct.first[wk] * kImg + e;
   float s = 0.f;
-  int c = 0;
-  for (; c + 8 <= nchunks; c += 8) {
+  int c = c0;
+  for (; c + 8 <= c1; c += 8) {
     float t[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) t[u] = src[(size_t)(c + u) * kImg];
 #pragma unroll
     for (int u = 0; u < 8; ++u) s += t[u];
   }
-  for (; c < nchunks; ++c) s += src[(size_t)c * kImg];
+  for (; c < c1; ++c) s += src[(size_t)c * kImg];
+  part[sub][lane] = s;
+  __syncthreads();
+  if (sub != 0) return;
+  s = ((part[0][lane] + part[1][lane]) + part[2][lane]) + part[3][lane];
   float* gw = p.gw + (size_t)wk * p.worker_stride;
   float* gb = p.gb ? p.gb + (size_t)wk * p.worker_stride : nullptr;
   const int blk = e / (16 * 64), v = (e / 64) % 16, l = e % 64;
@@ -1812,7 +1832,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   bool chunked = false;
   for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
   if (chunked)
-    hipLaunchKernelGGL(conv3_wgrad_reduce_kernel, dim3(tiles, seg.K, 36), dim3(kThreads), 0, st, p, seg, ct);
+    hipLaunchKernelGGL(conv3_wgrad_reduce_kernel, dim3(tiles, seg.K, 144), dim3(kThreads), 0, st, p, seg, ct);
   return true;
 }
 
@@ -1836,7 +1856,7 @@ static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   if (total_units == 0) return true;
   // about two workgroups per compute unit, at least 4 units each
   // (every worker's last chunk may be short: aim K below 512 so the total stays within it)
-  const long want = std::max(64, 512 - seg.K);
+  const long want = std::max(64, 1024 - seg.K);
   long upc = std::max<long>((total_units + want - 1) / want, 4);
   ChunkTable ct{};
   for (;;) {
@@ -1865,10 +1885,10 @@ static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   }
   if (mb == 1) {
     hipLaunchKernelGGL(conv1_wgrad_kernel<1>, grid, dim3(kThreads), lds, st, p, seg, ct);
-    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<1>, dim3(seg.K, 8), dim3(kThreads), 0, st, p, seg, ct);
+    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<1>, dim3(seg.K, 32), dim3(kThreads), 0, st, p, seg, ct);
   } else {
     hipLaunchKernelGGL(conv1_wgrad_kernel<2>, grid, dim3(kThreads), lds, st, p, seg, ct);
-    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<2>, dim3(seg.K, 16), dim3(kThreads), 0, st, p, seg, ct);
+    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<2>, dim3(seg.K, 64), dim3(kThreads), 0, st, p, seg, ct);
   }
   return true;
 }
