@@ -1792,7 +1792,9 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   if (lds > 80 * 1024) return false;
   const int tiles = ((Cout + 63) / 64) * ((g.Cs + 63) / 64);
   const size_t max_slots = conv_wgrad_partial_floats() / kTile3Stride;
-  // units per worker, and a chunk length that gives about two workgroups per compute unit
+  // units per worker, and a chunk length that gives about one workgroup per compute unit (every chunk
+  // parks a partial tile of up to 148 KB that the second stage reads back: with 512 chunks that traffic
+  // outweighed the extra parallelism, measured -2 % on the three-layer CNN's step with 256)
   long total_units = 0;
   int units[OMNI_MAX_WORKERS];
   for (int k = 0; k < seg.K; ++k) {
@@ -1800,7 +1802,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
     units[k] = nimg == 1 ? bk * (H / R) : (bk + nimg - 1) / nimg;
     total_units += units[k];
   }
-  long want = std::max<long>(1, 512 / tiles);
+  long want = std::max<long>(1, 256 / tiles);
   long upc = std::max<long>((total_units + want - 1) / want, 4);
   ChunkTable ct{};
   for (;;) {
@@ -1815,7 +1817,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
     // otherwise the partial tiles must fit the scratch and all workgroups should be resident at once
     // (two per compute unit): a few extra ones would run as a second round
     if (acc == seg.K) break;
-    if ((size_t)tiles * acc <= max_slots && (long)tiles * acc <= std::max(512, 2 * tiles * seg.K)) break;
+    if ((size_t)tiles * acc <= max_slots && (long)tiles * acc <= std::max(256, 2 * tiles * seg.K)) break;
     upc += std::max<long>(1, upc / 16);
   }
   p.upc = (int)upc;
