@@ -35,6 +35,9 @@
 //     channels per workgroup; taps are row offsets into the patch.
 // Kernel A also has a mode for the dgrad of stride-2 layers that multiplies only
 // the filter taps an input position can meet (a quarter of a 3x3 filter).
+// The first layer (3 input channels stored as 8) has two more: kernel F (forward, the
+// filter bank in registers) and kernel G (weight gradient, (tap, channel) pairs as the
+// columns of the product).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -1764,8 +1767,8 @@ void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
 }
 
 // 3x3 / stride 1 / pad 1 and a map whose rows tile into units of 128 positions: kernel C.  (Also
-// for the first layer's 8 stored channels: most of its 64-channel tile is empty, but the matrix
-// pipe is not what that layer waits for.)  Returns false if the shape does not qualify.
+// for a first layer with 8 stored channels on maps that are not 32 wide, which kernel G does not
+// take: most of the 64-channel tile is then empty.)  Returns false if the shape does not qualify.
 static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                         size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                         float* partial) {
