@@ -213,7 +213,11 @@ def main():
         one_step()
     torch.cuda.synchronize()
 
+    # the dominant kernel is bracketed by HIP events on every 8th step of the timed loop (a pair of
+    # event packets costs about 3 us on the stream; on every step that is 2 % of this workload's step)
     kcls, klayer, kbound = DOMINANT[w.name]
+    sample_every = 8 if args.steps >= 64 else 1
+    omni.net_timing_sample(net, sample_every)
     omni.net_timing_enable(net, kcls, klayer, args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -223,6 +227,7 @@ def main():
     dt = time.perf_counter() - t0
     k_ms, k_n = omni.net_timing_read(net)
     omni.net_timing_enable(net, -1, -1, 1)
+    omni.net_timing_sample(net, 1)
     final_loss = float(loss.item())
     assert np.isfinite(final_loss), "loss diverged"
 
@@ -271,7 +276,8 @@ def main():
     roofline = {"bound": kbound, "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
                 "unit": unit, "frac": achieved / peak,
                 "traffic": measured_traffic(w.name, f"{kcls}[layer {klayer}]"),
-                "avg_launch_us": kernel_s * 1e6, "launches": int(k_n)}
+                "avg_launch_us": kernel_s * 1e6, "launches": int(k_n),
+                "sampled": f"every {sample_every} steps of the timed loop"}
 
     out = {
         "metric": "samples/sec per ragged weighted SGD step (fwd+bwd+reduce+update)",

@@ -239,6 +239,11 @@ enum {
 };
 int omni_net_timing_enable(omni_net* net, int32_t kernel_class, int32_t layer, int32_t max_launches);
 int omni_net_timing_read(omni_net* net, double* total_ms, int64_t* launches);
+/* Bracket only every `every`-th matching launch (default 1: all of them).  An event pair
+ * costs a few microseconds on the stream; sampling keeps a measurement that runs inside a
+ * timed loop from stretching it.  Applies from the next omni_net_timing_enable on;
+ * max_launches there counts bracketed launches. */
+int omni_net_timing_sample(omni_net* net, int32_t every);
 
 void omni_net_destroy(omni_net* net);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
+    "omni_net_timing_sample",
     "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
     "omni_dyn_create", "omni_dyn_observe", "omni_dyn_adjust", "omni_dyn_get", "omni_dyn_destroy",
     "omni_asp_schedule", "omni_asp_update",
@@ -84,6 +85,7 @@ def _load():
     lib.omni_net_destroy.restype = None
     lib.omni_net_timing_enable.argtypes = [vp, i32, i32, i32]
     lib.omni_net_timing_read.argtypes = [vp, P(C.c_double), P(C.c_int64)]
+    lib.omni_net_timing_sample.argtypes = [vp, i32]
     lib.omni_weighted_sgd.argtypes = [vp, vp, vp, sz, sz, P(i32), i32, f32, vp]
     lib.omni_softmax_xent.argtypes = [vp, vp, vp, i32, P(i32), i32, vp, vp, vp, vp, vp]
     lib.omni_weighted_sgd_momentum.argtypes = [vp, vp, vp, vp, sz, sz, P(i32), i32, f32, f32, f32, vp]
@@ -238,6 +240,10 @@ def net_activation(net, workspace, layer: int, rows: int, dtype: str = "f32"):
 def net_timing_enable(net, kernel_class, layer: int = -1, max_launches: int = 4096):
     cls = KERNEL_CLASSES[kernel_class] if isinstance(kernel_class, str) else int(kernel_class)
     _check(lib.omni_net_timing_enable(net, cls, layer, max_launches))
+
+
+def net_timing_sample(net, every: int):
+    _check(lib.omni_net_timing_sample(net, int(every)))
 
 
 def net_timing_read(net):

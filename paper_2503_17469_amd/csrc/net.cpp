@@ -70,6 +70,8 @@ struct omni_net {
   std::vector<hipEvent_t> sync_ev;  // fork / join points of one step (timing disabled)
   // optional event timing of one kernel class
   int time_class = -1, time_layer = -1;
+  int time_every = 1;            // bracket every time_every-th matching launch
+  long time_seen = 0;
   std::vector<hipEvent_t> ev;   // pairs: start, stop
   size_t ev_used = 0;           // events recorded since the last read
 
@@ -89,6 +91,7 @@ struct TimedScope {
   bool on;
   TimedScope(omni_net* n, hipStream_t s, int cls, int layer) : net(n), st(s) {
     on = n->time_class == cls && (n->time_layer < 0 || n->time_layer == layer) && n->ev_used + 2 <= n->ev.size();
+    if (on) on = (n->time_seen++ % n->time_every) == 0;     // every time_every-th matching launch is bracketed
     if (on) (void)hipEventRecord(net->ev[net->ev_used], st);
   }
   ~TimedScope() {
@@ -330,6 +333,15 @@ int omni_net_timing_enable(omni_net* net, int32_t kernel_class, int32_t layer, i
   }
   net->time_class = kernel_class;
   net->time_layer = layer;
+  net->time_seen = 0;
+  return OMNI_OK;
+}
+
+int omni_net_timing_sample(omni_net* net, int32_t every) {
+  if (!net) return fail(OMNI_EINVAL, "omni_net_timing_sample: NULL net");
+  if (every < 1) return fail(OMNI_EINVAL, "omni_net_timing_sample: every=%d", every);
+  net->time_every = every;
+  net->time_seen = 0;
   return OMNI_OK;
 }
 

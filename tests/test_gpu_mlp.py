@@ -192,3 +192,35 @@ def test_max_workers():
     params = synth.he_normal_params(layers, 64, False)
     x, labels = synth.make_batch(640, off[-1], (1, 1, dims[0]), dims[-1], False)
     _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag="mlp-64-workers")
+
+
+def test_kernel_timing_counts_and_sampling():
+    """The event brackets the benchmark reads: every matching launch, or every n-th; a class that
+    does not occur in the network records nothing; timing off leaves the step's results unchanged."""
+    import paper_2503_17469_amd as omni
+    w = synth.workload(0)
+    b, off = controller_run(w.T, w.B)
+    run = GpuRun(w.layers, w.in_shape, "f32", w.K, w.B)
+    try:
+        base = run.step(w.params, w.x, w.labels, off, 0.1)
+        omni.net_timing_enable(run.net, "linear_wgrad", 0, 16)
+        for _ in range(5):
+            timed = run.step(w.params, w.x, w.labels, off, 0.1)
+        ms, n = omni.net_timing_read(run.net)
+        assert n == 5 and 0.0 < ms < 50.0
+        assert np.array_equal(timed["params"], base["params"])
+        omni.net_timing_sample(run.net, 3)
+        omni.net_timing_enable(run.net, "linear_wgrad", 0, 16)
+        for _ in range(7):
+            run.step(w.params, w.x, w.labels, off, 0.1)
+        ms, n = omni.net_timing_read(run.net)
+        assert n == 3                                      # launches 0, 3 and 6
+        omni.net_timing_sample(run.net, 1)
+        omni.net_timing_enable(run.net, "conv_fwd", -1, 4)
+        run.step(w.params, w.x, w.labels, off, 0.1)
+        assert omni.net_timing_read(run.net)[1] == 0
+        omni.net_timing_enable(run.net, -1, -1, 1)
+        with pytest.raises(omni.OmniError):
+            omni.net_timing_sample(run.net, 0)
+    finally:
+        run.close()
