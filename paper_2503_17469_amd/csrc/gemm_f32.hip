@@ -224,6 +224,7 @@ struct GemmParams {
   uint32_t* counters;  // FWD / DGRAD split-K: one per tile, zero between launches
   size_t c_worker_stride;  // WGRAD: floats between consecutive workers' outputs
   float* bias_grad;        // WGRAD: per worker column sums of A (at + worker*c_worker_stride), may be null
+  int c_vec;               // WGRAD: every worker's output rows are 16-byte aligned (16-byte stores allowed)
   int ngroups;             // WGRAD: consecutive workers are dealt to this many workgroups per tile (gridDim.y)
   int gfirst[9];           // WGRAD: first worker of every group; gfirst[ngroups] = K
 };
@@ -233,12 +234,15 @@ struct GemmParams {
 // and out around the MFMAs of every step, 64 extra vector instructions per 16 MFMAs, because the
 // per-worker flush inside the loop reads and zeroes them.)
 template <int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
-__global__ __launch_bounds__(kThreads, 2) void gemm_f32_kernel(GemmParams p, Segments seg) {
+__global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32_kernel(GemmParams p, Segments seg) {
   using SA = Slab<kTile, BK, A_MC>;
   using SB = Slab<kTile, BK, B_MC>;
   constexpr int kStage = SA::kFloats + SB::kFloats;
   __shared__ __attribute__((aligned(16))) float lds[2 * kStage];
   __shared__ uint32_t arrival;
+  __shared__ float bred[4][kTile];                 // WGRAD: the four wavefronts' bias-gradient partial sums
+  constexpr int kFlushStride = kTile + 4;          // WGRAD: row stride of the output tile staged for the flush
+  static_assert(kTile * kFlushStride <= kStage, "the staged output tile must fit one LDS stage");
   auto sA = [&](int stage) { return lds + stage * kStage; };
   auto sB = [&](int stage) { return lds + stage * kStage + SA::kFloats; };
 
@@ -399,21 +403,45 @@ __global__ __launch_bounds__(kThreads, 2) void gemm_f32_kernel(GemmParams p, Seg
       SA::zero_outside(sA(1 - CUR), k01 - ks1, kend1 - ks1, tid);                                       \
       SB::zero_outside(sB(1 - CUR), k01 - ks1, kend1 - ks1, tid);                                       \
     }                                                                                                   \
-    if (want_bias_grad && tid < kTile) {                                                                \
-      /* A is the output-gradient slab [kk][row]: its column sums are the bias gradient. */             \
-      _Pragma("unroll 8") for (int kk = 0; kk < BK; ++kk) bsum += sA(CUR)[kk * SA::kStride + tid];      \
+    if (want_bias_grad) {                                                                               \
+      /* A is the output-gradient slab [kk][row]: its column sums are the bias gradient.  Each */       \
+      /* wavefront adds a quarter of the slab's reduction steps; the quarters meet at the flush. */     \
+      _Pragma("unroll") for (int kk = 0; kk < BK / 4; ++kk)                                             \
+        bsum += sA(CUR)[(wave * (BK / 4) + kk) * SA::kStride + lane];                                   \
     }                                                                                                   \
     if (MODE == MODE_WGRAD && w1 != w0) {                                                               \
       /* this worker's rows are done: its tile goes out (stores only; the prefetch stays in flight) */ \
       float* C = p.C + (size_t)w0 * p.c_worker_stride;                                                  \
-      if (j < p.N) {                                                                                    \
-        _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                                \
-          const int i = ibase + 8 * (v / 4) + (v % 4);                                                  \
-          if (i < p.M) C[(size_t)i * p.ldc + j] = acc[v] + acc2[v];                                     \
+      if (VEC && p.c_vec) {                                                                             \
+        /* through the LDS stage that was just multiplied, so that every thread writes 16-byte pieces */ \
+        /* of whole 256-byte rows (scattered 4-byte stores, 16 per lane, cost 3 us per launch)        */ \
+        float* tile = sA(CUR);                                                                          \
+        __syncthreads(); /* every wavefront is done reading this stage */                               \
+        _Pragma("unroll") for (int v = 0; v < 16; ++v)                                                  \
+          tile[(wrow + 4 * (lane >> 5) + 8 * (v / 4) + (v % 4)) * kFlushStride + wcol + (lane & 31)] = acc[v] + acc2[v]; \
+        if (want_bias_grad) bred[wave][lane] = bsum;                                                    \
+        __syncthreads();                                                                                \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q) {                                                 \
+          const int idx = tid + kThreads * q, r = idx >> 4, c4 = (idx & 15) * 4;                         \
+          if (row0 + r < p.M && col0 + c4 < p.N)                                                        \
+            *reinterpret_cast<v4f*>(C + (size_t)(row0 + r) * p.ldc + col0 + c4) =                       \
+                *reinterpret_cast<const v4f*>(tile + r * kFlushStride + c4);                            \
+        }                                                                                               \
+      } else {                                                                                          \
+        if (j < p.N) {                                                                                  \
+          _Pragma("unroll") for (int v = 0; v < 16; ++v) {                                              \
+            const int i = ibase + 8 * (v / 4) + (v % 4);                                                \
+            if (i < p.M) C[(size_t)i * p.ldc + j] = acc[v] + acc2[v];                                   \
+          }                                                                                             \
+        }                                                                                               \
+        if (want_bias_grad) {                                                                           \
+          bred[wave][lane] = bsum;                                                                      \
+          __syncthreads();                                                                              \
         }                                                                                               \
       }                                                                                                 \
       if (want_bias_grad && tid < kTile && row0 + tid < p.M)                                            \
-        p.bias_grad[(size_t)w0 * p.c_worker_stride + row0 + tid] = bsum;                                \
+        p.bias_grad[(size_t)w0 * p.c_worker_stride + row0 + tid] =                                      \
+            ((bred[0][tid] + bred[1][tid]) + bred[2][tid]) + bred[3][tid];                              \
       bsum = 0.f;                                                                                       \
       _Pragma("unroll") for (int v = 0; v < 16; ++v) acc[v] = acc2[v] = 0.f;                            \
     }                                                                                                   \
@@ -571,6 +599,7 @@ void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw
   GemmParams p{};
   p.A = dy; p.B = x; p.C = gw; p.M = cout; p.N = cin; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.c_worker_stride = worker_stride; p.bias_grad = gb;
+  p.c_vec = (aligned16(gw) && cin % 4 == 0 && worker_stride % 4 == 0) ? 1 : 0;
   const bool vec = aligned16(dy) && aligned16(x) && (cout % 4 == 0) && (cin % 4 == 0) && seg.off[seg.K] >= 32;
   launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, vec);
 }
