@@ -26,9 +26,10 @@ PEAK_HBM_GBS = 8000.0
 DOMINANT = {
     "tiny_mlp": ("linear_wgrad", 0, "mfma"),
     "mlp3072": ("linear_wgrad", 0, "mfma"),
-    # first conv layer, 3 input channels: 0.3 kflop per byte, far below the chip's ridge point
-    "cnn3": ("conv_wgrad", 0, "hbm"),
-    "cnn3_dynamic": ("conv_wgrad", 0, "hbm"),
+    # data gradient of the second conv layer (64 -> 32 channels on 16 x 16 maps): 2 x 9 x 64 x 32 flop per
+    # (64 + 32 + 32) x 2 bytes of activations = 144 flop per byte, below the chip's ridge point of 312
+    "cnn3": ("conv_dgrad", 3, "hbm"),
+    "cnn3_dynamic": ("conv_dgrad", 3, "hbm"),
     "resnet18": ("conv_fwd", 3, "mfma"),
 }
 
@@ -53,6 +54,18 @@ def wgrad_bytes(layers, in_shape, li, rows, K):
     hi, wi, ci = in_shape if L["src"] < 0 else shapes[L["src"]]
     ci_pad = (ci + 7) // 8 * 8
     return 2.0 * rows * (ho * wo * L["cout"] + hi * wi * ci_pad) + 4.0 * K * L["cout"] * L["k"] * L["k"] * L["cin"]
+
+
+def dgrad_bytes(layers, in_shape, li, rows):
+    """Algorithmic HBM bytes of one conv data-gradient launch of layer li (bf16): the output gradient read
+    once, the input gradient written once, and the layer input read once for the folded ReLU mask."""
+    import synth.nets as nets
+    L = layers[li]
+    shapes = nets.layer_shapes(layers, in_shape)
+    ho, wo, _ = shapes[li]
+    hi, wi, ci = in_shape if L["src"] < 0 else shapes[L["src"]]
+    ci_pad = (ci + 7) // 8 * 8
+    return 2.0 * rows * (ho * wo * L["cout"] + 2 * hi * wi * ci_pad)
 
 
 def cpu_baseline(w, off, budget_s=12.0):
@@ -271,7 +284,9 @@ def main():
         achieved = flops / kernel_s / 1e12
         peak, unit = PEAK_TFLOPS[w.dtype], "TFLOP/s"
     else:
-        achieved = wgrad_bytes(w.layers, w.in_shape, klayer, w.B, w.K) / kernel_s / 1e9
+        nbytes = (dgrad_bytes(w.layers, w.in_shape, klayer, w.B) if kcls == "conv_dgrad"
+                  else wgrad_bytes(w.layers, w.in_shape, klayer, w.B, w.K))
+        achieved = nbytes / kernel_s / 1e9
         peak, unit = PEAK_HBM_GBS, "GB/s"
     roofline = {"bound": kbound, "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
                 "unit": unit, "frac": achieved / peak,
