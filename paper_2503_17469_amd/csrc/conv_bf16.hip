@@ -454,19 +454,22 @@ constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread 
 // A workgroup walks `upw` consecutive units of one channel tile: the next unit's patch
 // and first weight slab travel to registers during the last taps of the current one,
 // so only the first unit of a workgroup waits for memory before it can multiply.
-template <int NP>   // NP: 16-byte patch pieces per thread
+// NB: 32-channel blocks of output per workgroup (2: a 64-channel tile; 1: layers with at most 32
+// output channels, which would leave half of every fragment read and MFMA of the wide tile empty).
+template <int NP, int NB>   // NP: 16-byte patch pieces per thread
 __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) {
+  constexpr int TN = 32 * NB;   // output channels per workgroup
   extern __shared__ __attribute__((aligned(16))) unsigned char smemD[];
   const int W = p.W, H = p.H, R = p.R;
   const int PW = W + 2, PR = R + 2;
   const int npatch = p.nimg * PR * PW;                    // patch positions
   bf16_t* sP = reinterpret_cast<bf16_t*>(smemD);          // [npatch][kRowD]
-  bf16_t* sW = sP + (size_t)npatch * kRowD;               // 2 x [64][kRowD]
+  bf16_t* sW = sP + (size_t)npatch * kRowD;               // 2 x [TN][kRowD]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 31, h = lane >> 5;
-  const int tiles_n = (p.N + 63) / 64;
+  const int tiles_n = (p.N + TN - 1) / TN;
   const int group = blockIdx.x / tiles_n, tile_n = blockIdx.x - group * tiles_n;
-  const int col0 = tile_n * 64;
+  const int col0 = tile_n * TN;
   const int K = 9 * p.Cs;
   const int ubeg = group * p.upw, uend = min(p.units, ubeg + p.upw);
 
@@ -488,12 +491,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     bottom |= (pr == PR - 1 ? 1u : 0u) << t;
     img4 |= (uint64_t)il << (4 * t);
   }
-  // ---- weight staging: rows tid/8 and tid/8 + 32 of the 64-channel tile, octet tid % 8
+  // ---- weight staging: rows tid/8 (and tid/8 + 32) of the channel tile, octet tid % 8
   const int wr = tid >> 3, woct = tid & 7;
-  long woff[2];
+  long woff[NB];
   uint32_t wvalid = 0;
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < NB; ++i) {
     const int r = col0 + wr + 32 * i;
     const bool in = r < p.N;
     woff[i] = in ? (long)r * K + woct * 8 : 0;
@@ -511,7 +514,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   const int bfrag = j * kRowD + h * 8;
 
   const bf16_t* const zp = static_cast<const bf16_t*>(p.zero);   // absent pieces are read from a page of zeros
-  u32x4 rp[NP], rw[2];
+  u32x4 rp[NP], rw[NB];
   uint32_t pvalid = 0;
   // unit -> first image, first row, images present
   auto unit_geom = [&](int unit, int& n0, int& r0, int& nvalid) {
@@ -546,14 +549,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   };
   auto load_w = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
+    for (int i = 0; i < NB; ++i) {
       rw[i] = *reinterpret_cast<const u32x4*>(((wvalid >> i) & 1u) ? p.wgt + (woff[i] + k0) : zp);
     }
   };
   auto store_w = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
-      *reinterpret_cast<u32x4*>(sW + buf * 64 * kRowD + (wr + 32 * i) * kRowD + woct * 8) = rw[i];
+    for (int i = 0; i < NB; ++i)
+      *reinterpret_cast<u32x4*>(sW + buf * TN * kRowD + (wr + 32 * i) * kRowD + woct * 8) = rw[i];
   };
 
   const int nslice = p.Cs / 64;   // the patch is re-staged per 64-channel slice
@@ -564,11 +567,11 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     store_patch();
     store_w(0);
     __syncthreads();
-    v16f acc[2][2];
+    v16f acc[2][NB];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-      for (int b = 0; b < 2; ++b)
+      for (int b = 0; b < NB; ++b)
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
@@ -585,20 +588,20 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
         if (tap == 4) load_patch(last_slice ? min(unit + 1, uend - 1) : unit, last_slice ? 0 : cs + 1);
         __builtin_amdgcn_sched_barrier(0);   // the loads stay here, a whole tap ahead of their use
         const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRowD;
-        const bf16_t* wb = sW + cur * 64 * kRowD + bfrag;
+        const bf16_t* wb = sW + cur * TN * kRowD + bfrag;
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk) {
-          bf16x8 fa[2], fb[2];
+          bf16x8 fa[2], fb[NB];
 #pragma unroll
           for (int a = 0; a < 2; ++a)
             fa[a] = as_bf16x8(*reinterpret_cast<const u32x4*>(sP + pbase[a] + toff + kk * 16));
 #pragma unroll
-          for (int b = 0; b < 2; ++b)
+          for (int b = 0; b < NB; ++b)
             fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(wb + b * 32 * kRowD + kk * 16));
 #pragma unroll
           for (int a = 0; a < 2; ++a)
 #pragma unroll
-            for (int b = 0; b < 2; ++b)
+            for (int b = 0; b < NB; ++b)
               acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[a], fb[b], acc[a][b], 0, 0, 0);
         }
         __builtin_amdgcn_sched_barrier(0);   // nothing that touches the loaded registers moves above the MFMAs
@@ -616,10 +619,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     unit_geom(unit, n0, r0, nvalid);
     const long out_base = ((long)n0 * H + r0) * W;   // the unit's positions are contiguous rows of `out`
     const int npos = nvalid * R * W;                 // live positions of this unit
-    constexpr int kOutPitch = 64 + 4;
+    constexpr int kOutPitch = TN + 4;
     float* so = reinterpret_cast<float*>(smemD);
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
+    for (int b = 0; b < NB; ++b) {
       const int jl = b * 32 + j;
       const int c = col0 + jl;
       const float bj = (p.bias && c < p.N) ? p.bias[c] : 0.f;
@@ -635,9 +638,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     }
     __syncthreads();
 #pragma unroll
-    for (int it = 0; it < kUnitD * 8 / kThreads; ++it) {
+    for (int it = 0; it < kUnitD * (TN / 8) / kThreads; ++it) {
       const int c = tid + kThreads * it;
-      const int il = c >> 3, jl = (c & 7) * 8;
+      const int il = c / (TN / 8), jl = (c % (TN / 8)) * 8;
       const int jg = col0 + jl;
       if (il >= npos || jg >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
       float v[8];
@@ -1683,29 +1686,33 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
   p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0; p.zero = g.zero;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
-  const size_t stage = ((size_t)npatch + 2 * 64) * kRowD * sizeof(bf16_t);
-  const size_t outt = (size_t)kUnitD * (64 + 4) * sizeof(float);
+  const int nb = N <= 32 ? 1 : 2;                 // a 32-channel tile for layers with at most 32 output channels
+  const int tn = 32 * nb;
+  const size_t stage = ((size_t)npatch + 2 * tn) * kRowD * sizeof(bf16_t);
+  const size_t outt = (size_t)kUnitD * (tn + 4) * sizeof(float);
   const size_t lds = std::max(stage, outt);
   if (lds > 80 * 1024) return false;
   const int big = npatch * 8 > 11 * kThreads ? 1 : 0;
   const int units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
-  const int tiles_n = (N + 63) / 64;
+  const int tiles_n = (N + tn - 1) / tn;
   // several units per workgroup once there are enough workgroups to fill the chip a few times over
   int upw = 1;
   while (upw < 4 && (long)units * tiles_n / (upw * 2) >= 2048) upw *= 2;
   p.units = units; p.upw = upw;
   const dim3 grid(((units + upw - 1) / upw) * tiles_n);
-  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
-#define OMNI_CONV3(NP_)                                                                         \
+  static size_t configured[2][2] = {{0, 0}, {0, 0}};   // raising the dynamic LDS limit is a per-function host call
+#define OMNI_CONV3(NP_, NB_)                                                                    \
   {                                                                                             \
-    if (lds > configured[big]) {                                                                \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_>),         \
+    if (lds > configured[big][NB_ - 1]) {                                                       \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_, NB_>),    \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
-      configured[big] = lds;                                                                    \
+      configured[big][NB_ - 1] = lds;                                                           \
     }                                                                                           \
-    hipLaunchKernelGGL((conv3_gemm_kernel<NP_>), grid, dim3(kThreads), lds, st, p);             \
+    hipLaunchKernelGGL((conv3_gemm_kernel<NP_, NB_>), grid, dim3(kThreads), lds, st, p);        \
   }
-  if (big) OMNI_CONV3(13) else OMNI_CONV3(11)
+  if (nb == 1) { if (big) OMNI_CONV3(13, 1) else OMNI_CONV3(11, 1) }
+  else
+  { if (big) OMNI_CONV3(13, 2) else OMNI_CONV3(11, 2) }
 #undef OMNI_CONV3
   return true;
 }
