@@ -151,3 +151,14 @@ def test_first_layer_weight_gradient_kernel(c1, B, cuts):
             params[s:e] = synth.to_bf16_grid(rng.standard_normal(e - s).astype(np.float32) * 0.2)
     x, y = synth.make_batch(900 + c1, B, (32, 32, 3), 10, True)
     _check_step(layers, (32, 32, 3), params, x, y, cuts, 0.05, f"cnn3-32px-c{c1}", check_acts=(B <= 64))
+
+
+def test_first_layer_weight_gradient_kernel_many_workers():
+    """The same kernel with 64 workers of 1 to 3 images each (8 to 24 strips per worker)."""
+    rng = np.random.default_rng(66)
+    b = [int(v) for v in rng.integers(1, 4, size=64)]
+    off = [int(v) for v in [0] + list(np.cumsum(b))]
+    layers = synth.cnn3(num_classes=10, hw=32, chans=(3, 16, 16, 32))
+    params = synth.he_normal_params(layers, 77, True)
+    x, y = synth.make_batch(977, off[-1], (32, 32, 3), 10, True)
+    _check_step(layers, (32, 32, 3), params, x, y, off, 0.05, "cnn3-32px-64-workers", check_acts=False)
