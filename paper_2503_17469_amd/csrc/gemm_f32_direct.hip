@@ -262,6 +262,10 @@ void launch_direct(hipStream_t st, DirectParams& p) {
 // split, and every wavefront gets at least two steps.
 bool small_batch_shape(int rows, int cols, int kred) {
   const long tiles64 = (long)((rows + 63) / 64) * ((cols + 63) / 64);
+  // with fewer than ~100 of this kernel's 32 x 64 tiles most compute units would sit idle while a
+  // few walk a quarter of the reduction each: the split-K kernel spreads such a product better
+  const long tiles32 = (long)((rows + 31) / 32) * ((cols + 63) / 64);
+  if (tiles32 < 100) return false;
   return rows >= 1 && tiles64 < 256 && kred % kStep == 0 && kred / kStep >= 8 &&
          (long)rows * kred < (1L << 30) && (long)cols * kred < (1L << 30);   // 32-bit element offsets
 }

@@ -65,6 +65,9 @@ def test_config1_mlp3072():
     # ragged row tile (77 = 2*32 + 13), ragged column tile (200 = 3*64 + 8), uneven steps per wavefront (320/32 = 10)
     ([256, 320, 200, 10], [0, 3, 40, 41, 77]),
     ([288, 256, 30, 5], [0, 31, 32, 33]),          # one row tile, 30-column tile, 9 steps
+    # enough 32 x 64 tiles (7 x 16) for the small-batch kernels, with a ragged last row tile (201 rows) and
+    # a half-full last column tile (992 columns): forward of layer 0 and data gradient of layer 1
+    ([256, 992, 512, 10], [0, 3, 90, 91, 201]),
 ])
 def test_ragged_shapes(dims, off):
     layers = synth.mlp(dims)
