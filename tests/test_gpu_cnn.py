@@ -80,6 +80,11 @@ def test_cnn_with_biases_and_odd_batches():
     (16, (3, 64, 96, 64), 21, [0, 1, 8, 21]),
     # conv2 64->64 on 16x16 maps (one image per forward unit, two units per image for wgrad), conv3 on 8x8
     (32, (3, 64, 64, 128), 9, [0, 2, 9]),
+    # the 32-channel output tile of the forward / data-gradient patch kernel: conv2 64->24 (forward: a tile
+    # three quarters full; its data gradient reduces over 24, another kernel), conv3 24->64 (data gradient:
+    # 24 outputs from a reduction over 64)
+    (16, (3, 64, 24, 64), 21, [0, 5, 6, 21]),
+    (32, (3, 64, 32, 64), 10, [0, 3, 10]),
 ])
 def test_cnn_patch_kernels(hw, chans, B, cuts):
     layers = synth.cnn3(num_classes=10, hw=hw, chans=chans)
