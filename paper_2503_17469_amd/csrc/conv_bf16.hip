@@ -456,15 +456,21 @@ constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread 
 // so only the first unit of a workgroup waits for memory before it can multiply.
 // NB: 32-channel blocks of output per workgroup (2: a 64-channel tile; 1: layers with at most 32
 // output channels, which would leave half of every fragment read and MFMA of the wide tile empty).
-template <int NP, int NB>   // NP: 16-byte patch pieces per thread
+// KC: channels of the reduction staged at a time (64; 32 for layers with 32, 96, ... input channels, whose
+// patch rows are then 80 bytes: sixteen lanes still cover all 64 banks).
+template <int NP, int NB, int KC>   // NP: 16-byte patch pieces per thread
 __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) {
   constexpr int TN = 32 * NB;   // output channels per workgroup
+  constexpr int OC = KC / 8;    // 16-byte pieces per patch position and per weight row
+  constexpr int kRow = KC + 8;  // elements per LDS row
+  constexpr int RP = kThreads / OC;               // weight rows staged per pass
+  constexpr int WP = (TN + RP - 1) / RP;          // passes
   extern __shared__ __attribute__((aligned(16))) unsigned char smemD[];
   const int W = p.W, H = p.H, R = p.R;
   const int PW = W + 2, PR = R + 2;
   const int npatch = p.nimg * PR * PW;                    // patch positions
-  bf16_t* sP = reinterpret_cast<bf16_t*>(smemD);          // [npatch][kRowD]
-  bf16_t* sW = sP + (size_t)npatch * kRowD;               // 2 x [TN][kRowD]
+  bf16_t* sP = reinterpret_cast<bf16_t*>(smemD);          // [npatch][kRow]
+  bf16_t* sW = sP + (size_t)npatch * kRow;                // 2 x [TN][kRow]
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 31, h = lane >> 5;
   const int tiles_n = (p.N + TN - 1) / TN;
@@ -473,16 +479,16 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   const int K = 9 * p.Cs;
   const int ubeg = group * p.upw, uend = min(p.units, ubeg + p.upw);
 
-  // ---- patch staging tasks: piece x = tid + 256 t -> patch position x / 8, channel octet x % 8.
+  // ---- patch staging tasks: piece x = tid + 256 t -> patch position x / OC, channel octet x % OC.
   // Relative to the unit's first image and row; which pieces exist depends on the unit.
   int prel[NP];                // element offset relative to the unit (the host checks the tensor has fewer than 2^31)
   uint32_t col_ok = 0, top = 0, bottom = 0;   // piece t: inside the image's columns / in the first / last patch row
   uint64_t img4 = 0;                           // piece t: image within the unit, 4 bits each
-  const int npieces = npatch * 8;
+  const int npieces = npatch * OC;
 #pragma unroll
   for (int t = 0; t < NP; ++t) {
     const int x = tid + t * kThreads;
-    const int pp = min(x, npieces - 1) >> 3, oct = x & 7;
+    const int pp = min(x, npieces - 1) / OC, oct = x % OC;
     const int il = pp / (PR * PW), rem = pp - il * (PR * PW);
     const int pr = rem / PW, pc = rem - pr * PW;
     prel[t] = ((il * H + pr - 1) * W + pc - 1) * p.Cs + oct * 8;
@@ -491,14 +497,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     bottom |= (pr == PR - 1 ? 1u : 0u) << t;
     img4 |= (uint64_t)il << (4 * t);
   }
-  // ---- weight staging: rows tid/8 (and tid/8 + 32) of the channel tile, octet tid % 8
-  const int wr = tid >> 3, woct = tid & 7;
-  long woff[NB];
+  // ---- weight staging: rows tid/OC (+ RP per pass) of the channel tile, octet tid % OC
+  const int wr = tid / OC, woct = tid % OC;
+  long woff[WP];
   uint32_t wvalid = 0;
 #pragma unroll
-  for (int i = 0; i < NB; ++i) {
-    const int r = col0 + wr + 32 * i;
-    const bool in = r < p.N;
+  for (int i = 0; i < WP; ++i) {
+    const int r = col0 + wr + RP * i;
+    const bool in = r < p.N && wr + RP * i < TN;
     woff[i] = in ? (long)r * K + woct * 8 : 0;
     wvalid |= (in ? 1u : 0u) << i;
   }
@@ -509,12 +515,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     const int pos = wave * 64 + a * 32 + j;
     const int rr = pos / W, w = pos - rr * W;
     const int il = rr / R, r = rr - il * R;
-    pbase[a] = ((il * PR + r) * PW + w) * kRowD + h * 8;   // patch origin is (-1, -1): tap (u, v) adds u*PW + v
+    pbase[a] = ((il * PR + r) * PW + w) * kRow + h * 8;   // patch origin is (-1, -1): tap (u, v) adds u*PW + v
   }
-  const int bfrag = j * kRowD + h * 8;
+  const int bfrag = j * kRow + h * 8;
 
   const bf16_t* const zp = static_cast<const bf16_t*>(p.zero);   // absent pieces are read from a page of zeros
-  u32x4 rp[NP], rw[NB];
+  u32x4 rp[NP], rw[WP];
   uint32_t pvalid = 0;
   // unit -> first image, first row, images present
   auto unit_geom = [&](int unit, int& n0, int& r0, int& nvalid) {
@@ -529,7 +535,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
   auto load_patch = [&](int unit, int cs) {
     int n0, r0, nvalid;
     unit_geom(unit, n0, r0, nvalid);
-    const int ubase = (n0 * H + r0) * W * p.Cs + cs * 64;
+    const int ubase = (n0 * H + r0) * W * p.Cs + cs * KC;
     // the first / last patch row lies outside the image when the unit touches its top / bottom edge
     pvalid = col_ok & ~(r0 == 0 ? top : 0u) & ~(r0 + R == H ? bottom : 0u);
 #pragma unroll
@@ -544,22 +550,23 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     for (int t = 0; t < NP; ++t) {
       const int x = tid + t * kThreads;
       if (x < npieces)
-        *reinterpret_cast<u32x4*>(sP + (x >> 3) * kRowD + (x & 7) * 8) = rp[t];
+        *reinterpret_cast<u32x4*>(sP + (x / OC) * kRow + (x % OC) * 8) = rp[t];
     }
   };
   auto load_w = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < NB; ++i) {
+    for (int i = 0; i < WP; ++i) {
       rw[i] = *reinterpret_cast<const u32x4*>(((wvalid >> i) & 1u) ? p.wgt + (woff[i] + k0) : zp);
     }
   };
   auto store_w = [&](int buf) {
 #pragma unroll
-    for (int i = 0; i < NB; ++i)
-      *reinterpret_cast<u32x4*>(sW + buf * TN * kRowD + (wr + 32 * i) * kRowD + woct * 8) = rw[i];
+    for (int i = 0; i < WP; ++i)
+      if (wr + RP * i < TN)   // (a pass may cover more rows than the tile has)
+        *reinterpret_cast<u32x4*>(sW + buf * TN * kRow + (wr + RP * i) * kRow + woct * 8) = rw[i];
   };
 
-  const int nslice = p.Cs / 64;   // the patch is re-staged per 64-channel slice
+  const int nslice = p.Cs / KC;   // the patch is re-staged per KC-channel slice
   load_patch(min(ubeg, p.units - 1), 0);
   load_w(0);
   for (int unit = ubeg; unit < uend; ++unit) {
@@ -582,22 +589,22 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
         const int cur = tap & 1 ? 1 - (cs & 1) : (cs & 1);   // step cs*9 + tap, odd/even (9 taps per slice)
         const int u = tap / 3, v = tap - u * 3;
         // next step's weights (always issued): next tap, next slice, or the next unit's first slab
-        if (tap < 8) load_w((tap + 1) * p.Cs + cs * 64);
-        else load_w(last_slice ? 0 : (cs + 1) * 64);
+        if (tap < 8) load_w((tap + 1) * p.Cs + cs * KC);
+        else load_w(last_slice ? 0 : (cs + 1) * KC);
         // the next slice's patch (or the next unit's first) starts its way to registers a few taps early
         if (tap == 4) load_patch(last_slice ? min(unit + 1, uend - 1) : unit, last_slice ? 0 : cs + 1);
         __builtin_amdgcn_sched_barrier(0);   // the loads stay here, a whole tap ahead of their use
-        const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRowD;
-        const bf16_t* wb = sW + cur * TN * kRowD + bfrag;
+        const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRow;
+        const bf16_t* wb = sW + cur * TN * kRow + bfrag;
 #pragma unroll
-        for (int kk = 0; kk < 4; ++kk) {
+        for (int kk = 0; kk < KC / 16; ++kk) {
           bf16x8 fa[2], fb[NB];
 #pragma unroll
           for (int a = 0; a < 2; ++a)
             fa[a] = as_bf16x8(*reinterpret_cast<const u32x4*>(sP + pbase[a] + toff + kk * 16));
 #pragma unroll
           for (int b = 0; b < NB; ++b)
-            fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(wb + b * 32 * kRowD + kk * 16));
+            fb[b] = as_bf16x8(*reinterpret_cast<const u32x4*>(wb + b * 32 * kRow + kk * 16));
 #pragma unroll
           for (int a = 0; a < 2; ++a)
 #pragma unroll
@@ -1667,13 +1674,15 @@ static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
   hipLaunchKernelGGL((conv_gemm2_kernel<TN, MODE>), dim3(tiles), dim3(kThreads), kBytes, st, p);
 }
 
-// 3x3 / pad 1 / stride 1 (forward, or dgrad of such a layer) with channels a multiple of 64 and a
+// 3x3 / pad 1 / stride 1 (forward, or dgrad of such a layer) with channels a multiple of 32 and a
 // map whose rows tile into units of 256 positions: kernel D.  Returns false if the shape does not qualify.
 static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                        const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
   const int H = g.Hs, W = g.Ws;
   if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
-  if (g.Cs % 64 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
+  if (g.Cs % 32 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
+  const int kc = g.Cs % 64 == 0 ? 64 : 32;        // channels of the reduction staged at a time
+  const int oc = kc / 8;
   if ((long)M * g.Cs >= (1L << 31)) return false;   // 32-bit element offsets in the kernel
   if (W < 8 || W > kUnitD || kUnitD % W != 0) return false;
   const int R = std::min(H, kUnitD / W);
@@ -1681,18 +1690,18 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   const int nimg = kUnitD / (R * W);
   if (nimg > 1 && R != H) return false;
   const int npatch = nimg * (R + 2) * (W + 2);
-  if (npatch * 8 > kMaxPatchPieces * kThreads) return false;
+  if (npatch * oc > kMaxPatchPieces * kThreads) return false;
   Conv3Params p{};
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
   p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0; p.zero = g.zero;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
   const int nb = N <= 32 ? 1 : 2;                 // a 32-channel tile for layers with at most 32 output channels
   const int tn = 32 * nb;
-  const size_t stage = ((size_t)npatch + 2 * tn) * kRowD * sizeof(bf16_t);
+  const size_t stage = ((size_t)npatch + 2 * tn) * (kc + 8) * sizeof(bf16_t);
   const size_t outt = (size_t)kUnitD * (tn + 4) * sizeof(float);
   const size_t lds = std::max(stage, outt);
   if (lds > 80 * 1024) return false;
-  const int big = npatch * 8 > 11 * kThreads ? 1 : 0;
+  const int big = npatch * oc > 11 * kThreads ? 1 : 0;
   const int units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
   const int tiles_n = (N + tn - 1) / tn;
   // several units per workgroup once there are enough workgroups to fill the chip a few times over
@@ -1700,19 +1709,22 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   while (upw < 4 && (long)units * tiles_n / (upw * 2) >= 2048) upw *= 2;
   p.units = units; p.upw = upw;
   const dim3 grid(((units + upw - 1) / upw) * tiles_n);
-  static size_t configured[2][2] = {{0, 0}, {0, 0}};   // raising the dynamic LDS limit is a per-function host call
-#define OMNI_CONV3(NP_, NB_)                                                                    \
+  static size_t configured[2][2][2] = {};   // raising the dynamic LDS limit is a per-function host call
+#define OMNI_CONV3(NP_, NB_, KC_)                                                               \
   {                                                                                             \
-    if (lds > configured[big][NB_ - 1]) {                                                       \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_, NB_>),    \
+    size_t& conf = configured[big][NB_ - 1][KC_ == 64 ? 0 : 1];                                 \
+    if (lds > conf) {                                                                           \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_, NB_, KC_>), \
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
-      configured[big][NB_ - 1] = lds;                                                           \
+      conf = lds;                                                                               \
     }                                                                                           \
-    hipLaunchKernelGGL((conv3_gemm_kernel<NP_, NB_>), grid, dim3(kThreads), lds, st, p);        \
+    hipLaunchKernelGGL((conv3_gemm_kernel<NP_, NB_, KC_>), grid, dim3(kThreads), lds, st, p);   \
   }
-  if (nb == 1) { if (big) OMNI_CONV3(13, 1) else OMNI_CONV3(11, 1) }
+#define OMNI_CONV3_KC(NP_, NB_) { if (kc == 64) OMNI_CONV3(NP_, NB_, 64) else OMNI_CONV3(NP_, NB_, 32) }
+  if (nb == 1) { if (big) OMNI_CONV3_KC(13, 1) else OMNI_CONV3_KC(11, 1) }
   else
-  { if (big) OMNI_CONV3(13, 2) else OMNI_CONV3(11, 2) }
+  { if (big) OMNI_CONV3_KC(13, 2) else OMNI_CONV3_KC(11, 2) }
+#undef OMNI_CONV3_KC
 #undef OMNI_CONV3
   return true;
 }
