@@ -26,10 +26,10 @@ PEAK_HBM_GBS = 8000.0
 DOMINANT = {
     "tiny_mlp": ("linear_wgrad", 0, "mfma"),
     "mlp3072": ("linear_wgrad", 0, "mfma"),
-    # data gradient of the second conv layer (64 -> 32 channels on 16 x 16 maps): 2 x 9 x 64 x 32 flop per
-    # (64 + 32 + 32) x 2 bytes of activations = 144 flop per byte, below the chip's ridge point of 312
-    "cnn3": ("conv_dgrad", 3, "hbm"),
-    "cnn3_dynamic": ("conv_dgrad", 3, "hbm"),
+    # weight gradient of the second conv layer (32 -> 64 channels on 16 x 16 maps): 2 x 9 x 32 x 64 flop per
+    # (64 + 32) x 2 bytes of activations = 192 flop per byte, below the chip's ridge point of 312
+    "cnn3": ("conv_wgrad", 3, "hbm"),
+    "cnn3_dynamic": ("conv_wgrad", 3, "hbm"),
     "resnet18": ("conv_fwd", 3, "mfma"),
 }
 

@@ -1317,12 +1317,22 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
       }
       }
     }
-    if (want_bias && tid < 64) {
-      // rows of dY^T are output channels: their sums over positions are the bias gradient
-      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA + tid * kSA);
-#pragma unroll 16
-      for (int d = 0; d < kUnit / 2; ++d) bsum += bf16_lo(rowp[d]) + bf16_hi(rowp[d]);
+    if (want_bias) {
+      // rows of dY^T are output channels: their sums over positions are the bias gradient; every
+      // wavefront adds a quarter of the unit's positions (one wavefront walking all 128 was a serial
+      // chain of a thousand cycles per unit that the other three waited for at the next barrier)
+      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA + lane * kSA) + wave * (kUnit / 8);
+#pragma unroll
+      for (int d = 0; d < kUnit / 8; ++d) bsum += bf16_lo(rowp[d]) + bf16_hi(rowp[d]);
     }
+  }
+  if (want_bias) {
+    // the four quarters meet, in wavefront order
+    __syncthreads();
+    float* quarter = reinterpret_cast<float*>(sA);
+    quarter[tid] = bsum;
+    __syncthreads();
+    if (tid < 64) bsum = ((quarter[tid] + quarter[64 + tid]) + quarter[128 + tid]) + quarter[192 + tid];
   }
 
   const int ci = ci0 + wci + j;
