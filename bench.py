@@ -252,6 +252,20 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     value = w.B * args.steps / dt
 
+    # spread of single steps: every step of a second, shorter loop between two events of its own
+    # (the event packets add about 3 us to each, which is why the headline loop above has none inside)
+    n_each = min(200, args.steps)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
+    for e0, e1 in evs:
+        e0.record()
+        one_step()
+        e1.record()
+    torch.cuda.synchronize()
+    each_us = np.sort(np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in evs]))
+    step_spread = {"unit": "us", "n": n_each, "median": float(np.percentile(each_us, 50)),
+                   "p10": float(np.percentile(each_us, 10)), "p90": float(np.percentile(each_us, 90)),
+                   "note": "device time of single steps, each between two events of its own"}
+
     # the fused weighted-reduce + SGD kernel against the HBM roofline (separate short loop, same buffers)
     n_upd = min(200, args.steps)
     omni.net_timing_enable(net, "update", -1, n_upd)
@@ -283,6 +297,22 @@ def main():
     # the asynchronous variant keeps one workspace per worker; it is measured on the default workload only
     asp = None if (args.no_asp or w.name != "mlp3072") else asp_variant(omni, torch, net, w, b, off, params, x, y, lr)
 
+    # what a plain device-to-device copy reaches on this GPU (256 MiB read + 256 MiB written per copy, more
+    # than the Infinity Cache holds): the practical ceiling beside the 8 TB/s the rooflines divide by
+    cp_src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    cp_dst = torch.empty_like(cp_src)
+    for _ in range(3):
+        cp_dst.copy_(cp_src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n_copy = 20
+    c0.record()
+    for _ in range(n_copy):
+        cp_dst.copy_(cp_src)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 2.0 * cp_src.numel() * n_copy / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del cp_src, cp_dst
+
     kernel_s = k_ms / max(k_n, 1) * 1e-3
     if kbound == "mfma":
         flops = layer_flops(w.layers, w.in_shape, klayer, w.B)
@@ -308,6 +338,7 @@ def main():
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "device_ms_per_step": device_ms_per_step,
+        "step_spread": step_spread,
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -327,6 +358,8 @@ def main():
                                      "frac": mom_gbs / PEAK_HBM_GBS,
                                      "traffic": measured_traffic(w.name, "update_momentum"), "bytes_per_launch": mom_bytes,
                                      "avg_launch_us": m_ms / max(m_n, 1) * 1e3},
+        "hbm_copy_ceiling": {"achieved": copy_gbs, "unit": "GB/s", "bytes_per_copy": 2.0 * (256 << 20),
+                             "note": "plain device-to-device copy, read + write counted"},
         "final_loss": final_loss,
     }
     if asp is not None:
