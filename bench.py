@@ -314,8 +314,16 @@ def main():
     del cp_src, cp_dst
 
     kernel_s = k_ms / max(k_n, 1) * 1e-3
+    klabel = f"{kcls}[layer {klayer}]"
     if kbound == "mfma":
-        flops = layer_flops(w.layers, w.in_shape, klayer, w.B)
+        covered = [klayer]
+        if kcls == "linear_wgrad":
+            # an fp32 network computes the weight gradients of all fully connected layers before the
+            # classifier head in one launch, timed as layer 0: its flop are those of all of them
+            covered = [i for i, L in enumerate(w.layers) if L["op"] == "linear"][:-1]
+            if len(covered) > 1:
+                klabel = f"{kcls}[layers {', '.join(str(i) for i in covered)}: one launch]"
+        flops = sum(layer_flops(w.layers, w.in_shape, i, w.B) for i in covered)
         achieved = flops / kernel_s / 1e12
         peak, unit = PEAK_TFLOPS[w.dtype], "TFLOP/s"
     else:
@@ -323,9 +331,9 @@ def main():
                   else wgrad_bytes(w.layers, w.in_shape, klayer, w.B, w.K))
         achieved = nbytes / kernel_s / 1e9
         peak, unit = PEAK_HBM_GBS, "GB/s"
-    roofline = {"bound": kbound, "kernel": f"{kcls}[layer {klayer}]", "achieved": achieved, "peak": peak,
+    roofline = {"bound": kbound, "kernel": klabel, "achieved": achieved, "peak": peak,
                 "unit": unit, "frac": achieved / peak,
-                "traffic": measured_traffic(w.name, f"{kcls}[layer {klayer}]"),
+                "traffic": measured_traffic(w.name, klabel),
                 "avg_launch_us": kernel_s * 1e6, "launches": int(k_n),
                 "sampled": f"every {sample_every} steps of the timed loop"}
 

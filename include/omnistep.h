@@ -225,7 +225,10 @@ int omni_net_activation(const omni_net* net, const void* workspace, int32_t laye
  * recorded until the next read.  omni_net_timing_read waits for the recorded
  * events, returns their summed elapsed time and count, and clears the record.
  * kernel_class < 0 disables timing.  Events are created inside the enable call
- * (never inside omni_step).  Returns OMNI_EINVAL on a bad class. */
+ * (never inside omni_step).  Returns OMNI_EINVAL on a bad class.
+ * In an fp32 network the weight gradients of all fully connected layers before
+ * the classifier head run as ONE launch; it counts as a launch of the lowest
+ * layer index it covers (layer 0 of a multi-layer perceptron). */
 enum {
   OMNI_KERNEL_LINEAR_FWD = 0,
   OMNI_KERNEL_LINEAR_DGRAD = 1,

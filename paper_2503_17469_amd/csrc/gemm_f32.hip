@@ -23,7 +23,9 @@
 //   * wgrad gives every workgroup one output tile position and lets it walk
 //     through ALL workers' row ranges one after the other, flushing the
 //     accumulator into worker k's gradient when k's rows end.  Every workgroup
-//     then does the same amount of work however ragged the b_k are.
+//     then does the same amount of work however ragged the b_k are.  The
+//     weight gradients of several layers can share one launch
+//     (linear_wgrad_f32_batch): their workgroups follow each other in one grid.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -233,8 +235,10 @@ struct GemmParams {
 // ordinary vector registers.  With accumulation registers it copied all 32 accumulator registers in
 // and out around the MFMAs of every step, 64 extra vector instructions per 16 MFMAs, because the
 // per-worker flush inside the loop reads and zeroes them.)
+// The whole workgroup program; (bx, by) is the workgroup's place in a launch of nbx workgroups along x.
 template <int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
-__global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32_kernel(GemmParams p, Segments seg) {
+__device__ __forceinline__ void gemm_f32_body(const GemmParams& p, const Segments& seg, const int bx, const int by,
+                                              const int nbx) {
   using SA = Slab<kTile, BK, A_MC>;
   using SB = Slab<kTile, BK, B_MC>;
   constexpr int kStage = SA::kFloats + SB::kFloats;
@@ -249,7 +253,7 @@ __global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int tiles_n = (p.N + kTile - 1) / kTile;
   const int tiles_m = (p.M + kTile - 1) / kTile;
-  int tile = blockIdx.x, split = 0;
+  int tile = bx, split = 0;
   const int splits = (MODE == MODE_WGRAD) ? 1 : p.splits;
   if (MODE != MODE_WGRAD) {
     // Forward / dgrad launch tiles*splits workgroups in one dimension.  They are
@@ -257,10 +261,10 @@ __global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32
     // owns a contiguous run of (split, tile) pairs, split-major: an XCD then
     // works on ONE slice of the reduction, and that slice of both operands
     // (a few MB) stays in its own L2 while all its tiles sweep over it.
-    int g = blockIdx.x;
+    int g = bx;
     if (p.xcd_remap) {
-      const int per = gridDim.x >> 3;
-      g = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
+      const int per = nbx >> 3;
+      g = (bx & 7) * per + (bx >> 3);
     }
     const int tiles = tiles_m * tiles_n;
     split = g / tiles;
@@ -275,10 +279,10 @@ __global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32
   // The reduction is a stream of slabs over one or more consecutive ranges
   // ("workers"); the accumulator is flushed whenever a range ends.  A slab is
   // (range index w, start k0, end of its range kend); w == nrange marks the end.
-  const int nrange = (MODE == MODE_WGRAD) ? p.gfirst[blockIdx.y + 1] : 1;
+  const int nrange = (MODE == MODE_WGRAD) ? p.gfirst[by + 1] : 1;
   int w0 = 0, k00, kend0;
   if (MODE == MODE_WGRAD) {
-    w0 = p.gfirst[blockIdx.y];
+    w0 = p.gfirst[by];
     k00 = seg.off[w0];
     kend0 = seg.off[w0 + 1];
   } else {
@@ -520,7 +524,53 @@ __global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32
   }
 }
 
+template <int BK, bool A_MC, bool B_MC, int MODE, bool VEC>
+__global__ __launch_bounds__(kThreads, MODE == MODE_WGRAD ? 3 : 2) void gemm_f32_kernel(GemmParams p, Segments seg) {
+  gemm_f32_body<BK, A_MC, B_MC, MODE, VEC>(p, seg, (int)blockIdx.x, (int)blockIdx.y, (int)gridDim.x);
+}
+
+// Weight gradients of several layers in ONE launch: the workgroups of the problems follow each other
+// along x (problem i owns start[i] .. start[i+1]-1, tiles fastest, then worker groups).  A launch
+// has a start-up and a drain during which the matrix pipes idle; run together, one problem's
+// workgroups start while another's finish.
+constexpr int kMaxBatch = 8;
+struct WgradBatch {
+  int n;
+  int start[kMaxBatch + 1];
+  GemmParams prob[kMaxBatch];
+};
+
+template <int BK, bool VEC>
+__global__ __launch_bounds__(kThreads, 3) void gemm_f32_wgrad_batch_kernel(WgradBatch b, Segments seg) {
+  int pi = 0;
+  for (int i = 1; i < b.n; ++i)
+    if ((int)blockIdx.x >= b.start[i]) pi = i;
+  const GemmParams& p = b.prob[pi];
+  const int local = (int)blockIdx.x - b.start[pi];
+  const int tiles = ((p.M + kTile - 1) / kTile) * ((p.N + kTile - 1) / kTile);
+  const int by = local / tiles;
+  gemm_f32_body<BK, true, true, MODE_WGRAD, VEC>(p, seg, local - by * tiles, by, tiles);
+}
+
 inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Deals the workers of a weight-gradient problem to workgroups per tile (p.gfirst, p.ngroups):
+// with few tiles, groups of consecutive workers with about equal row counts (each worker stays
+// whole, so nothing is summed across workgroups).  `want` is the number of workgroups to aim for.
+int plan_worker_groups(GemmParams& p, const Segments& seg, int tiles, int want) {
+  int G = tiles >= want ? 1 : std::min(std::min(8, seg.K), (want + tiles - 1) / tiles);
+  const int B = seg.off[seg.K];
+  p.gfirst[0] = 0;
+  int g = 1;
+  for (int w = 1; w < seg.K && g < G; ++w) {
+    // start group g at the first worker whose start reaches g/G of the rows (keeping every later group non-empty)
+    if ((long)seg.off[w] * G >= (long)g * B || seg.K - w <= G - g) p.gfirst[g++] = w;
+  }
+  G = g;
+  p.gfirst[G] = seg.K;
+  p.ngroups = G;
+  return G;
+}
 
 template <int BK, bool A_MC, bool B_MC, int MODE>
 void launch(hipStream_t st, GemmParams& p, const Segments& seg, int splits, bool vec) {
@@ -528,23 +578,7 @@ void launch(hipStream_t st, GemmParams& p, const Segments& seg, int splits, bool
   p.splits = splits;
   p.xcd_remap = (MODE != MODE_WGRAD && (tiles * splits) % 8 == 0) ? 1 : 0;
   dim3 grid(tiles * splits, 1, 1);
-  if (MODE == MODE_WGRAD) {
-    // With few tiles, the workers are dealt to several workgroups per tile: groups of
-    // consecutive workers with about equal row counts (each worker stays whole, so
-    // nothing is summed across workgroups).
-    int G = tiles >= 512 ? 1 : std::min(std::min(8, seg.K), (512 + tiles - 1) / tiles);
-    const int B = seg.off[seg.K];
-    p.gfirst[0] = 0;
-    int g = 1;
-    for (int w = 1; w < seg.K && g < G; ++w) {
-      // start group g at the first worker whose start reaches g/G of the rows (keeping every later group non-empty)
-      if ((long)seg.off[w] * G >= (long)g * B || seg.K - w <= G - g) p.gfirst[g++] = w;
-    }
-    G = g;
-    p.gfirst[G] = seg.K;
-    p.ngroups = G;
-    grid = dim3(tiles, G, 1);
-  }
+  if (MODE == MODE_WGRAD) grid = dim3(tiles, plan_worker_groups(p, seg, tiles, 512), 1);
   if (vec)
     hipLaunchKernelGGL((gemm_f32_kernel<BK, A_MC, B_MC, MODE, true>), grid, dim3(kThreads), 0, st, p, seg);
   else
@@ -594,14 +628,48 @@ void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const flo
   launch<32, false, true, MODE_DGRAD>(st, p, seg, pick_splits(gemm_tiles(rows, cin), cout, 32, sw), vec);
 }
 
+static bool wgrad_params(GemmParams& p, const LinearWgradJob& j, size_t worker_stride, const Segments& seg) {
+  p = GemmParams{};
+  p.A = j.dy; p.B = j.x; p.C = j.gw; p.M = j.cout; p.N = j.cin; p.lda = j.cout; p.ldb = j.cin; p.ldc = j.cin;
+  p.c_worker_stride = worker_stride; p.bias_grad = j.gb;
+  p.c_vec = (aligned16(j.gw) && j.cin % 4 == 0 && worker_stride % 4 == 0) ? 1 : 0;
+  return aligned16(j.dy) && aligned16(j.x) && (j.cout % 4 == 0) && (j.cin % 4 == 0) && seg.off[seg.K] >= 32;
+}
+
 void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw, float* gb,
                       size_t worker_stride, const Segments& seg, int cin, int cout) {
-  GemmParams p{};
-  p.A = dy; p.B = x; p.C = gw; p.M = cout; p.N = cin; p.lda = cout; p.ldb = cin; p.ldc = cin;
-  p.c_worker_stride = worker_stride; p.bias_grad = gb;
-  p.c_vec = (aligned16(gw) && cin % 4 == 0 && worker_stride % 4 == 0) ? 1 : 0;
-  const bool vec = aligned16(dy) && aligned16(x) && (cout % 4 == 0) && (cin % 4 == 0) && seg.off[seg.K] >= 32;
+  GemmParams p;
+  const LinearWgradJob job{dy, x, gw, gb, cin, cout};
+  const bool vec = wgrad_params(p, job, worker_stride, seg);
   launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, vec);
+}
+
+void linear_wgrad_f32_batch(hipStream_t st, const LinearWgradJob* jobs, int n, size_t worker_stride,
+                            const Segments& seg) {
+  // problems that can take the mask-free loads share launches of up to kMaxBatch; the others go alone
+  WgradBatch b{};
+  auto flush = [&]() {
+    if (b.n == 1) {
+      GemmParams p = b.prob[0];
+      launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, true);
+    } else if (b.n > 1) {
+      hipLaunchKernelGGL((gemm_f32_wgrad_batch_kernel<32, true>), dim3(b.start[b.n]), dim3(kThreads), 0, st, b, seg);
+    }
+    b.n = 0;
+  };
+  for (int i = 0; i < n; ++i) {
+    GemmParams p;
+    if (!wgrad_params(p, jobs[i], worker_stride, seg)) {
+      launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, false);
+      continue;
+    }
+    const int tiles = gemm_tiles(p.M, p.N);
+    const int G = plan_worker_groups(p, seg, tiles, 512);
+    b.start[b.n + 1] = b.start[b.n] + tiles * G;
+    b.prob[b.n++] = p;
+    if (b.n == kMaxBatch) flush();
+  }
+  flush();
 }
 
 }  // namespace omni

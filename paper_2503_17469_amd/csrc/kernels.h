@@ -36,6 +36,17 @@ bool linear_dgrad_f32_direct(hipStream_t st, const float* dy, const float* w, co
 // seg.off[k]..seg.off[k+1]-1, and gb + k*worker_stride the column sums of dy_k (gb may be null).
 void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw, float* gb,
                       size_t worker_stride, const Segments& seg, int cin, int cout);
+// The same for several layers at once (same workers, same worker_stride): one launch where the
+// shapes allow it, so that the start-up and drain of one layer's workgroups overlap the others' work.
+struct LinearWgradJob {
+  const float* dy;   // [rows][cout]
+  const float* x;    // [rows][cin]
+  float* gw;         // worker 0's [cout][cin]
+  float* gb;         // worker 0's [cout], may be null
+  int cin, cout;
+};
+void linear_wgrad_f32_batch(hipStream_t st, const LinearWgradJob* jobs, int n, size_t worker_stride,
+                            const Segments& seg);
 
 // ---- classifier head (head.hip): last fully connected layer with few outputs ----
 // `bf16` selects the storage type of x, w and dx (bf16 words) versus fp32; the
