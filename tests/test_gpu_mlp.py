@@ -80,6 +80,21 @@ def test_ragged_shapes(dims, off):
     _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag=f"mlp{dims}")
 
 
+def test_deep_stack_batched_weight_gradients():
+    """Twelve fully connected layers: their weight gradients share launches of at most eight problems
+    (8 + 2 + the odd-width layer and its neighbour, which cannot take the shared launch, alone)."""
+    dims = [96, 64, 80, 64, 72, 64, 45, 64, 96, 64, 128, 64, 10]
+    off = [0, 7, 40, 41, 120]
+    layers = synth.mlp(dims)
+    rng = np.random.default_rng(77)
+    params = synth.he_normal_params(layers, 9, False)
+    params += (rng.standard_normal(params.size) * 0.05).astype(np.float32)
+    B = off[-1]
+    x = rng.standard_normal((B, dims[0])).astype(np.float32)
+    labels = rng.integers(0, dims[-1], B).astype(np.int32)
+    _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag="deep-mlp")
+
+
 def test_step_flags_and_determinism():
     w = synth.workload(0)
     b, off = controller_run(w.T, w.B)
