@@ -1118,6 +1118,12 @@ struct Wgrad3Params {
 };
 constexpr int kUnit = 128;
 constexpr int kSA = 2 * kUnit + 16;                 // bytes between channels of dY^T
+// Channel rows 8 apart are a multiple of 32 words apart: the eight channel octets that the lanes of
+// one transposing write cover would all land in the same banks (measured: 87 % of the LDS cycles of
+// the staging writes were bank conflicts).  Every group of eight rows is therefore moved by another
+// 16 bytes; 16-byte fragment reads stay aligned and evenly spread.
+constexpr int kSkewPad = 128;   // room for the skew of 64 rows (7 x 16 bytes), kept a multiple of 128
+__device__ inline int row_skew(int row) { return (row >> 3) * 16; }
 constexpr int kTile3Floats = 9 * 16 * kThreads;    // one partial tile
 constexpr int kTile3Stride = kTile3Floats + 64;
 
@@ -1155,7 +1161,7 @@ template <bool W4>
 __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p, Segments seg, ChunkTable ct) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem3[];
   unsigned char* sA = smem3;                 // dY^T: 64 rows of kSA bytes
-  unsigned char* sX = smem3 + 64 * kSA;      // X^T: 64 rows of p.SX bytes
+  unsigned char* sX = smem3 + 64 * kSA + kSkewPad;   // X^T: 64 rows of p.SX bytes (both arrays: + the skew)
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int j = lane & 31, h = lane >> 5;
   const int tiles_ci = (p.Cin + 63) / 64;
@@ -1175,7 +1181,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
 
   // The halo columns of the patch are never written again: they stay zero.  So do the rows of
   // channels past the end of the tensor (their staging tasks are skipped altogether).
-  for (int i = tid * 16; i < 64 * kSA + 64 * p.SX; i += kThreads * 16)
+  for (int i = tid * 16; i < 64 * kSA + 64 * p.SX + 2 * kSkewPad; i += kThreads * 16)
     *reinterpret_cast<u32x4*>(smem3 + i) = u32x4{0u, 0u, 0u, 0u};
 
   // ---- staging tasks (the same for every unit, relative to the unit's first image and row)
@@ -1188,7 +1194,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     a_rel = (a_il * H + (rr - a_il * R)) * W + w;
   }
   const bool a_chan_ok = co0 + 8 * a_oct < p.Cout;
-  unsigned char* a_dst = sA + (8 * a_oct) * kSA + 8 * (tid >> 3);
+  unsigned char* a_dst = sA + (8 * a_oct) * kSA + row_skew(8 * a_oct) + 8 * (tid >> 3);
   // X: 8 octets x (W/4 groups of 4 columns) x patch rows, two tasks per thread
   const int wq = W >> 2;
   const int ntasks = p.prows * wq * 8;
@@ -1204,7 +1210,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     x_il[t] = pr / (R + 2);
     x_rr[t] = pr - x_il[t] * (R + 2);                       // input row = first row + x_rr - 1
     x_rel[t] = ((x_il[t] * H + x_rr[t] - 1) * W + 4 * wg) * p.Cin + 8 * oct;
-    x_dst[t] = (8 * oct) * p.SX + (pr * p.Wp + 4 * wg + (W4 ? 2 : 8)) * 2;
+    x_dst[t] = (8 * oct) * p.SX + row_skew(8 * oct) + (pr * p.Wp + 4 * wg + (W4 ? 2 : 8)) * 2;
     x_task[t] = x_task[t] && ci0 + 8 * oct < p.Cin;   // false: no such piece, or a channel octet past the end
   }
 
@@ -1216,8 +1222,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
     const int il = rr / R;
     offB[ks] = ((il * (R + 2) + (rr - il * R)) * p.Wp + (W4 ? 0 : w0 + 8)) * 2;
   }
-  const unsigned char* a_frag = sA + (wco + j) * kSA + h * 16;
-  const unsigned char* x_frag = sX + (wci + j) * p.SX;
+  const unsigned char* a_frag = sA + (wco + j) * kSA + row_skew(wco + j) + h * 16;
+  const unsigned char* x_frag = sX + (wci + j) * p.SX + row_skew(wci + j);
   const int row_shift = p.Wp * 2;
 
   v16f acc[9];
@@ -1321,7 +1327,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
       // rows of dY^T are output channels: their sums over positions are the bias gradient; every
       // wavefront adds a quarter of the unit's positions (one wavefront walking all 128 was a serial
       // chain of a thousand cycles per unit that the other three waited for at the next barrier)
-      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA + lane * kSA) + wave * (kUnit / 8);
+      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA + lane * kSA + row_skew(lane)) + wave * (kUnit / 8);
 #pragma unroll
       for (int d = 0; d < kUnit / 8; ++d) bsum += bf16_lo(rowp[d]) + bf16_hi(rowp[d]);
     }
@@ -1820,7 +1826,7 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   p.SX = words * 4;
   p.partial = partial;
   p.zero = g.zero;
-  const size_t lds = (size_t)64 * kSA + (size_t)64 * p.SX;
+  const size_t lds = (size_t)64 * kSA + (size_t)64 * p.SX + 2 * kSkewPad;   // + the row skew of both arrays
   if (lds > 80 * 1024) return false;
   const int tiles = ((Cout + 63) / 64) * ((g.Cs + 63) / 64);
   const size_t max_slots = conv_wgrad_partial_floats() / kTile3Stride;
