@@ -849,8 +849,14 @@ struct ChunkTable {
 template <int TM, int TN>
 __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, Segments seg, ChunkTable ct) {
   constexpr int BM = 64 * TM, BN = 64 * TN;   // output tile: BM output channels x BN reduction columns
-  constexpr int kRow = BK + 4;               // 72-byte rows: 8-byte accesses, 8 rows apart lands 16 banks apart
-  constexpr int kA = BM * kRow, kB = BN * kRow;
+  // 80-byte rows: a fragment is one aligned 16-byte read, and 8 consecutive rows spread those reads
+  // over all banks.  Rows 8 apart would land in the same banks, and the channel pieces that the lanes
+  // of one transposing write cover are 8 rows apart: every group of 8 rows is moved by another 16
+  // bytes, so that 16 consecutive lanes (8 pieces x 2 position groups) write 16 different bank pairs.
+  // (72-byte rows with 8-byte fragment reads measured 70 % of their LDS cycles as bank conflicts.)
+  constexpr int kRow = BK + 8;
+  auto roff = [](int row) { return row * kRow + (row >> 3) * 8; };
+  constexpr int kA = BM * kRow + BM, kB = BN * kRow + BN;
   constexpr int kTileFloats = TM * TN * 16 * kThreads;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (kA + kB)];
   __shared__ int tab[kMaxPieces];
@@ -884,7 +890,10 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, 
   const bool is_a = tid < BM;
   const int t2 = is_a ? tid : tid - BM;
   const int npiece = is_a ? BM / 8 : BN / 8;
-  const int piece = t2 % npiece, mg = t2 / npiece;
+  // consecutive lanes: 8 pieces (128 contiguous bytes of one position), then 2 position groups, then
+  // the second 8 pieces if there are 16, then the remaining position groups
+  const int piece = npiece == 8 ? (t2 & 7) : ((t2 & 7) | ((t2 >> 1) & 8));
+  const int mg = npiece == 8 ? (t2 >> 3) : (((t2 >> 3) & 1) | ((t2 >> 4) & 6));
   const bool task = tid < BM + BN;   // (mg < 8 follows)
   int bu = 0, bv = 0, bci = 0;
   bool piece_ok;
@@ -931,7 +940,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, 
   auto store_slab = [&](int s) {
     if (!task) return;
     const u32x4* c = r;
-    bf16_t* dst = (is_a ? sA(s) : sB(s)) + (piece * 8) * kRow + mg * 4;
+    bf16_t* dst = (is_a ? sA(s) : sB(s)) + roff(piece * 8) + mg * 4;
     // word d of piece q holds channels 2d (low half) and 2d+1 (high half) of position q
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
@@ -945,9 +954,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, 
     }
   };
   auto frag = [&](const bf16_t* base, int row, int ko) {
-    const u32x2 lo = *reinterpret_cast<const u32x2*>(base + row * kRow + ko);
-    const u32x2 hi = *reinterpret_cast<const u32x2*>(base + row * kRow + ko + 4);
-    return as_bf16x8(u32x4{lo[0], lo[1], hi[0], hi[1]});
+    return as_bf16x8(*reinterpret_cast<const u32x4*>(base + roff(row) + ko));
   };
 
   const int nslab = (mend - mbeg + BK - 1) / BK;
@@ -973,9 +980,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, 
     }
     if (want_bias && tid < BM) {
       // rows of the dY slab are output channels: their sums over positions are the bias gradient
-      const uint32_t* rowp = reinterpret_cast<const uint32_t*>(sA(cur) + tid * kRow);
+      const u32x4* rowp = reinterpret_cast<const u32x4*>(sA(cur) + roff(tid));
 #pragma unroll
-      for (int d = 0; d < BK / 2; ++d) bsum += bf16_lo(rowp[d]) + bf16_hi(rowp[d]);
+      for (int d = 0; d < BK / 8; ++d) {
+        const u32x4 q = rowp[d];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) bsum += bf16_lo(q[e]) + bf16_hi(q[e]);
+      }
     }
     if (s + 1 < nslab) {
       store_slab(cur ^ 1);
