@@ -1166,10 +1166,36 @@ __device__ inline void transpose_store(const u32x4 c[4], unsigned char* dst, int
   }
 }
 
-// W4: maps four columns wide (a patch row is 8 elements = one 16-byte read, data in columns 2-5;
+// WM = 4: maps four columns wide (a patch row is 8 elements = one 16-byte read, data in columns 2-5;
 // a group of 8 reduction positions is two image rows).
-template <bool W4>
+// WM = 8, 16, 32: the map width is known.  The two halves of a wavefront read neighbouring windows
+// of 8 columns, so the one element to the left and to the right of a window is either the zero halo
+// or sits in a register of the partner lane in the other half: it comes over with a swap of the
+// wavefront's halves instead of two more LDS reads per tap row (4-byte reads 16-byte-aligned rows
+// apart use a quarter of the banks: measured, they were all of this kernel's read conflicts and
+// more LDS time than the fragments themselves).  WM = 0: any other width, with those reads.
+__device__ inline uint32_t from_partner(uint32_t send, bool upper) {
+  // lanes 32-63 receive what lanes 0-31 sent, and the other way round
+  const u32x2 sw = __builtin_amdgcn_permlane32_swap(send, send, false, false);
+  return upper ? sw[0] : sw[1];
+}
+
+// The three taps of one filter row: q holds the window's 8 columns (two per word), pl the word
+// before it (its upper half is the column to the left), pn the word after (lower half: to the right).
+__device__ inline void wgrad3_taps(v16f (&acc)[9], int du, const bf16x8 fa, const u32x4 q, uint32_t pl, uint32_t pn) {
+  const uint32_t m01 = __builtin_amdgcn_alignbit(q[1], q[0], 16);
+  const uint32_t m12 = __builtin_amdgcn_alignbit(q[2], q[1], 16);
+  const uint32_t m23 = __builtin_amdgcn_alignbit(q[3], q[2], 16);
+  const u32x4 left = {__builtin_amdgcn_alignbit(q[0], pl, 16), m01, m12, m23};
+  const u32x4 right = {m01, m12, m23, __builtin_amdgcn_alignbit(pn, q[3], 16)};
+  acc[du * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(left), acc[du * 3 + 0], 0, 0, 0);
+  acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(q), acc[du * 3 + 1], 0, 0, 0);
+  acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
+}
+
+template <int WM>
 __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p, Segments seg, ChunkTable ct) {
+  constexpr bool W4 = WM == 4;
   extern __shared__ __attribute__((aligned(16))) unsigned char smem3[];
   unsigned char* sA = smem3;                 // dY^T: 64 rows of kSA bytes
   unsigned char* sX = smem3 + 64 * kSA + kSkewPad;   // X^T: 64 rows of p.SX bytes (both arrays: + the skew)
@@ -1316,21 +1342,41 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
           acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(mid), acc[du * 3 + 1], 0, 0, 0);
           acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
         }
+      } else if constexpr (WM == 32) {
+        // a map row is two reduction steps: windows A | B (this step) and C | D (the next), A and C
+        // in the lower half of the wavefront, B and D in the upper
+        if (ks & 1) continue;   // done together with the step before
+        const bf16x8 fa2 = as_bf16x8(*reinterpret_cast<const u32x4*>(a_frag + (ks + 1) * 32));
+        const bool up = h != 0;
+#pragma unroll
+        for (int du = 0; du < 3; ++du) {
+          const u32x4 q = *reinterpret_cast<const u32x4*>(x_frag + offB[ks] + du * row_shift);
+          const u32x4 q2 = *reinterpret_cast<const u32x4*>(x_frag + offB[ks + 1] + du * row_shift);
+          const uint32_t r1 = from_partner(up ? q[0] : q[3], up);    // A gets B's first, B gets A's last
+          const uint32_t r2 = from_partner(up ? q[3] : q2[0], up);   // C gets B's last, B gets C's first
+          const uint32_t r3 = from_partner(up ? q2[0] : q2[3], up);  // C gets D's first, D gets C's last
+          const uint32_t pl = up ? r1 : 0u, pn = up ? r2 : r1;
+          const uint32_t pl2 = up ? r3 : r2, pn2 = up ? 0u : r3;
+          wgrad3_taps(acc, du, fa, q, pl, pn);
+          wgrad3_taps(acc, du, fa2, q2, pl2, pn2);
+        }
       } else {
 #pragma unroll
       for (int du = 0; du < 3; ++du) {
         const unsigned char* xb = x_frag + offB[ks] + du * row_shift;
         const u32x4 q = *reinterpret_cast<const u32x4*>(xb);
-        const uint32_t pl = *reinterpret_cast<const uint32_t*>(xb - 4);
-        const uint32_t pn = *reinterpret_cast<const uint32_t*>(xb + 16);
-        const uint32_t m01 = __builtin_amdgcn_alignbit(q[1], q[0], 16);
-        const uint32_t m12 = __builtin_amdgcn_alignbit(q[2], q[1], 16);
-        const uint32_t m23 = __builtin_amdgcn_alignbit(q[3], q[2], 16);
-        const u32x4 left = {__builtin_amdgcn_alignbit(q[0], pl, 16), m01, m12, m23};
-        const u32x4 right = {m01, m12, m23, __builtin_amdgcn_alignbit(pn, q[3], 16)};
-        acc[du * 3 + 0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(left), acc[du * 3 + 0], 0, 0, 0);
-        acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(q), acc[du * 3 + 1], 0, 0, 0);
-        acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
+        uint32_t pl, pn;
+        if constexpr (WM == 8) {
+          pl = 0u; pn = 0u;                      // a window is a whole map row: halo on both sides
+        } else if constexpr (WM == 16) {
+          const bool up = h != 0;                // a map row is the two windows of this step
+          const uint32_t r = from_partner(up ? q[0] : q[3], up);
+          pl = up ? r : 0u; pn = up ? 0u : r;
+        } else {
+          pl = *reinterpret_cast<const uint32_t*>(xb - 4);
+          pn = *reinterpret_cast<const uint32_t*>(xb + 16);
+        }
+        wgrad3_taps(acc, du, fa, q, pl, pn);
       }
       }
     }
@@ -1870,16 +1916,19 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
     upc += std::max<long>(1, upc / 16);
   }
   p.upc = (int)upc;
-  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
-  if (lds > configured[w4]) {
-    const void* fn = w4 ? reinterpret_cast<const void*>(&conv3_wgrad_kernel<true>)
-                        : reinterpret_cast<const void*>(&conv3_wgrad_kernel<false>);
-    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured[w4] = lds;
+  // kernel variant by map width: 4, 8, 16, 32, or any other (index 4)
+  const int variant = w4 ? 0 : W == 8 ? 1 : W == 16 ? 2 : W == 32 ? 3 : 4;
+  using KernelFn = void (*)(Wgrad3Params, Segments, ChunkTable);
+  static const KernelFn kernels[5] = {conv3_wgrad_kernel<4>, conv3_wgrad_kernel<8>, conv3_wgrad_kernel<16>,
+                                      conv3_wgrad_kernel<32>, conv3_wgrad_kernel<0>};
+  static size_t configured[5] = {0, 0, 0, 0, 0};   // raising the dynamic LDS limit is a per-function host call
+  if (lds > configured[variant]) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernels[variant]),
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured[variant] = lds;
   }
   const dim3 grid(tiles, ct.first[seg.K]);
-  if (w4) hipLaunchKernelGGL(conv3_wgrad_kernel<true>, grid, dim3(kThreads), lds, st, p, seg, ct);
-  else hipLaunchKernelGGL(conv3_wgrad_kernel<false>, grid, dim3(kThreads), lds, st, p, seg, ct);
+  hipLaunchKernelGGL(kernels[variant], grid, dim3(kThreads), lds, st, p, seg, ct);
   bool chunked = false;
   for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
   if (chunked)
