@@ -849,13 +849,14 @@ struct ChunkTable {
 template <int TM, int TN>
 __global__ __launch_bounds__(kThreads, 2) void conv_wgrad_kernel(WgradParams p, Segments seg, ChunkTable ct) {
   constexpr int BM = 64 * TM, BN = 64 * TN;   // output tile: BM output channels x BN reduction columns
-  // 80-byte rows: a fragment is one aligned 16-byte read, and 8 consecutive rows spread those reads
-  // over all banks.  Rows 8 apart would land in the same banks, and the channel pieces that the lanes
-  // of one transposing write cover are 8 rows apart: every group of 8 rows is moved by another 16
-  // bytes, so that 16 consecutive lanes (8 pieces x 2 position groups) write 16 different bank pairs.
-  // (72-byte rows with 8-byte fragment reads measured 70 % of their LDS cycles as bank conflicts.)
+  // 80-byte rows: a fragment is one aligned 16-byte read, and the 16 consecutive rows that sixteen
+  // lanes read spread evenly over the 64 read banks.  Rows 8 apart would land in the same banks, and
+  // the channel pieces that the lanes of one transposing write cover are 8 rows apart: every group of
+  // 16 rows is moved by another 32 bytes, so that the pieces of a write spread over the four quarters
+  // of the 32 write banks while no fragment read is disturbed.  (72-byte rows with 8-byte fragment
+  // reads measured 70 % of their LDS cycles as bank conflicts.)
   constexpr int kRow = BK + 8;
-  auto roff = [](int row) { return row * kRow + (row >> 3) * 8; };
+  auto roff = [](int row) { return row * kRow + (row >> 4) * 16; };
   constexpr int kA = BM * kRow + BM, kB = BN * kRow + BN;
   constexpr int kTileFloats = TM * TN * 16 * kThreads;
   __shared__ __attribute__((aligned(16))) bf16_t lds[2 * (kA + kB)];
@@ -1129,10 +1130,15 @@ struct Wgrad3Params {
 };
 constexpr int kUnit = 128;
 constexpr int kSA = 2 * kUnit + 16;                 // bytes between channels of dY^T
-// Channel rows 8 apart are a multiple of 32 words apart: the eight channel octets that the lanes of
-// one transposing write cover would all land in the same banks (measured: 87 % of the LDS cycles of
-// the staging writes were bank conflicts).  Every group of eight rows is therefore moved by another
-// 16 bytes; 16-byte fragment reads stay aligned and evenly spread.
+// Channel rows 8 apart are a multiple of 32 words apart: the eight channel octets that sixteen lanes
+// of one transposing write cover would all land in the same banks (measured: 87 % of the LDS cycles
+// of the staging writes were bank conflicts).  Every group of eight rows is therefore moved by
+// another 16 bytes, which makes the writes conflict-free.  The price is on the other side: the 16
+// consecutive rows that sixteen lanes of a 16-byte fragment read cover now overlap in one bank group
+// (measured: fragment reads conflict-free before, 63 % conflict cycles after), still far fewer
+// conflict cycles in all (5.6e7 -> 1.5e7 per launch on 64-channel 32 x 32 maps together with the
+// lane swaps below).  A skew per sixteen rows leaves the reads alone but brings the write conflicts
+// back (2.4e7 in all).
 constexpr int kSkewPad = 128;   // room for the skew of 64 rows (7 x 16 bytes), kept a multiple of 128
 __device__ inline int row_skew(int row) { return (row >> 3) * 16; }
 constexpr int kTile3Floats = 9 * 16 * kThreads;    // one partial tile
