@@ -458,7 +458,8 @@ constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread 
 // output channels, which would leave half of every fragment read and MFMA of the wide tile empty).
 // KC: channels of the reduction staged at a time (64; 32 for layers with 32, 96, ... input channels, whose
 // patch rows are then 80 bytes: sixteen lanes still cover all 64 banks).
-template <int NP, int NB, int KC>   // NP: 16-byte patch pieces per thread
+// W8: maps 8 wide with units of whole groups of 8 map rows (see the fragment addresses below).
+template <int NP, int NB, int KC, bool W8>   // NP: 16-byte patch pieces per thread
 __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) {
   constexpr int TN = 32 * NB;   // output channels per workgroup
   constexpr int OC = KC / 8;    // 16-byte pieces per patch position and per weight row
@@ -509,10 +510,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
     wvalid |= (in ? 1u : 0u) << i;
   }
   // ---- fragment addresses: this wavefront's positions wave*64 + a*32 + j
+  // On maps 8 wide, sixteen consecutive lanes of a fragment read would cover two consecutive map
+  // rows, whose patch rows (10 positions apart) share two of the sixteen bank groups (measured: 40 %
+  // of this kernel's LDS cycles were conflicts there, against 15 % on wider maps).  Map rows 4 apart
+  // are exactly complementary, so the wavefront takes the 8 map rows of its 64 positions in the order
+  // 0 4 1 5 2 6 3 7; the epilogue puts every result back in its place.
+  constexpr bool w8 = W8;
+  auto row_order = [](int t) { return (t >> 1) + 4 * (t & 1); };   // t: 0..7
   int pbase[2];
 #pragma unroll
   for (int a = 0; a < 2; ++a) {
-    const int pos = wave * 64 + a * 32 + j;
+    int pos = wave * 64 + a * 32 + j;
+    if (w8) pos = wave * 64 + row_order(a * 4 + (j >> 3)) * 8 + (j & 7);
     const int rr = pos / W, w = pos - rr * W;
     const int il = rr / R, r = rr - il * R;
     pbase[a] = ((il * PR + r) * PW + w) * kRow + h * 8;   // patch origin is (-1, -1): tap (u, v) adds u*PW + v
@@ -637,7 +646,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
       for (int a = 0; a < 2; ++a)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-          const int il = wave * 64 + a * 32 + 8 * (v / 4) + 4 * h + (v % 4);
+          // accumulator register v of lane (j, h) is row 8 (v/4) + 4 h + v%4 of the block: map row a*4 + v/4 of the wavefront's eight
+          const int il = wave * 64 + (w8 ? row_order(a * 4 + v / 4) * 8 : a * 32 + 8 * (v / 4)) + 4 * h + (v % 4);
           float val = acc[a][b][v] + bj;
           if (p.relu) val = val > 0.f ? val : 0.f;
           so[il * kOutPitch + jl] = val;
@@ -1788,22 +1798,25 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   while (upw < 4 && (long)units * tiles_n / (upw * 2) >= 2048) upw *= 2;
   p.units = units; p.upw = upw;
   const dim3 grid(((units + upw - 1) / upw) * tiles_n);
-  static size_t configured[2][2][2] = {};   // raising the dynamic LDS limit is a per-function host call
-#define OMNI_CONV3(NP_, NB_, KC_)                                                               \
-  {                                                                                             \
-    size_t& conf = configured[big][NB_ - 1][KC_ == 64 ? 0 : 1];                                 \
-    if (lds > conf) {                                                                           \
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_, NB_, KC_>), \
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);          \
-      conf = lds;                                                                               \
-    }                                                                                           \
-    hipLaunchKernelGGL((conv3_gemm_kernel<NP_, NB_, KC_>), grid, dim3(kThreads), lds, st, p);   \
+  const bool w8 = W == 8 && R % 8 == 0;
+  static size_t configured[2][2][2][2] = {};   // raising the dynamic LDS limit is a per-function host call
+#define OMNI_CONV3(NP_, NB_, KC_, W8_)                                                                \
+  {                                                                                                   \
+    size_t& conf = configured[big][NB_ - 1][KC_ == 64 ? 0 : 1][W8_ ? 1 : 0];                          \
+    if (lds > conf) {                                                                                 \
+      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_gemm_kernel<NP_, NB_, KC_, W8_>), \
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);                \
+      conf = lds;                                                                                     \
+    }                                                                                                 \
+    hipLaunchKernelGGL((conv3_gemm_kernel<NP_, NB_, KC_, W8_>), grid, dim3(kThreads), lds, st, p);    \
   }
-#define OMNI_CONV3_KC(NP_, NB_) { if (kc == 64) OMNI_CONV3(NP_, NB_, 64) else OMNI_CONV3(NP_, NB_, 32) }
+#define OMNI_CONV3_W8(NP_, NB_, KC_) { if (w8) OMNI_CONV3(NP_, NB_, KC_, true) else OMNI_CONV3(NP_, NB_, KC_, false) }
+#define OMNI_CONV3_KC(NP_, NB_) { if (kc == 64) OMNI_CONV3_W8(NP_, NB_, 64) else OMNI_CONV3_W8(NP_, NB_, 32) }
   if (nb == 1) { if (big) OMNI_CONV3_KC(13, 1) else OMNI_CONV3_KC(11, 1) }
   else
   { if (big) OMNI_CONV3_KC(13, 2) else OMNI_CONV3_KC(11, 2) }
 #undef OMNI_CONV3_KC
+#undef OMNI_CONV3_W8
 #undef OMNI_CONV3
   return true;
 }
