@@ -226,6 +226,10 @@ int omni_net_activation(const omni_net* net, const void* workspace, int32_t laye
  * events, returns their summed elapsed time and count, and clears the record.
  * kernel_class < 0 disables timing.  Events are created inside the enable call
  * (never inside omni_step).  Returns OMNI_EINVAL on a bad class.
+ * Two classes are timed more exactly where they are a single kernel launch (the
+ * fp32 weight gradients below, and OMNI_KERNEL_UPDATE): their event pair is bound
+ * to the kernel's own start and end time stamps instead of bracketing it on the
+ * stream, which leaves the 2-3 microseconds of the event packets out.
  * In an fp32 network the weight gradients of all fully connected layers before
  * the classifier head run as ONE launch; it counts as a launch of the lowest
  * layer index it covers (layer 0 of a multi-layer perceptron). */

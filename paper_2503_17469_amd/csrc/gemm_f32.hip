@@ -27,6 +27,7 @@
 //     weight gradients of several layers can share one launch
 //     (linear_wgrad_f32_batch): their workgroups follow each other in one grid.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <algorithm>
 
@@ -645,15 +646,25 @@ void linear_wgrad_f32(hipStream_t st, const float* dy, const float* x, float* gw
 }
 
 void linear_wgrad_f32_batch(hipStream_t st, const LinearWgradJob* jobs, int n, size_t worker_stride,
-                            const Segments& seg) {
+                            const Segments& seg, const KernelTimer* timer) {
   // problems that can take the mask-free loads share launches of up to kMaxBatch; the others go alone
   WgradBatch b{};
+  // exact timing needs everything in ONE launch of the shared kernel; otherwise the events go around the launches
+  bool one_launch = n >= 2 && n <= kMaxBatch;
+  for (int i = 0; i < n && one_launch; ++i) {
+    GemmParams p;
+    one_launch = wgrad_params(p, jobs[i], worker_stride, seg);
+  }
+  const bool bracket = timer && !one_launch;
+  if (bracket) (void)hipEventRecord(timer->start, st);
   auto flush = [&]() {
     if (b.n == 1) {
       GemmParams p = b.prob[0];
       launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, true);
     } else if (b.n > 1) {
-      hipLaunchKernelGGL((gemm_f32_wgrad_batch_kernel<32, true>), dim3(b.start[b.n]), dim3(kThreads), 0, st, b, seg);
+      hipExtLaunchKernelGGL((gemm_f32_wgrad_batch_kernel<32, true>), dim3(b.start[b.n]), dim3(kThreads), 0, st,
+                            timer && one_launch ? timer->start : nullptr, timer && one_launch ? timer->stop : nullptr,
+                            0, b, seg);
     }
     b.n = 0;
   };
@@ -670,6 +681,7 @@ void linear_wgrad_f32_batch(hipStream_t st, const LinearWgradJob* jobs, int n, s
     if (b.n == kMaxBatch) flush();
   }
   flush();
+  if (bracket) (void)hipEventRecord(timer->stop, st);
 }
 
 }  // namespace omni

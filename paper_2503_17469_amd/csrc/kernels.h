@@ -10,6 +10,15 @@
 
 namespace omni {
 
+// Optional exact timing of ONE kernel launch: the two events receive the kernel's own start and end
+// time stamps (hipExtLaunchKernelGGL) instead of bracketing the launch on the stream, where the
+// event packets themselves add 2-3 microseconds.  A launcher that ends up making several launches
+// records the events around them instead.
+struct KernelTimer {
+  hipEvent_t start;
+  hipEvent_t stop;
+};
+
 // Scratch for split reductions: partial tiles plus one arrival counter per tile.
 // Counters must be zero before the first launch; every launch leaves them zero.
 struct SplitWorkspace {
@@ -46,7 +55,7 @@ struct LinearWgradJob {
   int cin, cout;
 };
 void linear_wgrad_f32_batch(hipStream_t st, const LinearWgradJob* jobs, int n, size_t worker_stride,
-                            const Segments& seg);
+                            const Segments& seg, const KernelTimer* timer = nullptr);
 
 // ---- classifier head (head.hip): last fully connected layer with few outputs ----
 // `bf16` selects the storage type of x, w and dx (bf16 words) versus fp32; the
@@ -137,7 +146,7 @@ void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int
 // theta -= lr*velocity (velocity [P], read and written).
 void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
                       const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity = nullptr,
-                      float momentum = 0.f, float weight_decay = 0.f);
+                      float momentum = 0.f, float weight_decay = 0.f, const KernelTimer* timer = nullptr);
 void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v);
 
 }  // namespace omni

@@ -86,18 +86,23 @@ struct omni_net {
 namespace {
 // Records an event pair around the launches made while it is alive, if the
 // network is timing this (class, layer) and has event pairs left.
+// With `exact`, the scope records nothing itself: timer() hands the pair to a launcher that binds it
+// to its kernel's own start and end time stamps.
 struct TimedScope {
   omni_net* net;
   hipStream_t st;
-  bool on;
-  TimedScope(omni_net* n, hipStream_t s, int cls, int layer) : net(n), st(s) {
+  bool on, exact;
+  omni::KernelTimer kt{nullptr, nullptr};
+  TimedScope(omni_net* n, hipStream_t s, int cls, int layer, bool exact_ = false) : net(n), st(s), exact(exact_) {
     on = n->time_class == cls && (n->time_layer < 0 || n->time_layer == layer) && n->ev_used + 2 <= n->ev.size();
-    if (on) on = (n->time_seen++ % n->time_every) == 0;     // every time_every-th matching launch is bracketed
-    if (on) (void)hipEventRecord(net->ev[net->ev_used], st);
+    if (on) on = (n->time_seen++ % n->time_every) == 0;     // every time_every-th matching launch is timed
+    if (on) kt = omni::KernelTimer{net->ev[net->ev_used], net->ev[net->ev_used + 1]};
+    if (on && !exact) (void)hipEventRecord(kt.start, st);
   }
+  const omni::KernelTimer* timer() const { return on && exact ? &kt : nullptr; }
   ~TimedScope() {
     if (on) {
-      (void)hipEventRecord(net->ev[net->ev_used + 1], st);
+      if (!exact) (void)hipEventRecord(kt.stop, st);
       net->ev_used += 2;
     }
   }
@@ -481,9 +486,9 @@ void step_f32(StepCtx& c) {
   }
   if (!jobs.empty()) {
     // reported under the lowest layer it covers
-    TimedScope ts(net, st, OMNI_KERNEL_LINEAR_WGRAD, first_job_layer);
+    TimedScope ts(net, st, OMNI_KERNEL_LINEAR_WGRAD, first_job_layer, true);
     // (last layer's problem first in the launch: measured 47.1 us against 48.8 us the other way round)
-    omni::linear_wgrad_f32_batch(st, jobs.data(), (int)jobs.size(), net->P_stride, c.seg);
+    omni::linear_wgrad_f32_batch(st, jobs.data(), (int)jobs.size(), net->P_stride, c.seg, ts.timer());
   }
 }
 
@@ -704,9 +709,9 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
 
   // ---- weighted aggregation + update
   if (!(flags & OMNI_STEP_NO_UPDATE)) {
-    TimedScope ts(net, c.st, OMNI_KERNEL_UPDATE, -1);
+    TimedScope ts(net, c.st, OMNI_KERNEL_UPDATE, -1, true);
     omni::weighted_sgd_f32(c.st, params, c.G, net->P_stride, net->P, c.seg, lr, nullptr, net->velocity,
-                           net->momentum, net->weight_decay);
+                           net->momentum, net->weight_decay, ts.timer());
   }
 
   hipError_t e = hipGetLastError();

@@ -1,6 +1,7 @@
 // Bandwidth-bound kernels of the step: softmax cross-entropy over the ragged
 // batch, and the fused weighted gradient aggregation + SGD update.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include "common.h"
 #include "kernels.h"
@@ -224,7 +225,7 @@ void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int
 
 void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
                       const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity, float momentum,
-                      float weight_decay) {
+                      float weight_decay, const KernelTimer* timer) {
   Lambdas lam{};
   const double B = (double)seg.off[seg.K];
   for (int k = 0; k < seg.K; ++k) lam.v[k] = (float)((double)(seg.off[k + 1] - seg.off[k]) / B);
@@ -235,8 +236,9 @@ void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t 
   if (blocks < 1) blocks = 1;
   const dim3 grid((unsigned)blocks), block(256);
 #define OMNI_UPD(SH, MO)                                                                                         \
-  hipLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, params, velocity, grads, stride, P, seg.K, \
-                     lam, opt, shadow_bf16)
+  hipExtLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, timer ? timer->start : nullptr,       \
+                        timer ? timer->stop : nullptr, 0, params, velocity, grads, stride, P, seg.K, lam, opt,   \
+                        shadow_bf16)
   if (velocity) {
     if (shadow_bf16) OMNI_UPD(true, true); else OMNI_UPD(false, true);
   } else {
