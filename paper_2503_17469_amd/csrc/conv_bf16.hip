@@ -446,6 +446,7 @@ struct Conv3Params {
   const float* bias;
   const bf16_t* mask;
   int relu, accumulate;
+  bf16_t* pool;        // forward only, may be null: [rows*(H/2)*(W/2)][N], the 2 x 2 max pooling of `out`
 };
 constexpr int kUnitD = 256;
 constexpr int kRowD = 64 + 8;   // elements per LDS row (144 bytes): 16-byte reads land 4 banks apart
@@ -680,6 +681,35 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
       }
       Piece<bf16_t>::store(p.out + idx, v);
     }
+    if (p.pool) {
+      // 2 x 2 max pooling of the unit straight from the staged tile (rounding to bf16 is monotonic:
+      // the maximum of the rounded values is the rounded maximum).  A unit is whole rows of whole
+      // images, so its pooled positions are a contiguous run of the pooled tensor too.
+      const int Wh = W >> 1, Rh = R >> 1;
+      const long pool_base = ((long)n0 * (H >> 1) + (r0 >> 1)) * Wh;
+      const int npool = nvalid * Rh * Wh;
+#pragma unroll
+      for (int it = 0; it < (kUnitD / 4) * (TN / 8) / kThreads; ++it) {
+        const int c = tid + kThreads * it;
+        const int q = c / (TN / 8), jl = (c % (TN / 8)) * 8;
+        const int jg = col0 + jl;
+        if (q >= npool || jg >= p.N) continue;
+        const int img = q / (Rh * Wh), rem = q - img * (Rh * Wh);
+        const int pr = rem / Wh, pw = rem - pr * Wh;
+        const float* s0 = so + ((img * R + 2 * pr) * W + 2 * pw) * kOutPitch + jl;
+        float m[8];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+          const v4f a = *reinterpret_cast<const v4f*>(s0 + 4 * half);
+          const v4f b = *reinterpret_cast<const v4f*>(s0 + kOutPitch + 4 * half);
+          const v4f cc = *reinterpret_cast<const v4f*>(s0 + W * kOutPitch + 4 * half);
+          const v4f d = *reinterpret_cast<const v4f*>(s0 + (W + 1) * kOutPitch + 4 * half);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) m[4 * half + e] = fmaxf(fmaxf(a[e], b[e]), fmaxf(cc[e], d[e]));
+        }
+        Piece<bf16_t>::store(p.pool + (size_t)(pool_base + q) * p.N + jg, m);
+      }
+    }
     __syncthreads();   // the staging area is about to be refilled
   }
 }
@@ -701,6 +731,7 @@ struct Conv1Params {
   const float* bias;
   int relu;
   const void* zero;
+  bf16_t* pool;        // may be null: [rows*(H/2)*(W/2)][N], the 2 x 2 max pooling of `out`
 };
 
 template <int NBLK>   // 32-channel blocks of output channels: 1 or 2
@@ -834,6 +865,30 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_fwd_kernel(Conv1Params p) {
       if (il < npos && jl < p.N)   // N is a multiple of 8
         *reinterpret_cast<u32x4*>(p.out + (size_t)(out_base + il) * p.N + jl) =
             *reinterpret_cast<const u32x4*>(so + il * kPitch + jl);
+    }
+    if (p.pool) {
+      // 2 x 2 max pooling of the unit from the staged rows (a unit is whole rows of whole images: its
+      // pooled positions are a contiguous run of the pooled tensor)
+      const int Wh = W >> 1, Rh = R >> 1;
+      const long pool_base = ((long)n0 * (H >> 1) + (r0 >> 1)) * Wh;
+      const int npool = nvalid * Rh * Wh;
+#pragma unroll
+      for (int it = 0; it < ((kUnitD / 4) * kPieces + kThreads - 1) / kThreads; ++it) {
+        const int c = tid + kThreads * it;
+        const int q = c / kPieces, jl = (c % kPieces) * 8;
+        if (q >= npool || jl >= p.N) continue;
+        const int img = q / (Rh * Wh), rem = q - img * (Rh * Wh);
+        const int pr = rem / Wh, pw = rem - pr * Wh;
+        const bf16_t* s0 = so + ((img * R + 2 * pr) * W + 2 * pw) * kPitch + jl;
+        float a[8], b[8], cc[8], d[8], m[8];
+        Piece<bf16_t>::load(s0, a);
+        Piece<bf16_t>::load(s0 + kPitch, b);
+        Piece<bf16_t>::load(s0 + W * kPitch, cc);
+        Piece<bf16_t>::load(s0 + (W + 1) * kPitch, d);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) m[e] = fmaxf(fmaxf(a[e], b[e]), fmaxf(cc[e], d[e]));
+        Piece<bf16_t>::store(p.pool + (size_t)(pool_base + q) * p.N + jl, m);
+      }
     }
     // (the next iteration's patch store touches sP only; `so` is rewritten after the next barrier)
   }
@@ -1766,7 +1821,8 @@ static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
 // 3x3 / pad 1 / stride 1 (forward, or dgrad of such a layer) with channels a multiple of 32 and a
 // map whose rows tile into units of 256 positions: kernel D.  Returns false if the shape does not qualify.
 static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
-                       const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
+                       const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
+                       bf16_t* pool, bool* pooled) {
   const int H = g.Hs, W = g.Ws;
   if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
   if (g.Cs % 32 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
@@ -1784,6 +1840,9 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
   p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0; p.zero = g.zero;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
+  // the pooled copy is written from the same staged tile when a unit holds whole 2 x 2 windows
+  p.pool = (pool && !mask && !accumulate && !g.transposed && H % 2 == 0 && W % 2 == 0 && R % 2 == 0) ? pool : nullptr;
+  *pooled = p.pool != nullptr;
   const int nb = N <= 32 ? 1 : 2;                 // a 32-channel tile for layers with at most 32 output channels
   const int tn = 32 * nb;
   const size_t stage = ((size_t)npatch + 2 * tn) * (kc + 8) * sizeof(bf16_t);
@@ -1823,7 +1882,8 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
 
 // First layer forward (8 stored channels, 3x3 / pad 1 / stride 1, at most 64 outputs): kernel F.
 static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
-                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
+                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
+                      bf16_t* pool, bool* pooled) {
   const int H = g.Hs, W = g.Ws;
   if (g.transposed || mask || accumulate || g.Cs != 8 || g.ks != 3 || g.stride != 1 || g.pad != 1) return false;
   if (g.Hp != H || g.Wp != W || N % 8 != 0 || N > 64 || (long)g.rows * H * W != M) return false;
@@ -1837,6 +1897,8 @@ static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16
   Conv1Params p{};
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.N = N; p.R = R; p.nimg = nimg;
   p.bias = bias; p.relu = relu ? 1 : 0; p.zero = g.zero;
+  p.pool = (pool && H % 2 == 0 && W % 2 == 0 && R % 2 == 0) ? pool : nullptr;
+  *pooled = p.pool != nullptr;
   p.units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
   p.upw = 1;
   while (p.upw < 8 && p.units / (p.upw * 2) >= 1024) p.upw *= 2;
@@ -1848,10 +1910,12 @@ static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16
   return true;
 }
 
-void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
-                    const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate) {
-  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate)) return;
-  if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate)) return;
+bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                    const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
+                    bf16_t* pool_out) {
+  bool pooled = false;
+  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, &pooled)) return pooled;
+  if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, &pooled)) return pooled;
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
@@ -1875,6 +1939,7 @@ void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
   }
   if (N > 64) OMNI_GEMM2(2) else OMNI_GEMM2(1)
 #undef OMNI_GEMM2
+  return false;
 }
 
 // 3x3 / stride 1 / pad 1 and a map whose rows tile into units of 128 positions: kernel C.  (Also

@@ -90,8 +90,12 @@ constexpr int kConvCounters = 16384;         // words of scratch that stay zero 
 size_t conv_wgrad_partial_floats();
 bool conv_shape_supported(const ConvGeom& g, long positions);
 // out[M][N] = gather(src)[M][K] * wgt[N][K]^T (+bias) (ReLU) (masked where mask <= 0) (+= out)
-void conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
-                    const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate);
+// With pool_out (forward of a layer that a 2 x 2 max pooling follows): the kernels that hold a whole
+// unit of output rows in LDS also write [rows*(Hp/2)*(Wp/2)][N] = the pooling of `out`, and the call
+// returns true; false means `out` alone was written and the caller pools it itself.
+bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                    const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
+                    bf16_t* pool_out = nullptr);
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).
 void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,

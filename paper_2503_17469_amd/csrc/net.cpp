@@ -553,6 +553,7 @@ void step_bf16(StepCtx& c) {
   }
 
   // ---- forward over the concatenated batch
+  int pooled_layer = -1;   // a max pooling layer whose output the convolution before it has already written
   for (int i = 0; i < n_layers - 1; ++i) {
     const Layer& L = net->layers[i];
     if (L.fused_away) continue;
@@ -560,10 +561,18 @@ void step_bf16(StepCtx& c) {
       TimedScope ts(net, st, L.d.op == OMNI_OP_CONV ? OMNI_KERNEL_CONV_FWD : OMNI_KERNEL_LINEAR_FWD, i);
       const omni::ConvGeom g = fwd_geom(L);
       const Tensor& to = net->tensors[L.out];
-      omni::conv_gemm_bf16(st, act(L.in0), shadow + L.wsh_off, actw(L.out), rows * to.h * to.w, L.d.cout, g,
-                           L.has_b ? c.params + L.b_off : nullptr, nullptr, to.relu, false);
+      // the next layer that runs, if it pools this layer's output (its only consumer then)
+      int nx = i + 1;
+      while (nx < n_layers - 1 && net->layers[nx].fused_away) ++nx;
+      const bool pool_next = L.d.op == OMNI_OP_CONV && nx < n_layers - 1 &&
+                             net->layers[nx].d.op == OMNI_OP_MAXPOOL2 && net->layers[nx].in0 == L.out;
+      const bool pooled =
+          omni::conv_gemm_bf16(st, act(L.in0), shadow + L.wsh_off, actw(L.out), rows * to.h * to.w, L.d.cout, g,
+                               L.has_b ? c.params + L.b_off : nullptr, nullptr, to.relu, false,
+                               pool_next ? actw(net->layers[nx].out) : nullptr);
+      if (pooled) pooled_layer = nx;
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
-      omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
+      if (i != pooled_layer) omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
     } else if (L.d.op == OMNI_OP_BN) {
       omni::bn_forward_bf16(st, act(L.in0), actw(L.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
                             c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial);
