@@ -15,15 +15,15 @@ __device__ inline float bf16_to_f32(bf16_t h) { return __uint_as_float((uint32_t
 __device__ inline float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ inline float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
-// Round to nearest, ties to even (NaN is not expected on this path and is not special-cased).
-__device__ inline bf16_t f32_to_bf16(float f) {
-  uint32_t u = __float_as_uint(f);
-  u += 0x7FFFu + ((u >> 16) & 1u);
-  return (bf16_t)(u >> 16);
-}
+// Round to nearest, ties to even, two values per instruction: gfx950 converts in hardware
+// (v_cvt_pk_bf16_f32; the same rounding in integer arithmetic cost about five instructions per value,
+// which showed in every epilogue that stores bf16).
 __device__ inline uint32_t pack_bf16(float lo, float hi) {
-  return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+  typedef float f32x2 __attribute__((ext_vector_type(2)));
+  typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f32x2{lo, hi}, bf16x2));
 }
+__device__ inline bf16_t f32_to_bf16(float f) { return (bf16_t)(pack_bf16(f, 0.f) & 0xFFFFu); }
 
 // One 16-byte piece of a row as floats: 4 fp32 or 8 bf16.
 template <typename T> struct Piece;

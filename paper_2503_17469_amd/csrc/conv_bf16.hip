@@ -447,8 +447,22 @@ struct Conv3Params {
   const bf16_t* mask;
   int relu, accumulate;
   bf16_t* pool;        // forward only, may be null: [rows*(H/2)*(W/2)][N], the 2 x 2 max pooling of `out`
+  uint8_t* pool_code;  // with pool: one byte per pooled element, which of the four inputs the gradient goes to
 };
 constexpr int kUnitD = 256;
+
+// Where the gradient of a 2 x 2 max pooling goes: the first of the four inputs (scan order (0,0),
+// (0,1), (1,0), (1,1)) that holds the maximum, or nowhere (4) when a ReLU folded into the pooled
+// tensor has zeroed the maximum.  The comparison is on the values as stored (bf16).
+__device__ inline uint32_t pool_code_of(float a, float b, float c, float d, bool relu, float& m) {
+  m = a;
+  uint32_t k = 0;
+  if (b > m) { m = b; k = 1; }
+  if (c > m) { m = c; k = 2; }
+  if (d > m) { m = d; k = 3; }
+  return (relu && !(m > 0.f)) ? 4u : k;
+}
+__device__ inline float as_stored(float v) { return bf16_to_f32(f32_to_bf16(v)); }
 constexpr int kRowD = 64 + 8;   // elements per LDS row (144 bytes): 16-byte reads land 4 banks apart
 constexpr int kMaxPatchPieces = 13;   // 16-byte pieces of the patch per thread (up to 416 patch positions)
 
@@ -698,6 +712,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
         const int pr = rem / Wh, pw = rem - pr * Wh;
         const float* s0 = so + ((img * R + 2 * pr) * W + 2 * pw) * kOutPitch + jl;
         float m[8];
+        u32x2 code = {0u, 0u};
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
           const v4f a = *reinterpret_cast<const v4f*>(s0 + 4 * half);
@@ -705,9 +720,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
           const v4f cc = *reinterpret_cast<const v4f*>(s0 + W * kOutPitch + 4 * half);
           const v4f d = *reinterpret_cast<const v4f*>(s0 + (W + 1) * kOutPitch + 4 * half);
 #pragma unroll
-          for (int e = 0; e < 4; ++e) m[4 * half + e] = fmaxf(fmaxf(a[e], b[e]), fmaxf(cc[e], d[e]));
+          for (int e = 0; e < 4; ++e)
+            code[half] |= pool_code_of(as_stored(a[e]), as_stored(b[e]), as_stored(cc[e]), as_stored(d[e]),
+                                       p.relu != 0, m[4 * half + e]) << (8 * e);
         }
         Piece<bf16_t>::store(p.pool + (size_t)(pool_base + q) * p.N + jg, m);
+        *reinterpret_cast<u32x2*>(p.pool_code + (size_t)(pool_base + q) * p.N + jg) = code;
       }
     }
     __syncthreads();   // the staging area is about to be refilled
@@ -732,6 +750,7 @@ struct Conv1Params {
   int relu;
   const void* zero;
   bf16_t* pool;        // may be null: [rows*(H/2)*(W/2)][N], the 2 x 2 max pooling of `out`
+  uint8_t* pool_code;  // with pool: one byte per pooled element (see pool_code_of)
 };
 
 template <int NBLK>   // 32-channel blocks of output channels: 1 or 2
@@ -885,9 +904,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_fwd_kernel(Conv1Params p) {
         Piece<bf16_t>::load(s0 + kPitch, b);
         Piece<bf16_t>::load(s0 + W * kPitch, cc);
         Piece<bf16_t>::load(s0 + (W + 1) * kPitch, d);
+        u32x2 code = {0u, 0u};
 #pragma unroll
-        for (int e = 0; e < 8; ++e) m[e] = fmaxf(fmaxf(a[e], b[e]), fmaxf(cc[e], d[e]));
+        for (int e = 0; e < 8; ++e)
+          code[e >> 2] |= pool_code_of(a[e], b[e], cc[e], d[e], p.relu != 0, m[e]) << (8 * (e & 3));
         Piece<bf16_t>::store(p.pool + (size_t)(pool_base + q) * p.N + jl, m);
+        *reinterpret_cast<u32x2*>(p.pool_code + (size_t)(pool_base + q) * p.N + jl) = code;
       }
     }
     // (the next iteration's patch store touches sP only; `so` is rewritten after the next barrier)
@@ -1822,7 +1844,7 @@ static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
 // map whose rows tile into units of 256 positions: kernel D.  Returns false if the shape does not qualify.
 static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                        const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                       bf16_t* pool, bool* pooled) {
+                       bf16_t* pool, uint8_t* pool_code, bool* pooled) {
   const int H = g.Hs, W = g.Ws;
   if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
   if (g.Cs % 32 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
@@ -1841,7 +1863,9 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0; p.zero = g.zero;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
   // the pooled copy is written from the same staged tile when a unit holds whole 2 x 2 windows
-  p.pool = (pool && !mask && !accumulate && !g.transposed && H % 2 == 0 && W % 2 == 0 && R % 2 == 0) ? pool : nullptr;
+  p.pool = (pool && pool_code && !mask && !accumulate && !g.transposed && H % 2 == 0 && W % 2 == 0 && R % 2 == 0)
+               ? pool : nullptr;
+  p.pool_code = pool_code;
   *pooled = p.pool != nullptr;
   const int nb = N <= 32 ? 1 : 2;                 // a 32-channel tile for layers with at most 32 output channels
   const int tn = 32 * nb;
@@ -1883,7 +1907,7 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
 // First layer forward (8 stored channels, 3x3 / pad 1 / stride 1, at most 64 outputs): kernel F.
 static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                       const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                      bf16_t* pool, bool* pooled) {
+                      bf16_t* pool, uint8_t* pool_code, bool* pooled) {
   const int H = g.Hs, W = g.Ws;
   if (g.transposed || mask || accumulate || g.Cs != 8 || g.ks != 3 || g.stride != 1 || g.pad != 1) return false;
   if (g.Hp != H || g.Wp != W || N % 8 != 0 || N > 64 || (long)g.rows * H * W != M) return false;
@@ -1897,7 +1921,8 @@ static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16
   Conv1Params p{};
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.N = N; p.R = R; p.nimg = nimg;
   p.bias = bias; p.relu = relu ? 1 : 0; p.zero = g.zero;
-  p.pool = (pool && H % 2 == 0 && W % 2 == 0 && R % 2 == 0) ? pool : nullptr;
+  p.pool = (pool && pool_code && H % 2 == 0 && W % 2 == 0 && R % 2 == 0) ? pool : nullptr;
+  p.pool_code = pool_code;
   *pooled = p.pool != nullptr;
   p.units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
   p.upw = 1;
@@ -1912,10 +1937,10 @@ static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16
 
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                    bf16_t* pool_out) {
+                    bf16_t* pool_out, uint8_t* pool_code) {
   bool pooled = false;
-  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, &pooled)) return pooled;
-  if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, &pooled)) return pooled;
+  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled)) return pooled;
+  if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled)) return pooled;
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;

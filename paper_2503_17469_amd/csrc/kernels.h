@@ -90,12 +90,14 @@ constexpr int kConvCounters = 16384;         // words of scratch that stay zero 
 size_t conv_wgrad_partial_floats();
 bool conv_shape_supported(const ConvGeom& g, long positions);
 // out[M][N] = gather(src)[M][K] * wgt[N][K]^T (+bias) (ReLU) (masked where mask <= 0) (+= out)
-// With pool_out (forward of a layer that a 2 x 2 max pooling follows): the kernels that hold a whole
-// unit of output rows in LDS also write [rows*(Hp/2)*(Wp/2)][N] = the pooling of `out`, and the call
-// returns true; false means `out` alone was written and the caller pools it itself.
+// With pool_out and pool_code (forward of a layer that a 2 x 2 max pooling follows): the kernels that
+// hold a whole unit of output rows in LDS also write [rows*(Hp/2)*(Wp/2)][N] = the pooling of `out`
+// and, one byte per pooled element, which of the four inputs its gradient goes to (0-3 in scan
+// order, first maximum; 4: none, the ReLU folded into `out` zeroed it); the call then returns true.
+// False means `out` alone was written and the caller pools it itself.
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                    bf16_t* pool_out = nullptr);
+                    bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr);
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).
 void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
@@ -121,6 +123,10 @@ void pad_channels_bf16(hipStream_t st, const bf16_t* x, bf16_t* xp, long pixels,
 void maxpool2_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, int H, int W, int C);
 // din = dout routed to the first maximum of each 2x2 window (scan order), zero elsewhere;
 // with relu_mask also zero where the maximum is not positive.
+// The same from the codes conv_gemm_bf16 wrote with the pooled tensor (8 bytes of codes per 16 of
+// gradient instead of four 16-byte pieces of the pooling's input).
+void maxpool2_bwd_coded_bf16(hipStream_t st, const uint8_t* code, const bf16_t* dout, bf16_t* din, int rows, int H,
+                             int W, int C);
 void maxpool2_bwd_bf16(hipStream_t st, const bf16_t* in, const bf16_t* dout, bf16_t* din, int rows, int H, int W,
                        int C, bool relu_mask);
 

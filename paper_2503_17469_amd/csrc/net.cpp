@@ -45,6 +45,7 @@ struct Layer {
   size_t wt_off = 0;            // transposed copy [cin_pad][taps][cout] for dgrad
   bool need_dgrad = false;
   size_t stat_off = 0;          // batch norm: float offset of [K_max][C][2] statistics (then as many for the backward means)
+  size_t code_off = 0;          // max pooling: byte offset of one code per output element (where its gradient goes)
 };
 
 }  // namespace
@@ -298,6 +299,8 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
     t.act_off = take(bytes);
     t.grad_off = take(bytes);
   }
+  for (Layer& L : net->layers)
+    if (L.d.op == OMNI_OP_MAXPOOL2) L.code_off = take((size_t)B_max * net->tensors[L.out].elems);
   net->ws_bytes = pos;
   *out = net;
   return OMNI_OK;
@@ -554,6 +557,7 @@ void step_bf16(StepCtx& c) {
 
   // ---- forward over the concatenated batch
   int pooled_layer = -1;   // a max pooling layer whose output the convolution before it has already written
+  std::vector<char> coded(n_layers, 0);   // ... together with the codes its backward pass then reads
   for (int i = 0; i < n_layers - 1; ++i) {
     const Layer& L = net->layers[i];
     if (L.fused_away) continue;
@@ -569,8 +573,9 @@ void step_bf16(StepCtx& c) {
       const bool pooled =
           omni::conv_gemm_bf16(st, act(L.in0), shadow + L.wsh_off, actw(L.out), rows * to.h * to.w, L.d.cout, g,
                                L.has_b ? c.params + L.b_off : nullptr, nullptr, to.relu, false,
-                               pool_next ? actw(net->layers[nx].out) : nullptr);
-      if (pooled) pooled_layer = nx;
+                               pool_next ? actw(net->layers[nx].out) : nullptr,
+                               pool_next ? reinterpret_cast<uint8_t*>(c.ws + net->layers[nx].code_off) : nullptr);
+      if (pooled) { pooled_layer = nx; coded[nx] = 1; }
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
       if (i != pooled_layer) omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
     } else if (L.d.op == OMNI_OP_BN) {
@@ -638,8 +643,12 @@ void step_bf16(StepCtx& c) {
         written[L.in0] = 1;
       }
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
-      omni::maxpool2_bwd_bf16(st, act(L.in0), grad(L.out), grad(L.in0), rows, L.ih, L.iw, L.ic,
-                              net->tensors[L.in0].relu);
+      if (coded[i])
+        omni::maxpool2_bwd_coded_bf16(st, reinterpret_cast<const uint8_t*>(c.ws + L.code_off), grad(L.out),
+                                      grad(L.in0), rows, L.ih, L.iw, L.ic);
+      else
+        omni::maxpool2_bwd_bf16(st, act(L.in0), grad(L.out), grad(L.in0), rows, L.ih, L.iw, L.ic,
+                                net->tensors[L.in0].relu);
       written[L.in0] = 1;
     } else if (L.d.op == OMNI_OP_BN) {
       float* stats = bn_area + L.stat_off;

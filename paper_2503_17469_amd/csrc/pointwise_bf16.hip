@@ -110,6 +110,34 @@ __global__ __launch_bounds__(256) void maxpool2_bwd_kernel(const bf16_t* __restr
   for (int q = 0; q < 4; ++q) Piece<bf16_t>::store(din + offs[q], o[q]);
 }
 
+// one thread = 8 channels of one pooled position; the codes say where each gradient goes
+__global__ __launch_bounds__(256) void maxpool2_bwd_coded_kernel(const uint8_t* __restrict__ code,
+                                                                 const bf16_t* __restrict__ dout,
+                                                                 bf16_t* __restrict__ din, long n_out, int H, int W,
+                                                                 int C) {
+  const long i = (long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n_out) return;
+  const int c8 = C / 8;
+  const int cc = (int)(i % c8);
+  long r = i / c8;
+  const int wo = (int)(r % (W / 2)); r /= (W / 2);
+  const int ho = (int)(r % (H / 2));
+  const long n = r / (H / 2);
+  const long o00 = (((n * H + 2 * ho) * W + 2 * wo) * (long)C) + cc * 8;
+  const long offs[4] = {o00, o00 + C, o00 + (long)W * C, o00 + (long)W * C + C};   // (dy, dx) scan order
+  const u32x2 k = *reinterpret_cast<const u32x2*>(code + i * 8);
+  float g[8], o[4][8];
+  Piece<bf16_t>::load(dout + i * 8, g);
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const uint32_t ke = (k[e >> 2] >> (8 * (e & 3))) & 0xFFu;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) o[q][e] = ke == (uint32_t)q ? g[e] : 0.f;
+  }
+#pragma unroll
+  for (int q = 0; q < 4; ++q) Piece<bf16_t>::store(din + offs[q], o[q]);
+}
+
 inline unsigned blocks_for(long n) { return (unsigned)((n + 255) / 256); }
 
 }  // namespace
@@ -141,6 +169,13 @@ void pad_channels_bf16(hipStream_t st, const bf16_t* x, bf16_t* xp, long pixels,
 void maxpool2_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, int H, int W, int C) {
   const long n_out = (long)rows * (H / 2) * (W / 2) * (C / 8);
   hipLaunchKernelGGL(maxpool2_fwd_kernel, dim3(blocks_for(n_out)), dim3(256), 0, st, in, out, n_out, H, W, C);
+}
+
+void maxpool2_bwd_coded_bf16(hipStream_t st, const uint8_t* code, const bf16_t* dout, bf16_t* din, int rows, int H,
+                             int W, int C) {
+  const long n_out = (long)rows * (H / 2) * (W / 2) * (C / 8);
+  hipLaunchKernelGGL(maxpool2_bwd_coded_kernel, dim3(blocks_for(n_out)), dim3(256), 0, st, code, dout, din, n_out, H,
+                     W, C);
 }
 
 void maxpool2_bwd_bf16(hipStream_t st, const bf16_t* in, const bf16_t* dout, bf16_t* din, int rows, int H, int W,
