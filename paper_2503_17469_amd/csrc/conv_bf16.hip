@@ -1615,6 +1615,10 @@ struct Wgrad1Params {
   int Cout, cin_real, H;
   int upc;              // units per chunk
   float* partial;       // [chunk][MB * 2 * 16 * 64] accumulator images
+  // POOLED kernels: dy is not read; it is rebuilt from the gradient of the 2 x 2 max pooling that
+  // follows the layer and the pooling's codes (one byte per pooled element: which input took it)
+  const bf16_t* dpool;  // [rows][H/2][16][Cout]
+  const uint8_t* code;  // [rows][H/2][16][Cout]
 };
 constexpr int kG_W = 32, kG_R = 4, kG_Unit = kG_W * kG_R;        // 128 positions
 constexpr int kG_PatchCols = kG_W + 2, kG_PatchRows = kG_R + 2;
@@ -1634,7 +1638,11 @@ __device__ inline void wgrad1_emit(const Wgrad1Params& p, float* gw, float* gb, 
   }
 }
 
-template <int MB>
+// POOLED: the layer's output gradient was never written.  Every position takes the gradient of its
+// pooling window where the window's code names it and zero elsewhere: 16 + 8 bytes of pooled data
+// per piece (shared by the four positions of a window, so mostly cache hits) instead of 16 bytes
+// of a full-resolution tensor that a pooling-backward pass would have had to write first.
+template <int MB, bool POOLED>
 __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p, Segments seg, ChunkTable ct) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smemg[];
   const int SY = p.Cout * 2 + 8;                         // bytes per position of the staged dY strip
@@ -1658,15 +1666,23 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
   const int ny = kG_Unit * ppp;                            // pieces per unit: 128 ... 1024
   constexpr int kYMax = 4;                                 // Cout <= 64
   u32x4 ry[kYMax], rx;
+  u32x2 rk[kYMax];                                          // POOLED: the codes that go with ry
   const bool has_x = tid < kG_PatchRows * kG_W;
   const int xr = tid / kG_W, xc = tid % kG_W;              // patch row 0..5 (image row strip*4 - 1 + xr), column
   auto fetch = [&](int u) {
     const int img = seg.off[wk] + u / upi, row0 = (u % upi) * kG_R;
-    const bf16_t* ybase = p.dy + ((size_t)(img * p.H + row0) * kG_W) * p.Cout;
+    const bf16_t* ybase = POOLED ? nullptr : p.dy + ((size_t)(img * p.H + row0) * kG_W) * p.Cout;
 #pragma unroll
     for (int i = 0; i < kYMax; ++i) {
       const int q = min(tid + kThreads * i, ny - 1);       // surplus slots re-read the last piece
-      ry[i] = *reinterpret_cast<const u32x4*>(ybase + (size_t)q * 8);
+      if constexpr (POOLED) {
+        const int pos = q / ppp, oct = q - pos * ppp;
+        const size_t pi = ((size_t)(img * (p.H >> 1) + ((row0 + (pos >> 5)) >> 1)) * (kG_W / 2) + ((pos & 31) >> 1));
+        ry[i] = *reinterpret_cast<const u32x4*>(p.dpool + pi * p.Cout + oct * 8);
+        rk[i] = *reinterpret_cast<const u32x2*>(p.code + pi * p.Cout + oct * 8);
+      } else {
+        ry[i] = *reinterpret_cast<const u32x4*>(ybase + (size_t)q * 8);
+      }
     }
     const int grow = row0 - 1 + xr;
     const bool in = has_x && grow >= 0 && grow < p.H;
@@ -1682,6 +1698,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
     for (int i = 0; i < kYMax; ++i) {
       const int q = tid + kThreads * i;
       if (q < ny) {
+        if constexpr (POOLED) {
+          // keep a channel's gradient where its code names this position's place in the window
+          const int pos = q / ppp;
+          const uint32_t slot = (uint32_t)(((pos >> 5) & 1) * 2 + (pos & 1));
+#pragma unroll
+          for (int d2 = 0; d2 < 4; ++d2) {
+            const uint32_t kk = rk[i][d2 >> 1] >> (16 * (d2 & 1));
+            const uint32_t lo = (kk & 0xFFu) == slot ? 0x0000FFFFu : 0u;
+            const uint32_t hi = ((kk >> 8) & 0xFFu) == slot ? 0xFFFF0000u : 0u;
+            ry[i][d2] &= lo | hi;
+          }
+        }
         unsigned char* d = sY + (q / ppp) * SY + (q % ppp) * 16;    // 8-byte aligned (SY is 8 mod 16)
         *reinterpret_cast<u32x2*>(d) = u32x2{ry[i][0], ry[i][1]};
         *reinterpret_cast<u32x2*>(d + 8) = u32x2{ry[i][2], ry[i][3]};
@@ -2047,18 +2075,27 @@ static bool conv3_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
 
 // The first layer (3 channels stored as 8) on 32-wide maps: kernel G.  Returns false if the shape
 // does not qualify.
-static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
-                        size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
-                        float* partial) {
+static bool conv1_wgrad_shape(int Cout, int cin_real, const ConvGeom& g) {
   const int H = g.Hs, W = g.Ws;
   if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.transposed || g.Hp != H || g.Wp != W) return false;
   if (g.Cs != 8 || cin_real > 4 || cin_real < 1 || W != kG_W || H % kG_R != 0) return false;
-  if (Cout % 8 != 0 || Cout < 8 || Cout > 64) return false;
+  return Cout % 8 == 0 && Cout >= 8 && Cout <= 64;
+}
+
+bool conv_wgrad_pooled_supported(int Cout, int cin_real, const ConvGeom& g) { return conv1_wgrad_shape(Cout, cin_real, g); }
+
+static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
+                        size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
+                        float* partial, const bf16_t* dpool, const uint8_t* code) {
+  const int H = g.Hs;
+  if (!conv1_wgrad_shape(Cout, cin_real, g)) return false;
   const int mb = Cout > 32 ? 2 : 1;
   const size_t img_floats = (size_t)mb * 2 * 16 * 64;
   Wgrad1Params p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
   p.Cout = Cout; p.cin_real = cin_real; p.H = H; p.partial = partial;
+  p.dpool = dpool; p.code = code;
+  const bool pooled = dpool != nullptr;
   const int upi = H / kG_R;
   long total_units = 0;
   for (int k = 0; k < seg.K; ++k) total_units += (long)(seg.off[k + 1] - seg.off[k]) * upi;
@@ -2085,27 +2122,28 @@ static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   const dim3 grid(ct.first[seg.K]);
   bool chunked = false;
   for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
-  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
-  if (lds > configured[mb - 1]) {
-    const void* fn = mb == 1 ? reinterpret_cast<const void*>(&conv1_wgrad_kernel<1>)
-                             : reinterpret_cast<const void*>(&conv1_wgrad_kernel<2>);
-    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    configured[mb - 1] = lds;
+  using KernelFn = void (*)(Wgrad1Params, Segments, ChunkTable);
+  static const KernelFn kernels[2][2] = {{conv1_wgrad_kernel<1, false>, conv1_wgrad_kernel<1, true>},
+                                         {conv1_wgrad_kernel<2, false>, conv1_wgrad_kernel<2, true>}};
+  static size_t configured[2][2] = {};   // raising the dynamic LDS limit is a per-function host call
+  const KernelFn fn = kernels[mb - 1][pooled ? 1 : 0];
+  if (lds > configured[mb - 1][pooled ? 1 : 0]) {
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured[mb - 1][pooled ? 1 : 0] = lds;
   }
-  if (mb == 1) {
-    hipLaunchKernelGGL(conv1_wgrad_kernel<1>, grid, dim3(kThreads), lds, st, p, seg, ct);
-    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<1>, dim3(seg.K, 32), dim3(kThreads), 0, st, p, seg, ct);
-  } else {
-    hipLaunchKernelGGL(conv1_wgrad_kernel<2>, grid, dim3(kThreads), lds, st, p, seg, ct);
-    if (chunked) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<2>, dim3(seg.K, 64), dim3(kThreads), 0, st, p, seg, ct);
+  hipLaunchKernelGGL(fn, grid, dim3(kThreads), lds, st, p, seg, ct);
+  if (chunked) {
+    if (mb == 1) hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<1>, dim3(seg.K, 32), dim3(kThreads), 0, st, p, seg, ct);
+    else hipLaunchKernelGGL(conv1_wgrad_reduce_kernel<2>, dim3(seg.K, 64), dim3(kThreads), 0, st, p, seg, ct);
   }
   return true;
 }
 
 void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
-                     float* partial, uint32_t* counters) {
-  if (conv1_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
+                     float* partial, uint32_t* counters, const bf16_t* dpool, const uint8_t* pool_code) {
+  if (conv1_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial, dpool, pool_code)) return;
+  if (dpool) return;   // (callers ask conv_wgrad_pooled_supported first; nothing else can read the pooled form)
   if (conv3_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
   WgradParams p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;

@@ -99,9 +99,15 @@ bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
                     bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr);
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).
+// With dpool and pool_code (only where conv_wgrad_pooled_supported says so: the first-layer kernel),
+// dy is not read: the layer's output gradient is taken from the gradient of the 2 x 2 max pooling
+// that follows the layer ([rows*(Hp/2)*(Wp/2)][Cout]) and the pooling's codes, so that it never has
+// to be written out at full resolution.
 void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
-                     float* partial, uint32_t* counters);
+                     float* partial, uint32_t* counters, const bf16_t* dpool = nullptr,
+                     const uint8_t* pool_code = nullptr);
+bool conv_wgrad_pooled_supported(int Cout, int cin_real, const ConvGeom& g);
 
 // ---- bf16 pointwise kernels (pointwise_bf16.hip) ----
 // fp32 weights [cout][taps][cin_real] -> bf16 [cout][taps][cin_pad] (zero padded) and,

@@ -59,6 +59,7 @@ struct omni_net {
   size_t ws_bytes = 0;
   size_t grads_off = 0, loss_rows_off = 0, status_off = 0, partial_off = 0, counters_off = 0;
   size_t shadow_off = 0, shadow_elems = 0, xpad_off = 0, conv_partial_off = 0, conv_counters_off = 0;
+  size_t conv_partial2_off = 0;     // chunk scratch of the second side stream
   size_t bn_off = 0, bn_floats = 0, bn_partial_off = 0;
   int bn_cmax = 0;
   int classes = 0;
@@ -68,7 +69,9 @@ struct omni_net {
   float momentum = 0.f, weight_decay = 0.f;
   // Side stream for parameter-gradient kernels: they only feed the final update,
   // so they run beside the input-gradient chain instead of in front of it.
-  hipStream_t side = nullptr;
+  // (Two of them, each with a chunk scratch of its own, taking the layers' weight gradients in turn:
+  // one stream ran them strictly one after the other although they do not depend on each other.)
+  hipStream_t side = nullptr, side2 = nullptr;
   std::vector<hipEvent_t> sync_ev;  // fork / join points of one step (timing disabled)
   // optional event timing of one kernel class
   int time_class = -1, time_layer = -1;
@@ -81,6 +84,7 @@ struct omni_net {
     for (hipEvent_t e : ev) (void)hipEventDestroy(e);
     for (hipEvent_t e : sync_ev) (void)hipEventDestroy(e);
     if (side) (void)hipStreamDestroy(side);
+    if (side2) (void)hipStreamDestroy(side2);
   }
 };
 
@@ -287,6 +291,7 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
   if (bf) {
     net->conv_counters_off = take(omni::kConvCounters * sizeof(uint32_t));
     net->conv_partial_off = take(omni::conv_wgrad_partial_floats() * sizeof(float));
+    net->conv_partial2_off = take(omni::conv_wgrad_partial_floats() * sizeof(float));
     net->shadow_off = take(net->shadow_elems * 2);
     if (in_c % 8 != 0) net->xpad_off = take((size_t)B_max * in_h * in_w * ((in_c + 7) / 8 * 8) * 2);
     if (net->bn_floats) {
@@ -377,32 +382,57 @@ struct StepCtx {
   omni_net* net;
   hipStream_t st;
   hipStream_t side;      // equals st when no side stream could be made
+  hipStream_t side2;     // equals side when no second one could be made
   size_t sync_used = 0;
-  // the side stream may start once everything enqueued on the main stream so far is done
-  void fork() {
-    if (side == st) return;
+  // a side stream may start once everything enqueued on the main stream so far is done
+  void fork(hipStream_t& to) {
+    if (to == st) return;
     if (sync_used == net->sync_ev.size()) {
       hipEvent_t e;
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { side = st; return; }
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { to = st; return; }
       net->sync_ev.push_back(e);
     }
     hipEvent_t e = net->sync_ev[sync_used++];
     (void)hipEventRecord(e, st);
-    (void)hipStreamWaitEvent(side, e, 0);
+    (void)hipStreamWaitEvent(to, e, 0);
   }
-  // the main stream waits for everything enqueued on the side stream so far
-  void join() {
-    if (side == st || !forked) return;
+  void fork() { fork(side); }
+  // The two halves of a fork, for when main-stream work is enqueued in between: the side stream
+  // then waits only for what preceded the record, and the main stream's next kernel is not held up
+  // by the host calls that set the side stream going.
+  hipEvent_t fork_record() {
     if (sync_used == net->sync_ev.size()) {
       hipEvent_t e;
-      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { (void)hipStreamSynchronize(side); return; }
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
       net->sync_ev.push_back(e);
     }
     hipEvent_t e = net->sync_ev[sync_used++];
-    (void)hipEventRecord(e, side);
+    (void)hipEventRecord(e, st);
+    return e;
+  }
+  void fork_wait(hipStream_t& to, hipEvent_t e) {
+    if (to == st) return;
+    if (!e) { to = st; return; }   // no event: fall back to the main stream (ordered by itself)
+    (void)hipStreamWaitEvent(to, e, 0);
+  }
+  // the main stream waits for everything enqueued on the side streams so far
+  void join_one(hipStream_t from) {
+    if (from == st) return;
+    if (sync_used == net->sync_ev.size()) {
+      hipEvent_t e;
+      if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { (void)hipStreamSynchronize(from); return; }
+      net->sync_ev.push_back(e);
+    }
+    hipEvent_t e = net->sync_ev[sync_used++];
+    (void)hipEventRecord(e, from);
     (void)hipStreamWaitEvent(st, e, 0);
   }
-  bool forked = false;
+  void join() {
+    if (!forked) return;
+    join_one(side);
+    if (side2 != side && forked2) join_one(side2);
+  }
+  bool forked = false, forked2 = false;
   char* ws;
   float* params;
   const void* x;
@@ -610,6 +640,12 @@ void step_bf16(StepCtx& c) {
   }
 
   // ---- backward
+  // A max pooling right after the FIRST layer (which needs no input gradient) does not write that
+  // layer's output gradient out: the layer's weight-gradient kernel reads the pooled gradient and
+  // the pooling's codes itself.  pooled_from[j] = that pooling layer, for conv layer j.
+  std::vector<int> pooled_from(n_layers, -1);
+  float* conv_partial2 = reinterpret_cast<float*>(c.ws + net->conv_partial2_off);
+  bool second = false;   // which side stream (and scratch) takes the next weight gradient
   for (int i = n_layers - 2; i >= 0; --i) {
     const Layer& L = net->layers[i];
     if (L.fused_away) continue;
@@ -617,17 +653,11 @@ void step_bf16(StepCtx& c) {
       const omni::ConvGeom g = fwd_geom(L);
       const Tensor& to = net->tensors[L.out];
       const bool conv = L.d.op == OMNI_OP_CONV;
-      {
-        // Parameter gradients run on the side stream beside the input-gradient chain.  ALL of
-        // them do, the first layer's included: they share one scratch area for chunk partials,
-        // so they must stay ordered among themselves.
-        c.fork();
-        c.forked = true;
-        hipStream_t ws_ = c.side;
-        TimedScope ts(net, ws_, conv ? OMNI_KERNEL_CONV_WGRAD : OMNI_KERNEL_LINEAR_WGRAD, i);
-        omni::conv_wgrad_bf16(ws_, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
-                              net->P_stride, L.d.cout, L.d.cin, g, c.seg, conv_partial, conv_counters);
-      }
+      // Parameter gradients run on the side streams beside the input-gradient chain.  ALL of
+      // them do, the first layer's included.  The point they wait for is recorded first, then the
+      // input gradient goes to the main stream, and only then are the side stream's wait and
+      // launches issued: the main chain (the longer one) never waits for those host calls.
+      hipEvent_t ready = c.fork_record();
       if (L.in0 >= 0) {
         TimedScope ts(net, st, conv ? OMNI_KERNEL_CONV_DGRAD : OMNI_KERNEL_LINEAR_DGRAD, i);
         omni::ConvGeom d = g;
@@ -642,8 +672,30 @@ void step_bf16(StepCtx& c) {
                              ti.relu ? act(L.in0) : nullptr, false, written[L.in0] != 0);
         written[L.in0] = 1;
       }
+      {
+        const bool use2 = second && c.side2 != c.side;
+        second = !second;
+        c.fork_wait(use2 ? c.side2 : c.side, ready);
+        c.forked = true;
+        if (use2) c.forked2 = true;
+        hipStream_t ws_ = use2 ? c.side2 : c.side;
+        TimedScope ts(net, ws_, conv ? OMNI_KERNEL_CONV_WGRAD : OMNI_KERNEL_LINEAR_WGRAD, i);
+        const int pl = pooled_from[i];
+        omni::conv_wgrad_bf16(ws_, grad(L.out), act(L.in0), c.G + L.w_off, L.has_b ? c.G + L.b_off : nullptr,
+                              net->P_stride, L.d.cout, L.d.cin, g, c.seg, use2 ? conv_partial2 : conv_partial,
+                              conv_counters,
+                              pl >= 0 ? grad(net->layers[pl].out) : nullptr,
+                              pl >= 0 ? reinterpret_cast<const uint8_t*>(c.ws + net->layers[pl].code_off) : nullptr);
+      }
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
-      if (coded[i])
+      int prod = -1;   // the layer that produced the pooling's input
+      for (int j = i - 1; j >= 0 && prod < 0; --j)
+        if (!net->layers[j].fused_away && net->layers[j].out == L.in0) prod = j;
+      if (coded[i] && prod >= 0 && net->layers[prod].d.op == OMNI_OP_CONV && net->layers[prod].in0 < 0 &&
+          omni::conv_wgrad_pooled_supported(net->layers[prod].d.cout, net->layers[prod].d.cin,
+                                            fwd_geom(net->layers[prod]))) {
+        pooled_from[prod] = i;
+      } else if (coded[i])
         omni::maxpool2_bwd_coded_bf16(st, reinterpret_cast<const uint8_t*>(c.ws + L.code_off), grad(L.out),
                                       grad(L.in0), rows, L.ih, L.iw, L.ic);
       else
@@ -719,7 +771,9 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   }
 
   if (!net->side && hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess) net->side = nullptr;
+  if (!net->side2 && hipStreamCreateWithFlags(&net->side2, hipStreamNonBlocking) != hipSuccess) net->side2 = nullptr;
   c.side = net->side ? net->side : c.st;
+  c.side2 = (net->side && net->side2) ? net->side2 : c.side;
 
   if (net->dtype == OMNI_F32) step_f32(c);
   else step_bf16(c);
