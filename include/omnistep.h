@@ -218,6 +218,19 @@ const uint32_t* omni_net_status(const omni_net* net, const void* workspace);
 int omni_net_activation(const omni_net* net, const void* workspace, int32_t layer,
                         const void** ptr, size_t* elems_per_row);
 
+/* Optional replay of repeated steps as a HIP graph.  A step is a chain of a few dozen short kernels
+ * on up to three streams; launched one by one, the host calls and the waits between the streams cost
+ * as much time as the kernels of a small network.  With the switch on, omni_step compares everything
+ * its launches depend on (stream, all pointers, K, off, lr, flags, optimiser settings) with the call
+ * before: the second call in a row with the same values is captured from the stream into a graph
+ * (and run as one), later calls with these values launch that graph.  Different values, a step in
+ * which a timed launch is due, the NULL stream, or a workspace used for the first time are enqueued
+ * launch by launch as always; results are the same either way (same kernels, same order).  The
+ * caller's stream must not be under capture itself.  Off by default; switching it off drops the
+ * graph.  omni_net_graph_replays counts the steps that were replayed. */
+int omni_net_graph_enable(omni_net* net, int32_t on);
+int64_t omni_net_graph_replays(const omni_net* net);
+
 /* Optional device-side timing of one kernel class inside omni_step, for
  * roofline reports.  After omni_net_timing_enable, every launch of that class
  * (for layer `layer`, or all layers if layer < 0) is bracketed by a pair of HIP

@@ -27,7 +27,7 @@ EXPORTS = [
     "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
-    "omni_net_timing_sample",
+    "omni_net_timing_sample", "omni_net_graph_enable", "omni_net_graph_replays",
     "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
     "omni_dyn_create", "omni_dyn_observe", "omni_dyn_adjust", "omni_dyn_get", "omni_dyn_destroy",
     "omni_asp_schedule", "omni_asp_update",
@@ -86,6 +86,9 @@ def _load():
     lib.omni_net_timing_enable.argtypes = [vp, i32, i32, i32]
     lib.omni_net_timing_read.argtypes = [vp, P(C.c_double), P(C.c_int64)]
     lib.omni_net_timing_sample.argtypes = [vp, i32]
+    lib.omni_net_graph_enable.argtypes = [vp, i32]
+    lib.omni_net_graph_replays.argtypes = [vp]
+    lib.omni_net_graph_replays.restype = C.c_int64
     lib.omni_weighted_sgd.argtypes = [vp, vp, vp, sz, sz, P(i32), i32, f32, vp]
     lib.omni_softmax_xent.argtypes = [vp, vp, vp, i32, P(i32), i32, vp, vp, vp, vp, vp]
     lib.omni_weighted_sgd_momentum.argtypes = [vp, vp, vp, vp, sz, sz, P(i32), i32, f32, f32, f32, vp]
@@ -244,6 +247,14 @@ def net_timing_enable(net, kernel_class, layer: int = -1, max_launches: int = 40
 
 def net_timing_sample(net, every: int):
     _check(lib.omni_net_timing_sample(net, int(every)))
+
+
+def net_graph_enable(net, on: bool = True):
+    _check(lib.omni_net_graph_enable(net, 1 if on else 0))
+
+
+def net_graph_replays(net) -> int:
+    return int(lib.omni_net_graph_replays(net))
 
 
 def net_timing_read(net):

@@ -662,9 +662,11 @@ void linear_wgrad_f32_batch(hipStream_t st, const LinearWgradJob* jobs, int n, s
       GemmParams p = b.prob[0];
       launch<32, true, true, MODE_WGRAD>(st, p, seg, 1, true);
     } else if (b.n > 1) {
-      hipExtLaunchKernelGGL((gemm_f32_wgrad_batch_kernel<32, true>), dim3(b.start[b.n]), dim3(kThreads), 0, st,
-                            timer && one_launch ? timer->start : nullptr, timer && one_launch ? timer->stop : nullptr,
-                            0, b, seg);
+      if (timer && one_launch)
+        hipExtLaunchKernelGGL((gemm_f32_wgrad_batch_kernel<32, true>), dim3(b.start[b.n]), dim3(kThreads), 0, st,
+                              timer->start, timer->stop, 0, b, seg);
+      else
+        hipLaunchKernelGGL((gemm_f32_wgrad_batch_kernel<32, true>), dim3(b.start[b.n]), dim3(kThreads), 0, st, b, seg);
     }
     b.n = 0;
   };

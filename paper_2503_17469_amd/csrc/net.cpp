@@ -11,6 +11,7 @@
 #include <cmath>
 #include <new>
 #include <algorithm>
+#include <cstring>
 #include <vector>
 
 #include "common.h"
@@ -73,6 +74,16 @@ struct omni_net {
   // one stream ran them strictly one after the other although they do not depend on each other.)
   hipStream_t side = nullptr, side2 = nullptr;
   std::vector<hipEvent_t> sync_ev;  // fork / join points of one step (timing disabled)
+  // Optional replay of a repeated step as a HIP graph (omni_net_graph_enable): the key is everything
+  // the launches depend on; a step whose key was seen the call before is captured, later ones replay.
+  bool graph_on = false;
+  std::vector<uint64_t> graph_key, seen_key;
+  hipGraphExec_t graph_exec = nullptr;
+  long graph_matches = 0;        // launches of the timed class inside the captured step
+  long step_matches = 0;         // ... inside the step being enqueued
+  long last_matches = -1;        // ... inside the last step enqueued launch by launch (-1: none yet)
+  long graph_replays = 0;
+  bool capturing = false;        // between begin and end of a stream capture: no event is recorded
   // optional event timing of one kernel class
   int time_class = -1, time_layer = -1;
   int time_every = 1;            // bracket every time_every-th matching launch
@@ -85,6 +96,7 @@ struct omni_net {
     for (hipEvent_t e : sync_ev) (void)hipEventDestroy(e);
     if (side) (void)hipStreamDestroy(side);
     if (side2) (void)hipStreamDestroy(side2);
+    if (graph_exec) (void)hipGraphExecDestroy(graph_exec);
   }
 };
 
@@ -99,8 +111,11 @@ struct TimedScope {
   bool on, exact;
   omni::KernelTimer kt{nullptr, nullptr};
   TimedScope(omni_net* n, hipStream_t s, int cls, int layer, bool exact_ = false) : net(n), st(s), exact(exact_) {
-    on = n->time_class == cls && (n->time_layer < 0 || n->time_layer == layer) && n->ev_used + 2 <= n->ev.size();
+    const bool match = n->time_class == cls && (n->time_layer < 0 || n->time_layer == layer);
+    if (match) n->step_matches++;
+    on = match && n->ev_used + 2 <= n->ev.size();
     if (on) on = (n->time_seen++ % n->time_every) == 0;     // every time_every-th matching launch is timed
+    if (n->capturing) on = false;   // (a step in which a launch is due for timing is not captured in the first place)
     if (on) kt = omni::KernelTimer{net->ev[net->ev_used], net->ev[net->ev_used + 1]};
     if (on && !exact) (void)hipEventRecord(kt.start, st);
   }
@@ -338,6 +353,13 @@ int omni_net_timing_enable(omni_net* net, int32_t kernel_class, int32_t layer, i
   if (!net) return fail(OMNI_EINVAL, "omni_net_timing_enable: NULL net");
   if (kernel_class >= OMNI_KERNEL_CLASSES) return fail(OMNI_EINVAL, "omni_net_timing_enable: bad class %d", kernel_class);
   net->ev_used = 0;
+  // how many launches of the timed class a step has is learnt from the next step enqueued launch by
+  // launch; a captured step counted them for the class of its day
+  net->last_matches = -1;
+  net->graph_matches = 0;
+  if (net->graph_exec) { (void)hipGraphExecDestroy(net->graph_exec); net->graph_exec = nullptr; }
+  net->graph_key.clear();
+  net->seen_key.clear();
   if (kernel_class < 0) { net->time_class = -1; return OMNI_OK; }
   if (max_launches < 1 || max_launches > (1 << 20)) return fail(OMNI_EINVAL, "omni_net_timing_enable: bad max_launches");
   while (net->ev.size() < (size_t)max_launches * 2) {
@@ -761,6 +783,49 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   c.loss_per_worker = loss_per_worker;
   c.loss = loss;
 
+  // ---- a repeated step as a graph: replay, capture, or enqueue launch by launch
+  bool capture = false;
+  if (net->graph_on) {
+    std::vector<uint64_t> key;
+    auto put = [&](const void* q) { key.push_back((uint64_t)reinterpret_cast<uintptr_t>(q)); };
+    put(stream); put(params); put(x); put(labels); put(workspace); put(loss_per_worker); put(loss);
+    put(net->velocity);
+    uint32_t lr_bits, mo_bits, wd_bits;
+    std::memcpy(&lr_bits, &lr, 4); std::memcpy(&mo_bits, &net->momentum, 4); std::memcpy(&wd_bits, &net->weight_decay, 4);
+    key.push_back(((uint64_t)lr_bits << 32) | flags);
+    key.push_back(((uint64_t)mo_bits << 32) | wd_bits);
+    key.push_back((uint64_t)K);
+    for (int k = 0; k <= K; ++k) key.push_back((uint64_t)off[k]);
+    // Event timing records into events on the stream, which a replay cannot do: a step in which a
+    // launch of the timed class is due for its event pair is enqueued launch by launch.
+    bool timed_now = false;
+    if (net->time_class >= 0) {
+      if (net->last_matches < 0) timed_now = true;   // not known yet how many such launches a step has
+      else if (net->ev_used + 2 <= net->ev.size())
+        for (long j = 0; j < net->last_matches && !timed_now; ++j)
+          timed_now = ((net->time_seen + j) % net->time_every) == 0;
+    }
+    if (!timed_now && stream != nullptr && net->ws_ready == workspace && net->side && net->side2) {
+      if (net->graph_exec && key == net->graph_key) {
+        if (hipGraphLaunch(net->graph_exec, static_cast<hipStream_t>(stream)) != hipSuccess)
+          return fail(OMNI_EHIP, "omni_step: graph launch failed");
+        net->time_seen += net->graph_matches;
+        net->graph_replays++;
+        return OMNI_OK;
+      }
+      capture = key == net->seen_key;    // the second call in a row with this key
+    }
+    net->seen_key = key;
+    if (capture) {
+      if (hipStreamBeginCapture(static_cast<hipStream_t>(stream), hipStreamCaptureModeThreadLocal) != hipSuccess) {
+        (void)hipGetLastError();
+        capture = false;
+      }
+    }
+  }
+  net->capturing = capture;
+  net->step_matches = 0;
+
   // Arrival counters of the split reductions must start at zero; every launch
   // returns them to zero, so this runs once per workspace.
   if (net->ws_ready != workspace) {
@@ -786,10 +851,41 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
                            net->momentum, net->weight_decay, ts.timer());
   }
 
+  if (capture) {
+    net->capturing = false;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    if (hipStreamEndCapture(c.st, &graph) != hipSuccess || !graph)
+      return fail(OMNI_EHIP, "omni_step: stream capture failed");
+    const hipError_t ie = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    (void)hipGraphDestroy(graph);
+    if (ie != hipSuccess) return fail(OMNI_EHIP, "omni_step: graph instantiation failed: %s", hipGetErrorString(ie));
+    if (net->graph_exec) (void)hipGraphExecDestroy(net->graph_exec);
+    net->graph_exec = exec;
+    net->graph_key = net->seen_key;
+    net->graph_matches = net->step_matches;
+    if (hipGraphLaunch(exec, c.st) != hipSuccess) return fail(OMNI_EHIP, "omni_step: graph launch failed");
+  }
+  net->last_matches = net->step_matches;
+
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return fail(OMNI_EHIP, "omni_step: launch failed: %s", hipGetErrorString(e));
   return OMNI_OK;
 }
+
+int omni_net_graph_enable(omni_net* net, int32_t on) {
+  if (!net) return fail(OMNI_EINVAL, "omni_net_graph_enable: NULL net");
+  net->graph_on = on != 0;
+  if (!net->graph_on) {
+    if (net->graph_exec) (void)hipGraphExecDestroy(net->graph_exec);
+    net->graph_exec = nullptr;
+    net->graph_key.clear();
+    net->seen_key.clear();
+  }
+  return OMNI_OK;
+}
+
+int64_t omni_net_graph_replays(const omni_net* net) { return net ? net->graph_replays : 0; }
 
 int omni_weighted_sgd(void* stream, float* params, const float* grads, size_t stride, size_t P,
                       const int32_t* b, int32_t K, float lr, void* shadow_bf16) {

@@ -235,14 +235,17 @@ void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t 
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
   const dim3 grid((unsigned)blocks), block(256);
-#define OMNI_UPD(SH, MO)                                                                                         \
-  hipExtLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, timer ? timer->start : nullptr,       \
-                        timer ? timer->stop : nullptr, 0, params, velocity, grads, stride, P, seg.K, lam, opt,   \
-                        shadow_bf16)
+#define OMNI_UPD(SH, MO)                                                                                           \
+  if (timer)                                                                                                       \
+    hipExtLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, timer->start, timer->stop, 0, params, \
+                          velocity, grads, stride, P, seg.K, lam, opt, shadow_bf16);                               \
+  else                                                                                                             \
+    hipLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, params, velocity, grads, stride, P,      \
+                       seg.K, lam, opt, shadow_bf16)
   if (velocity) {
-    if (shadow_bf16) OMNI_UPD(true, true); else OMNI_UPD(false, true);
+    if (shadow_bf16) { OMNI_UPD(true, true); } else { OMNI_UPD(false, true); }
   } else {
-    if (shadow_bf16) OMNI_UPD(true, false); else OMNI_UPD(false, false);
+    if (shadow_bf16) { OMNI_UPD(true, false); } else { OMNI_UPD(false, false); }
   }
 #undef OMNI_UPD
 }
