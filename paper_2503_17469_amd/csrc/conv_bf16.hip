@@ -1667,22 +1667,33 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
   constexpr int kYMax = 4;                                 // Cout <= 64
   u32x4 ry[kYMax], rx;
   u32x2 rk[kYMax];                                          // POOLED: the codes that go with ry
+  // a thread's pieces are the same in every unit: where each comes from (relative to the unit) and goes
+  int ysrc[kYMax], ydst[kYMax];
+  uint32_t yslot[kYMax];
+#pragma unroll
+  for (int i = 0; i < kYMax; ++i) {
+    const int q = min(tid + kThreads * i, ny - 1);         // surplus slots re-read the last piece
+    const int pos = q / ppp, oct = q - pos * ppp;
+    ydst[i] = pos * SY + oct * 16;                          // 8-byte aligned (SY is 8 mod 16)
+    // POOLED: the unit's four rows are two pooled rows of 16; the window of position (r, c) is (r/2, c/2)
+    ysrc[i] = POOLED ? (((pos >> 6) * (kG_W / 2) + ((pos & 31) >> 1)) * p.Cout + oct * 8) : q * 8;
+    yslot[i] = (uint32_t)(((pos >> 5) & 1) * 2 + (pos & 1));
+  }
   const bool has_x = tid < kG_PatchRows * kG_W;
   const int xr = tid / kG_W, xc = tid % kG_W;              // patch row 0..5 (image row strip*4 - 1 + xr), column
   auto fetch = [&](int u) {
     const int img = seg.off[wk] + u / upi, row0 = (u % upi) * kG_R;
-    const bf16_t* ybase = POOLED ? nullptr : p.dy + ((size_t)(img * p.H + row0) * kG_W) * p.Cout;
+    if constexpr (POOLED) {
+      const size_t ubase = ((size_t)(img * (p.H >> 1) + (row0 >> 1)) * (kG_W / 2)) * p.Cout;
 #pragma unroll
-    for (int i = 0; i < kYMax; ++i) {
-      const int q = min(tid + kThreads * i, ny - 1);       // surplus slots re-read the last piece
-      if constexpr (POOLED) {
-        const int pos = q / ppp, oct = q - pos * ppp;
-        const size_t pi = ((size_t)(img * (p.H >> 1) + ((row0 + (pos >> 5)) >> 1)) * (kG_W / 2) + ((pos & 31) >> 1));
-        ry[i] = *reinterpret_cast<const u32x4*>(p.dpool + pi * p.Cout + oct * 8);
-        rk[i] = *reinterpret_cast<const u32x2*>(p.code + pi * p.Cout + oct * 8);
-      } else {
-        ry[i] = *reinterpret_cast<const u32x4*>(ybase + (size_t)q * 8);
+      for (int i = 0; i < kYMax; ++i) {
+        ry[i] = *reinterpret_cast<const u32x4*>(p.dpool + ubase + ysrc[i]);
+        rk[i] = *reinterpret_cast<const u32x2*>(p.code + ubase + ysrc[i]);
       }
+    } else {
+      const bf16_t* ybase = p.dy + ((size_t)(img * p.H + row0) * kG_W) * p.Cout;
+#pragma unroll
+      for (int i = 0; i < kYMax; ++i) ry[i] = *reinterpret_cast<const u32x4*>(ybase + ysrc[i]);
     }
     const int grow = row0 - 1 + xr;
     const bool in = has_x && grow >= 0 && grow < p.H;
@@ -1700,8 +1711,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
       if (q < ny) {
         if constexpr (POOLED) {
           // keep a channel's gradient where its code names this position's place in the window
-          const int pos = q / ppp;
-          const uint32_t slot = (uint32_t)(((pos >> 5) & 1) * 2 + (pos & 1));
+          const uint32_t slot = yslot[i];
 #pragma unroll
           for (int d2 = 0; d2 < 4; ++d2) {
             const uint32_t kk = rk[i][d2 >> 1] >> (16 * (d2 & 1));
@@ -1710,7 +1720,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
             ry[i][d2] &= lo | hi;
           }
         }
-        unsigned char* d = sY + (q / ppp) * SY + (q % ppp) * 16;    // 8-byte aligned (SY is 8 mod 16)
+        unsigned char* d = sY + ydst[i];
         *reinterpret_cast<u32x2*>(d) = u32x2{ry[i][0], ry[i][1]};
         *reinterpret_cast<u32x2*>(d + 8) = u32x2{ry[i][2], ry[i][3]};
       }
