@@ -751,6 +751,7 @@ struct Conv1Params {
   const void* zero;
   bf16_t* pool;        // may be null: [rows*(H/2)*(W/2)][N], the 2 x 2 max pooling of `out`
   uint8_t* pool_code;  // with pool: one byte per pooled element (see pool_code_of)
+  int raw3;            // src is [rows][H][W][3]: a pixel is three 2-byte loads, channels 3-7 are zero
 };
 
 template <int NBLK>   // 32-channel blocks of output channels: 1 or 2
@@ -791,7 +792,7 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_fwd_kernel(Conv1Params p) {
     const int pr = rem / PW, pc = rem - pr * PW;
     pil[t] = il; ppr[t] = pr;
     pcol[t] = tid + t * kThreads < npatch && pc >= 1 && pc <= W;
-    prel[t] = ((il * H + pr - 1) * W + pc - 1) * 8;
+    prel[t] = ((il * H + pr - 1) * W + pc - 1) * (p.raw3 ? 3 : 8);
   }
   // ---- fragment addresses: positions wave*64 + a*32 + j, tap offset by lane half
   int pbase[2];
@@ -821,12 +822,14 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_fwd_kernel(Conv1Params p) {
   auto load_patch = [&](int unit) {
     int n0, r0, nvalid;
     unit_geom(unit, n0, r0, nvalid);
-    const long ubase = ((long)n0 * H + r0) * W * 8;
+    const long ubase = ((long)n0 * H + r0) * W * (p.raw3 ? 3 : 8);
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
       const int row = r0 + ppr[t] - 1;
       const bool in = pcol[t] && pil[t] < nvalid && row >= 0 && row < H;
-      rp[t] = *reinterpret_cast<const u32x4*>(in ? p.src + (ubase + prel[t]) : zp);
+      const bf16_t* q = in ? p.src + (ubase + prel[t]) : zp;
+      if (p.raw3) rp[t] = u32x4{(uint32_t)q[0] | ((uint32_t)q[1] << 16), (uint32_t)q[2], 0u, 0u};
+      else rp[t] = *reinterpret_cast<const u32x4*>(q);
     }
   };
 
@@ -1619,6 +1622,7 @@ struct Wgrad1Params {
   // follows the layer and the pooling's codes (one byte per pooled element: which input took it)
   const bf16_t* dpool;  // [rows][H/2][16][Cout]
   const uint8_t* code;  // [rows][H/2][16][Cout]
+  int raw3;             // src is [rows][H][32][3]: a pixel is three 2-byte loads
 };
 constexpr int kG_W = 32, kG_R = 4, kG_Unit = kG_W * kG_R;        // 128 positions
 constexpr int kG_PatchCols = kG_W + 2, kG_PatchRows = kG_R + 2;
@@ -1697,8 +1701,13 @@ __global__ __launch_bounds__(kThreads, 2) void conv1_wgrad_kernel(Wgrad1Params p
     }
     const int grow = row0 - 1 + xr;
     const bool in = has_x && grow >= 0 && grow < p.H;
-    const bf16_t* xp = p.src + ((size_t)(img * p.H + (in ? grow : 0)) * kG_W + xc) * 8;
-    rx = *reinterpret_cast<const u32x4*>(has_x ? xp : p.src);
+    const bf16_t* xp = p.src + ((size_t)(img * p.H + (in ? grow : 0)) * kG_W + xc) * (p.raw3 ? 3 : 8);
+    if (p.raw3) {
+      const bf16_t* q = has_x ? xp : p.src;
+      rx = u32x4{(uint32_t)q[0] | ((uint32_t)q[1] << 16), (uint32_t)q[2], 0u, 0u};
+    } else {
+      rx = *reinterpret_cast<const u32x4*>(has_x ? xp : p.src);
+    }
     if (!in) rx = u32x4{0, 0, 0, 0};
     rx[2] = (rx[2] & 0xFFFF0000u) | 0x3F80u;               // channel 4 := 1.0 (the bias column reads it)
   };
@@ -1884,7 +1893,7 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
                        const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
                        bf16_t* pool, uint8_t* pool_code, bool* pooled) {
   const int H = g.Hs, W = g.Ws;
-  if (g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
+  if (g.raw3 || g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
   if (g.Cs % 32 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
   const int kc = g.Cs % 64 == 0 ? 64 : 32;        // channels of the reduction staged at a time
   const int oc = kc / 8;
@@ -1943,20 +1952,28 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
 }
 
 // First layer forward (8 stored channels, 3x3 / pad 1 / stride 1, at most 64 outputs): kernel F.
-static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
-                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                      bf16_t* pool, uint8_t* pool_code, bool* pooled) {
+static bool conv1_fwd_shape(int N, const ConvGeom& g, long M) {
   const int H = g.Hs, W = g.Ws;
-  if (g.transposed || mask || accumulate || g.Cs != 8 || g.ks != 3 || g.stride != 1 || g.pad != 1) return false;
+  if (g.transposed || g.Cs != 8 || g.ks != 3 || g.stride != 1 || g.pad != 1) return false;
   if (g.Hp != H || g.Wp != W || N % 8 != 0 || N > 64 || (long)g.rows * H * W != M) return false;
   if (W < 8 || W > kUnitD || kUnitD % W != 0) return false;
   const int R = std::min(H, kUnitD / W);
   if (H % R != 0 || kUnitD % (R * W) != 0) return false;
   const int nimg = kUnitD / (R * W);
   if (nimg > 1 && R != H) return false;
+  return nimg * (R + 2) * (W + 2) <= 2 * kThreads;
+}
+
+static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
+                      bf16_t* pool, uint8_t* pool_code, bool* pooled) {
+  const int H = g.Hs, W = g.Ws;
+  if (mask || accumulate || !conv1_fwd_shape(N, g, M)) return false;
+  const int R = std::min(H, kUnitD / W);
+  const int nimg = kUnitD / (R * W);
   const int npatch = nimg * (R + 2) * (W + 2);
-  if (npatch > 2 * kThreads) return false;
   Conv1Params p{};
+  p.raw3 = g.raw3;
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.N = N; p.R = R; p.nimg = nimg;
   p.bias = bias; p.relu = relu ? 1 : 0; p.zero = g.zero;
   p.pool = (pool && pool_code && H % 2 == 0 && W % 2 == 0 && R % 2 == 0) ? pool : nullptr;
@@ -1979,6 +1996,7 @@ bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
   bool pooled = false;
   if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled)) return pooled;
   if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled)) return pooled;
+  if (g.raw3) return false;   // (callers ask conv_first_layer_raw_supported first: nothing else reads a 3-channel source)
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
@@ -2094,6 +2112,10 @@ static bool conv1_wgrad_shape(int Cout, int cin_real, const ConvGeom& g) {
 
 bool conv_wgrad_pooled_supported(int Cout, int cin_real, const ConvGeom& g) { return conv1_wgrad_shape(Cout, cin_real, g); }
 
+bool conv_first_layer_raw_supported(int Cout, int cin_real, const ConvGeom& g, long M) {
+  return cin_real == 3 && conv1_fwd_shape(Cout, g, M) && conv1_wgrad_shape(Cout, cin_real, g);
+}
+
 static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
                         size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                         float* partial, const bf16_t* dpool, const uint8_t* code) {
@@ -2105,6 +2127,7 @@ static bool conv1_wgrad(hipStream_t st, const bf16_t* dy, const bf16_t* src, flo
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
   p.Cout = Cout; p.cin_real = cin_real; p.H = H; p.partial = partial;
   p.dpool = dpool; p.code = code;
+  p.raw3 = g.raw3;
   const bool pooled = dpool != nullptr;
   const int upi = H / kG_R;
   long total_units = 0;
@@ -2153,7 +2176,7 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
                      size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                      float* partial, uint32_t* counters, const bf16_t* dpool, const uint8_t* pool_code) {
   if (conv1_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial, dpool, pool_code)) return;
-  if (dpool) return;   // (callers ask conv_wgrad_pooled_supported first; nothing else can read the pooled form)
+  if (dpool || g.raw3) return;   // (callers ask conv_wgrad_pooled_supported / conv_first_layer_raw_supported first)
   if (conv3_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
   WgradParams p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;

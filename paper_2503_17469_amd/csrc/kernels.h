@@ -84,7 +84,12 @@ struct ConvGeom {
   int transposed;       // 0: source = h*stride + u - pad.  1 (dgrad): t = h + pad - u, source = t/stride if divisible
   int K;                // ks*ks*Cs
   const void* zero;     // at least 16 bytes of zeros in device memory: where loads of absent pieces are pointed
+  int raw3;             // 1: the source tensor holds 3 channels per pixel as given (6 bytes), not the Cs = 8 the
+                        // kernels work on; only the first-layer kernels read it (conv_first_layer_raw_supported)
 };
+// True if both the forward and the weight-gradient pass of a first layer with this shape can read a
+// 3-channel source as it is, so that no padded copy of the network input has to be made.
+bool conv_first_layer_raw_supported(int Cout, int cin_real, const ConvGeom& g, long M);
 constexpr int kConvMaxPartialTiles = 2048;   // (tile, chunk) slots of wgrad scratch
 constexpr int kConvCounters = 16384;         // words of scratch that stay zero for the life of a workspace (the zero page)
 size_t conv_wgrad_partial_floats();

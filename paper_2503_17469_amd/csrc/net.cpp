@@ -556,11 +556,7 @@ void step_bf16(StepCtx& c) {
   bf16_t* shadow = reinterpret_cast<bf16_t*>(c.ws + net->shadow_off);
   const int in_c_pad = (net->in_c + 7) / 8 * 8;
   const bf16_t* x_in = static_cast<const bf16_t*>(c.x);
-  if (in_c_pad != net->in_c) {
-    bf16_t* xp = reinterpret_cast<bf16_t*>(c.ws + net->xpad_off);
-    omni::pad_channels_bf16(st, x_in, xp, (long)rows * net->in_h * net->in_w, net->in_c, in_c_pad);
-    x_in = xp;
-  }
+  bool raw_input = false;   // the layers that read the network input take its 3 channels as they are
   auto act = [&](int t) -> const bf16_t* {
     return t < 0 ? x_in : reinterpret_cast<const bf16_t*>(c.ws + net->tensors[t].act_off);
   };
@@ -588,8 +584,29 @@ void step_bf16(StepCtx& c) {
     g.transposed = 0;
     g.K = g.ks * g.ks * g.Cs;
     g.zero = conv_counters;   // zeroed once per workspace, never written
+    g.raw3 = (raw_input && L.in0 < 0) ? 1 : 0;
     return g;
   };
+
+  // ---- the network input: channel counts that are no multiple of 8 are padded into a copy, unless
+  // every layer that reads the input is a first-layer convolution whose kernels read 3 channels directly
+  if (in_c_pad != net->in_c) {
+    raw_input = net->in_c == 3;
+    for (int i = 0; i < n_layers && raw_input; ++i) {
+      const Layer& L = net->layers[i];
+      if (L.fused_away || L.in0 >= 0) continue;
+      if (L.d.op != OMNI_OP_CONV) { raw_input = false; break; }
+      const Tensor& to = net->tensors[L.out];
+      raw_input = false;   // (fwd_geom reads the flag: ask with the padded layout's geometry)
+      const omni::ConvGeom g = fwd_geom(L);
+      raw_input = omni::conv_first_layer_raw_supported(L.d.cout, L.d.cin, g, (long)rows * to.h * to.w);
+    }
+    if (!raw_input) {
+      bf16_t* xp = reinterpret_cast<bf16_t*>(c.ws + net->xpad_off);
+      omni::pad_channels_bf16(st, x_in, xp, (long)rows * net->in_h * net->in_w, net->in_c, in_c_pad);
+      x_in = xp;
+    }
+  }
 
   // ---- bf16 copies of the weights (forward layout, and transposed for dgrad)
   {
