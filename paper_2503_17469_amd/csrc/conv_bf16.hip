@@ -1895,15 +1895,17 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   const int H = g.Hs, W = g.Ws;
   if (g.raw3 || g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
   if (g.Cs % 32 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
-  const int kc = g.Cs % 64 == 0 ? 64 : 32;        // channels of the reduction staged at a time
-  const int oc = kc / 8;
   if ((long)M * g.Cs >= (1L << 31)) return false;   // 32-bit element offsets in the kernel
-  if (W < 8 || W > kUnitD || kUnitD % W != 0) return false;
+  if (W < 4 || W > kUnitD || kUnitD % W != 0) return false;
   const int R = std::min(H, kUnitD / W);
   if (H % R != 0 || kUnitD % (R * W) != 0) return false;
   const int nimg = kUnitD / (R * W);
   if (nimg > 1 && R != H) return false;
   const int npatch = nimg * (R + 2) * (W + 2);
+  // channels of the reduction staged at a time: 64 where the patch of a unit then fits the registers
+  // that carry it to LDS (on 4 x 4 maps a unit is 16 images and their halos are most of the patch)
+  const int kc = (g.Cs % 64 == 0 && npatch * 8 <= kMaxPatchPieces * kThreads) ? 64 : 32;
+  const int oc = kc / 8;
   if (npatch * oc > kMaxPatchPieces * kThreads) return false;
   Conv3Params p{};
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
