@@ -198,6 +198,14 @@ size_t omni_net_grad_stride(const omni_net* net);
  *   loss            dev [1] fp32: sum_k lambda_k L_k
  *   flags           OMNI_STEP_NO_UPDATE leaves params untouched (gradients only)
  *
+ * The step allocates no device memory and never synchronises with the device.
+ * The first steps of a network create what they need on the host side and keep
+ * it until omni_net_destroy: two side streams (default priority) on which the
+ * parameter gradients of a bf16 network run beside the input-gradient chain, a
+ * few events that order them with the caller's stream, and the dynamic-LDS limit
+ * of the kernels that need more than the default; later steps create nothing.
+ * All work of a step has been ordered back onto `stream` when the call returns.
+ *
  * After the step the workspace holds g_k (mean gradient of worker k) in row k
  * of the matrix returned by omni_net_worker_grads.  A label outside
  * [0, classes) sets bit 0 of the status word (omni_net_status) and contributes
