@@ -561,7 +561,13 @@ void step_bf16(StepCtx& c) {
     return t < 0 ? x_in : reinterpret_cast<const bf16_t*>(c.ws + net->tensors[t].act_off);
   };
   auto actw = [&](int t) { return reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].act_off); };
-  auto grad = [&](int t) { return reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].grad_off); };
+  // A tensor's gradient normally has a buffer of its own; where it would be a plain copy of another
+  // tensor's gradient (a residual add passes its output gradient on unchanged to an input that has no
+  // folded ReLU and no other consumer), it is that other buffer.
+  std::vector<bf16_t*> grad_alias(net->tensors.size(), nullptr);
+  auto grad = [&](int t) {
+    return grad_alias[t] ? grad_alias[t] : reinterpret_cast<bf16_t*>(c.ws + net->tensors[t].grad_off);
+  };
   float* bn_area = reinterpret_cast<float*>(c.ws + net->bn_off);
   double* bn_partial = reinterpret_cast<double*>(c.ws + net->bn_partial_off);
   float* conv_partial = reinterpret_cast<float*>(c.ws + net->conv_partial_off);
@@ -750,6 +756,11 @@ void step_bf16(StepCtx& c) {
     } else if (L.d.op == OMNI_OP_ADD) {
       const long elems = (long)rows * L.ih * L.iw * L.ic;
       for (int t : {L.in0, L.in1}) {
+        if (!net->tensors[t].relu && net->tensors[t].consumers == 1 && !written[t]) {
+          grad_alias[t] = grad(L.out);   // nothing to mask, nothing to add to: no copy
+          written[t] = 1;
+          continue;
+        }
         omni::route_grad_bf16(st, grad(L.out), net->tensors[t].relu ? act(t) : nullptr, grad(t), elems,
                               written[t] != 0);
         written[t] = 1;
