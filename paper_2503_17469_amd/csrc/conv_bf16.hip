@@ -118,6 +118,7 @@ struct ConvParams {
   const float* bias;   // [N] or null
   const bf16_t* mask;  // [M][N] or null: the value passes where mask > 0
   int relu, accumulate;
+  const bf16_t* addend;   // [M][N] or null: added to the product before the mask (a second gradient contribution)
 };
 
 // Balance of kernel A: the vector ALU shares issue slots with the matrix pipe, and
@@ -404,6 +405,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv_gemm2_kernel(ConvParams p) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
     const size_t idx = (size_t)i * p.N + j;
+    if (p.addend) {
+      float av[8];
+      Piece<bf16_t>::load(p.addend + idx, av);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) v[e] += av[e];
+    }
     if (p.mask) {
       float mv[8];
       Piece<bf16_t>::load(p.mask + idx, mv);
@@ -448,6 +455,7 @@ struct Conv3Params {
   int relu, accumulate;
   bf16_t* pool;        // forward only, may be null: [rows*(H/2)*(W/2)][N], the 2 x 2 max pooling of `out`
   uint8_t* pool_code;  // with pool: one byte per pooled element, which of the four inputs the gradient goes to
+  const bf16_t* addend;   // may be null: [rows*H*W][N] added to the product before the mask
 };
 constexpr int kUnitD = 256;
 
@@ -681,6 +689,12 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_gemm_kernel(Conv3Params p) 
 #pragma unroll
       for (int e = 0; e < 4; ++e) { v[e] = lo[e]; v[4 + e] = hi[e]; }
       const size_t idx = (size_t)(out_base + il) * p.N + jg;
+      if (p.addend) {
+        float av[8];
+        Piece<bf16_t>::load(p.addend + idx, av);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] += av[e];
+      }
       if (p.mask) {
         float mv[8];
         Piece<bf16_t>::load(p.mask + idx, mv);
@@ -1891,7 +1905,7 @@ static void launch_gemm2(hipStream_t st, const ConvParams& p, int tiles) {
 // map whose rows tile into units of 256 positions: kernel D.  Returns false if the shape does not qualify.
 static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                        const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                       bf16_t* pool, uint8_t* pool_code, bool* pooled) {
+                       bf16_t* pool, uint8_t* pool_code, bool* pooled, const bf16_t* addend) {
   const int H = g.Hs, W = g.Ws;
   if (g.raw3 || g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
   if (g.Cs % 32 != 0 || N % 8 != 0 || (long)g.rows * H * W != M) return false;
@@ -1915,6 +1929,7 @@ static bool conv3_gemm(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf1
   p.pool = (pool && pool_code && !mask && !accumulate && !g.transposed && H % 2 == 0 && W % 2 == 0 && R % 2 == 0)
                ? pool : nullptr;
   p.pool_code = pool_code;
+  p.addend = addend;
   *pooled = p.pool != nullptr;
   const int nb = N <= 32 ? 1 : 2;                 // a 32-channel tile for layers with at most 32 output channels
   const int tn = 32 * nb;
@@ -1994,14 +2009,17 @@ static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16
 
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                    bf16_t* pool_out, uint8_t* pool_code) {
+                    bf16_t* pool_out, uint8_t* pool_code, const bf16_t* addend) {
   bool pooled = false;
-  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled)) return pooled;
-  if (conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled)) return pooled;
+  if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled, addend))
+    return pooled;
+  if (!addend && conv1_fwd(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled))
+    return pooled;
   if (g.raw3) return false;   // (callers ask conv_first_layer_raw_supported first: nothing else reads a 3-channel source)
   ConvParams p{};
   p.src = src; p.wgt = wgt; p.out = out; p.M = M; p.N = N; p.g = g;
   p.bias = bias; p.mask = mask; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
+  p.addend = addend;
   int tiles_m = (M + BM - 1) / BM;
   const bool chan_ok = g.Cs % BK2 == 0 && g.ks <= 3;
   const bool fast = chan_ok && (!g.transposed || g.stride == 1);

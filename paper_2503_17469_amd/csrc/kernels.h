@@ -102,7 +102,9 @@ bool conv_shape_supported(const ConvGeom& g, long positions);
 // False means `out` alone was written and the caller pools it itself.
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                    bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr);
+                    bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr, const bf16_t* addend = nullptr);
+// (addend, [M][N] or null, is added to the product before the mask: the input gradient of a layer
+// whose input also feeds a residual add takes the add's share along instead of a separate pass.)
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).
 // With dpool and pool_code (only where conv_wgrad_pooled_supported says so: the first-layer kernel),
 // dy is not read: the layer's output gradient is taken from the gradient of the 2 x 2 max pooling

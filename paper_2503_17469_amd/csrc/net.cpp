@@ -689,6 +689,9 @@ void step_bf16(StepCtx& c) {
   // layer's output gradient out: the layer's weight-gradient kernel reads the pooled gradient and
   // the pooling's codes itself.  pooled_from[j] = that pooling layer, for conv layer j.
   std::vector<int> pooled_from(n_layers, -1);
+  // A residual add's gradient for an input that a convolution also reads is not routed by a pass of
+  // its own: that convolution's input-gradient kernel adds it before its ReLU mask.
+  std::vector<const bf16_t*> pending_add(net->tensors.size(), nullptr);
   float* conv_partial2 = reinterpret_cast<float*>(c.ws + net->conv_partial2_off);
   bool second = false;   // which side stream (and scratch) takes the next weight gradient
   for (int i = n_layers - 2; i >= 0; --i) {
@@ -713,8 +716,10 @@ void step_bf16(StepCtx& c) {
         d.K = d.ks * d.ks * d.Cs;
         const Tensor& ti = net->tensors[L.in0];
         const int m_rows = conv ? rows * L.ih * L.iw : rows;
+        const bf16_t* addend = pending_add[L.in0];
+        pending_add[L.in0] = nullptr;
         omni::conv_gemm_bf16(st, grad(L.out), shadow + L.wt_off, grad(L.in0), m_rows, L.cin_pad, d, nullptr,
-                             ti.relu ? act(L.in0) : nullptr, false, written[L.in0] != 0);
+                             ti.relu ? act(L.in0) : nullptr, false, written[L.in0] != 0, nullptr, nullptr, addend);
         written[L.in0] = 1;
       }
       {
@@ -760,6 +765,15 @@ void step_bf16(StepCtx& c) {
           grad_alias[t] = grad(L.out);   // nothing to mask, nothing to add to: no copy
           written[t] = 1;
           continue;
+        }
+        if (net->tensors[t].consumers == 2 && !written[t] && !pending_add[t]) {
+          // the other consumer: a convolution or fully connected layer further down whose input gradient is still to come
+          bool taken = false;
+          for (int j = i - 1; j >= 0 && !taken; --j) {
+            const Layer& Lj = net->layers[j];
+            taken = !Lj.fused_away && is_param_op(Lj.d.op) && Lj.in0 == t && Lj.d.op == OMNI_OP_CONV;
+          }
+          if (taken) { pending_add[t] = grad(L.out); continue; }
         }
         omni::route_grad_bf16(st, grad(L.out), net->tensors[t].relu ? act(t) : nullptr, grad(t), elems,
                               written[t] != 0);
