@@ -222,7 +222,10 @@ const float* omni_net_worker_grads(const omni_net* net, const void* workspace);
 const uint32_t* omni_net_status(const omni_net* net, const void* workspace);
 /* Output of layer `layer` as stored by the last step: *ptr dev pointer (fp32 or
  * bf16 per dtype), *elems_per_row its row length.  Layers fused away into a
- * neighbour alias that neighbour's tensor.  OMNI_EINVAL on a bad index. */
+ * neighbour alias that neighbour's tensor.  One tensor is not stored at all: the
+ * output of a batch norm whose only consumer is the residual add right after it
+ * (the add's output is stored; the pointer returned for the batch norm layer then
+ * points at memory no step writes).  OMNI_EINVAL on a bad index. */
 int omni_net_activation(const omni_net* net, const void* workspace, int32_t layer,
                         const void** ptr, size_t* elems_per_row);
 

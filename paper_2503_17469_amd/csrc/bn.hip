@@ -188,7 +188,8 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16_t* __restrict_
                                                        const float* __restrict__ stats, const float* __restrict__ means,
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        int C, int hw, Segments seg, ShareTable tb, int relu,
-                                                       bf16_t* __restrict__ out) {
+                                                       bf16_t* __restrict__ out, const bf16_t* __restrict__ skip,
+                                                       int relu_add) {
   const int c8n = C / 8;
   const int ppar = 256 / c8n;                   // positions per trip
   const int tid = threadIdx.x;
@@ -215,12 +216,13 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16_t* __restrict_
     mn2[e] = BWD ? means[((size_t)wk * C + c0 + e) * 2 + 1] : 0.f;
   }
   for (long p = cbeg + lp; p < cend; p += 4 * ppar) {
-    float xv[4][8], dv[4][8];
+    float xv[4][8], dv[4][8];   // dv: the output gradient (backward) or the residual input (forward, with skip)
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const long q = min(p + (long)u * ppar, cend - 1);
       Piece<bf16_t>::load(x + q * C + c0, xv[u]);
       if (BWD) Piece<bf16_t>::load(dy + q * C + c0, dv[u]);
+      else if (skip) Piece<bf16_t>::load(skip + q * C + c0, dv[u]);
     }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -233,6 +235,11 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16_t* __restrict_
         if (!BWD) {
           float y = gm[e] * xh + bt[e];
           if (relu) y = y > 0.f ? y : 0.f;
+          if (skip) {
+            // the residual add that follows, on the normalised value as it would have been stored
+            y = bf16_to_f32(f32_to_bf16(y)) + dv[u][e];
+            if (relu_add) y = y > 0.f ? y : 0.f;
+          }
           o[e] = y;
         } else {
           o[e] = gm[e] * is[e] * (dv[u][e] - mn1[e] - xh * mn2[e]);
@@ -371,7 +378,8 @@ ShareTable bn_chunks(const Segments& seg, int C, int hw) {
 bool bn_shape_supported(int C) { return C % 8 == 0 && C >= 8 && C <= 2048; }
 
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
-                     const Segments& seg, bool relu, float* stats, double* partial) {
+                     const Segments& seg, bool relu, float* stats, double* partial, const bf16_t* skip,
+                     bool relu_add) {
   const ShareTable sp = bn_splits(seg, C);
   const int groups = (C + 63) / 64;
   hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(sp.first[seg.K], groups), dim3(256), 0, st, x, nullptr, nullptr,
@@ -379,7 +387,7 @@ void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* ga
   hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3(seg.K, groups), dim3(256), 0, st, partial, C, hw, seg, sp, stats);
   const ShareTable ch = bn_chunks(seg, C, hw);
   hipLaunchKernelGGL(bn_apply_kernel<false>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, nullptr, stats, nullptr,
-                     gamma, beta, C, hw, seg, ch, relu ? 1 : 0, y);
+                     gamma, beta, C, hw, seg, ch, relu ? 1 : 0, y, skip, relu_add ? 1 : 0);
 }
 
 void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
@@ -393,7 +401,7 @@ void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t*
                      g_gamma, g_beta, worker_stride);
   const ShareTable ch = bn_chunks(seg, C, hw);
   hipLaunchKernelGGL(bn_apply_kernel<true>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, dy, stats, means, gamma,
-                     nullptr, C, hw, seg, ch, 0, dx);
+                     nullptr, C, hw, seg, ch, 0, dx, nullptr, 0);
 }
 
 void add_fwd_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, bf16_t* out, long elems, bool relu) {

@@ -148,8 +148,11 @@ constexpr int kBnMaxSplits = 256;  // statistics scratch holds K * kBnMaxSplits 
 // stats: [K][C][2] (mean, 1/sqrt(var+eps)); partial: [K * kBnMaxSplits][C][2] doubles of scratch.
 // Channel counts the batch-norm kernels handle: a multiple of 8, at most 2048.
 bool bn_shape_supported(int C);
+// With skip: y = bn(x) (rounded as it would have been stored) + skip, then ReLU if relu_add: the residual
+// add that follows the normalisation, without writing and re-reading the normalised tensor.
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
-                     const Segments& seg, bool relu, float* stats, double* partial);
+                     const Segments& seg, bool relu, float* stats, double* partial, const bf16_t* skip = nullptr,
+                     bool relu_add = false);
 // means: [K][C][2] scratch; g_gamma / g_beta: worker k's entries at + k*worker_stride.
 void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
                       const Segments& seg, const float* stats, float* means, double* partial, float* g_gamma,

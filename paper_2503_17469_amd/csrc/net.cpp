@@ -632,6 +632,7 @@ void step_bf16(StepCtx& c) {
 
   // ---- forward over the concatenated batch
   int pooled_layer = -1;   // a max pooling layer whose output the convolution before it has already written
+  int added_layer = -1;    // a residual add that the batch norm before it has already done
   std::vector<char> coded(n_layers, 0);   // ... together with the codes its backward pass then reads
   for (int i = 0; i < n_layers - 1; ++i) {
     const Layer& L = net->layers[i];
@@ -654,11 +655,26 @@ void step_bf16(StepCtx& c) {
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
       if (i != pooled_layer) omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
     } else if (L.d.op == OMNI_OP_BN) {
-      omni::bn_forward_bf16(st, act(L.in0), actw(L.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
-                            c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial);
+      // a residual add that comes next and is this tensor's only consumer is done by the same kernel:
+      // the normalised tensor itself is then never stored (nothing in the backward pass reads it)
+      int nx = i + 1;
+      while (nx < n_layers - 1 && net->layers[nx].fused_away) ++nx;
+      const Layer& A = net->layers[nx];
+      const bool add_next = nx < n_layers - 1 && A.d.op == OMNI_OP_ADD && (A.in0 == L.out) != (A.in1 == L.out) &&
+                            net->tensors[L.out].consumers == 1 && !net->tensors[L.out].relu;
+      if (add_next) {
+        const int other = A.in0 == L.out ? A.in1 : A.in0;
+        omni::bn_forward_bf16(st, act(L.in0), actw(A.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
+                              c.seg, false, bn_area + L.stat_off, bn_partial, act(other), net->tensors[A.out].relu);
+        added_layer = nx;
+      } else {
+        omni::bn_forward_bf16(st, act(L.in0), actw(L.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
+                              c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial);
+      }
     } else if (L.d.op == OMNI_OP_ADD) {
-      omni::add_fwd_bf16(st, act(L.in0), act(L.in1), actw(L.out), (long)rows * L.ih * L.iw * L.ic,
-                         net->tensors[L.out].relu);
+      if (i != added_layer)
+        omni::add_fwd_bf16(st, act(L.in0), act(L.in1), actw(L.out), (long)rows * L.ih * L.iw * L.ic,
+                           net->tensors[L.out].relu);
     } else if (L.d.op == OMNI_OP_GAP) {
       omni::gap_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih * L.iw, L.ic);
     }

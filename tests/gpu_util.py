@@ -32,6 +32,20 @@ def param_tensor_slices(layers):
     return out
 
 
+def unstored_layers(layers):
+    """Layers whose output the library does not keep under their own index: a layer whose ReLU was
+    folded into it (compared at the ReLU layer), and a batch norm whose only consumer is the residual
+    add right after it (normalisation and add are one kernel: compared at the add)."""
+    out = {L["src"] for L in layers if L["op"] == "relu"}
+    for li, L in enumerate(layers[:-1]):
+        nxt = layers[li + 1]
+        if L["op"] == "bn" and nxt["op"] == "add" and (nxt["src"] == li) != (nxt.get("src2") == li):
+            users = sum(1 for M in layers if M.get("src") == li or M.get("src2") == li)
+            if users == 1:
+                out.add(li)
+    return out
+
+
 class GpuRun:
     """One network instance on the GPU with its buffers."""
 

@@ -7,7 +7,7 @@ from oracle import layers as OL
 from oracle import step as OS
 from oracle.controller import controller_run
 
-from gpu_util import GpuRun, assert_close, param_tensor_slices
+from gpu_util import GpuRun, assert_close, param_tensor_slices, unstored_layers
 
 pytestmark = pytest.mark.gpu
 TOL = 2e-2        # l2-relative, per tensor
@@ -41,7 +41,7 @@ def _check(layers, in_shape, params, x, y, off, lr, tag, check_acts=True):
         assert got["status"] == 0
         worst = 0.0
         if check_acts:
-            folded = {L["src"] for L in layers if L["op"] == "relu"}
+            folded = unstored_layers(layers)
             for li, lay in enumerate(layers):
                 if li in folded:
                     continue
@@ -136,7 +136,7 @@ def test_resnet18_reduced_batch():
     try:
         got = run.step(params, w.x, w.labels, off, w.lr)
         assert got["status"] == 0
-        folded = {L["src"] for L in w.layers if L["op"] == "relu"}
+        folded = unstored_layers(w.layers)
         for li in range(12):                      # the first blocks: not yet amplified
             if li in folded:
                 continue
@@ -218,7 +218,7 @@ def test_resnet18_full_size_sampled_worker():
     try:
         got = run.step(params, w.x, w.labels, off, 0.0, flags=1)
         assert got["status"] == 0
-        folded = {L["src"] for L in w.layers if L["op"] == "relu"}
+        folded = unstored_layers(w.layers)
         for li in range(12):
             if li in folded:
                 continue
