@@ -256,7 +256,11 @@ int64_t omni_net_graph_replays(const omni_net* net);
  * stream, which leaves the 2-3 microseconds of the event packets out.
  * In an fp32 network the weight gradients of all fully connected layers before
  * the classifier head run as ONE launch; it counts as a launch of the lowest
- * layer index it covers (layer 0 of a multi-layer perceptron). */
+ * layer index it covers (layer 0 of a multi-layer perceptron).  Likewise the
+ * head's own parameter gradients (with the per-worker losses) share a launch
+ * with the input gradient of the layer below it where that product takes the
+ * small-batch kernel: the launch counts as that layer's OMNI_KERNEL_LINEAR_DGRAD,
+ * and OMNI_KERNEL_LOSS then covers the head's forward / loss / dz kernel only. */
 enum {
   OMNI_KERNEL_LINEAR_FWD = 0,
   OMNI_KERNEL_LINEAR_DGRAD = 1,

@@ -26,6 +26,7 @@
 #include <type_traits>
 
 #include "common.h"
+#include "head_device.h"
 #include "kernels.h"
 
 namespace omni {
@@ -59,20 +60,25 @@ struct DirectParams {
 constexpr int kBlk = 32 * 36;
 struct Staged { v4f a[4], b0[4], b1[4]; };   // b0/b1 unused by dgrad (row-contiguous B is loaded directly)
 
+// LDS of one workgroup, in floats: the wavefronts' staging blocks, then their partial tiles.
 template <bool DGRAD, int NW>
-__global__ __launch_bounds__(64 * NW) void gemm_f32_direct_kernel(DirectParams p) {
+constexpr int direct_lds_floats() { return NW * (DGRAD ? 1 : 3) * kBlk + NW * 32 * 64; }
+
+// Workgroup `tile_index` of `n_tiles` (64 * NW threads); smem holds direct_lds_floats() floats, 16-byte aligned.
+template <bool DGRAD, int NW>
+__device__ __forceinline__ void gemm_f32_direct_body(const DirectParams& p, int tile_index, int n_tiles, float* smem) {
   constexpr int kWave = (DGRAD ? 1 : 3) * kBlk;
-  __shared__ __attribute__((aligned(16))) float stage[NW * kWave];
-  __shared__ float red[NW][32 * 64];
+  float* stage = smem;
+  float (*red)[32 * 64] = reinterpret_cast<float (*)[32 * 64]>(smem + NW * kWave);
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = lane & 31, h = lane >> 5;
   const int lrow = lane >> 3, lpiece = lane & 7;
   const int tiles_m = (p.M + 31) / 32;
-  int t = blockIdx.x;
+  int t = tile_index;
   // Workgroups are dealt to the 8 XCDs round-robin by index; re-order them so an
   // XCD owns a contiguous run of tiles (row tiles fastest): its L2 then holds a
   // few column panels of B once.
-  if (p.xcd_remap) t = (t & 7) * ((int)gridDim.x >> 3) + (t >> 3);
+  if (p.xcd_remap) t = (t & 7) * (n_tiles >> 3) + (t >> 3);
   const int tile_n = t / tiles_m, tile_m = t - tile_n * tiles_m;
   const int row0 = tile_m * 32, col0 = tile_n * 64;
   const int nsteps = p.K / kStep;
@@ -248,6 +254,32 @@ __global__ __launch_bounds__(64 * NW) void gemm_f32_direct_kernel(DirectParams p
   }
 }
 
+template <bool DGRAD, int NW>
+__global__ __launch_bounds__(64 * NW) void gemm_f32_direct_kernel(DirectParams p) {
+  __shared__ __attribute__((aligned(16))) float smem[direct_lds_floats<DGRAD, NW>()];
+  gemm_f32_direct_body<DGRAD, NW>(p, (int)blockIdx.x, (int)gridDim.x, smem);
+}
+
+// Two independent kernels of the fp32 backward pass in one launch: the input gradient of the layer
+// below the classifier, and the classifier's own parameter gradients with the losses (both need
+// only the head's output gradient).  The first dgrad_tiles workgroups are the product's tiles,
+// the rest the head's grid flattened row by row.  Launched one after the other, the second
+// starts when the first has drained; the product has fewer tiles than the chip has room for,
+// and the head's short workgroups run beside them.
+__global__ __launch_bounds__(256) void dgrad_and_head_wgrad_kernel(DirectParams p, int dgrad_tiles, HeadWgradParams h,
+                                                                   int head_gx, Segments seg) {
+  constexpr int kFloats = direct_lds_floats<true, 4>() > kHeadWgradLdsFloats ? direct_lds_floats<true, 4>()
+                                                                              : kHeadWgradLdsFloats;
+  __shared__ __attribute__((aligned(16))) float smem[kFloats];
+  const int b = blockIdx.x;
+  if (b < dgrad_tiles) {
+    gemm_f32_direct_body<true, 4>(p, b, dgrad_tiles, smem);
+  } else {
+    const int hb = b - dgrad_tiles;
+    head_wgrad_loss_body<float>(h, seg, hb % head_gx, hb / head_gx, smem);
+  }
+}
+
 inline bool aligned16(const void* q) { return (reinterpret_cast<uintptr_t>(q) & 15u) == 0; }
 
 template <bool DGRAD>
@@ -282,15 +314,34 @@ bool linear_fwd_f32_direct(hipStream_t st, const float* x, const float* w, const
   return true;
 }
 
+bool linear_dgrad_f32_direct_supported(const float* dy, const float* w, const float* mask, const float* dx, int rows,
+                                       int cin, int cout) {
+  return small_batch_shape(rows, cin, cout) && cin % 2 == 0 && aligned16(dy) && aligned16(w) && aligned16(dx) &&
+         (!mask || aligned16(mask));
+}
+
 bool linear_dgrad_f32_direct(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
                              int rows, int cin, int cout, bool accumulate) {
-  if (!small_batch_shape(rows, cin, cout) || cin % 2 != 0 || !aligned16(dy) || !aligned16(w) ||
-      !aligned16(dx) || (mask && !aligned16(mask)))
-    return false;
+  if (!linear_dgrad_f32_direct_supported(dy, w, mask, dx, rows, cin, cout)) return false;
   DirectParams p{};
   p.A = dy; p.B = w; p.C = dx; p.M = rows; p.N = cin; p.K = cout; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.mask = mask; p.accumulate = accumulate ? 1 : 0;
   launch_direct<true>(st, p);
+  return true;
+}
+
+bool linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
+                                      int rows, int cin, int cout, bool accumulate, const HeadWgradParams& head,
+                                      const Segments& seg) {
+  if (!linear_dgrad_f32_direct_supported(dy, w, mask, dx, rows, cin, cout)) return false;
+  DirectParams p{};
+  p.A = dy; p.B = w; p.C = dx; p.M = rows; p.N = cin; p.K = cout; p.lda = cout; p.ldb = cin; p.ldc = cin;
+  p.mask = mask; p.accumulate = accumulate ? 1 : 0;
+  const int tiles = ((p.M + 31) / 32) * ((p.N + 63) / 64);
+  p.xcd_remap = tiles % 8 == 0 ? 1 : 0;
+  const dim3 hg = head_wgrad_grid(head.cin, head.C, seg.K);
+  hipLaunchKernelGGL(dgrad_and_head_wgrad_kernel, dim3(tiles + hg.x * hg.y), dim3(256), 0, st, p, tiles, head,
+                     (int)hg.x, seg);
   return true;
 }
 

@@ -14,6 +14,7 @@
 
 #include "bf16.h"
 #include "common.h"
+#include "head_device.h"
 #include "kernels.h"
 
 namespace omni {
@@ -22,33 +23,6 @@ namespace {
 
 constexpr int kMaxClasses = 128;
 
-// Wavefront-wide reductions on the vector ALU's data-parallel primitives: two quad
-// permutes and two row mirrors leave every lane with the result of its row of 16, four
-// lane reads combine the rows.  (A butterfly of __shfl_xor goes through the LDS crossbar:
-// six dependent round trips of ~170 cycles each per reduction; with one wavefront per SIMD
-// nothing hides them, and the ten per-class sums of the classifier were most of this
-// kernel's time.)
-template <int CTRL>
-__device__ inline float dpp_move(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
-}
-__device__ inline float lane_value(float v, int lane) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
-}
-__device__ inline float wave_sum(float v) {
-  v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
-  v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
-  v += dpp_move<0x141>(v);   // row_half_mirror
-  v += dpp_move<0x140>(v);   // row_mirror
-  return (lane_value(v, 0) + lane_value(v, 16)) + (lane_value(v, 32) + lane_value(v, 48));
-}
-__device__ inline float wave_max(float v) {
-  v = fmaxf(v, dpp_move<0xB1>(v));
-  v = fmaxf(v, dpp_move<0x4E>(v));
-  v = fmaxf(v, dpp_move<0x141>(v));
-  v = fmaxf(v, dpp_move<0x140>(v));
-  return fmaxf(fmaxf(lane_value(v, 0), lane_value(v, 16)), fmaxf(lane_value(v, 32), lane_value(v, 48)));
-}
 __device__ inline int owner(const Segments& seg, int s) {
   int k = 0;
   while (k + 1 < seg.K && s >= seg.off[k + 1]) ++k;
@@ -200,129 +174,10 @@ __global__ __launch_bounds__(256) void head_fwd_loss_dgrad_kernel(
   }
 }
 
-// grid.x = K * ceil(cin/16) + 1, grid.y = ceil(C/16).  A workgroup is 16 input
-// columns x 16 row groups; each thread walks its share of the worker's rows.
-// The worker's dz rows (16 classes of them) are staged in LDS 256 rows at a time:
-// fetched per thread they would be 16 global loads per row, and the vector cache,
-// not the arithmetic, would set the pace.
 template <typename T>
-__global__ __launch_bounds__(256) void head_wgrad_loss_kernel(
-    const float* __restrict__ dz, const T* __restrict__ x, const int32_t* __restrict__ labels, int cin, int C,
-    Segments seg, float* __restrict__ gw, float* __restrict__ gb, size_t worker_stride,
-    const float* __restrict__ loss_rows, float* __restrict__ loss_per_worker, float* __restrict__ loss,
-    uint32_t* __restrict__ status) {
-  __shared__ float red[16][16][17];
-  __shared__ __attribute__((aligned(16))) float dzs[256][16];
-  const int tid = threadIdx.x;
-  const int jchunks = (cin + 15) / 16;
-
-  if ((int)blockIdx.x == seg.K * jchunks) {
-    // ---- the extra workgroup: losses and label check; one wavefront per worker
-    if (blockIdx.y != 0) return;
-    float* part = &red[0][0][0];
-    const int lane = tid & 63, wv = tid >> 6;
-    const int rows = seg.off[seg.K];
-    const float invB = 1.0f / (float)rows;
-    for (int k = wv; k < seg.K; k += 4) {
-      float a = 0.f;
-      for (int s = seg.off[k] + lane; s < seg.off[k + 1]; s += 64) a += loss_rows[s];
-      a = wave_sum(a);
-      if (lane == 0) {
-        const float bk = (float)(seg.off[k + 1] - seg.off[k]);
-        const float Lk = a / bk;
-        loss_per_worker[k] = Lk;
-        part[k] = bk * invB * Lk;   // lambda_k L_k
-      }
-    }
-    int badl = 0;
-    for (int s = tid; s < rows; s += 256) badl |= (labels[s] < 0 || labels[s] >= C) ? 1 : 0;
-    const int anybad = __syncthreads_or(badl);
-    if (tid == 0) {
-      float total = 0.f;
-      for (int k = 0; k < seg.K; ++k) total += part[k];
-      loss[0] = total;
-      status[0] = anybad ? 1u : 0u;
-    }
-    return;
-  }
-
-  const int wk = blockIdx.x / jchunks, jc = blockIdx.x % jchunks;
-  const int jl = tid & 15, rs = tid >> 4;
-  const int j = min(jc * 16 + jl, cin - 1);   // a column past the end shadows the last one and is not stored
-  const int c0 = blockIdx.y * 16;
-  const int nc = min(16, C - c0);
-  const int s_end = seg.off[wk + 1];
-  const bool want_bias = jc == 0 && gb != nullptr;
-  float acc[16];
-#pragma unroll
-  for (int c = 0; c < 16; ++c) acc[c] = 0.f;
-  float bsum = 0.f;   // class jl, rows rs, rs+16, ...
-
-  for (int base = seg.off[wk]; base < s_end; base += 256) {
-    const int n = min(256, s_end - base);
-    __syncthreads();   // the previous 256 rows have been consumed
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int f = tid + 256 * i, rr = f >> 4, c = f & 15;
-      const bool ok = rr < n && c < nc;
-      const float v = dz[(size_t)(base + (ok ? rr : 0)) * C + c0 + (ok ? c : 0)];
-      dzs[rr][c] = ok ? v : 0.f;
-    }
-    __syncthreads();
-    const T* xb = x + (size_t)base * cin + j;
-    int sl = rs;
-    for (; sl + 112 < n; sl += 128) {        // eight rows per trip: their loads overlap
-      float av[8];
-#pragma unroll
-      for (int u = 0; u < 8; ++u) av[u] = Piece<T>::get(xb + (size_t)(sl + 16 * u) * cin);
-#pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const v4f* d = reinterpret_cast<const v4f*>(&dzs[sl + 16 * u][0]);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const v4f dv = d[q];
-#pragma unroll
-          for (int e = 0; e < 4; ++e) acc[4 * q + e] += dv[e] * av[u];
-        }
-      }
-    }
-    for (; sl < n; sl += 16) {
-      const float a = Piece<T>::get(xb + (size_t)sl * cin);
-      const v4f* d = reinterpret_cast<const v4f*>(&dzs[sl][0]);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const v4f dv = d[q];
-#pragma unroll
-        for (int e = 0; e < 4; ++e) acc[4 * q + e] += dv[e] * a;
-      }
-    }
-    if (want_bias)
-      for (int r2 = rs; r2 < n; r2 += 16) bsum += dzs[r2][jl];
-  }
-
-#pragma unroll
-  for (int c = 0; c < 16; ++c) red[rs][c][jl] = acc[c];
-  __syncthreads();
-  {
-    const int c = tid >> 4, jj = tid & 15;
-    float t = 0.f;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) t += red[r][c][jj];
-    if (c < nc && jc * 16 + jj < cin)
-      gw[(size_t)wk * worker_stride + (size_t)(c0 + c) * cin + jc * 16 + jj] = t;
-  }
-  if (want_bias) {
-    // bias gradient: column sums of dz over the worker's rows, 16 row groups x 16 classes
-    __syncthreads();
-    float* r2 = &red[0][0][0];
-    r2[rs * 16 + jl] = bsum;
-    __syncthreads();
-    if (tid < 16 && tid < nc) {
-      float u = 0.f;
-      for (int r = 0; r < 16; ++r) u += r2[r * 16 + tid];
-      gb[(size_t)wk * worker_stride + c0 + tid] = u;
-    }
-  }
+__global__ __launch_bounds__(256) void head_wgrad_loss_kernel(HeadWgradParams h, Segments seg) {
+  __shared__ __attribute__((aligned(16))) float smem[kHeadWgradLdsFloats];
+  head_wgrad_loss_body<T>(h, seg, (int)blockIdx.x, (int)blockIdx.y, smem);
 }
 
 }  // namespace
@@ -373,14 +228,12 @@ void head_fwd_loss_dgrad(hipStream_t st, bool bf16, const void* x, const void* w
 void head_wgrad_loss(hipStream_t st, bool bf16, const float* dz, const void* x, const int32_t* labels, int cin,
                      int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
                      const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status) {
-  const int jchunks = (cin + 15) / 16;
-  dim3 grid(seg.K * jchunks + 1, (classes + 15) / 16, 1);
+  const HeadWgradParams h{dz, x, labels, cin, classes, gw, gb, worker_stride, loss_rows, loss_per_worker, loss, status};
+  const dim3 grid = head_wgrad_grid(cin, classes, seg.K);
   if (bf16)
-    hipLaunchKernelGGL(head_wgrad_loss_kernel<bf16_t>, grid, dim3(256), 0, st, dz, static_cast<const bf16_t*>(x),
-                       labels, cin, classes, seg, gw, gb, worker_stride, loss_rows, loss_per_worker, loss, status);
+    hipLaunchKernelGGL(head_wgrad_loss_kernel<bf16_t>, grid, dim3(256), 0, st, h, seg);
   else
-    hipLaunchKernelGGL(head_wgrad_loss_kernel<float>, grid, dim3(256), 0, st, dz, static_cast<const float*>(x),
-                       labels, cin, classes, seg, gw, gb, worker_stride, loss_rows, loss_per_worker, loss, status);
+    hipLaunchKernelGGL(head_wgrad_loss_kernel<float>, grid, dim3(256), 0, st, h, seg);
 }
 
 }  // namespace omni

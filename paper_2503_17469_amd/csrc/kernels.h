@@ -39,6 +39,8 @@ void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const flo
 // summation order; return false without launching when the shape does not qualify.
 bool linear_fwd_f32_direct(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
                            int rows, int cin, int cout, bool relu);
+bool linear_dgrad_f32_direct_supported(const float* dy, const float* w, const float* mask, const float* dx, int rows,
+                                       int cin, int cout);
 bool linear_dgrad_f32_direct(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
                              int rows, int cin, int cout, bool accumulate);
 // For every worker k: gw + k*worker_stride receives dy_k^T x_k ([cout][cin]) over rows
@@ -72,6 +74,27 @@ void head_fwd_loss_dgrad(hipStream_t st, bool bf16, const void* x, const void* w
 void head_wgrad_loss(hipStream_t st, bool bf16, const float* dz, const void* x, const int32_t* labels, int cin,
                      int classes, const Segments& seg, float* gw, float* gb, size_t worker_stride,
                      const float* loss_rows, float* loss_per_worker, float* loss, uint32_t* status);
+// Arguments of the head's parameter-gradient kernel.  x has the storage type T of the body's
+// instantiation (fp32, or bf16 words); everything else is fp32.
+struct HeadWgradParams {
+  const float* dz;            // [rows][classes], carries 1/b_k
+  const void* x;              // [rows][cin]
+  const int32_t* labels;      // [rows]
+  int cin, C;
+  float* gw;                  // worker k's [C][cin] at gw + k * worker_stride
+  float* gb;                  // worker k's [C] at gb + k * worker_stride, may be null
+  size_t worker_stride;
+  const float* loss_rows;     // [rows]
+  float* loss_per_worker;     // [K]
+  float* loss;                // [1]
+  uint32_t* status;           // [1]
+};
+// The input gradient of a fully connected fp32 layer (as linear_dgrad_f32) and the head's parameter
+// gradients (as head_wgrad_loss with fp32 x) in ONE launch; the two must not depend on each other.
+// False, with nothing launched, if the product's shape is not one the small-batch kernel takes.
+bool linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
+                                      int rows, int cin, int cout, bool accumulate, const HeadWgradParams& head,
+                                      const Segments& seg);
 
 // ---- bf16 convolutions / fully connected layers as implicit GEMMs (conv_bf16.hip) ----
 typedef uint16_t bf16_t;   // raw bfloat16 bits

@@ -501,6 +501,8 @@ void step_f32(StepCtx& c) {
   // ---- loss: dz already carries 1/b_k, so everything downstream is a per-worker mean gradient
   const int logits = last.out;
   std::vector<char> written(net->tensors.size(), 0);
+  int merge_layer = -1;
+  omni::HeadWgradParams head_wgrad{};
   if (fused_head) {
     TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
     const bool need_dx = last.in0 >= 0;
@@ -509,9 +511,24 @@ void step_f32(StepCtx& c) {
                               actw(logits), grad(logits), c.loss_rows, need_dx && net->tensors[last.in0].relu,
                               need_dx ? grad(last.in0) : nullptr, false);
     if (need_dx) written[last.in0] = 1;
-    omni::head_wgrad_loss(st, false, grad(logits), act(last.in0), c.labels, last.d.cin, last.d.cout, c.seg,
-                          c.G + last.w_off, last.has_b ? c.G + last.b_off : nullptr, net->P_stride, c.loss_rows,
-                          c.loss_per_worker, c.loss, c.status);
+    // The head's parameter gradients and the next layer's input gradient both wait for this kernel only:
+    // where the latter takes the small-batch kernel the two share a launch (below), reported as that layer's dgrad.
+    for (int i = n_layers - 2; i >= 0 && merge_layer < 0; --i) {
+      const Layer& L = net->layers[i];
+      if (L.fused_away) continue;
+      if (L.in0 >= 0 && omni::linear_dgrad_f32_direct_supported(grad(L.out), params + L.w_off,
+                                                                net->tensors[L.in0].relu ? act(L.in0) : nullptr,
+                                                                grad(L.in0), rows, L.d.cin, L.d.cout))
+        merge_layer = i;
+      break;
+    }
+    head_wgrad = omni::HeadWgradParams{grad(logits), act(last.in0), c.labels, last.d.cin, last.d.cout,
+                                       c.G + last.w_off, last.has_b ? c.G + last.b_off : nullptr, net->P_stride,
+                                       c.loss_rows, c.loss_per_worker, c.loss, c.status};
+    if (merge_layer < 0)
+      omni::head_wgrad_loss(st, false, head_wgrad.dz, head_wgrad.x, head_wgrad.labels, head_wgrad.cin, head_wgrad.C,
+                            c.seg, head_wgrad.gw, head_wgrad.gb, head_wgrad.worker_stride, head_wgrad.loss_rows,
+                            head_wgrad.loss_per_worker, head_wgrad.loss, head_wgrad.status);
   } else {
     TimedScope ts(net, st, OMNI_KERNEL_LOSS, n_layers - 1);
     omni::fill_u32(st, c.status, 1, 0u);
@@ -534,8 +551,13 @@ void step_f32(StepCtx& c) {
     if (L.in0 >= 0) {
       const Tensor& ti = net->tensors[L.in0];
       TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
-      omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, ti.relu ? act(L.in0) : nullptr, grad(L.in0), rows,
-                             L.d.cin, L.d.cout, written[L.in0] != 0, sw);
+      const float* mask = ti.relu ? act(L.in0) : nullptr;
+      if (i == merge_layer)
+        omni::linear_dgrad_f32_with_head_wgrad(st, grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin,
+                                               L.d.cout, written[L.in0] != 0, head_wgrad, c.seg);
+      else
+        omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin, L.d.cout,
+                               written[L.in0] != 0, sw);
       written[L.in0] = 1;
     }
   }
