@@ -180,7 +180,7 @@ def main():
     ap.add_argument("--no-asp", action="store_true", help="skip the asynchronous-variant measurement")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on ONE GPU; --gpus must be 1 (no collectives or sharding exist here)")
+        sys.exit("bench.py: this library runs on ONE GPU; --gpus must be 1 (no collectives or sharding exist here)")
 
     import numpy as np
     import torch
