@@ -68,6 +68,9 @@ def test_config1_mlp3072():
     # enough 32 x 64 tiles (7 x 16) for the small-batch kernels, with a ragged last row tile (201 rows) and
     # a half-full last column tile (992 columns): forward of layer 0 and data gradient of layer 1
     ([256, 992, 512, 10], [0, 3, 90, 91, 201]),
+    # the same with 7 x 15 tiles: not a multiple of the 8 XCDs, so the tiles keep their launch order; in both
+    # cases the classifier's parameter gradients ride in the launch of layer 1's data gradient
+    ([256, 960, 512, 10], [0, 3, 90, 91, 201]),
 ])
 def test_ragged_shapes(dims, off):
     layers = synth.mlp(dims)
@@ -210,6 +213,30 @@ def test_max_workers():
     params = synth.he_normal_params(layers, 64, False)
     x, labels = synth.make_batch(640, off[-1], (1, 1, dims[0]), dims[-1], False)
     _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag="mlp-64-workers")
+
+
+def test_head_gradients_share_the_launch_of_the_input_gradient_below():
+    """At the benchmark's size the classifier's parameter gradients and losses run in the launch of the
+    data gradient of the layer below: that launch is timed as the layer's data gradient, the loss class
+    keeps one launch per step, and the step's results do not depend on what is timed."""
+    import paper_2503_17469_amd as omni
+    w = synth.workload(1)
+    b, off = controller_run(w.T, w.B)
+    run = GpuRun(w.layers, w.in_shape, "f32", w.K, w.B)
+    try:
+        base = run.step(w.params, w.x, w.labels, off, w.lr)
+        for cls, layer in (("linear_dgrad", 2), ("loss", -1)):
+            omni.net_timing_enable(run.net, cls, layer, 8)
+            for _ in range(3):
+                timed = run.step(w.params, w.x, w.labels, off, w.lr)
+            ms, n = omni.net_timing_read(run.net)
+            assert n == 3 and 0.0 < ms / n < 1.0, (cls, ms, n)
+            assert np.array_equal(timed["params"], base["params"])
+            assert np.array_equal(timed["worker_grads"], base["worker_grads"])
+            assert np.array_equal(timed["loss_per_worker"], base["loss_per_worker"]) and timed["status"] == 0
+        omni.net_timing_enable(run.net, -1, -1, 1)
+    finally:
+        run.close()
 
 
 def test_kernel_timing_counts_and_sampling():
