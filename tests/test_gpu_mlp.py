@@ -83,6 +83,23 @@ def test_ragged_shapes(dims, off):
     _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag=f"mlp{dims}")
 
 
+def test_shared_launch_with_many_classes_and_no_head_bias():
+    """40 classes (three 16-class rows of classifier workgroups behind the input-gradient tiles of the
+    shared launch), a classifier without bias, eight ragged workers."""
+    dims = [256, 960, 512, 40]
+    off = [0, 1, 30, 31, 90, 140, 141, 200, 230]
+    layers = synth.mlp(dims)
+    layers[-1]["bias"] = False
+    layers[0]["bias"] = False
+    rng = np.random.default_rng(4040)
+    params = synth.he_normal_params(layers, 11, False)
+    params += (rng.standard_normal(params.size) * 0.05).astype(np.float32)
+    B = off[-1]
+    x = rng.standard_normal((B, dims[0])).astype(np.float32)
+    labels = rng.integers(0, dims[-1], B).astype(np.int32)
+    _check_step(layers, (1, 1, dims[0]), params, x, labels, off, 0.05, tag="mlp-40-classes")
+
+
 def test_deep_stack_batched_weight_gradients():
     """Twelve fully connected layers: their weight gradients share launches of at most eight problems
     (8 + 2 + the odd-width layer and its neighbour, which cannot take the shared launch, alone)."""
