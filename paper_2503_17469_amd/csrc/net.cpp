@@ -552,12 +552,18 @@ void step_f32(StepCtx& c) {
       const Tensor& ti = net->tensors[L.in0];
       TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
       const float* mask = ti.relu ? act(L.in0) : nullptr;
-      if (i == merge_layer)
-        omni::linear_dgrad_f32_with_head_wgrad(st, grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin,
-                                               L.d.cout, written[L.in0] != 0, head_wgrad, c.seg);
-      else
+      const bool shared = i == merge_layer &&
+                          omni::linear_dgrad_f32_with_head_wgrad(st, grad(L.out), params + L.w_off, mask, grad(L.in0),
+                                                                 rows, L.d.cin, L.d.cout, written[L.in0] != 0,
+                                                                 head_wgrad, c.seg);
+      if (!shared) {
+        if (i == merge_layer)   // (the same test said yes above; never leave the head's gradients out)
+          omni::head_wgrad_loss(st, false, head_wgrad.dz, head_wgrad.x, head_wgrad.labels, head_wgrad.cin,
+                                head_wgrad.C, c.seg, head_wgrad.gw, head_wgrad.gb, head_wgrad.worker_stride,
+                                head_wgrad.loss_rows, head_wgrad.loss_per_worker, head_wgrad.loss, head_wgrad.status);
         omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin, L.d.cout,
                                written[L.in0] != 0, sw);
+      }
       written[L.in0] = 1;
     }
   }
