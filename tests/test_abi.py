@@ -174,6 +174,28 @@ def test_measured_time_controller_matches_oracle_bit_for_bit():
             omni.dyn_destroy(ctl)
 
 
+def test_measured_time_controller_hand_worked_rules():
+    """The library's three global-batch rules on the hand-worked proposal b* = (20, 30, 50, 60) at B = 128
+    (sizes (30, 30, 40, 42), times (1.5, 1, 0.8, 0.7), mean time 1): the printed rule takes (160 - 128) / 4 = 8
+    from every worker, the multiplicative one rescales by 128 / 160, no rule keeps b* (sum 160)."""
+    want = {"additive": [12, 22, 42, 52], "multiplicative": [16, 24, 40, 48], "none": [20, 30, 50, 60]}
+    for rule, b_want in want.items():
+        ctl = omni.dyn_create(4, 128, 1, 0, 0.0, 1.0, rule, [30, 30, 40, 42])
+        try:
+            omni.dyn_observe(ctl, [1.5, 1.0, 0.8, 0.7])
+            b, off, changed = omni.dyn_adjust(ctl, 4)
+            assert b == b_want and off[-1] == sum(b_want) and changed, (rule, b)
+        finally:
+            omni.dyn_destroy(ctl)
+    # the printed rule with bounds (16, 45): 12 -> 16 and 52 -> 45, the sum leaves 128
+    ctl = omni.dyn_create(4, 128, 16, 45, 0.0, 1.0, "additive", [30, 30, 40, 42])
+    try:
+        omni.dyn_observe(ctl, [1.5, 1.0, 0.8, 0.7])
+        assert omni.dyn_adjust(ctl, 4)[0] == [16, 22, 42, 45]
+    finally:
+        omni.dyn_destroy(ctl)
+
+
 def test_measured_time_controller_errors():
     with pytest.raises(omni.OmniError):
         omni.dyn_create(4, 3)                      # fewer samples than workers
