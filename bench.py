@@ -5,7 +5,11 @@ A "step" is the whole hot path on one synthetic batch already resident in HBM:
 controller (throughputs -> b_k, offsets) + forward + loss + backward with
 per-worker gradients + weighted aggregation + SGD update.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload mlp3072]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload resnet18]
+
+The headline is the largest benchmark configuration (the ResNet-18-shaped net, B = 2048, K = 8,
+bf16 operands with fp32 accumulation); the other four configurations are timed in the same run and
+reported in the `configs` array of the same line.
 """
 import argparse
 import json
@@ -17,21 +21,13 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# fp32 dense MFMA peak and HBM peak of one MI355X (published figures)
+# dense MFMA peaks and HBM peak of one MI355X (published figures)
 PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
 PEAK_HBM_GBS = 8000.0
 
-# kernel whose roofline is reported, per workload: (timing class, layer index)
-# dominant kernel of every workload: (timing class, layer, roofline that bounds it)
-DOMINANT = {
-    "tiny_mlp": ("linear_wgrad", 0, "mfma"),
-    "mlp3072": ("linear_wgrad", 0, "mfma"),
-    # weight gradient of the second conv layer (32 -> 64 channels on 16 x 16 maps): 2 x 9 x 32 x 64 flop per
-    # (64 + 32) x 2 bytes of activations = 192 flop per byte, below the chip's ridge point of 312
-    "cnn3": ("conv_wgrad", 3, "hbm"),
-    "cnn3_dynamic": ("conv_wgrad", 3, "hbm"),
-    "resnet18": ("conv_fwd", 3, "mfma"),
-}
+# contraction kernel classes of a step, per dtype (names of the library's timing classes)
+CLASSES = {"f32": ("linear_fwd", "linear_dgrad", "linear_wgrad"), "bf16": ("conv_fwd", "conv_dgrad", "conv_wgrad")}
+PREWARM_S = 2.0     # steps are repeated for at least this long before anything is timed (clocks settle)
 
 
 def layer_flops(layers, in_shape, li, rows):
@@ -44,53 +40,51 @@ def layer_flops(layers, in_shape, li, rows):
     return 2.0 * rows * ho * wo * L["cout"] * L["k"] * L["k"] * L["cin"]
 
 
-def wgrad_bytes(layers, in_shape, li, rows, K):
-    """Algorithmic HBM bytes of one conv weight-gradient launch of layer li: the output gradient and
-    the (channel-padded, bf16) layer input read once, K per-worker fp32 gradients written."""
-    import synth.nets as nets
-    L = layers[li]
-    shapes = nets.layer_shapes(layers, in_shape)
-    ho, wo, _ = shapes[li]
-    hi, wi, ci = in_shape if L["src"] < 0 else shapes[L["src"]]
-    ci_pad = (ci + 7) // 8 * 8
-    return 2.0 * rows * (ho * wo * L["cout"] + hi * wi * ci_pad) + 4.0 * K * L["cout"] * L["k"] * L["k"] * L["cin"]
+def class_flops(w, cls):
+    """Algorithmic flop per step of all launches the timing class `cls` covers.
+
+    bf16 networks: the class covers the convolutions (the classifier head is its own class).
+    fp32 networks: the fully connected layers before the classifier head; their input gradients
+    exist for every layer but the first."""
+    op = "conv" if cls.startswith("conv") else "linear"
+    idx = [i for i, L in enumerate(w.layers) if L["op"] == op]
+    if op == "linear":
+        idx = idx[:-1]                         # the head runs in fused kernels of the loss class
+    if cls.endswith("dgrad"):
+        idx = [i for i in idx if w.layers[i]["src"] >= 0]
+    return sum(layer_flops(w.layers, w.in_shape, i, w.B) for i in idx), idx
 
 
-def dgrad_bytes(layers, in_shape, li, rows):
-    """Algorithmic HBM bytes of one conv data-gradient launch of layer li (bf16): the output gradient read
-    once, the input gradient written once, and the layer input read once for the folded ReLU mask."""
-    import synth.nets as nets
-    L = layers[li]
-    shapes = nets.layer_shapes(layers, in_shape)
-    ho, wo, _ = shapes[li]
-    hi, wi, ci = in_shape if L["src"] < 0 else shapes[L["src"]]
-    ci_pad = (ci + 7) // 8 * 8
-    return 2.0 * rows * (ho * wo * L["cout"] + 2 * hi * wi * ci_pad)
+def cpu_baseline(w, rows, budget_s=12.0):
+    """The CPU oracle timed on the host cores on a sub-batch of the same workload: `rows` rows split
+    over the same K workers in the same proportions (the controller run on the same throughputs).
+    The K workers' passes run on a thread pool (the oracle's own `pmap` hook), one BLAS thread each."""
+    from concurrent.futures import ThreadPoolExecutor
 
+    from threadpoolctl import threadpool_limits
 
-def cpu_baseline(w, off, budget_s=12.0):
-    """The CPU oracle, as it stands, timed on the host cores on the same workload."""
     from oracle import step as oracle_step
-    try:
-        from threadpoolctl import threadpool_info
-        threads = max([i.get("num_threads", 1) for i in threadpool_info()] or [1])
-    except Exception:
-        threads = os.cpu_count() or 1
-    x = w.x
+    from oracle.controller import controller_run
+    rows = min(rows, w.B)
+    b, off = controller_run(w.T, rows)
     store = None
     if w.dtype == "bf16":
         from oracle import layers as oracle_layers
         store = oracle_layers.round_bf16
+    x = w.x[:rows].reshape((rows,) + tuple(w.in_shape))
+    threads = max(1, min(w.K, os.cpu_count() or 1))
     n = 0
-    t0 = time.perf_counter()
-    while True:
-        oracle_step.sgd_step(w.layers, w.params, x, w.labels, off, w.lr, store=store)
-        n += 1
-        el = time.perf_counter() - t0
-        if el >= budget_s:
-            break
-    return {"value": w.B * n / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
-            "sample": f"{n} full steps of the same workload (B={w.B}), fp64 numpy, {el:.1f} s"}
+    with ThreadPoolExecutor(threads) as ex, threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        while True:
+            oracle_step.sgd_step(w.layers, w.params, x, w.labels[:rows], off, w.lr, store=store, pmap=ex.map)
+            n += 1
+            el = time.perf_counter() - t0
+            if el >= budget_s:
+                break
+    what = "full steps of the same workload" if rows == w.B else f"steps on a {rows}-row sub-batch of the same workload"
+    return {"value": rows * n / el, "unit": "samples/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"{n} {what} (b={b}), fp64 numpy, one thread per worker, {el:.1f} s"}
 
 
 def measured_traffic(workload, key):
@@ -100,34 +94,191 @@ def measured_traffic(workload, key):
     taken; a figure for a kernel that has changed since is not reported."""
     import hashlib
     import re
-    root = os.path.dirname(os.path.abspath(__file__))
-    path = os.path.join(root, "profiles", f"step_{workload}_hbm_traffic.md")
+    path = os.path.join(ROOT, "profiles", f"step_{workload}_hbm_traffic.md")
     if not os.path.exists(path):
         return None
     for line in open(path):
         m = re.match(r"\s*traffic (.+?) bytes=(\S+) source=(\S+) sha256=([0-9a-f]{64})\s*$", line)
         if not m or m.group(1) != key:
             continue
-        src = os.path.join(root, m.group(3))
+        src = os.path.join(ROOT, m.group(3))
         if os.path.exists(src) and hashlib.sha256(open(src, "rb").read()).hexdigest() == m.group(4):
             return float(m.group(2))
     return None
 
 
-def asp_variant(omni, torch, net, w, b, off, params, x, y, lr, rounds=50):
+class Job:
+    """One workload on the GPU: network, buffers, controller; `step()` is one pass of the hot path."""
+
+    def __init__(self, name, lr=1e-3):
+        import torch
+
+        import paper_2503_17469_amd as omni
+        import synth
+        self.omni, self.torch = omni, torch
+        self.w = w = synth.workload(synth.CONFIG_NAMES.index(name))
+        self.ctl = omni.ctl_create(w.K, w.B)
+        # the dynamic configuration walks the workers' throughputs: a new split of the batch every step
+        self.walk = synth.throughput_walk(w.seed, w.K, 200) if name == "cnn3_dynamic" else [w.T]
+        self.i = 0
+        omni.ctl_set_throughputs(self.ctl, w.T)
+        self.b, self.off = omni.ctl_run(self.ctl, w.K)
+        self.net = omni.net_create(w.layers, w.in_shape, w.dtype, w.K, w.B)
+        self.ws = torch.zeros(omni.net_workspace_bytes(self.net), dtype=torch.uint8, device="cuda")
+        self.params = torch.from_numpy(w.params).cuda()
+        x = torch.from_numpy(w.x.reshape(w.B, -1)).cuda()
+        self.x = x.to(torch.bfloat16) if w.dtype == "bf16" else x
+        self.y = torch.from_numpy(w.labels).cuda()
+        self.lpw = torch.zeros(w.K, device="cuda")
+        self.loss = torch.zeros(1, device="cuda")
+        self.lr = lr      # a small learning rate keeps the synthetic problem finite over thousands of steps
+
+    def step(self, params=None):
+        omni, w = self.omni, self.w
+        omni.ctl_set_throughputs(self.ctl, self.walk[self.i % len(self.walk)])
+        self.i += 1
+        bb, oo = omni.ctl_run(self.ctl, w.K)
+        omni.step(self.net, self.params if params is None else params, self.x, self.y, oo, bb, self.lr, self.ws,
+                  self.lpw, self.loss)
+
+    def prewarm(self, min_steps, min_s):
+        n, t0 = 0, time.perf_counter()
+        while n < min_steps or time.perf_counter() - t0 < min_s:
+            self.step()
+            n += 1
+            if n % 16 == 0:
+                self.torch.cuda.synchronize()
+        self.torch.cuda.synchronize()
+        return n, time.perf_counter() - t0
+
+    def timed(self, steps):
+        """(wall seconds, device milliseconds) of `steps` steps, nothing else on the stream in between."""
+        torch = self.torch
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ev0.record()
+        for _ in range(steps):
+            self.step()
+        ev1.record()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0, ev0.elapsed_time(ev1)
+
+    def class_time(self, cls, steps, params=None):
+        """Summed device time and number of launches of one kernel class over `steps` steps, every launch
+        between HIP events of its own on the stream it runs on (a separate loop: never inside `timed`)."""
+        omni = self.omni
+        omni.net_timing_sample(self.net, 1)
+        omni.net_timing_enable(self.net, cls, -1, 4096)
+        for _ in range(steps):
+            self.step(params)
+        self.torch.cuda.synchronize()
+        ms, n = omni.net_timing_read(self.net)
+        omni.net_timing_enable(self.net, -1, -1, 1)
+        return ms, n
+
+    def rooflines(self, steps):
+        """Per contraction class: algorithmic flop of all its launches in a step / their summed duration."""
+        w = self.w
+        out = []
+        for cls in CLASSES[w.dtype]:
+            flops, idx = class_flops(w, cls)
+            if not idx:
+                continue
+            ms, n = self.class_time(cls, steps)
+            if n == 0:
+                continue
+            per_step_s = ms * 1e-3 / steps
+            ach = flops / per_step_s / 1e12
+            label = f"{cls}: all {n // steps} launches of a step, layers {idx[0]}..{idx[-1]}, time-weighted"
+            out.append({"bound": "mfma", "kernel": label, "achieved": ach, "peak": PEAK_TFLOPS[w.dtype],
+                        "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[w.dtype],
+                        "traffic": measured_traffic(w.name, cls), "flop_per_step": flops,
+                        "us_per_step": per_step_s * 1e6, "avg_launch_us": ms * 1e3 / n, "launches": int(n),
+                        "steps": steps})
+        return out
+
+    def update_roofline(self, steps, momentum=False):
+        omni, torch, w = self.omni, self.torch, self.w
+        params = None
+        if momentum:
+            params = self.params.clone()
+            vel = torch.zeros_like(params)
+            omni.net_set_momentum(self.net, vel, 0.9, 5e-4)
+        ms, n = self.class_time("update", steps, params)
+        if momentum:
+            omni.net_set_momentum(self.net, None, 0.0, 0.0)
+        nbytes = (w.K + (4 if momentum else 2)) * 4.0 * w.P
+        gbs = nbytes / (ms / max(n, 1) * 1e-3) / 1e9
+        r = {"bound": "hbm", "kernel": "weighted reduce + momentum SGD with weight decay" if momentum
+             else "weighted reduce + SGD", "achieved": gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+             "frac": gbs / PEAK_HBM_GBS, "traffic": measured_traffic(w.name, "update_momentum" if momentum else "update"),
+             "bytes_per_launch": nbytes, "avg_launch_us": ms / max(n, 1) * 1e3, "launches": int(n)}
+        if nbytes < 256e6:
+            r["note"] = "working set below 256 MB may be served from the Infinity Cache"
+        return r
+
+    def close(self):
+        self.omni.net_destroy(self.net)
+        self.omni.ctl_destroy(self.ctl)
+        del self.ws
+
+
+def copy_ceiling(torch):
+    """What a plain device-to-device copy reaches (256 MiB read + 256 MiB written per copy, more than the
+    Infinity Cache holds): the practical ceiling beside the 8 TB/s the HBM fractions divide by."""
+    src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = 20
+    c0.record()
+    for _ in range(n):
+        dst.copy_(src)
+    c1.record()
+    torch.cuda.synchronize()
+    gbs = 2.0 * src.numel() * n / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    return {"achieved": gbs, "unit": "GB/s", "bytes_per_copy": 2.0 * (256 << 20),
+            "note": "plain device-to-device copy, read + write counted"}
+
+
+def read_ceiling(torch, omni, K=8, P=11220132):
+    """A read-dominated stream of the update kernel's own shape: K + 1 fp32 arrays read, 1 written, far more
+    than the Infinity Cache holds (the library's own update kernel on buffers of its own, back to back)."""
+    stride = (P + 63) // 64 * 64
+    G = torch.ones(K, stride, device="cuda")
+    th = torch.zeros(P, device="cuda")
+    b = [1] * K
+    for _ in range(3):
+        omni.weighted_sgd(th, G, b, 1e-6, P=P)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = 20
+    c0.record()
+    for _ in range(n):
+        omni.weighted_sgd(th, G, b, 1e-6, P=P)
+    c1.record()
+    torch.cuda.synchronize()
+    nbytes = (K + 2) * 4.0 * P
+    return {"achieved": nbytes * n / (c0.elapsed_time(c1) * 1e-3) / 1e9, "unit": "GB/s", "bytes_per_launch": nbytes,
+            "note": f"update kernel alone, back to back: {K}+1 arrays read, 1 written"}
+
+
+def asp_variant(job, rounds=50):
     """The asynchronous variant (Algorithm 2) on the same network, data and batch split: simulated
     workers whose speed matches their batch size push in turn; every push is one launch of the push
     kernel followed by that worker's next gradient (forward + backward over its own rows, one worker,
     no update) at the model it has just pulled.  Reports samples/s over all pushes and the push kernel
     against the HBM roofline (model read, gradient read, model written: 12 bytes per parameter)."""
-    K, B = w.K, w.B
-    server = params.clone()
+    omni, torch, w, net = job.omni, job.torch, job.w, job.net
+    K, B, b, off, lr = w.K, w.B, job.b, job.off, job.lr
+    server = job.params.clone()
     nbytes = omni.net_workspace_bytes(net)
     wss = [torch.zeros(nbytes, dtype=torch.uint8, device="cuda") for _ in range(K)]
     lpw = torch.zeros(1, device="cuda")
     loss = torch.zeros(1, device="cuda")
-    xs = [x[off[k]:off[k + 1]] for k in range(K)]
-    ys = [y[off[k]:off[k + 1]] for k in range(K)]
+    xs = [job.x[off[k]:off[k + 1]] for k in range(K)]
+    ys = [job.y[off[k]:off[k + 1]] for k in range(K)]
     grads = [omni.net_worker_grads(net, wss[k], 1)[0] for k in range(K)]
     n_events = rounds * K
     worker, version = omni.asp_schedule(w.T, b, n_events)
@@ -149,7 +300,6 @@ def asp_variant(omni, torch, net, w, b, off, params, x, y, lr, rounds=50):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     samples = sum(b[k] for k in worker)
-    # the push kernel alone, bracketed by events on the stream it is launched on
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     n_push = 200
     e0.record()
@@ -170,14 +320,37 @@ def asp_variant(omni, torch, net, w, b, off, params, x, y, lr, rounds=50):
                                       "Infinity Cache"}}
 
 
+def side_config(name, budget_s=1.0):
+    """A short measurement of another benchmark configuration for the `configs` array."""
+    job = Job(name)
+    try:
+        n_warm, _ = job.prewarm(5, 0.5)
+        wall, _ = job.timed(8)
+        steps = max(8, min(4000, int(budget_s / (wall / 8))))
+        wall, dev_ms = job.timed(steps)
+        roofs = job.rooflines(max(2, min(20, steps)))
+        dom = max(roofs, key=lambda r: r["us_per_step"]) if roofs else None
+        w = job.w
+        out = {"workload": name, "dtype": w.dtype, "K": w.K, "B": w.B, "params": int(w.P), "steps": steps,
+               "ms_per_step": wall / steps * 1e3, "device_ms_per_step": dev_ms / steps,
+               "value": w.B * steps / wall, "unit": "samples/s", "roofline": dom,
+               "roofline_update": job.update_roofline(max(2, min(50, steps)))}
+        if name == "mlp3072":
+            out["asp_variant"] = asp_variant(job)     # (one workspace per simulated worker: on this workload only)
+        return out
+    finally:
+        job.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000, help="timed steps (use ~50 for resnet18)")
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--workload", default="mlp3072")
+    ap.add_argument("--steps", type=int, default=100, help="timed steps of the headline workload")
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="resnet18")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-asp", action="store_true", help="skip the asynchronous-variant measurement")
+    ap.add_argument("--no-side-configs", action="store_true", help="skip the other configurations' short runs")
+    ap.add_argument("--no-rooflines", action="store_true", help="headline loop only (for profiling runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on ONE GPU; --gpus must be 1 (no collectives or sharding exist here)")
@@ -190,29 +363,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    idx = synth.CONFIG_NAMES.index(args.workload)
-    w = synth.workload(idx)
-
-    ctl = omni.ctl_create(w.K, w.B)
-    omni.ctl_set_throughputs(ctl, w.T)
-    b, off = omni.ctl_run(ctl, w.K)
-
-    net = omni.net_create(w.layers, w.in_shape, w.dtype, w.K, w.B)
-    ws = torch.zeros(omni.net_workspace_bytes(net), dtype=torch.uint8, device="cuda")
-    params = torch.from_numpy(w.params).cuda()
-    x = torch.from_numpy(w.x.reshape(w.B, -1)).cuda()
-    if w.dtype == "bf16":
-        x = x.to(torch.bfloat16)
-    y = torch.from_numpy(w.labels).cuda()
-    lpw = torch.zeros(w.K, device="cuda")
-    loss = torch.zeros(1, device="cuda")
-    # a small learning rate keeps the synthetic problem finite over thousands of steps
-    lr = 1e-3
-
-    def one_step():
-        omni.ctl_set_throughputs(ctl, w.T)
-        bb, oo = omni.ctl_run(ctl, w.K)
-        omni.step(net, params, x, y, oo, bb, lr, ws, lpw, loss)
+    job = Job(args.workload)
+    w = job.w
 
     # One plain device-to-device copy of known size (256 MiB read + 256 MiB written): under
     # `rocprofv3 --pmc FETCH_SIZE` / `WRITE_SIZE` its counters calibrate the traffic figures.
@@ -222,120 +374,16 @@ def main():
     torch.cuda.synchronize()
     del cal_src, cal_dst
 
-    for _ in range(args.warmup):
-        one_step()
-    torch.cuda.synchronize()
+    # W untimed steps as asked, then more of the same until the GPU has been busy for PREWARM_S seconds:
+    # a handful of steps does not bring the clocks up, and a short timed loop would report the ramp
+    prewarm_steps, prewarm_s = job.prewarm(args.warmup, PREWARM_S)
 
-    # the dominant kernel is bracketed by HIP events on every 8th step of the timed loop (a pair of
-    # event packets costs about 3 us on the stream; on every step that is 2 % of this workload's step)
-    kcls, klayer, kbound = DOMINANT[w.name]
-    sample_every = 8 if args.steps >= 64 else 1
-    omni.net_timing_sample(net, sample_every)
-    omni.net_timing_enable(net, kcls, klayer, args.steps)
-    torch.cuda.synchronize()
-    # device-only time of the same loop: two events on the stream the steps are enqueued on
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        one_step()
-    ev1.record()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    device_ms_per_step = ev0.elapsed_time(ev1) / args.steps
-    k_ms, k_n = omni.net_timing_read(net)
-    omni.net_timing_enable(net, -1, -1, 1)
-    omni.net_timing_sample(net, 1)
-    final_loss = float(loss.item())
+    # ---- the headline: exactly K steps, nothing but the steps on the stream
+    dt, dev_ms = job.timed(args.steps)
+    final_loss = float(job.loss.item())
     assert np.isfinite(final_loss), "loss diverged"
-
     ms_per_step = dt / args.steps * 1e3
     value = w.B * args.steps / dt
-
-    # spread of single steps: every step of a second, shorter loop between two events of its own
-    # (the event packets add about 3 us to each, which is why the headline loop above has none inside)
-    n_each = min(200, args.steps)
-    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
-    for e0, e1 in evs:
-        e0.record()
-        one_step()
-        e1.record()
-    torch.cuda.synchronize()
-    each_us = np.sort(np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in evs]))
-    step_spread = {"unit": "us", "n": n_each, "median": float(np.percentile(each_us, 50)),
-                   "p10": float(np.percentile(each_us, 10)), "p90": float(np.percentile(each_us, 90)),
-                   "note": "device time of single steps, each between two events of its own"}
-
-    # the fused weighted-reduce + SGD kernel against the HBM roofline (separate short loop, same buffers)
-    n_upd = min(200, args.steps)
-    omni.net_timing_enable(net, "update", -1, n_upd)
-    for _ in range(n_upd):
-        one_step()
-    torch.cuda.synchronize()
-    u_ms, u_n = omni.net_timing_read(net)
-    omni.net_timing_enable(net, -1, -1, 1)
-    upd_bytes = (w.K + 2) * 4.0 * w.P
-    upd_gbs = upd_bytes / (u_ms / max(u_n, 1) * 1e-3) / 1e9
-
-    # the same kernel with the momentum / weight-decay update of the paper's experiments selected
-    # (velocity read and written beside the parameters); on a copy of the parameters, after everything else
-    params_m = params.clone()
-    vel = torch.zeros_like(params_m)
-    omni.net_set_momentum(net, vel, 0.9, 5e-4)
-    omni.net_timing_enable(net, "update", -1, n_upd)
-    for _ in range(n_upd):
-        omni.ctl_set_throughputs(ctl, w.T)
-        bb, oo = omni.ctl_run(ctl, w.K)
-        omni.step(net, params_m, x, y, oo, bb, lr, ws, lpw, loss)
-    torch.cuda.synchronize()
-    m_ms, m_n = omni.net_timing_read(net)
-    omni.net_timing_enable(net, -1, -1, 1)
-    omni.net_set_momentum(net, None, 0.0, 0.0)
-    mom_bytes = (w.K + 4) * 4.0 * w.P
-    mom_gbs = mom_bytes / (m_ms / max(m_n, 1) * 1e-3) / 1e9
-
-    # the asynchronous variant keeps one workspace per worker; it is measured on the default workload only
-    asp = None if (args.no_asp or w.name != "mlp3072") else asp_variant(omni, torch, net, w, b, off, params, x, y, lr)
-
-    # what a plain device-to-device copy reaches on this GPU (256 MiB read + 256 MiB written per copy, more
-    # than the Infinity Cache holds): the practical ceiling beside the 8 TB/s the rooflines divide by
-    cp_src = torch.empty(256 << 20, dtype=torch.uint8, device="cuda").fill_(1)
-    cp_dst = torch.empty_like(cp_src)
-    for _ in range(3):
-        cp_dst.copy_(cp_src)
-    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    n_copy = 20
-    c0.record()
-    for _ in range(n_copy):
-        cp_dst.copy_(cp_src)
-    c1.record()
-    torch.cuda.synchronize()
-    copy_gbs = 2.0 * cp_src.numel() * n_copy / (c0.elapsed_time(c1) * 1e-3) / 1e9
-    del cp_src, cp_dst
-
-    kernel_s = k_ms / max(k_n, 1) * 1e-3
-    klabel = f"{kcls}[layer {klayer}]"
-    if kbound == "mfma":
-        covered = [klayer]
-        if kcls == "linear_wgrad":
-            # an fp32 network computes the weight gradients of all fully connected layers before the
-            # classifier head in one launch, timed as layer 0: its flop are those of all of them
-            covered = [i for i, L in enumerate(w.layers) if L["op"] == "linear"][:-1]
-            if len(covered) > 1:
-                klabel = f"{kcls}[layers {', '.join(str(i) for i in covered)}: one launch]"
-        flops = sum(layer_flops(w.layers, w.in_shape, i, w.B) for i in covered)
-        achieved = flops / kernel_s / 1e12
-        peak, unit = PEAK_TFLOPS[w.dtype], "TFLOP/s"
-    else:
-        nbytes = (dgrad_bytes(w.layers, w.in_shape, klayer, w.B) if kcls == "conv_dgrad"
-                  else wgrad_bytes(w.layers, w.in_shape, klayer, w.B, w.K))
-        achieved = nbytes / kernel_s / 1e9
-        peak, unit = PEAK_HBM_GBS, "GB/s"
-    roofline = {"bound": kbound, "kernel": klabel, "achieved": achieved, "peak": peak,
-                "unit": unit, "frac": achieved / peak,
-                "traffic": measured_traffic(w.name, klabel),
-                "avg_launch_us": kernel_s * 1e6, "launches": int(k_n),
-                "sampled": f"every {sample_every} steps of the timed loop"}
 
     out = {
         "metric": "samples/sec per ragged weighted SGD step (fwd+bwd+reduce+update)",
@@ -345,37 +393,52 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": ms_per_step,
-        "device_ms_per_step": device_ms_per_step,
-        "step_spread": step_spread,
+        "device_ms_per_step": dev_ms / args.steps,
+        "prewarm": {"steps": prewarm_steps, "seconds": prewarm_s,
+                    "note": "untimed steps before the timed loop: --warmup of them, then until the time is up"},
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "f32" if w.dtype == "f32" else "bf16",
+        "dtype": w.dtype,
+        "dtype_note": ("bf16 operands and stored activations, fp32 accumulation, fp32 parameters, gradients, loss "
+                       "and update" if w.dtype == "bf16" else "fp32 throughout"),
         "data": "synthetic",
-        "config": {"workload": w.name, "K": w.K, "B": w.B, "b": b, "params": int(w.P),
-                   "net": "MLP 3072-1024-1024-10 fp32" if w.name == "mlp3072" else w.name,
+        "config": {"workload": w.name, "K": w.K, "B": w.B, "b": job.b, "params": int(w.P),
                    "includes": "controller+offsets+fwd+loss+bwd+weighted reduce+SGD"},
-        "roofline": roofline,
-        "roofline_update": {"bound": "hbm", "kernel": "weighted reduce + SGD", "achieved": upd_gbs,
-                            "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": upd_gbs / PEAK_HBM_GBS,
-                            "traffic": measured_traffic(w.name, "update"),
-                            "bytes_per_launch": upd_bytes, "avg_launch_us": u_ms / max(u_n, 1) * 1e3,
-                            "note": "working set below 256 MB may be served from the Infinity Cache"},
-        "roofline_update_momentum": {"bound": "hbm", "kernel": "weighted reduce + momentum SGD with weight decay",
-                                     "achieved": mom_gbs, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                                     "frac": mom_gbs / PEAK_HBM_GBS,
-                                     "traffic": measured_traffic(w.name, "update_momentum"), "bytes_per_launch": mom_bytes,
-                                     "avg_launch_us": m_ms / max(m_n, 1) * 1e3},
-        "hbm_copy_ceiling": {"achieved": copy_gbs, "unit": "GB/s", "bytes_per_copy": 2.0 * (256 << 20),
-                             "note": "plain device-to-device copy, read + write counted"},
         "final_loss": final_loss,
     }
-    if asp is not None:
-        out["asp_variant"] = asp
+
+    if not args.no_rooflines:
+        # spread of single steps: every step of a second loop between two events of its own
+        n_each = max(10, min(200, args.steps))
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_each)]
+        for e0, e1 in evs:
+            e0.record()
+            job.step()
+            e1.record()
+        torch.cuda.synchronize()
+        each_us = np.sort(np.array([e0.elapsed_time(e1) * 1e3 for e0, e1 in evs]))
+        out["step_spread"] = {"unit": "us", "n": n_each, "median": float(np.percentile(each_us, 50)),
+                              "p10": float(np.percentile(each_us, 10)), "p90": float(np.percentile(each_us, 90)),
+                              "note": "device time of single steps, each between two events of its own"}
+        # contraction classes, each in a loop of its own (event pairs around every launch of the class)
+        n_cls = max(5, min(50, args.steps))
+        roofs = job.rooflines(n_cls)
+        out["roofline"] = max(roofs, key=lambda r: r["us_per_step"])     # the class the step spends most time in
+        out["roofline_classes"] = roofs
+        total_flop = sum(r["flop_per_step"] for r in roofs)
+        out["step_mfma_frac"] = total_flop / (dev_ms / args.steps * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype]
+        n_upd = max(10, min(200, args.steps))
+        out["roofline_update"] = job.update_roofline(n_upd)
+        out["roofline_update_momentum"] = job.update_roofline(n_upd, momentum=True)
+        out["hbm_copy_ceiling"] = copy_ceiling(torch)
+        out["hbm_read_ceiling"] = read_ceiling(torch, omni)
+    job.close()
+
+    if not args.no_side_configs:
+        out["configs"] = [side_config(n) for n in synth.CONFIG_NAMES if n != w.name]
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(w, off)
-    omni.net_destroy(net)
-    omni.ctl_destroy(ctl)
+        out["cpu_baseline"] = cpu_baseline(w, 256 if w.name == "resnet18" else w.B)
     print(json.dumps(out))
 
 

@@ -179,7 +179,11 @@ size_t omni_net_param_count(const omni_net* net);
 
 /* Bytes of device workspace omni_step needs (activations, activation
  * gradients, the K_max per-worker gradient rows, small tables).  The caller
- * allocates it (256-byte aligned) and may reuse it across steps. */
+ * allocates it (256-byte aligned) and may reuse it across steps, for other
+ * networks or for anything else in between: a step relies on nothing that an
+ * earlier step left in it (the few words that must be zero when a kernel
+ * starts are cleared by the step itself), so fresh, recycled and overwritten
+ * memory all do.  Steps that share one workspace must not overlap in time. */
 size_t omni_net_workspace_bytes(const omni_net* net);
 
 /* Row stride, in floats, of the per-worker gradient matrix (>= P, multiple of 64). */
@@ -196,7 +200,11 @@ size_t omni_net_grad_stride(const omni_net* net);
  *   workspace       dev, omni_net_workspace_bytes(net) bytes
  *   loss_per_worker dev [K] fp32: L_k = mean loss over worker k's rows
  *   loss            dev [1] fp32: sum_k lambda_k L_k
- *   flags           OMNI_STEP_NO_UPDATE leaves params untouched (gradients only)
+ *   flags           OMNI_STEP_NO_UPDATE leaves params untouched (gradients only);
+ *                   OMNI_STEP_KEEP_REDUCED_GRAD also stores the aggregated gradient
+ *                   g = sum_k lambda_k g_k of equation bspweightedgrads (the update
+ *                   forms it in registers and otherwise never writes it) where
+ *                   omni_net_reduced_grad points; other bits are OMNI_EINVAL
  *
  * The step allocates no device memory and never synchronises with the device.
  * The first steps of a network create what they need on the host side and keep
@@ -210,7 +218,7 @@ size_t omni_net_grad_stride(const omni_net* net);
  * of the matrix returned by omni_net_worker_grads.  A label outside
  * [0, classes) sets bit 0 of the status word (omni_net_status) and contributes
  * zero loss and zero gradient. */
-enum { OMNI_STEP_NO_UPDATE = 1u };
+enum { OMNI_STEP_NO_UPDATE = 1u, OMNI_STEP_KEEP_REDUCED_GRAD = 2u };
 
 int omni_step(omni_net* net, void* stream, float* params, const void* x,
               const int32_t* labels, const int32_t* off, const int32_t* b, int32_t K,
@@ -228,6 +236,22 @@ const uint32_t* omni_net_status(const omni_net* net, const void* workspace);
  * points at memory no step writes).  OMNI_EINVAL on a bad index. */
 int omni_net_activation(const omni_net* net, const void* workspace, int32_t layer,
                         const void** ptr, size_t* elems_per_row);
+
+/* g = sum_k lambda_k g_k, dev [P] fp32, as the last step with OMNI_STEP_KEEP_REDUCED_GRAD left it
+ * (the AllReduce line of procedure Train, Algorithm 1, before the update consumes it). */
+const float* omni_net_reduced_grad(const omni_net* net, const void* workspace);
+/* Gradient of worker k's mean loss L_k, on the rows of worker k (the 1/b_k of equation
+ * bspweightedgrads is inside), with respect to the output of layer
+ * `layer`, as the last step left it: *ptr dev pointer with the layout and type of omni_net_activation
+ * (bf16, fp32 for the logits and for fp32 networks).  For a layer whose ReLU was folded into it the
+ * gradient is the one with respect to the value BEFORE the ReLU (already zero where the stored output
+ * is zero).  Layers fused away alias their neighbour as in omni_net_activation, and an input of a
+ * residual add that nothing else reads shares the add's buffer.  OMNI_EINVAL on a bad index, and for a
+ * tensor whose gradient that step did not store: a layer nothing differentiable depends on, and the
+ * first convolution of a network when a 2 x 2 max pooling follows it (its weight-gradient kernel
+ * rebuilds that gradient from the pooled one). */
+int omni_net_activation_grad(const omni_net* net, const void* workspace, int32_t layer,
+                             const void** ptr, size_t* elems_per_row);
 
 /* Optional replay of repeated steps as a HIP graph.  A step is a chain of a few dozen short kernels
  * on up to three streams; launched one by one, the host calls and the waits between the streams cost
@@ -291,8 +315,8 @@ void omni_net_destroy(omni_net* net);
 int omni_weighted_sgd(void* stream, float* params, const float* grads, size_t stride,
                       size_t P, const int32_t* b, int32_t K, float lr, void* shadow_bf16);
 
-/* The optimiser of the paper's experiments (Section "Evaluation", model hyperparameters:
- * "SGD with momentum 0.9 and weight decay 5e-4"), fused with the aggregation of equation
+/* The optimiser of the paper's experiments (Section "Evaluation", model hyperparameters: momentum
+ * SGD, coefficient 0.9, with an L2 weight decay of 5e-4 or 1e-4), fused with the aggregation of equation
  * bspweightedgrads.  The paper prints no formula; this is the update of the framework it
  * names (no dampening, no Nesterov look-ahead, L2 penalty folded into the gradient):
  *   g = sum_k (b[k] / sum_i b[i]) * grads[k*stride + j]
@@ -310,8 +334,8 @@ int omni_weighted_sgd_momentum(void* stream, float* params, float* velocity, con
  * effect from the next omni_step. */
 int omni_net_set_momentum(omni_net* net, float* velocity, float momentum, float weight_decay);
 
-/* Stepwise learning-rate schedule of the same hyperparameter list ("initial LR 0.1 that
- * decays by a factor of 10 after 15, 30 and 45 epochs"): *lr_out = lr0 * gamma^m with m
+/* Stepwise learning-rate schedule of the same hyperparameter list (for instance 0.1 at the start,
+ * divided by ten once epochs 15, 30 and 45 are reached): *lr_out = lr0 * gamma^m with m
  * the number of milestones <= epoch (epochs counted from 0).  Host only, double
  * arithmetic; milestones host [n], may be NULL when n == 0. */
 int omni_lr_step_decay(double lr0, double gamma, const int32_t* milestones, int32_t n,
@@ -408,7 +432,8 @@ void omni_asp_ps_destroy(omni_asp_ps* ps);
  * loss_rows[s] = -log softmax(z_s)[y_s] and dz_s = (softmax(z_s) - e_{y_s}) / b_k
  * (the 1/|b_k| of equation bspweightedgrads), then L_k and sum_k lambda_k L_k.
  *   z dev [off[K]][C] fp32, labels dev int32, dz dev like z, loss_rows dev [off[K]],
- *   loss_per_worker dev [K], loss dev [1], status dev [1] (bit 0: bad label), off host [K+1]. */
+ *   loss_per_worker dev [K], loss dev [1], status dev [1] (cleared by the call, then bit 0 is set
+ *   if a label lies outside [0, C)), off host [K+1]. */
 int omni_softmax_xent(void* stream, const float* z, const int32_t* labels, int32_t C,
                       const int32_t* off, int32_t K, float* dz, float* loss_rows,
                       float* loss_per_worker, float* loss, uint32_t* status);

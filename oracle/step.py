@@ -174,21 +174,26 @@ class StepResult:
     acts: Optional[list] = field(default=None, repr=False)   # per worker, per layer
 
 
-def sgd_step(net, theta, x, labels, off: Sequence[int], lr: float, store=None, keep_acts=False) -> StepResult:
+def sgd_step(net, theta, x, labels, off: Sequence[int], lr: float, store=None, keep_acts=False,
+             pmap=map) -> StepResult:
     """One weighted-aggregation SGD step over K workers whose rows are
-    x[off[k]:off[k+1]]."""
+    x[off[k]:off[k+1]].  The workers' passes are independent of each other; `pmap` (default: the
+    builtin map, one worker after the other) lets a caller run them side by side, e.g. a thread
+    pool's map.  The aggregation below is the same either way."""
     theta = np.asarray(theta, dtype=np.float64)
     K = len(off) - 1
     B = off[K] - off[0]
     Lk = np.zeros(K)
     gk = np.zeros((K, theta.size))
     acts = []
-    for k in range(K):
+
+    def worker(k):
         s0, s1 = off[k], off[k + 1]
-        b_k = s1 - s0
-        loss_rows, g, a = forward_backward(net, theta, x[s0:s1], labels[s0:s1], 1.0 / b_k,
-                                           store=store, keep_acts=keep_acts)
-        Lk[k] = loss_rows.sum() / b_k
+        return forward_backward(net, theta, x[s0:s1], labels[s0:s1], 1.0 / (s1 - s0), store=store,
+                                keep_acts=keep_acts)
+
+    for k, (loss_rows, g, a) in enumerate(pmap(worker, range(K))):
+        Lk[k] = loss_rows.sum() / (off[k + 1] - off[k])
         gk[k] = g
         acts.append(a)
     g = np.zeros(theta.size)

@@ -26,6 +26,7 @@ EXPORTS = [
     "omni_ctl_create", "omni_ctl_set_throughputs", "omni_ctl_run", "omni_ctl_destroy",
     "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
+    "omni_net_activation_grad", "omni_net_reduced_grad",
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
     "omni_net_timing_sample", "omni_net_graph_enable", "omni_net_graph_replays",
     "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
@@ -81,6 +82,9 @@ def _load():
     lib.omni_net_status.argtypes = [vp, vp]
     lib.omni_net_status.restype = vp
     lib.omni_net_activation.argtypes = [vp, vp, i32, P(vp), P(sz)]
+    lib.omni_net_activation_grad.argtypes = [vp, vp, i32, P(vp), P(sz)]
+    lib.omni_net_reduced_grad.argtypes = [vp, vp]
+    lib.omni_net_reduced_grad.restype = vp
     lib.omni_net_destroy.argtypes = [vp]
     lib.omni_net_destroy.restype = None
     lib.omni_net_timing_enable.argtypes = [vp, i32, i32, i32]
@@ -205,6 +209,9 @@ def net_destroy(net):
     lib.omni_net_destroy(net)
 
 
+STEP_NO_UPDATE, STEP_KEEP_REDUCED_GRAD = 1, 2
+
+
 def step(net, params, x, labels, off, b, lr, workspace, loss_per_worker, loss, flags: int = 0, stream=None):
     K = len(b)
     _check(lib.omni_step(net, stream if stream is not None else _stream(), _ptr(params), _ptr(x), _ptr(labels),
@@ -238,6 +245,26 @@ def net_activation(net, workspace, layer: int, rows: int, dtype: str = "f32"):
     if dtype == "f32":
         return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 4].view(torch.float32).view(rows, n.value)
     return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 2].view(torch.bfloat16).view(rows, n.value)
+
+
+def net_activation_grad(net, workspace, layer: int, rows: int, dtype: str = "f32"):
+    import torch
+    p = C.c_void_p()
+    n = C.c_size_t()
+    _check(lib.omni_net_activation_grad(net, _ptr(workspace), layer, C.byref(p), C.byref(n)))
+    byte_off = p.value - workspace.data_ptr()
+    if dtype == "f32":
+        return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 4].view(torch.float32).view(rows, n.value)
+    return workspace.view(torch.uint8)[byte_off:byte_off + rows * n.value * 2].view(torch.bfloat16).view(rows, n.value)
+
+
+def net_reduced_grad(net, workspace):
+    """[P] view of the aggregated gradient a step with STEP_KEEP_REDUCED_GRAD stored."""
+    import torch
+    P = net_param_count(net)
+    base = lib.omni_net_reduced_grad(net, _ptr(workspace))
+    byte_off = base - workspace.data_ptr()
+    return workspace.view(torch.uint8)[byte_off:byte_off + P * 4].view(torch.float32)
 
 
 def net_timing_enable(net, kernel_class, layer: int = -1, max_launches: int = 4096):

@@ -304,9 +304,13 @@ bool small_batch_shape(int rows, int cols, int kred) {
 
 }  // namespace
 
+bool linear_fwd_f32_direct_supported(const float* x, const float* w, int rows, int cin, int cout) {
+  return small_batch_shape(rows, cout, cin) && aligned16(x) && aligned16(w);
+}
+
 bool linear_fwd_f32_direct(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
                            int rows, int cin, int cout, bool relu) {
-  if (!small_batch_shape(rows, cout, cin) || !aligned16(x) || !aligned16(w)) return false;
+  if (!linear_fwd_f32_direct_supported(x, w, rows, cin, cout)) return false;
   DirectParams p{};
   p.A = x; p.B = w; p.C = y; p.M = rows; p.N = cout; p.K = cin; p.lda = cin; p.ldb = cin; p.ldc = cout;
   p.bias = bias; p.relu = relu ? 1 : 0;
@@ -330,10 +334,9 @@ bool linear_dgrad_f32_direct(hipStream_t st, const float* dy, const float* w, co
   return true;
 }
 
-bool linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
+void linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
                                       int rows, int cin, int cout, bool accumulate, const HeadWgradParams& head,
                                       const Segments& seg) {
-  if (!linear_dgrad_f32_direct_supported(dy, w, mask, dx, rows, cin, cout)) return false;
   DirectParams p{};
   p.A = dy; p.B = w; p.C = dx; p.M = rows; p.N = cin; p.K = cout; p.lda = cout; p.ldb = cin; p.ldc = cin;
   p.mask = mask; p.accumulate = accumulate ? 1 : 0;
@@ -342,7 +345,6 @@ bool linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const flo
   const dim3 hg = head_wgrad_grid(head.cin, head.C, seg.K);
   hipLaunchKernelGGL(dgrad_and_head_wgrad_kernel, dim3(tiles + hg.x * hg.y), dim3(256), 0, st, p, tiles, head,
                      (int)hg.x, seg);
-  return true;
 }
 
 }  // namespace omni

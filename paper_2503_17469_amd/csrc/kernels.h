@@ -20,7 +20,7 @@ struct KernelTimer {
 };
 
 // Scratch for split reductions: partial tiles plus one arrival counter per tile.
-// Counters must be zero before the first launch; every launch leaves them zero.
+// Counters must be zero when a launch starts; every launch leaves them zero.
 struct SplitWorkspace {
   float* partial = nullptr;      // kSplitPartialFloats floats
   uint32_t* counters = nullptr;  // kSplitMaxTiles words
@@ -37,6 +37,7 @@ void linear_dgrad_f32(hipStream_t st, const float* dy, const float* w, const flo
                       int rows, int cin, int cout, bool accumulate, const SplitWorkspace& sw);
 // Small-batch variants (gemm_f32_direct.hip): same results as the two above up to
 // summation order; return false without launching when the shape does not qualify.
+bool linear_fwd_f32_direct_supported(const float* x, const float* w, int rows, int cin, int cout);
 bool linear_fwd_f32_direct(hipStream_t st, const float* x, const float* w, const float* bias, float* y,
                            int rows, int cin, int cout, bool relu);
 bool linear_dgrad_f32_direct_supported(const float* dy, const float* w, const float* mask, const float* dx, int rows,
@@ -91,8 +92,8 @@ struct HeadWgradParams {
 };
 // The input gradient of a fully connected fp32 layer (as linear_dgrad_f32) and the head's parameter
 // gradients (as head_wgrad_loss with fp32 x) in ONE launch; the two must not depend on each other.
-// False, with nothing launched, if the product's shape is not one the small-batch kernel takes.
-bool linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
+// Only for products that linear_dgrad_f32_direct_supported accepts (the caller asks first).
+void linear_dgrad_f32_with_head_wgrad(hipStream_t st, const float* dy, const float* w, const float* mask, float* dx,
                                       int rows, int cin, int cout, bool accumulate, const HeadWgradParams& head,
                                       const Segments& seg);
 
@@ -114,7 +115,8 @@ struct ConvGeom {
 // 3-channel source as it is, so that no padded copy of the network input has to be made.
 bool conv_first_layer_raw_supported(int Cout, int cin_real, const ConvGeom& g, long M);
 constexpr int kConvMaxPartialTiles = 2048;   // (tile, chunk) slots of wgrad scratch
-constexpr int kConvCounters = 16384;         // words of scratch that stay zero for the life of a workspace (the zero page)
+constexpr int kZeroPageWords = 64;           // 256 bytes of zeros that loads of absent pieces are pointed at (16 are read);
+                                             // cast_weights_bf16 clears them at the start of every step
 size_t conv_wgrad_partial_floats();
 bool conv_shape_supported(const ConvGeom& g, long positions);
 // out[M][N] = gather(src)[M][K] * wgt[N][K]^T (+bias) (ReLU) (masked where mask <= 0) (+= out)
@@ -154,7 +156,9 @@ struct CastTable {
   int n;
   CastEntry e[kCastMaxEntries];
 };
-void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, const CastEntry* entries, int n);
+// zero_page (may be null): kZeroPageWords words that the same launch sets to zero.
+void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, const CastEntry* entries, int n,
+                       uint32_t* zero_page = nullptr);
 void pad_channels_bf16(hipStream_t st, const bf16_t* x, bf16_t* xp, long pixels, int c_real, int c_pad);
 void maxpool2_fwd_bf16(hipStream_t st, const bf16_t* in, bf16_t* out, int rows, int H, int W, int C);
 // din = dout routed to the first maximum of each 2x2 window (scan order), zero elsewhere;
@@ -195,7 +199,12 @@ void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int
 // theta -= lr*velocity (velocity [P], read and written).
 void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
                       const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity = nullptr,
-                      float momentum = 0.f, float weight_decay = 0.f, const KernelTimer* timer = nullptr);
+                      float momentum = 0.f, float weight_decay = 0.f, const KernelTimer* timer = nullptr,
+                      float* gout = nullptr);
+// (gout, [P] or null, also receives the aggregated gradient sum_k lambda[k] * grads[k].)
+// The aggregation alone: gout[j] = sum_k lambda[k] * grads[k*stride + j].
+void weighted_reduce_f32(hipStream_t st, const float* grads, size_t stride, size_t P, const Segments& seg,
+                         float* gout);
 void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v);
 
 }  // namespace omni

@@ -20,6 +20,7 @@
 namespace {
 
 constexpr size_t kAlign = 256;
+constexpr size_t kNoGrad = ~(size_t)0;
 inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 struct Tensor {
@@ -62,9 +63,13 @@ struct omni_net {
   size_t shadow_off = 0, shadow_elems = 0, xpad_off = 0, conv_partial_off = 0, conv_counters_off = 0;
   size_t conv_partial2_off = 0;     // chunk scratch of the second side stream
   size_t bn_off = 0, bn_floats = 0, bn_partial_off = 0;
+  size_t reduced_off = 0;           // g = sum_k lambda_k g_k, written only on request
   int bn_cmax = 0;
+  // Where the last step left each tensor's gradient (byte offset into the workspace; kNoGrad: that step
+  // did not store it).  Two tensors may share a buffer: a residual add hands its output gradient on.
+  std::vector<size_t> grad_view;
   int classes = 0;
-  const void* ws_ready = nullptr;   // workspace whose arrival counters are known to be zero
+  const void* ws_ready = nullptr;   // workspace of the last step
   // optimiser: velocity == nullptr is plain SGD
   float* velocity = nullptr;
   float momentum = 0.f, weight_decay = 0.f;
@@ -299,12 +304,13 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
   size_t pos = 0;
   auto take = [&](size_t bytes) { const size_t o = pos; pos += align_up(bytes, kAlign); return o; };
   net->grads_off = take((size_t)K_max * net->P_stride * sizeof(float));
+  net->reduced_off = take(net->P_stride * sizeof(float));
   net->loss_rows_off = take((size_t)B_max * sizeof(float));
   net->status_off = take(kAlign);
   net->counters_off = take(omni::kSplitMaxTiles * sizeof(uint32_t));
   net->partial_off = take(omni::kSplitPartialFloats * sizeof(float));
   if (bf) {
-    net->conv_counters_off = take(omni::kConvCounters * sizeof(uint32_t));
+    net->conv_counters_off = take(omni::kZeroPageWords * sizeof(uint32_t));
     net->conv_partial_off = take(omni::conv_wgrad_partial_floats() * sizeof(float));
     net->conv_partial2_off = take(omni::conv_wgrad_partial_floats() * sizeof(float));
     net->shadow_off = take(net->shadow_elems * 2);
@@ -322,6 +328,7 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
   for (Layer& L : net->layers)
     if (L.d.op == OMNI_OP_MAXPOOL2) L.code_off = take((size_t)B_max * net->tensors[L.out].elems);
   net->ws_bytes = pos;
+  net->grad_view.assign(net->tensors.size(), kNoGrad);
   *out = net;
   return OMNI_OK;
 }
@@ -344,6 +351,22 @@ int omni_net_activation(const omni_net* net, const void* ws, int32_t layer, cons
   const Tensor& t = net->tensors[net->layers[layer].out];
   *ptr = static_cast<const char*>(ws) + t.act_off;
   *elems = t.elems;
+  return OMNI_OK;
+}
+
+const float* omni_net_reduced_grad(const omni_net* net, const void* ws) {
+  if (!net || !ws) return nullptr;
+  return reinterpret_cast<const float*>(static_cast<const char*>(ws) + net->reduced_off);
+}
+int omni_net_activation_grad(const omni_net* net, const void* ws, int32_t layer, const void** ptr, size_t* elems) {
+  if (!net || !ws || !ptr || !elems) return fail(OMNI_EINVAL, "omni_net_activation_grad: NULL argument");
+  if (layer < 0 || layer >= (int)net->layers.size())
+    return fail(OMNI_EINVAL, "omni_net_activation_grad: bad layer %d", layer);
+  const int t = net->layers[layer].out;
+  if (net->grad_view[t] == kNoGrad)
+    return fail(OMNI_EINVAL, "omni_net_activation_grad: the last step did not store the gradient of layer %d's output", layer);
+  *ptr = static_cast<const char*>(ws) + net->grad_view[t];
+  *elems = net->tensors[t].elems;
   return OMNI_OK;
 }
 
@@ -483,6 +506,17 @@ void step_f32(StepCtx& c) {
   omni::SplitWorkspace sw;
   sw.partial = reinterpret_cast<float*>(c.ws + net->partial_off);
   sw.counters = reinterpret_cast<uint32_t*>(c.ws + net->counters_off);
+  // The arrival counters of the split reductions must be zero when a launch that uses them starts.
+  // Every such launch leaves them zero, but the workspace is the caller's memory (fresh, re-allocated at
+  // the same address, shared with another network, written in between): the first launch of a step
+  // that may split its reduction is therefore preceded by a fill.  A step whose products all take the
+  // small-batch kernel never touches the counters and pays nothing.
+  bool counters_clear = false;
+  auto before_split_launch = [&]() {
+    if (counters_clear) return;
+    omni::fill_u32(st, sw.counters, omni::kSplitMaxTiles, 0u);
+    counters_clear = true;
+  };
 
   const int n_layers = (int)net->layers.size();
   const Layer& last = net->layers[n_layers - 1];
@@ -493,6 +527,8 @@ void step_f32(StepCtx& c) {
   for (int i = 0; i < n_layers; ++i) {
     const Layer& L = net->layers[i];
     if (L.fused_away || (fused_head && i == n_layers - 1)) continue;
+    if (!omni::linear_fwd_f32_direct_supported(act(L.in0), params + L.w_off, rows, L.d.cin, L.d.cout))
+      before_split_launch();
     TimedScope ts(net, st, OMNI_KERNEL_LINEAR_FWD, i);
     omni::linear_fwd_f32(st, act(L.in0), params + L.w_off, L.has_b ? params + L.b_off : nullptr, actw(L.out), rows,
                          L.d.cin, L.d.cout, net->tensors[L.out].relu, sw);
@@ -550,20 +586,18 @@ void step_f32(StepCtx& c) {
     first_job_layer = i;
     if (L.in0 >= 0) {
       const Tensor& ti = net->tensors[L.in0];
-      TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
       const float* mask = ti.relu ? act(L.in0) : nullptr;
-      const bool shared = i == merge_layer &&
-                          omni::linear_dgrad_f32_with_head_wgrad(st, grad(L.out), params + L.w_off, mask, grad(L.in0),
-                                                                 rows, L.d.cin, L.d.cout, written[L.in0] != 0,
-                                                                 head_wgrad, c.seg);
-      if (!shared) {
-        if (i == merge_layer)   // (the same test said yes above; never leave the head's gradients out)
-          omni::head_wgrad_loss(st, false, head_wgrad.dz, head_wgrad.x, head_wgrad.labels, head_wgrad.cin,
-                                head_wgrad.C, c.seg, head_wgrad.gw, head_wgrad.gb, head_wgrad.worker_stride,
-                                head_wgrad.loss_rows, head_wgrad.loss_per_worker, head_wgrad.loss, head_wgrad.status);
+      if (i != merge_layer &&
+          !omni::linear_dgrad_f32_direct_supported(grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin,
+                                                   L.d.cout))
+        before_split_launch();
+      TimedScope ts(net, st, OMNI_KERNEL_LINEAR_DGRAD, i);
+      if (i == merge_layer)   // (chosen above by the very test the shared launcher requires)
+        omni::linear_dgrad_f32_with_head_wgrad(st, grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin,
+                                               L.d.cout, written[L.in0] != 0, head_wgrad, c.seg);
+      else
         omni::linear_dgrad_f32(st, grad(L.out), params + L.w_off, mask, grad(L.in0), rows, L.d.cin, L.d.cout,
                                written[L.in0] != 0, sw);
-      }
       written[L.in0] = 1;
     }
   }
@@ -573,6 +607,8 @@ void step_f32(StepCtx& c) {
     // (last layer's problem first in the launch: measured 47.1 us against 48.8 us the other way round)
     omni::linear_wgrad_f32_batch(st, jobs.data(), (int)jobs.size(), net->P_stride, c.seg, ts.timer());
   }
+  for (size_t t = 0; t < net->tensors.size(); ++t)
+    net->grad_view[t] = (written[t] || (int)t == logits) ? net->tensors[t].grad_off : kNoGrad;
 }
 
 // ------------------------------------------------------------------ bf16 path
@@ -617,7 +653,7 @@ void step_bf16(StepCtx& c) {
     }
     g.transposed = 0;
     g.K = g.ks * g.ks * g.Cs;
-    g.zero = conv_counters;   // zeroed once per workspace, never written
+    g.zero = conv_counters;   // a few bytes of zeros, cleared by this step's first launch and not written otherwise
     g.raw3 = (raw_input && L.in0 < 0) ? 1 : 0;
     return g;
   };
@@ -655,7 +691,9 @@ void step_bf16(StepCtx& c) {
       e.cin_pad = L.cin_pad;
       casts.push_back(e);
     }
-    omni::cast_weights_bf16(st, c.params, shadow, casts.data(), (int)casts.size());
+    // (the same launch clears the few bytes of zeros that loads of absent pieces are pointed at: the workspace
+    // is the caller's memory, so nothing in it is taken to have survived since the last step)
+    omni::cast_weights_bf16(st, c.params, shadow, casts.data(), (int)casts.size(), conv_counters);
   }
 
   // ---- forward over the concatenated batch
@@ -733,6 +771,7 @@ void step_bf16(StepCtx& c) {
   // layer's output gradient out: the layer's weight-gradient kernel reads the pooled gradient and
   // the pooling's codes itself.  pooled_from[j] = that pooling layer, for conv layer j.
   std::vector<int> pooled_from(n_layers, -1);
+  std::vector<char> not_stored(net->tensors.size(), 0);   // ... and such a gradient exists nowhere
   // A residual add's gradient for an input that a convolution also reads is not routed by a pass of
   // its own: that convolution's input-gradient kernel adds it before its ReLU mask.
   std::vector<const bf16_t*> pending_add(net->tensors.size(), nullptr);
@@ -789,6 +828,7 @@ void step_bf16(StepCtx& c) {
           omni::conv_wgrad_pooled_supported(net->layers[prod].d.cout, net->layers[prod].d.cin,
                                             fwd_geom(net->layers[prod]))) {
         pooled_from[prod] = i;
+        not_stored[L.in0] = 1;
       } else if (coded[i])
         omni::maxpool2_bwd_coded_bf16(st, reinterpret_cast<const uint8_t*>(c.ws + L.code_off), grad(L.out),
                                       grad(L.in0), rows, L.ih, L.iw, L.ic);
@@ -829,6 +869,10 @@ void step_bf16(StepCtx& c) {
       written[L.in0] = 1;
     }
   }
+  for (size_t t = 0; t < net->tensors.size(); ++t) {
+    const bool have = (written[t] && !not_stored[t]) || (int)t == last.out;
+    net->grad_view[t] = have ? (size_t)(reinterpret_cast<char*>(grad((int)t)) - c.ws) : kNoGrad;
+  }
 }
 
 }  // namespace
@@ -849,6 +893,8 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   }
   if (off[K] > net->B_max) return fail(OMNI_ECAPACITY, "omni_step: %d rows exceed B_max=%d", off[K], net->B_max);
   if (!std::isfinite(lr)) return fail(OMNI_EINVAL, "omni_step: lr is not finite");
+  if (flags & ~(uint32_t)(OMNI_STEP_NO_UPDATE | OMNI_STEP_KEEP_REDUCED_GRAD))
+    return fail(OMNI_EINVAL, "omni_step: unknown flag bits 0x%x", flags);
   if ((reinterpret_cast<uintptr_t>(params) & 15u) || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
       (reinterpret_cast<uintptr_t>(x) & 15u))
     return fail(OMNI_EINVAL, "omni_step: params/x must be 16-byte and workspace 256-byte aligned");
@@ -912,14 +958,7 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   net->capturing = capture;
   net->step_matches = 0;
 
-  // Arrival counters of the split reductions must start at zero; every launch
-  // returns them to zero, so this runs once per workspace.
-  if (net->ws_ready != workspace) {
-    omni::fill_u32(c.st, reinterpret_cast<uint32_t*>(c.ws + net->counters_off), omni::kSplitMaxTiles, 0u);
-    if (net->dtype == OMNI_BF16)
-      omni::fill_u32(c.st, reinterpret_cast<uint32_t*>(c.ws + net->conv_counters_off), omni::kConvCounters, 0u);
-    net->ws_ready = workspace;
-  }
+  net->ws_ready = workspace;   // (only tells the graph switch that this workspace has been stepped on before)
 
   if (!net->side && hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess) net->side = nullptr;
   if (!net->side2 && hipStreamCreateWithFlags(&net->side2, hipStreamNonBlocking) != hipSuccess) net->side2 = nullptr;
@@ -931,10 +970,13 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   c.join();
 
   // ---- weighted aggregation + update
+  float* reduced = (flags & OMNI_STEP_KEEP_REDUCED_GRAD) ? reinterpret_cast<float*>(c.ws + net->reduced_off) : nullptr;
   if (!(flags & OMNI_STEP_NO_UPDATE)) {
     TimedScope ts(net, c.st, OMNI_KERNEL_UPDATE, -1, true);
     omni::weighted_sgd_f32(c.st, params, c.G, net->P_stride, net->P, c.seg, lr, nullptr, net->velocity,
-                           net->momentum, net->weight_decay, ts.timer());
+                           net->momentum, net->weight_decay, ts.timer(), reduced);
+  } else if (reduced) {
+    omni::weighted_reduce_f32(c.st, c.G, net->P_stride, net->P, c.seg, reduced);
   }
 
   if (capture) {
@@ -1073,6 +1115,7 @@ int omni_softmax_xent(void* stream, const float* z, const int32_t* labels, int32
     if (off[k + 1] <= off[k]) return fail(OMNI_EINVAL, "omni_softmax_xent: worker %d has no rows", k);
     seg.off[k + 1] = off[k + 1];
   }
+  omni::fill_u32(static_cast<hipStream_t>(stream), status, 1, 0u);   // the kernel only ever sets bits
   omni::softmax_xent_f32(static_cast<hipStream_t>(stream), z, labels, C, seg, dz, loss_rows, loss_per_worker, loss,
                          status);
   hipError_t e = hipGetLastError();

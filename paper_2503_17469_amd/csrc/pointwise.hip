@@ -133,11 +133,13 @@ __device__ inline void apply_update(v4f& th, v4f& v, const v4f& g, const Optim& 
   }
 }
 
-template <bool SHADOW, bool MOM>
+// KEEPG: the aggregated gradient g itself is also written to gout (4 more bytes per parameter; for
+// callers that want to look at it: the update alone never stores it).
+template <bool SHADOW, bool MOM, bool KEEPG>
 __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ params, float* __restrict__ velocity,
                                                            const float* __restrict__ grads, size_t stride,
                                                            size_t P, int K, Lambdas lam, Optim opt,
-                                                           uint16_t* __restrict__ shadow) {
+                                                           uint16_t* __restrict__ shadow, float* __restrict__ gout) {
   const size_t n4 = P / 4;
   const size_t nthreads = (size_t)gridDim.x * blockDim.x;
   const size_t t = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -171,6 +173,10 @@ __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ p
       g0 += lam.v[k] * __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * i0));
       g1 += lam.v[k] * __builtin_nontemporal_load(reinterpret_cast<const v4f*>(grads + (size_t)k * stride + 4 * j1));
     }
+    if (KEEPG) {
+      *reinterpret_cast<v4f*>(gout + 4 * i0) = g0;
+      if (has1) *reinterpret_cast<v4f*>(gout + 4 * i1) = g1;
+    }
     apply_update<MOM>(th0, v0, g0, opt);
     apply_update<MOM>(th1, v1, g1, opt);
     *reinterpret_cast<v4f*>(params + 4 * i0) = th0;
@@ -194,6 +200,7 @@ __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ p
     const size_t j = n4 * 4 + threadIdx.x;
     float g = 0.f;
     for (int k = 0; k < K; ++k) g += lam.v[k] * grads[(size_t)k * stride + j];
+    if (KEEPG) gout[j] = g;
     float th = params[j];
     if (MOM) {
       const float d = g + opt.weight_decay * th;
@@ -205,6 +212,16 @@ __global__ __launch_bounds__(256) void weighted_sgd_kernel(float* __restrict__ p
     }
     params[j] = th;
     if (SHADOW) shadow[j] = bf16_rne(th);
+  }
+}
+
+// g = sum_k lambda_k G[k] alone (equation bspweightedgrads without the update), same summation order.
+__global__ __launch_bounds__(256) void weighted_reduce_kernel(const float* __restrict__ grads, size_t stride, size_t P,
+                                                              int K, Lambdas lam, float* __restrict__ gout) {
+  for (size_t j = (size_t)blockIdx.x * blockDim.x + threadIdx.x; j < P; j += (size_t)gridDim.x * blockDim.x) {
+    float g = 0.f;
+    for (int k = 0; k < K; ++k) g += lam.v[k] * grads[(size_t)k * stride + j];
+    gout[j] = g;
   }
 }
 
@@ -223,31 +240,47 @@ void softmax_xent_f32(hipStream_t st, const float* z, const int32_t* labels, int
   hipLaunchKernelGGL(loss_reduce_kernel, dim3(1), dim3(256), 0, st, loss_rows, seg, loss_per_worker, loss);
 }
 
-void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
-                      const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity, float momentum,
-                      float weight_decay, const KernelTimer* timer) {
+static Lambdas lambdas_of(const Segments& seg) {
   Lambdas lam{};
   const double B = (double)seg.off[seg.K];
   for (int k = 0; k < seg.K; ++k) lam.v[k] = (float)((double)(seg.off[k + 1] - seg.off[k]) / B);
+  return lam;
+}
+
+void weighted_sgd_f32(hipStream_t st, float* params, const float* grads, size_t stride, size_t P,
+                      const Segments& seg, float lr, uint16_t* shadow_bf16, float* velocity, float momentum,
+                      float weight_decay, const KernelTimer* timer, float* gout) {
+  const Lambdas lam = lambdas_of(seg);
   const Optim opt{lr, momentum, weight_decay};
   const size_t n4 = P / 4;
   size_t blocks = (n4 + 511) / 512;          // two columns per thread per trip
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
   const dim3 grid((unsigned)blocks), block(256);
-#define OMNI_UPD(SH, MO)                                                                                           \
-  if (timer)                                                                                                       \
-    hipExtLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, timer->start, timer->stop, 0, params, \
-                          velocity, grads, stride, P, seg.K, lam, opt, shadow_bf16);                               \
-  else                                                                                                             \
-    hipLaunchKernelGGL((weighted_sgd_kernel<SH, MO>), grid, block, 0, st, params, velocity, grads, stride, P,      \
-                       seg.K, lam, opt, shadow_bf16)
+#define OMNI_UPD(SH, MO, KG)                                                                                        \
+  if (timer)                                                                                                        \
+    hipExtLaunchKernelGGL((weighted_sgd_kernel<SH, MO, KG>), grid, block, 0, st, timer->start, timer->stop, 0,      \
+                          params, velocity, grads, stride, P, seg.K, lam, opt, shadow_bf16, gout);                  \
+  else                                                                                                              \
+    hipLaunchKernelGGL((weighted_sgd_kernel<SH, MO, KG>), grid, block, 0, st, params, velocity, grads, stride, P,   \
+                       seg.K, lam, opt, shadow_bf16, gout)
+#define OMNI_UPD2(SH, MO)                                 \
+  if (gout) { OMNI_UPD(SH, MO, true); } else { OMNI_UPD(SH, MO, false); }
   if (velocity) {
-    if (shadow_bf16) { OMNI_UPD(true, true); } else { OMNI_UPD(false, true); }
+    if (shadow_bf16) { OMNI_UPD2(true, true) } else { OMNI_UPD2(false, true) }
   } else {
-    if (shadow_bf16) { OMNI_UPD(true, false); } else { OMNI_UPD(false, false); }
+    if (shadow_bf16) { OMNI_UPD2(true, false) } else { OMNI_UPD2(false, false) }
   }
+#undef OMNI_UPD2
 #undef OMNI_UPD
+}
+
+void weighted_reduce_f32(hipStream_t st, const float* grads, size_t stride, size_t P, const Segments& seg,
+                         float* gout) {
+  size_t blocks = (P + 255) / 256;
+  if (blocks > 4096) blocks = 4096;
+  hipLaunchKernelGGL(weighted_reduce_kernel, dim3((unsigned)blocks), dim3(256), 0, st, grads, stride, P, seg.K,
+                     lambdas_of(seg), gout);
 }
 
 void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v) {

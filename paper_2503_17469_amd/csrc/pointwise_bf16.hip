@@ -16,7 +16,8 @@ namespace {
 // layer is pure launch latency (4 x 4.6 us at the three-layer CNN).  The table travels in the
 // kernel arguments.
 __global__ __launch_bounds__(256) void cast_weights_kernel(CastTable tab, const float* __restrict__ params,
-                                                           bf16_t* __restrict__ shadow) {
+                                                           bf16_t* __restrict__ shadow, uint32_t* __restrict__ zero_page) {
+  if (zero_page && blockIdx.x == 0 && threadIdx.x < kZeroPageWords) zero_page[threadIdx.x] = 0u;
   int e = 0;
   while (e + 1 < tab.n && (int)blockIdx.x >= tab.e[e + 1].first_block) ++e;
   const CastEntry t = tab.e[e];
@@ -142,7 +143,8 @@ inline unsigned blocks_for(long n) { return (unsigned)((n + 255) / 256); }
 
 }  // namespace
 
-void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, const CastEntry* entries, int n) {
+void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, const CastEntry* entries, int n,
+                       uint32_t* zero_page) {
   for (int base = 0; base < n; base += kCastMaxEntries) {
     CastTable tab{};
     tab.n = std::min(n - base, kCastMaxEntries);
@@ -152,7 +154,9 @@ void cast_weights_bf16(hipStream_t st, const float* params, bf16_t* shadow, cons
       tab.e[i].first_block = blocks;
       blocks += (int)blocks_for((long)tab.e[i].cout * tab.e[i].taps * tab.e[i].cin_pad);
     }
-    if (blocks > 0) hipLaunchKernelGGL(cast_weights_kernel, dim3(blocks), dim3(256), 0, st, tab, params, shadow);
+    if (blocks > 0)
+      hipLaunchKernelGGL(cast_weights_kernel, dim3(blocks), dim3(256), 0, st, tab, params, shadow,
+                         base == 0 ? zero_page : nullptr);
   }
 }
 

@@ -11,7 +11,7 @@ The synthetic tensors stand in for the image datasets used in the paper's
 evaluation (section "Implementation and Cluster Setup"); only shapes and value
 distributions matter for one training step.
 """
-from .nets import mlp, cnn3, resnet18, param_count, param_slices, LayerList
+from .nets import mlp, cnn3, resnet18, param_count, param_slices, layer_shapes, LayerList
 from .data import (
     Workload,
     he_normal_params,
@@ -24,7 +24,7 @@ from .data import (
 )
 
 __all__ = [
-    "mlp", "cnn3", "resnet18", "param_count", "param_slices", "LayerList",
+    "mlp", "cnn3", "resnet18", "param_count", "param_slices", "layer_shapes", "LayerList",
     "Workload", "he_normal_params", "make_batch", "random_throughputs",
     "throughput_walk", "to_bf16_grid", "workload", "CONFIG_NAMES",
 ]

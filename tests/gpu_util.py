@@ -32,11 +32,10 @@ def param_tensor_slices(layers):
     return out
 
 
-def unstored_layers(layers):
-    """Layers whose output the library does not keep under their own index: a layer whose ReLU was
-    folded into it (compared at the ReLU layer), and a batch norm whose only consumer is the residual
-    add right after it (normalisation and add are one kernel: compared at the add)."""
-    out = {L["src"] for L in layers if L["op"] == "relu"}
+def fused_bn_layers(layers):
+    """Batch norms whose only consumer is the residual add right after them: normalisation and add are
+    one kernel, and the normalised tensor is never stored."""
+    out = set()
     for li, L in enumerate(layers[:-1]):
         nxt = layers[li + 1]
         if L["op"] == "bn" and nxt["op"] == "add" and (nxt["src"] == li) != (nxt.get("src2") == li):
@@ -44,6 +43,31 @@ def unstored_layers(layers):
             if users == 1:
                 out.add(li)
     return out
+
+
+def unstored_layers(layers):
+    """Layers whose output the library does not keep under their own index: a layer whose ReLU was
+    folded into it (compared at the ReLU layer), and a batch norm fused into the add after it
+    (compared at the add)."""
+    return {L["src"] for L in layers if L["op"] == "relu"} | fused_bn_layers(layers)
+
+
+class OraclePool:
+    """`with OraclePool() as pmap:` gives a map for `oracle.step.sgd_step(..., pmap=pmap)` that runs the
+    workers' passes on a thread pool (numpy releases the interpreter lock), one BLAS thread each."""
+
+    def __init__(self, threads=16):
+        from concurrent.futures import ThreadPoolExecutor
+        from threadpoolctl import threadpool_limits
+        self.ex, self.limits = ThreadPoolExecutor(threads), threadpool_limits(limits=1)
+
+    def __enter__(self):
+        return self.ex.map
+
+    def __exit__(self, *exc):
+        self.ex.shutdown()
+        self.limits.restore_original_limits()
+        return False
 
 
 class GpuRun:
@@ -64,7 +88,7 @@ class GpuRun:
     def close(self):
         self.omni.net_destroy(self.net)
 
-    def step(self, params_np, x_np, labels_np, off, lr, flags=0):
+    def step(self, params_np, x_np, labels_np, off, lr, flags=0, keep_g=True):
         torch = self.torch
         B = off[-1]
         b = [off[k + 1] - off[k] for k in range(len(off) - 1)]
@@ -73,10 +97,13 @@ class GpuRun:
         if self.dtype == "bf16":
             x = x.to(torch.bfloat16)          # exact: the generator put x on the bf16 grid
         labels = torch.from_numpy(np.ascontiguousarray(labels_np[:B], dtype=np.int32)).cuda()
+        if keep_g:
+            flags |= self.omni.STEP_KEEP_REDUCED_GRAD
         self.omni.step(self.net, params, x, labels, off, b, lr, self.ws, self.lpw, self.loss, flags)
         torch.cuda.synchronize()
         K = len(b)
         return dict(
+            grad=self.omni.net_reduced_grad(self.net, self.ws).cpu().numpy() if keep_g else None,
             params=params.cpu().numpy(),
             loss=float(self.loss.item()),
             loss_per_worker=self.lpw[:K].cpu().numpy(),

@@ -96,6 +96,17 @@ def test_softmax_xent(C, off):
         assert abs(loss.item() - L) <= 1e-5 * abs(L)
     else:
         assert np.abs(dzd.cpu().numpy()).max() == 0 and abs(loss.item()) == 0
+    # the status word reports THIS call: a label out of range sets bit 0, and the next clean call clears it again
+    if C > 1 and B > 1:
+        bad = y.copy()
+        bad[B // 2] = C
+        omni.softmax_xent(zd, torch.from_numpy(bad).cuda(), off, dzd, rows, lpw, loss, status)
+        torch.cuda.synchronize()
+        assert status.item() & 1
+        omni.softmax_xent(zd, yd, off, dzd, rows, lpw, loss, status)
+        torch.cuda.synchronize()
+        assert status.item() == 0
+        assert_close(dzd.cpu().numpy(), dz, 1e-5, "dz after a call with a bad label")
 
 
 @pytest.mark.parametrize("P,K,mu,wd", [(9610, 2, 0.9, 5e-4), (4206602, 4, 0.9, 5e-4), (1027, 5, 0.5, 0.0),

@@ -27,7 +27,7 @@ def _torch_bf16(y):
     return y.detach().to(torch.float32).to(torch.bfloat16).to(torch.float64)
 
 
-def _torch_forward_stored(net, theta, x, segments):
+def _torch_forward_stored(net, theta, x, segments, retain=False):
     """_torch_forward with every layer output but the last replaced, as it is produced, by its
     bf16 rounding (straight-through: the rounding passes gradients unchanged)."""
     import torch.nn.functional as F
@@ -74,6 +74,8 @@ def _torch_forward_stored(net, theta, x, segments):
             y = a.mean(dim=(2, 3), keepdim=True)
         if li != len(net) - 1:
             y = y + (_torch_bf16(y) - y).detach()
+        if retain:
+            y.retain_grad()
         acts.append(y)
     return acts[-1].reshape(x.shape[0], -1), acts
 
