@@ -225,6 +225,24 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x,
               float lr, void* workspace, float* loss_per_worker, float* loss,
               uint32_t flags);
 
+/* omni_step for callers that cannot allocate device memory or have none to hand over as a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same step,
+ * same kernels, same results bit for bit; the workspace is a fixed array of
+ * OMNI_STATIC_WORKSPACE_BYTES inside the library's device image (each GPU the library runs on holds
+ * its own copy until the process ends) instead of an argument.  The call allocates nothing and
+ * creates nothing (no device memory, no stream, no event: a network that has not been stepped by
+ * omni_step before runs entirely on `stream`).  OMNI_ECAPACITY, with nothing launched, if
+ * omni_net_workspace_bytes(net) exceeds the array: in practice fp32 networks of a few layers at small
+ * batch sizes (a bf16 network's weight-gradient scratch alone is larger).  The other arguments and
+ * errors are omni_step's.  Every call on a GPU uses that GPU's one array: calls that overlap in time
+ * on the same GPU (different streams, different networks, different threads) race; serialise them.
+ * The per-worker gradients, activations and the status word stay inside the array and cannot be
+ * viewed; params, loss_per_worker and loss are the outputs. */
+#define OMNI_STATIC_WORKSPACE_BYTES (32u << 20)
+int omni_step_static(omni_net* net, void* stream, float* params, const void* x,
+                     const int32_t* labels, const int32_t* off, const int32_t* b, int32_t K,
+                     float lr, float* loss_per_worker, float* loss, uint32_t flags);
+
 /* Views into a workspace (device pointers; valid while the workspace is). */
 const float* omni_net_worker_grads(const omni_net* net, const void* workspace);
 const uint32_t* omni_net_status(const omni_net* net, const void* workspace);

@@ -26,7 +26,7 @@ EXPORTS = [
     "omni_ctl_create", "omni_ctl_set_throughputs", "omni_ctl_run", "omni_ctl_destroy",
     "omni_net_create", "omni_net_param_count", "omni_net_workspace_bytes", "omni_net_grad_stride",
     "omni_step", "omni_net_worker_grads", "omni_net_status", "omni_net_activation", "omni_net_destroy",
-    "omni_net_activation_grad", "omni_net_reduced_grad",
+    "omni_net_activation_grad", "omni_net_reduced_grad", "omni_step_static",
     "omni_weighted_sgd", "omni_softmax_xent", "omni_net_timing_enable", "omni_net_timing_read",
     "omni_net_timing_sample", "omni_net_graph_enable", "omni_net_graph_replays",
     "omni_weighted_sgd_momentum", "omni_net_set_momentum", "omni_lr_step_decay",
@@ -77,6 +77,7 @@ def _load():
     lib.omni_net_grad_stride.argtypes = [vp]
     lib.omni_net_grad_stride.restype = sz
     lib.omni_step.argtypes = [vp, vp, vp, vp, vp, P(i32), P(i32), i32, f32, vp, vp, vp, u32]
+    lib.omni_step_static.argtypes = [vp, vp, vp, vp, vp, P(i32), P(i32), i32, f32, vp, vp, u32]
     lib.omni_net_worker_grads.argtypes = [vp, vp]
     lib.omni_net_worker_grads.restype = vp
     lib.omni_net_status.argtypes = [vp, vp]
@@ -217,6 +218,16 @@ def step(net, params, x, labels, off, b, lr, workspace, loss_per_worker, loss, f
     _check(lib.omni_step(net, stream if stream is not None else _stream(), _ptr(params), _ptr(x), _ptr(labels),
                          _i32(off), _i32(b), K, float(lr), _ptr(workspace), _ptr(loss_per_worker), _ptr(loss),
                          flags))
+
+
+STATIC_WORKSPACE_BYTES = 32 << 20
+
+
+def step_static(net, params, x, labels, off, b, lr, loss_per_worker, loss, flags: int = 0, stream=None):
+    """omni_step on the library's own fixed workspace (nothing is allocated or created by the call)."""
+    K = len(b)
+    _check(lib.omni_step_static(net, stream if stream is not None else _stream(), _ptr(params), _ptr(x), _ptr(labels),
+                                _i32(off), _i32(b), K, float(lr), _ptr(loss_per_worker), _ptr(loss), flags))
 
 
 def net_worker_grads(net, workspace, K: int):

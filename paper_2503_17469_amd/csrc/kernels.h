@@ -207,4 +207,10 @@ void weighted_reduce_f32(hipStream_t st, const float* grads, size_t stride, size
                          float* gout);
 void fill_u32(hipStream_t st, uint32_t* p, size_t n, uint32_t v);
 
+// The body of omni_step (net.cpp).  may_create = false: nothing is created on the way, not even the
+// side streams of a network that has none yet (the step then runs on the caller's stream alone).
+int step_impl(omni_net* net, void* stream, float* params, const void* x, const int32_t* labels, const int32_t* off,
+              const int32_t* b, int32_t K, float lr, void* workspace, float* loss_per_worker, float* loss,
+              uint32_t flags, bool may_create);
+
 }  // namespace omni

@@ -446,6 +446,7 @@ struct StepCtx {
   // then waits only for what preceded the record, and the main stream's next kernel is not held up
   // by the host calls that set the side stream going.
   hipEvent_t fork_record() {
+    if (side == st && side2 == st) return nullptr;   // one stream only: nothing to order
     if (sync_used == net->sync_ev.size()) {
       hipEvent_t e;
       if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) return nullptr;
@@ -882,6 +883,16 @@ extern "C" {
 int omni_step(omni_net* net, void* stream, float* params, const void* x, const int32_t* labels,
               const int32_t* off, const int32_t* b, int32_t K, float lr, void* workspace,
               float* loss_per_worker, float* loss, uint32_t flags) {
+  return omni::step_impl(net, stream, params, x, labels, off, b, K, lr, workspace, loss_per_worker, loss, flags, true);
+}
+
+}  // extern "C"
+
+// may_create: the step may create the side streams it has not got yet (and with them, later, the events
+// that order them); without it a network that has none runs the whole step on the caller's stream.
+int omni::step_impl(omni_net* net, void* stream, float* params, const void* x, const int32_t* labels,
+                    const int32_t* off, const int32_t* b, int32_t K, float lr, void* workspace,
+                    float* loss_per_worker, float* loss, uint32_t flags, bool may_create) {
   if (!net || !params || !x || !labels || !off || !b || !workspace || !loss_per_worker || !loss)
     return fail(OMNI_EINVAL, "omni_step: NULL argument");
   if (K < 1) return fail(OMNI_EINVAL, "omni_step: K=%d", K);
@@ -960,8 +971,10 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
 
   net->ws_ready = workspace;   // (only tells the graph switch that this workspace has been stepped on before)
 
-  if (!net->side && hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess) net->side = nullptr;
-  if (!net->side2 && hipStreamCreateWithFlags(&net->side2, hipStreamNonBlocking) != hipSuccess) net->side2 = nullptr;
+  if (may_create) {
+    if (!net->side && hipStreamCreateWithFlags(&net->side, hipStreamNonBlocking) != hipSuccess) net->side = nullptr;
+    if (!net->side2 && hipStreamCreateWithFlags(&net->side2, hipStreamNonBlocking) != hipSuccess) net->side2 = nullptr;
+  }
   c.side = net->side ? net->side : c.st;
   c.side2 = (net->side && net->side2) ? net->side2 : c.side;
 
@@ -1000,6 +1013,8 @@ int omni_step(omni_net* net, void* stream, float* params, const void* x, const i
   if (e != hipSuccess) return fail(OMNI_EHIP, "omni_step: launch failed: %s", hipGetErrorString(e));
   return OMNI_OK;
 }
+
+extern "C" {
 
 int omni_net_graph_enable(omni_net* net, int32_t on) {
   if (!net) return fail(OMNI_EINVAL, "omni_net_graph_enable: NULL net");
