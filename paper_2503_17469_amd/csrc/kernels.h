@@ -128,6 +128,11 @@ bool conv_shape_supported(const ConvGeom& g, long positions);
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
                     bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr, const bf16_t* addend = nullptr);
+// The wide-tile kernel for 3x3 / stride 1 / pad 1 layers (conv3_wide_bf16.hip): same arguments and result as
+// conv_gemm_bf16 without pooling; false, with nothing launched, if the shape does not qualify.
+bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
+                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
+                     const bf16_t* addend);
 // (addend, [M][N] or null, is added to the product before the mask: the input gradient of a layer
 // whose input also feeds a residual add takes the add's share along instead of a separate pass.)
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).
