@@ -399,7 +399,7 @@ bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_
   }
   if (!ma) return false;
   const int units = nimg == 1 ? g.rows * (H / R) : (g.rows + nimg - 1) / nimg;
-  if ((long)units * tiles_n < 64) return false;   // too little work to fill the chip this way: the generic kernels spread it better
+  if ((long)units * tiles_n < 32) return false;   // too little work to fill the chip this way: the generic kernels spread it better
   const bool w8 = W == 8 && R % 8 == 0;
   const int need = (npatch * OC + kThreads - 1) / kThreads;   // patch pieces per thread
   WideParams p{};

@@ -133,6 +133,15 @@ bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t
 bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
                      const bf16_t* addend);
+// Input gradient of a residual block's entry (conv3s2_dgrad_bf16.hip): dx [rows][H][W][Cin] receives the gradient
+// coming back through a 3x3 / stride-2 / pad-1 convolution (dy [rows][H/2][W/2][Cout], wt its transposed weights
+// [Cin][9][Cout]) and, if dy_sc is not null, through the 1x1 / stride-2 projection beside it (dy_sc
+// [rows][H/2][W/2][Cout_sc], wt_sc [Cin][Cout_sc]) in one pass; mask / accumulate / addend as conv_gemm_bf16.
+// False, with nothing launched, for shapes it does not take (conv3s2_dgrad_supported tells beforehand).
+bool conv3s2_dgrad_supported(int rows, int H, int W, int Cin, int Cout, int Cout_sc);
+bool conv3s2_dgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* wt, int Cout, const bf16_t* dy_sc,
+                        const bf16_t* wt_sc, int Cout_sc, bf16_t* dx, int rows, int H, int W, int Cin,
+                        const bf16_t* mask, bool accumulate, const bf16_t* addend, const void* zero);
 // (addend, [M][N] or null, is added to the product before the mask: the input gradient of a layer
 // whose input also feeds a residual add takes the add's share along instead of a separate pass.)
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).

@@ -778,6 +778,24 @@ void step_bf16(StepCtx& c) {
   std::vector<const bf16_t*> pending_add(net->tensors.size(), nullptr);
   float* conv_partial2 = reinterpret_cast<float*>(c.ws + net->conv_partial2_off);
   bool second = false;   // which side stream (and scratch) takes the next weight gradient
+  // The entry of a residual block: its input feeds a 3x3 / stride-2 convolution and the 1x1 / stride-2
+  // projection of the shortcut, and nothing else.  The projection comes first in this backward walk: its
+  // input gradient is not launched on its own but handed to the 3x3 convolution's, whose kernel writes
+  // both contributions in one pass.  partner[m] = the projection layer whose gradient conv m takes along.
+  std::vector<int> partner(n_layers, -1);
+  auto entry_partner = [&](int sc) {   // the 3x3 / stride-2 convolution beside projection layer sc, or -1
+    const Layer& S = net->layers[sc];
+    if (S.d.op != OMNI_OP_CONV || S.d.ksize != 1 || S.d.stride != 2 || S.d.pad != 0 || S.in0 < 0) return -1;
+    if (net->tensors[S.in0].consumers != 2 || written[S.in0] || pending_add[S.in0]) return -1;
+    for (int m = sc - 1; m >= 0; --m) {
+      const Layer& M = net->layers[m];
+      if (M.fused_away || M.d.op != OMNI_OP_CONV || M.in0 != S.in0) continue;
+      const bool shape = M.d.ksize == 3 && M.d.stride == 2 && M.d.pad == 1 && M.cin_pad == S.cin_pad &&
+                         net->tensors[M.out].h == net->tensors[S.out].h && net->tensors[M.out].w == net->tensors[S.out].w;
+      return shape && omni::conv3s2_dgrad_supported(rows, M.ih, M.iw, M.cin_pad, M.d.cout, S.d.cout) ? m : -1;
+    }
+    return -1;
+  };
   for (int i = n_layers - 2; i >= 0; --i) {
     const Layer& L = net->layers[i];
     if (L.fused_away) continue;
@@ -790,7 +808,23 @@ void step_bf16(StepCtx& c) {
       // input gradient goes to the main stream, and only then are the side stream's wait and
       // launches issued: the main chain (the longer one) never waits for those host calls.
       hipEvent_t ready = c.fork_record();
-      if (L.in0 >= 0) {
+      const int takes_me = conv && L.in0 >= 0 ? entry_partner(i) : -1;
+      if (takes_me >= 0) partner[takes_me] = i;   // (this projection's input gradient rides with that convolution's)
+      bool dgrad_done = takes_me >= 0;
+      if (L.in0 >= 0 && !dgrad_done && conv && L.d.ksize == 3 && L.d.stride == 2 && L.d.pad == 1) {
+        // a stride-2 3x3 convolution: the one-pass kernel, with the shortcut's projection if it waits for it
+        TimedScope ts(net, st, OMNI_KERNEL_CONV_DGRAD, i);
+        const Tensor& ti = net->tensors[L.in0];
+        const int sc = partner[i];
+        const bf16_t* addend = pending_add[L.in0];
+        dgrad_done = omni::conv3s2_dgrad_bf16(
+            st, grad(L.out), shadow + L.wt_off, L.d.cout, sc >= 0 ? grad(net->layers[sc].out) : nullptr,
+            sc >= 0 ? shadow + net->layers[sc].wt_off : nullptr, sc >= 0 ? net->layers[sc].d.cout : 0, grad(L.in0), rows,
+            L.ih, L.iw, L.cin_pad, ti.relu ? act(L.in0) : nullptr, written[L.in0] != 0, addend, conv_counters);
+        if (dgrad_done) { pending_add[L.in0] = nullptr; written[L.in0] = 1; }
+        // (entry_partner asked conv3s2_dgrad_supported with these very shapes: a projection is never left behind)
+      }
+      if (L.in0 >= 0 && !dgrad_done) {
         TimedScope ts(net, st, conv ? OMNI_KERNEL_CONV_DGRAD : OMNI_KERNEL_LINEAR_DGRAD, i);
         omni::ConvGeom d = g;
         d.Hs = to.h; d.Ws = to.w; d.Cs = L.d.cout;      // gather from dY
