@@ -20,6 +20,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <type_traits>
 
 #include "bf16.h"
 #include "common.h"
@@ -111,7 +112,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
   const bf16_t* const wfrag = sW + j * kRow + h * 8;
 
   const bf16_t* const zp = static_cast<const bf16_t*>(p.zero);
-  u32x4 rp[NPP], rw[9];
+  // Two staging sets: a slice is requested TWO slices before it is needed (a slice is at most 36 matrix instructions
+  // per wavefront, about half a microsecond: one slice of distance left every slice waiting for memory).
+  u32x4 rp[2][NPP], rw[2][9];
   auto unit_geom = [&](int unit, int& n0, int& r0, int& nvalid) {
     if (p.nimg == 1) {
       const int upi = H / R, img = unit / upi;
@@ -121,7 +124,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
     }
   };
   // slice s of `unit`: s < nslice: 32 channels of dy with all nine taps' weights; else of dys with its one slab
-  auto load_slice = [&](int unit, int s) {
+  auto load_slice = [&](int set, int unit, int s) {
     const bool main = s < nslice;
     const bf16_t* src = main ? p.dy : p.dys;
     const int cs_total = main ? p.Cs : p.Cs2;
@@ -130,7 +133,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
                               : p.wts + ((long)(col0 + wrow) * p.Cs2 + c0 + poct * 8);
 #pragma unroll
     for (int t = 0; t < 9; ++t)
-      rw[t] = *reinterpret_cast<const u32x4*>((wvalid && (main || t == 0)) ? wsrc + (main ? t * p.Cs : 0) : zp);
+      rw[set][t] = *reinterpret_cast<const u32x4*>((wvalid && (main || t == 0)) ? wsrc + (main ? t * p.Cs : 0) : zp);
     int n0, r0, nvalid;
     unit_geom(unit, n0, r0, nvalid);
     const long ubase = ((long)n0 * H2 + (r0 >> 1)) * W2;
@@ -138,21 +141,29 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
     for (int t = 0; t < NPP; ++t) {
       const int il = (int)(img8 >> (8 * t)) & 255, pr = (int)(prow8 >> (8 * t)) & 255;
       const bool in = ((pcol_ok >> t) & 1u) && il < nvalid && (r0 >> 1) + pr < H2;
-      rp[t] = *reinterpret_cast<const u32x4*>(in ? src + ((ubase + prel[t]) * cs_total + c0 + poct * 8) : zp);
+      rp[set][t] = *reinterpret_cast<const u32x4*>(in ? src + ((ubase + prel[t]) * cs_total + c0 + poct * 8) : zp);
     }
   };
-  auto store_slice = [&]() {
+  auto store_slice = [&](int set) {
 #pragma unroll
-    for (int t = 0; t < 9; ++t) *reinterpret_cast<u32x4*>(wdst + t * kTN * kRow) = rw[t];
+    for (int t = 0; t < 9; ++t) *reinterpret_cast<u32x4*>(wdst + t * kTN * kRow) = rw[set][t];
 #pragma unroll
     for (int t = 0; t < NPP; ++t) {
       const int x = tid + t * kThreads;
-      if (x < npieces) *reinterpret_cast<u32x4*>(sP + (x / OC) * kRow + (x % OC) * 8) = rp[t];
+      if (x < npieces) *reinterpret_cast<u32x4*>(sP + (x / OC) * kRow + (x % OC) * 8) = rp[set][t];
     }
   };
+  // the slice `ahead` slices after (unit, s), running on into the next unit of this workgroup
+  auto load_ahead = [&](int set, int unit, int s, int ahead) {
+    int u = unit, t = s + ahead;
+    if (t >= nall) { t -= nall; u = min(unit + 1, uend - 1); }
+    load_slice(set, u, t);
+  };
 
-  load_slice(min(ubeg, p.units - 1), 0);
-  store_slice();
+  // (nall is even -- the launcher sees to it -- so slice s of every unit lives in set s & 1)
+  load_slice(0, min(ubeg, p.units - 1), 0);
+  store_slice(0);
+  load_ahead(1, min(ubeg, p.units - 1), 0, 1);
   __syncthreads();
 
   for (int unit = ubeg; unit < uend; ++unit) {
@@ -169,9 +180,9 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
-    for (int s = 0; s < nall; ++s) {
-      const bool last = s + 1 == nall;
-      load_slice(last ? min(unit + 1, uend - 1) : unit, last ? 0 : s + 1);
+    auto slice = [&](int s, auto set_tag) {
+      constexpr int SET = decltype(set_tag)::value;
+      load_ahead(SET, unit, s, 2);   // (set SET held this slice until the end of the slice before: free now)
       if (s < nslice) {
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
@@ -205,8 +216,12 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
         }
       }
       __syncthreads();
-      store_slice();
+      store_slice(SET ^ 1);   // the next slice, requested a slice ago
       __syncthreads();
+    };
+    for (int s = 0; s < nall; s += 2) {
+      slice(s, std::integral_constant<int, 0>{});
+      slice(s + 1, std::integral_constant<int, 1>{});
     }
 
     // ---- epilogue, straight from registers (see conv3_wide_bf16.hip): after the swap of the wavefront's halves
@@ -269,6 +284,7 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
 
 bool conv3s2_dgrad_supported(int rows, int H, int W, int Cin, int Cout, int Cout_sc) {
   if (H % 2 || W % 2 || Cin % 8 != 0 || Cin <= 32 || Cout % KC != 0 || Cout_sc % KC != 0) return false;
+  if ((Cout / KC + Cout_sc / KC) % 2 != 0) return false;   // (slices alternate between two staging sets)
   if ((long)rows * H * W * std::max(Cin, std::max(Cout, Cout_sc)) >= (1L << 31)) return false;   // 32-bit element offsets
   if (W < 4 || W > kUnit || kUnit % W != 0) return false;
   const int R = std::min(H, kUnit / W);
