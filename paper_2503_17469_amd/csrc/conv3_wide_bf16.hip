@@ -192,8 +192,10 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
         for (int v = 0; v < 16; ++v) acc[a][b][v] = 0.f;
 
     // epilogue operands of the input gradient (mask; addend or the old output), one 16-byte piece per (b, half)
-    // of a block row a: two sets, the first fetched during the last taps, the others one block row ahead
-    constexpr int ESETS = MA == 4 ? 2 : 1;   // (at 256 registers per lane there is room for one set: the other workgroup covers the wait)
+    // of a block row a, in two sets.  MA = 4: the first set is fetched during the last taps, the others one
+    // block row ahead.  MA = 2 (256 registers per lane): a set that is live inside the tap loop spills, so both
+    // block rows are fetched when the loop has ended and the other workgroup's matrix instructions cover the wait.
+    constexpr int ESETS = 2;
     u32x4 em[ESETS][BWD ? 4 : 1], ea[ESETS][BWD ? 4 : 1];
     auto load_epi = [&](int a, int set) {
 #pragma unroll
@@ -227,7 +229,7 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
         const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRow;
         const int un = (tap + 1) / 3, vn = (tap + 1) - un * 3;
         const int toff_next = (p.flip ? (2 - un) * PW + (2 - vn) : un * PW + vn) * kRow;
-        if (BWD && tap == 6 && last_slice) load_epi(0, 0);
+        if (BWD && MA == 4 && tap == 6 && last_slice) load_epi(0, 0);
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           const int step = tap * KK + kk;
@@ -276,8 +278,8 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
     // ---- epilogue, straight from registers.  Register v of block (a, b) in lane (j, h) is channel
     // b*32 + 8 (v/4) + 4 h + v%4 of position ipos[a].  Swapping registers v and v + 4 between the
     // wavefront's halves leaves lane (j, 0) with channels 0-7 (and 16-23), lane (j, 1) with 8-15 (24-31).
-    float bias8[4][8];
-    if (p.bias) {
+    float bias8[BWD ? 1 : 4][8];
+    if (!BWD && p.bias) {
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
         const int c = min(col0 + (bq >> 1) * 32 + (bq & 1) * 16 + h * 8, p.N - 8);
@@ -286,11 +288,12 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
         for (int e = 0; e < 4; ++e) { bias8[bq][e] = b0[e]; bias8[bq][4 + e] = b1[e]; }
       }
     }
+    if (BWD && MA == 2) { load_epi(0, 0); load_epi(1, 1); }
 #pragma unroll
     for (int a = 0; a < MA; ++a) {
       const bool row_in = ipos[a] < npos;
       const size_t row = (size_t)(out_base + ipos[a]) * p.N;
-      if (BWD && ESETS == 2 && a + 1 < MA) load_epi(a + 1, (a + 1) & 1);
+      if (BWD && MA == 4 && a + 1 < MA) load_epi(a + 1, (a + 1) & 1);
       if (BWD && ESETS == 1 && a > 0) load_epi(a, 0);
 #pragma unroll
       for (int b = 0; b < 2; ++b)
@@ -306,11 +309,11 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
           }
           const int c = col0 + b * 32 + q * 16 + h * 8;
           if (!row_in || c >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
-          if (p.bias) {
+          if (!BWD && p.bias) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) val[e] += bias8[b * 2 + q][e];
+            for (int e = 0; e < 8; ++e) val[e] += bias8[BWD ? 0 : b * 2 + q][e];
           }
-          if (p.relu) {
+          if (!BWD && p.relu) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) val[e] = val[e] > 0.f ? val[e] : 0.f;
           }
@@ -341,7 +344,7 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
 template <int MA, int NP, bool W8>
 void launch_wide(hipStream_t st, const WideParams& p, dim3 grid, size_t lds, bool bwd) {
   static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
-  if constexpr (MA == 4) if (bwd) {
+  if (bwd) {
     if (lds > configured[1]) {
       (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_wide_kernel<MA, NP, W8, true>),
                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -383,13 +386,14 @@ bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_
   const int tiles_n = (N + kTN - 1) / kTN;
   // Units of 256 positions with two workgroups per compute unit where both fit LDS (one workgroup's loads,
   // stores and epilogue then run under the other's matrix instructions); units of 512 with one otherwise.
-  // (The input gradient's epilogue operands do not fit beside the rest in 256 registers: it takes the wide unit.)
+  // Two 256-register kernels also share a SIMD with the weight-gradient kernels of the side streams; a
+  // 512-register wavefront has its SIMD to itself, and the two chains then merely take turns.
   const bool bwd = mask || addend || accumulate;
+  if (bwd && (bias || relu)) return false;   // the input-gradient epilogue carries neither (32 registers it needs elsewhere)
   int ma = 0, R = 0, nimg = 0, npatch = 0;
   size_t lds = 0;
   for (int cand : {2, 4}) {
     int r, n;
-    if (cand == 2 && bwd) continue;
     if (!unit_shape(H, W, 128 * cand, r, n)) continue;
     const int np_ = n * (r + 2) * (W + 2);
     const size_t l = ((size_t)np_ + 9 * kTN) * kRow * sizeof(bf16_t);   // patch + the nine taps' weights of a slice
@@ -414,8 +418,8 @@ bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_
   const int groups = (units + upw - 1) / upw;
   const dim3 grid(((groups + 7) / 8) * 8 * tiles_n);   // whole rounds of 8 groups: see the kernel's index mapping
   if (ma == 2) {
-    if (w8 && need <= 7) launch_wide<2, 7, true>(st, p, grid, lds, false);
-    else if (!w8 && need <= 6) launch_wide<2, 6, false>(st, p, grid, lds, false);
+    if (w8 && need <= 7) launch_wide<2, 7, true>(st, p, grid, lds, bwd);
+    else if (!w8 && need <= 6) launch_wide<2, 6, false>(st, p, grid, lds, bwd);
     else return false;
   } else {
     if (w8 && need <= 13) launch_wide<4, 13, true>(st, p, grid, lds, bwd);
