@@ -34,9 +34,8 @@ __device__ inline int owner_of_row(const Segments& seg, int n) {
 }
 
 // Work is dealt to workgroups in proportion to the workers' sizes: worker k owns the
-// splits / chunks first[k] .. first[k+1]-1, each covering an equal share of ITS positions,
-// so ragged b_k do not leave most of the chip waiting for the largest worker.
-struct ShareTable { int32_t first[OMNI_MAX_WORKERS + 1]; };
+// splits / chunks first[k] .. first[k+1]-1 of a ShareTable, each covering an equal share of ITS
+// positions, so ragged b_k do not leave most of the chip waiting for the largest worker.
 
 __device__ inline int share_owner(const ShareTable& tb, int K, int id) {
   int lo = 0, hi = K - 1;
@@ -379,11 +378,12 @@ bool bn_shape_supported(int C) { return C % 8 == 0 && C >= 8 && C <= 2048; }
 
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
                      const Segments& seg, bool relu, float* stats, double* partial, const bf16_t* skip,
-                     bool relu_add) {
-  const ShareTable sp = bn_splits(seg, C);
+                     bool relu_add, const ShareTable* presummed) {
+  const ShareTable sp = presummed ? *presummed : bn_splits(seg, C);
   const int groups = (C + 63) / 64;
-  hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(sp.first[seg.K], groups), dim3(256), 0, st, x, nullptr, nullptr,
-                     C, hw, seg, sp, partial);
+  if (!presummed)
+    hipLaunchKernelGGL(bn_partial_kernel<false>, dim3(sp.first[seg.K], groups), dim3(256), 0, st, x, nullptr,
+                       nullptr, C, hw, seg, sp, partial);
   hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3(seg.K, groups), dim3(256), 0, st, partial, C, hw, seg, sp, stats);
   const ShareTable ch = bn_chunks(seg, C, hw);
   hipLaunchKernelGGL(bn_apply_kernel<false>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, nullptr, stats, nullptr,

@@ -59,6 +59,13 @@ struct WideParams {
   const bf16_t* mask;     // [rows*H*W][N] or null: the value passes where mask > 0
   const bf16_t* addend;   // [rows*H*W][N] or null: added to the product before the mask
   int relu, accumulate;
+  // Workgroup g (after the XCD mapping below) takes units of ONE entry of this table: entry k owns the units
+  // ufirst[k] .. ufirst[k+1]-1 and the groups gfirst[k] .. gfirst[k+1]-1 of upw units each.  One entry that
+  // spans everything, or one per worker when the layer's batch-norm sums are wanted (a group's sums then
+  // belong to one worker).
+  int gK;
+  int32_t gfirst[OMNI_MAX_WORKERS + 1], ufirst[OMNI_MAX_WORKERS + 1];
+  double* stat_partial;   // STATS: [group][N][2] sums of the stored output and of its squares
 };
 
 __device__ inline bf16x8 as_bf16x8(u32x4 v) { return __builtin_bit_cast(bf16x8, v); }
@@ -72,10 +79,30 @@ constexpr int OC = KC / 8;        // 16-byte pieces per patch position and per w
 constexpr int KK = KC / 16;       // reduction steps per tap
 static_assert(kTN * OC == kThreads, "one weight piece per thread and tap");
 
+// One step of the statistics tree: the lane keeps half of its list (the upper half if bit DIST of its index
+// is set) and adds what its partner, DIST lanes away, holds of the same half.
+template <int DIST, int N, int LEN>
+__device__ inline void stat_exchange(float (&sv)[LEN], int j) {
+  if constexpr (LEN >= 2 * N) {
+    const bool upper = (j & DIST) != 0;
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const float keep = upper ? sv[N + i] : sv[i];
+      const float send = upper ? sv[i] : sv[N + i];
+      // ds_swizzle in bit-mask mode (groups of 32 lanes): the value comes from lane ^ DIST
+      const float recv = __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(send), (DIST << 10) | 0x1F));
+      sv[i] = keep + recv;
+    }
+  }
+}
+
 // MA: 32-position blocks per wavefront: 4 (a unit of 512 positions, one workgroup per compute unit) or 2 (256
 // positions, two workgroups per compute unit, whose load, store and compute phases overlap each other's).
-template <int MA, int NP, bool W8, bool BWD>
+// STATS (forward, MA = 2, no bias, no ReLU): the per-channel sums of the group's stored outputs and of their
+// squares go to p.stat_partial, the first pass of the batch norm that follows, without reading the tensor back.
+template <int MA, int NP, bool W8, bool BWD, bool STATS = false>
 __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(WideParams p) {
+  static_assert(!STATS || (MA == 2 && !BWD), "statistics come with the forward 256-position unit only");
   constexpr int WPOS = 32 * MA;   // positions per wavefront
   extern __shared__ __attribute__((aligned(16))) unsigned char smemW[];
   const int W = p.W, H = p.H, R = p.R;
@@ -93,10 +120,12 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
   const int on_xcd = blockIdx.x >> 3;
   const int tile_n = on_xcd % tiles_n;
   const int group = (on_xcd / tiles_n) * 8 + (blockIdx.x & 7);
-  if (group * p.upw >= p.units) return;   // (the grid is rounded up to whole rounds of 8 groups)
+  if (group >= p.gfirst[p.gK]) return;   // (the grid is rounded up to whole rounds of 8 groups)
+  int gk = 0;
+  while (gk + 1 < p.gK && group >= p.gfirst[gk + 1]) ++gk;
   const int col0 = tile_n * kTN;
   const int K = 9 * p.Cs;
-  const int ubeg = group * p.upw, uend = min(p.units, ubeg + p.upw);
+  const int ubeg = p.ufirst[gk] + (group - p.gfirst[gk]) * p.upw, uend = min(p.ufirst[gk + 1], ubeg + p.upw);
   const int nslice = p.Cs / KC;
 
   // ---- patch staging tasks: piece x = tid + 256 t -> patch position x / OC, channel octet x % OC
@@ -176,6 +205,8 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
   load_slice(min(ubeg, p.units - 1), 0);
   store_slice();
   __syncthreads();
+
+  double stat_sum[2] = {0.0, 0.0};   // STATS: this lane's two (channel, moment) pairs over the group's units, see below
 
   for (int unit = ubeg; unit < uend; ++unit) {
     int n0, r0, nvalid;
@@ -278,8 +309,9 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
     // ---- epilogue, straight from registers.  Register v of block (a, b) in lane (j, h) is channel
     // b*32 + 8 (v/4) + 4 h + v%4 of position ipos[a].  Swapping registers v and v + 4 between the
     // wavefront's halves leaves lane (j, 0) with channels 0-7 (and 16-23), lane (j, 1) with 8-15 (24-31).
-    float bias8[BWD ? 1 : 4][8];
-    if (!BWD && p.bias) {
+    constexpr bool AFFINE = !BWD && !STATS;   // bias and ReLU exist in the plain forward only
+    float bias8[AFFINE ? 4 : 1][8];
+    if (AFFINE && p.bias) {
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
         const int c = min(col0 + (bq >> 1) * 32 + (bq & 1) * 16 + h * 8, p.N - 8);
@@ -289,6 +321,13 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
       }
     }
     if (BWD && MA == 2) { load_epi(0, 0); load_epi(1, 1); }
+    // STATS: sv[which*32 + (b*2+q)*8 + e]: sums over this lane's positions of the stored values (which = 0) and
+    // of their squares (1)
+    float sv[STATS ? 64 : 1];
+    if (STATS) {
+#pragma unroll
+      for (int i = 0; i < 64; ++i) sv[STATS ? i : 0] = 0.f;
+    }
 #pragma unroll
     for (int a = 0; a < MA; ++a) {
       const bool row_in = ipos[a] < npos;
@@ -309,11 +348,11 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
           }
           const int c = col0 + b * 32 + q * 16 + h * 8;
           if (!row_in || c >= p.N) continue;   // N is a multiple of 8: a piece is wholly inside or outside
-          if (!BWD && p.bias) {
+          if (AFFINE && p.bias) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) val[e] += bias8[BWD ? 0 : b * 2 + q][e];
+            for (int e = 0; e < 8; ++e) val[e] += bias8[AFFINE ? b * 2 + q : 0][e];
           }
-          if (!BWD && p.relu) {
+          if (AFFINE && p.relu) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) val[e] = val[e] > 0.f ? val[e] : 0.f;
           }
@@ -335,32 +374,75 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
               for (int d = 0; d < 4; ++d) { val[2 * d] += bf16_lo(ad[d]); val[2 * d + 1] += bf16_hi(ad[d]); }
             }
           }
-          Piece<bf16_t>::store(p.out + row + c, val);
+          if (!STATS) {
+            Piece<bf16_t>::store(p.out + row + c, val);
+          } else {
+            u32x4 t;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) t[d] = pack_bf16(val[2 * d], val[2 * d + 1]);
+            *reinterpret_cast<u32x4*>(p.out + row + c) = t;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+              const float lo = bf16_lo(t[d]), hi = bf16_hi(t[d]);   // the values as stored
+              const int i = (b * 2 + q) * 8 + 2 * d;
+              sv[STATS ? i : 0] += lo;
+              sv[STATS ? i + 1 : 0] += hi;
+              sv[STATS ? 32 + i : 0] = fmaf(lo, lo, sv[STATS ? 32 + i : 0]);
+              sv[STATS ? 32 + i + 1 : 0] = fmaf(hi, hi, sv[STATS ? 32 + i + 1 : 0]);
+            }
+          }
         }
+    }
+    if (STATS) {
+      // The 32 lanes of a half hold 64 sums each over different positions.  Five exchange steps (lane distance
+      // 16, 8, 4, 2, 1): a lane keeps one half of its list and adds the partner's copy of that half, so the list
+      // halves while the positions covered double: a fixed tree, 62 additions instead of 320 for 64 separate
+      // reductions.  Lane j ends with entries 2 j' and 2 j' + 1, j' = its bits in the order they were used:
+      // which = bit 4 of j, b = bit 3, q = bit 2, e = 4 * bit 1 + 2 * bit 0 (+ 1 for the second entry).
+      stat_exchange<16, 32>(sv, j);
+      stat_exchange<8, 16>(sv, j);
+      stat_exchange<4, 8>(sv, j);
+      stat_exchange<2, 4>(sv, j);
+      stat_exchange<1, 2>(sv, j);
+      stat_sum[0] += (double)sv[0];
+      stat_sum[1] += (double)sv[STATS ? 1 : 0];
+    }
+  }
+  if (STATS) {
+    // the four wavefronts' sums meet in LDS (nobody reads patch or weights any more), added in wavefront order
+    double* red = reinterpret_cast<double*>(smemW);   // [4][2][64]
+    const int which = (j >> 4) & 1;
+    const int ch = ((j >> 3) & 1) * 32 + ((j >> 2) & 1) * 16 + h * 8 + ((j >> 1) & 1) * 4 + (j & 1) * 2;
+    red[(wave * 2 + which) * 64 + ch] = stat_sum[0];
+    red[(wave * 2 + which) * 64 + ch + 1] = stat_sum[1];
+    __syncthreads();
+    if (tid < 128) {
+      const int c = tid & 63, w = tid >> 6;
+      const double tot = ((red[(0 * 2 + w) * 64 + c] + red[(1 * 2 + w) * 64 + c]) + red[(2 * 2 + w) * 64 + c]) +
+                         red[(3 * 2 + w) * 64 + c];
+      if (col0 + c < p.N) p.stat_partial[((size_t)group * p.N + col0 + c) * 2 + w] = tot;
     }
   }
 }
 
+template <int MA, int NP, bool W8, bool BWD, bool STATS>
+void launch_variant(hipStream_t st, const WideParams& p, dim3 grid, size_t lds) {
+  static size_t configured = 0;   // raising the dynamic LDS limit is a per-function host call
+  const void* fn = reinterpret_cast<const void*>(&conv3_wide_kernel<MA, NP, W8, BWD, STATS>);
+  if (lds > configured) {
+    (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    configured = lds;
+  }
+  hipLaunchKernelGGL((conv3_wide_kernel<MA, NP, W8, BWD, STATS>), grid, dim3(kThreads), lds, st, p);
+}
+
 template <int MA, int NP, bool W8>
-void launch_wide(hipStream_t st, const WideParams& p, dim3 grid, size_t lds, bool bwd) {
-  static size_t configured[2] = {0, 0};   // raising the dynamic LDS limit is a per-function host call
-  if (bwd) {
-    if (lds > configured[1]) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_wide_kernel<MA, NP, W8, true>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      configured[1] = lds;
-    }
-    hipLaunchKernelGGL((conv3_wide_kernel<MA, NP, W8, true>), grid, dim3(kThreads), lds, st, p);
-    return;
+void launch_wide(hipStream_t st, const WideParams& p, dim3 grid, size_t lds, bool bwd, bool stats) {
+  if (bwd) return launch_variant<MA, NP, W8, true, false>(st, p, grid, lds);
+  if constexpr (MA == 2 && !W8) {
+    if (stats) return launch_variant<MA, NP, W8, false, true>(st, p, grid, lds);
   }
-  {
-    if (lds > configured[0]) {
-      (void)hipFuncSetAttribute(reinterpret_cast<const void*>(&conv3_wide_kernel<MA, NP, W8, false>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      configured[0] = lds;
-    }
-    hipLaunchKernelGGL((conv3_wide_kernel<MA, NP, W8, false>), grid, dim3(kThreads), lds, st, p);
-  }
+  launch_variant<MA, NP, W8, false, false>(st, p, grid, lds);
 }
 
 }  // namespace
@@ -378,7 +460,7 @@ bool unit_shape(int H, int W, int unit, int& R, int& nimg) {
 
 bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                     const bf16_t* addend) {
+                     const bf16_t* addend, BnStatRequest* stats) {
   const int H = g.Hs, W = g.Ws;
   if (g.raw3 || g.ks != 3 || g.stride != 1 || g.pad != 1 || g.Hp != H || g.Wp != W) return false;
   if (g.Cs % 32 != 0 || N % 8 != 0 || N <= 32 || (long)g.rows * H * W != M) return false;
@@ -414,18 +496,48 @@ bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_
   // the grid still covers the chip a few times over
   int upw = 1;
   while (upw < 8 && (long)units * tiles_n / (upw * 2) >= (ma == 2 ? 2048 : 1024)) upw *= 2;
+  // Batch-norm sums on the way out: units of one image (so a unit has one owner), no bias, no ReLU, and groups
+  // that do not cross from one worker to the next, few enough for the statistics scratch.
+  bool with_stats = false;
+  p.gK = 1;
+  p.ufirst[0] = 0; p.ufirst[1] = units;
+  if (stats && stats->partial && stats->seg && ma == 2 && nimg == 1 && !w8 && !bwd && !bias && !relu && N % kTN == 0 &&
+      stats->seg->off[stats->seg->K] == g.rows) {
+    const Segments& seg = *stats->seg;
+    const int upi = H / R;
+    int u = upw;
+    auto groups_at = [&](int per) {
+      long n = 0;
+      for (int k = 0; k < seg.K; ++k) n += ((long)(seg.off[k + 1] - seg.off[k]) * upi + per - 1) / per;
+      return n;
+    };
+    while (groups_at(u) > (long)seg.K * kBnMaxSplits && u < 64) u *= 2;
+    if (groups_at(u) <= (long)seg.K * kBnMaxSplits) {
+      with_stats = true;
+      upw = u;
+      p.gK = seg.K;
+      for (int k = 0; k <= seg.K; ++k) p.ufirst[k] = seg.off[k] * upi;
+      p.stat_partial = stats->partial;
+    }
+  }
   p.units = units; p.upw = upw;
-  const int groups = (units + upw - 1) / upw;
+  p.gfirst[0] = 0;
+  for (int k = 0; k < p.gK; ++k) p.gfirst[k + 1] = p.gfirst[k] + (p.ufirst[k + 1] - p.ufirst[k] + upw - 1) / upw;
+  const int groups = p.gfirst[p.gK];
   const dim3 grid(((groups + 7) / 8) * 8 * tiles_n);   // whole rounds of 8 groups: see the kernel's index mapping
   if (ma == 2) {
-    if (w8 && need <= 7) launch_wide<2, 7, true>(st, p, grid, lds, bwd);
-    else if (!w8 && need <= 6) launch_wide<2, 6, false>(st, p, grid, lds, bwd);
+    if (w8 && need <= 7) launch_wide<2, 7, true>(st, p, grid, lds, bwd, with_stats);
+    else if (!w8 && need <= 6) launch_wide<2, 6, false>(st, p, grid, lds, bwd, with_stats);
     else return false;
   } else {
-    if (w8 && need <= 13) launch_wide<4, 13, true>(st, p, grid, lds, bwd);
-    else if (!w8 && need <= 11) launch_wide<4, 11, false>(st, p, grid, lds, bwd);
-    else if (!w8 && need <= 18) launch_wide<4, 18, false>(st, p, grid, lds, bwd);
+    if (w8 && need <= 13) launch_wide<4, 13, true>(st, p, grid, lds, bwd, false);
+    else if (!w8 && need <= 11) launch_wide<4, 11, false>(st, p, grid, lds, bwd, false);
+    else if (!w8 && need <= 18) launch_wide<4, 18, false>(st, p, grid, lds, bwd, false);
     else return false;
+  }
+  if (with_stats) {
+    for (int k = 0; k <= p.gK; ++k) stats->table.first[k] = p.gfirst[k];
+    stats->done = true;
   }
   return true;
 }

@@ -2009,12 +2009,12 @@ static bool conv1_fwd(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16
 
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                    bf16_t* pool_out, uint8_t* pool_code, const bf16_t* addend) {
+                    bf16_t* pool_out, uint8_t* pool_code, const bf16_t* addend, BnStatRequest* stats) {
   bool pooled = false;
   // 3x3 / stride 1 / pad 1: the wide-tile kernel where the shape and the amount of work allow it (it has no
   // pooling epilogue), else the 256-position one
   if (!(pool_out && pool_code) &&
-      conv3_wide_bf16(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, addend))
+      conv3_wide_bf16(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, addend, stats))
     return false;
   if (conv3_gemm(st, src, wgt, out, M, N, g, bias, mask, relu, accumulate, pool_out, pool_code, &pooled, addend))
     return pooled;

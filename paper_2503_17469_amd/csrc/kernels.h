@@ -117,6 +117,20 @@ bool conv_first_layer_raw_supported(int Cout, int cin_real, const ConvGeom& g, l
 constexpr int kConvMaxPartialTiles = 2048;   // (tile, chunk) slots of wgrad scratch
 constexpr int kZeroPageWords = 64;           // 256 bytes of zeros that loads of absent pieces are pointed at (16 are read);
                                              // cast_weights_bf16 clears them at the start of every step
+// Statistics of a per-worker batch norm are summed in two stages: partial records [record][C][2] (doubles: the
+// sum of the values and of their squares over some positions of ONE worker), then, per worker, the records
+// first[k] .. first[k+1]-1 in order.
+struct ShareTable { int32_t first[OMNI_MAX_WORKERS + 1]; };
+constexpr int kBnMaxSplits = 256;  // the statistics scratch holds K * kBnMaxSplits records in all
+// A forward convolution whose output a batch norm normalises may write the first stage itself, from the
+// values it stores, instead of the batch norm reading the tensor once more: the caller fills partial and seg;
+// the kernel that takes the offer sets done and fills table (bn_forward_bf16 then skips its own first stage).
+struct BnStatRequest {
+  double* partial;       // [K * kBnMaxSplits][C][2]
+  const Segments* seg;
+  ShareTable table;
+  bool done;
+};
 size_t conv_wgrad_partial_floats();
 bool conv_shape_supported(const ConvGeom& g, long positions);
 // out[M][N] = gather(src)[M][K] * wgt[N][K]^T (+bias) (ReLU) (masked where mask <= 0) (+= out)
@@ -125,14 +139,16 @@ bool conv_shape_supported(const ConvGeom& g, long positions);
 // and, one byte per pooled element, which of the four inputs its gradient goes to (0-3 in scan
 // order, first maximum; 4: none, the ReLU folded into `out` zeroed it); the call then returns true.
 // False means `out` alone was written and the caller pools it itself.
+// stats (may be null): see BnStatRequest.
 bool conv_gemm_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                     const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                    bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr, const bf16_t* addend = nullptr);
+                    bf16_t* pool_out = nullptr, uint8_t* pool_code = nullptr, const bf16_t* addend = nullptr,
+                    BnStatRequest* stats = nullptr);
 // The wide-tile kernel for 3x3 / stride 1 / pad 1 layers (conv3_wide_bf16.hip): same arguments and result as
 // conv_gemm_bf16 without pooling; false, with nothing launched, if the shape does not qualify.
 bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_t* out, int M, int N,
                      const ConvGeom& g, const float* bias, const bf16_t* mask, bool relu, bool accumulate,
-                     const bf16_t* addend);
+                     const bf16_t* addend, BnStatRequest* stats = nullptr);
 // Input gradient of a residual block's entry (conv3s2_dgrad_bf16.hip): dx [rows][H][W][Cin] receives the gradient
 // coming back through a 3x3 / stride-2 / pad-1 convolution (dy [rows][H/2][W/2][Cout], wt its transposed weights
 // [Cin][9][Cout]) and, if dy_sc is not null, through the 1x1 / stride-2 projection beside it (dy_sc
@@ -185,15 +201,15 @@ void maxpool2_bwd_bf16(hipStream_t st, const bf16_t* in, const bf16_t* dout, bf1
                        int C, bool relu_mask);
 
 // ---- per-worker batch norm, residual add, global average pool (bn.hip) ----
-constexpr int kBnMaxSplits = 256;  // statistics scratch holds K * kBnMaxSplits position splits in all
 // stats: [K][C][2] (mean, 1/sqrt(var+eps)); partial: [K * kBnMaxSplits][C][2] doubles of scratch.
 // Channel counts the batch-norm kernels handle: a multiple of 8, at most 2048.
 bool bn_shape_supported(int C);
 // With skip: y = bn(x) (rounded as it would have been stored) + skip, then ReLU if relu_add: the residual
 // add that follows the normalisation, without writing and re-reading the normalised tensor.
+// presummed (may be null): the partial records are already in `partial`, laid out by this table.
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
                      const Segments& seg, bool relu, float* stats, double* partial, const bf16_t* skip = nullptr,
-                     bool relu_add = false);
+                     bool relu_add = false, const ShareTable* presummed = nullptr);
 // means: [K][C][2] scratch; g_gamma / g_beta: worker k's entries at + k*worker_stride.
 void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
                       const Segments& seg, const float* stats, float* means, double* partial, float* g_gamma,

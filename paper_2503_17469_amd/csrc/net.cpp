@@ -700,6 +700,8 @@ void step_bf16(StepCtx& c) {
   // ---- forward over the concatenated batch
   int pooled_layer = -1;   // a max pooling layer whose output the convolution before it has already written
   int added_layer = -1;    // a residual add that the batch norm before it has already done
+  int presummed_for = -1;  // a batch norm whose statistics' first pass the convolution before it has already done
+  omni::ShareTable presummed{};
   std::vector<char> coded(n_layers, 0);   // ... together with the codes its backward pass then reads
   for (int i = 0; i < n_layers - 1; ++i) {
     const Layer& L = net->layers[i];
@@ -713,12 +715,19 @@ void step_bf16(StepCtx& c) {
       while (nx < n_layers - 1 && net->layers[nx].fused_away) ++nx;
       const bool pool_next = L.d.op == OMNI_OP_CONV && nx < n_layers - 1 &&
                              net->layers[nx].d.op == OMNI_OP_MAXPOOL2 && net->layers[nx].in0 == L.out;
+      // ... or normalises it: the convolution is then offered the first pass of the statistics (the sums of
+      // what it stores), which the kernels that hold a worker-pure group of positions take
+      const bool bn_next = L.d.op == OMNI_OP_CONV && nx < n_layers - 1 && net->layers[nx].d.op == OMNI_OP_BN &&
+                           net->layers[nx].in0 == L.out && !to.relu && !L.has_b;
+      omni::BnStatRequest offer{bn_partial, &c.seg, {}, false};
       const bool pooled =
           omni::conv_gemm_bf16(st, act(L.in0), shadow + L.wsh_off, actw(L.out), rows * to.h * to.w, L.d.cout, g,
                                L.has_b ? c.params + L.b_off : nullptr, nullptr, to.relu, false,
                                pool_next ? actw(net->layers[nx].out) : nullptr,
-                               pool_next ? reinterpret_cast<uint8_t*>(c.ws + net->layers[nx].code_off) : nullptr);
+                               pool_next ? reinterpret_cast<uint8_t*>(c.ws + net->layers[nx].code_off) : nullptr,
+                               nullptr, bn_next ? &offer : nullptr);
       if (pooled) { pooled_layer = nx; coded[nx] = 1; }
+      if (bn_next && offer.done) { presummed = offer.table; presummed_for = nx; }
     } else if (L.d.op == OMNI_OP_MAXPOOL2) {
       if (i != pooled_layer) omni::maxpool2_fwd_bf16(st, act(L.in0), actw(L.out), rows, L.ih, L.iw, L.ic);
     } else if (L.d.op == OMNI_OP_BN) {
@@ -732,11 +741,13 @@ void step_bf16(StepCtx& c) {
       if (add_next) {
         const int other = A.in0 == L.out ? A.in1 : A.in0;
         omni::bn_forward_bf16(st, act(L.in0), actw(A.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
-                              c.seg, false, bn_area + L.stat_off, bn_partial, act(other), net->tensors[A.out].relu);
+                              c.seg, false, bn_area + L.stat_off, bn_partial, act(other), net->tensors[A.out].relu,
+                              i == presummed_for ? &presummed : nullptr);
         added_layer = nx;
       } else {
         omni::bn_forward_bf16(st, act(L.in0), actw(L.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
-                              c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial);
+                              c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial, nullptr, false,
+                              i == presummed_for ? &presummed : nullptr);
       }
     } else if (L.d.op == OMNI_OP_ADD) {
       if (i != added_layer)
