@@ -1452,6 +1452,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_kernel(Wgrad3Params p
           acc[du * 3 + 1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(mid), acc[du * 3 + 1], 0, 0, 0);
           acc[du * 3 + 2] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa, as_bf16x8(right), acc[du * 3 + 2], 0, 0, 0);
         }
+        // (keeps the next steps' patch rows from being read ahead of their turn: with them all in flight the
+        // 256 registers overflowed into scratch memory)
+        __builtin_amdgcn_sched_barrier(0);
       } else if constexpr (WM == 32) {
         // a map row is two reduction steps: windows A | B (this step) and C | D (the next), A and C
         // in the lower half of the wavefront, B and D in the upper
