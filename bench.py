@@ -55,6 +55,33 @@ def class_flops(w, cls):
     return sum(layer_flops(w.layers, w.in_shape, i, w.B) for i in idx), idx
 
 
+def step_tensor_bytes(w):
+    """Bytes of activation and gradient tensors one step has to move if every layer reads its operands and
+    writes its result exactly once (nothing fused, nothing re-read): a convolution or fully connected layer
+    reads its input and writes its output (forward), reads dY and writes dX (input gradient, where one is
+    needed), reads dY and X (weight gradient); a batch norm reads its input twice and writes once (forward)
+    and reads x and dy and writes dx (backward); pooling and residual adds read and write once each way;
+    plus the update's (K + 2) * 4 * P.  ReLUs are folded into their producers."""
+    import numpy as np
+
+    import synth.nets as nets
+    el = 2 if w.dtype == "bf16" else 4
+    shapes = nets.layer_shapes(w.layers, w.in_shape)
+    size = lambda i: float(np.prod(w.in_shape if i < 0 else shapes[i]))
+    total = 0.0
+    for i, L in enumerate(w.layers):
+        a, o = size(L["src"]), size(i)
+        if L["op"] in ("conv", "linear"):
+            total += (a + o) + (a + o) + ((a + o) if L["src"] >= 0 else 0.0)
+        elif L["op"] == "bn":
+            total += 3 * o + 3 * o
+        elif L["op"] == "add":
+            total += 3 * o + 3 * o
+        elif L["op"] in ("maxpool2", "gap"):
+            total += (a + o) + (a + o)
+    return total * el * w.B + (w.K + 2) * 4.0 * w.P
+
+
 def cpu_baseline(w, rows, budget_s=12.0):
     """The CPU oracle timed on the host cores on a sub-batch of the same workload: `rows` rows split
     over the same K workers in the same proportions (the controller run on the same throughputs).
@@ -428,6 +455,12 @@ def main():
         out["roofline_classes"] = roofs
         total_flop = sum(r["flop_per_step"] for r in roofs)
         out["step_mfma_frac"] = total_flop / (dev_ms / args.steps * 1e-3) / 1e12 / PEAK_TFLOPS[w.dtype]
+        nbytes = step_tensor_bytes(w)
+        out["step_hbm"] = {"bytes_per_step": nbytes, "achieved": nbytes / (dev_ms / args.steps * 1e-3) / 1e9,
+                           "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": nbytes / (dev_ms / args.steps * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                           "note": "every layer's operands read once and its result written once, per pass, "
+                                   "nothing fused: the unfused method's own traffic, not a counter reading"}
         n_upd = max(10, min(200, args.steps))
         out["roofline_update"] = job.update_roofline(n_upd)
         out["roofline_update_momentum"] = job.update_roofline(n_upd, momentum=True)
