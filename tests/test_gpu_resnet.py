@@ -287,6 +287,8 @@ def _check_many_workers(layers, in_shape, params, x, y, off, lr, tag):
     (512, 512, 1, 4, 6, 14, 16),   # 64 channel tiles x 16 workers: more (tile, worker) pairs than the weight-gradient
     (256, 256, 1, 8, 3, 7, 64),    # scratch has slots, so every worker must get exactly one chunk
     (64, 128, 2, 16, 2, 6, 64),
+    (64, 64, 1, 32, 1, 3, 24),     # workers of one to three images: the convolution's statistics groups end at every worker
+    (128, 128, 1, 16, 1, 4, 20),
 ])
 def test_block_many_workers(cin, cout, stride, hw, lo, hi, K):
     """Many small workers: batch norm over a handful of images each."""
