@@ -2206,6 +2206,7 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
   if (conv1_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial, dpool, pool_code)) return;
   if (dpool || g.raw3) return;   // (callers ask conv_wgrad_pooled_supported / conv_first_layer_raw_supported first)
   if (conv3_wgrad(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
+  if (g.stride == 2 && conv3_wgrad_tr_bf16(st, dy, src, gw, gb, worker_stride, Cout, cin_real, g, seg, partial)) return;
   WgradParams p{};
   p.dy = dy; p.src = src; p.gw = gw; p.gb = gb; p.worker_stride = worker_stride;
   p.Cout = Cout; p.cin_real = cin_real; p.g = g; p.partial = partial; p.counters = counters;

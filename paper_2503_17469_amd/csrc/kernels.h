@@ -170,6 +170,12 @@ void conv_wgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float*
                      float* partial, uint32_t* counters, const bf16_t* dpool = nullptr,
                      const uint8_t* pool_code = nullptr);
 bool conv_wgrad_pooled_supported(int Cout, int cin_real, const ConvGeom& g);
+// Weight gradient of a 3x3 / pad-1 convolution of stride 2 (or 1) without bias from operands left in their
+// [position][channel] layout (conv3_wgrad_tr_bf16.hip); arguments as conv_wgrad_bf16.  False, with nothing
+// launched, for shapes it does not take.
+bool conv3_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, float* gw, float* gb,
+                         size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
+                         float* partial);
 
 // ---- bf16 pointwise kernels (pointwise_bf16.hip) ----
 // fp32 weights [cout][taps][cin_real] -> bf16 [cout][taps][cin_pad] (zero padded) and,
