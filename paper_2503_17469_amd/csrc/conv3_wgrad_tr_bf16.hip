@@ -125,22 +125,18 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_tr_kernel(TrParams p,
   const int g = lane >> 4, s = lane & 15;
   const int chan = 16 * (g & 1) + 4 * (s & 3);
   const unsigned char* a_base = sA + (8 * (g >> 1) + (s >> 2)) * kSA + (wave * 32 + chan) * 2;
-  int xb[2];       // patch byte offset of this lane's position for read q at step 0 (tap (0, 0))
-  int kstep;       // ... added per reduction step
-  {
-#pragma unroll
-    for (int q = 0; q < 2; ++q) {
-      const int pos = 8 * (g >> 1) + 4 * q + (s >> 2);
-      const int il = pos / (R * Wo), rem = pos - il * (R * Wo);
-      const int r = rem / Wo, w = rem - r * Wo;
-      xb[q] = ((il * PR + S * r) * PW + S * w) * SX + chan * 2;
-    }
-    // positions 16 further on: Wo = 16 -> one row down; Wo = 8 -> two rows; Wo = 4 (units of whole images) -> one image
-    const int pos = 16;
+  // patch byte offset of a position of the unit (tap (0, 0))
+  auto patch_off = [&](int pos) {
     const int il = pos / (R * Wo), rem = pos - il * (R * Wo);
     const int r = rem / Wo, w = rem - r * Wo;
-    kstep = ((il * PR + S * r) * PW + S * w) * SX;
-  }
+    return ((il * PR + S * r) * PW + S * w) * SX;
+  };
+  // The sixteen positions of a reduction step start at a multiple of 16, which is the start of a map row or
+  // (maps 32 or more wide) the middle of one, and never reach into the next image: the offset of position
+  // 16 ks + i is that of 16 ks (the same for every lane: scalar arithmetic) plus that of i.
+  int xb[2];       // this lane's part, for read q
+#pragma unroll
+  for (int q = 0; q < 2; ++q) xb[q] = patch_off(8 * (g >> 1) + 4 * q + (s >> 2)) + chan * 2;
 
   v16f acc[9];
 #pragma unroll
@@ -198,8 +194,9 @@ __global__ __launch_bounds__(kThreads, 2) void conv3_wgrad_tr_kernel(TrParams p,
 #pragma unroll
     for (int ks = 0; ks < kUnit / 16; ++ks) {
       const bf16x8 fa = tr_pair(a_base + (16 * ks) * kSA, a_base + (16 * ks + 4) * kSA);
-      const unsigned char* x0 = sX + xb[0] + ks * kstep;
-      const unsigned char* x1 = sX + xb[1] + ks * kstep;
+      const int kofs = patch_off(16 * ks);
+      const unsigned char* x0 = sX + xb[0] + kofs;
+      const unsigned char* x1 = sX + xb[1] + kofs;
 #pragma unroll
       for (int tap = 0; tap < 9; ++tap) {
         const int toff = ((tap / 3) * PW + (tap % 3)) * SX;
@@ -279,13 +276,12 @@ bool conv3_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, fl
   const int S = g.stride, Ho = g.Hp, Wo = g.Wp, H = g.Hs, W = g.Ws;
   if (gb || g.ks != 3 || g.pad != 1 || g.transposed || g.raw3 || (S != 1 && S != 2)) return false;
   if (H != S * Ho || W != S * Wo || g.Cs % 8 != 0 || Cout % 8 != 0 || cin_real > g.Cs) return false;
-  // (sixteen positions further on must be the same step in the patch from everywhere: whole rows, and a
-  // unit that is part of one image or made of images of sixteen positions)
-  if (Wo < 4 || 16 % Wo != 0) return false;
+  // (a reduction step of sixteen positions must lie inside one map row or be made of whole rows of one image)
+  if (Wo < 4 || Wo > kUnit || (Wo % 16 != 0 && 16 % Wo != 0)) return false;
   const int R = std::min(Ho, kUnit / Wo);
-  if (Ho % R != 0 || kUnit % (R * Wo) != 0) return false;
+  if (Ho % R != 0 || kUnit % (R * Wo) != 0 || (R * Wo) % 16 != 0) return false;
   const int nimg = kUnit / (R * Wo);
-  if (nimg != 1 && !(nimg == 4 && R == Ho)) return false;
+  if ((nimg > 1 && R != Ho) || nimg > 15) return false;
   const int PR = S * (R - 1) + 3, PW = S * (Wo - 1) + 3;
   const int npatch = nimg * PR * PW;
   if (npatch * 4 > kNX * kThreads) return false;
