@@ -1,4 +1,4 @@
-// Weight gradient of 3x3 / pad-1 convolutions of stride 2 (and 1) in bf16 with fp32 accumulation, per worker
+// Weight gradient of 3x3 / pad-1 convolutions of stride 2 in bf16 with fp32 accumulation, per worker
 // (the gradient line of procedure Train, Algorithm 1, for one layer's filter bank):
 //
 //   G_k[co][u][v][ci] = sum over the output positions (n, h, w) of worker k of
@@ -274,7 +274,9 @@ bool conv3_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, fl
                          size_t worker_stride, int Cout, int cin_real, const ConvGeom& g, const Segments& seg,
                          float* partial) {
   const int S = g.stride, Ho = g.Hp, Wo = g.Wp, H = g.Hs, W = g.Ws;
-  if (gb || g.ks != 3 || g.pad != 1 || g.transposed || g.raw3 || (S != 1 && S != 2)) return false;
+  // (the kernel is written for any stride; stride-1 layers are not sent here: the transposed-patch kernel of
+  // conv_bf16.hip measured faster on every map width, by 0.07 to 0.64 ms per ResNet-18 step)
+  if (gb || g.ks != 3 || g.pad != 1 || g.transposed || g.raw3 || S != 2) return false;
   if (H != S * Ho || W != S * Wo || g.Cs % 8 != 0 || Cout % 8 != 0 || cin_real > g.Cs) return false;
   // (a reduction step of sixteen positions must lie inside one map row or be made of whole rows of one image)
   if (Wo < 4 || Wo > kUnit || (Wo % 16 != 0 && 16 % Wo != 0)) return false;
@@ -316,10 +318,9 @@ bool conv3_wgrad_tr_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* src, fl
     upc += std::max<long>(1, upc / 16);
   }
   p.upc = (int)upc;
-  const size_t lds = (size_t)kUnit * kSA + (size_t)npatch * (S == 2 ? 80 : 96);
+  const size_t lds = (size_t)kUnit * kSA + (size_t)npatch * 80;   // (80 bytes per patch position at stride 2: see the kernel)
   const dim3 grid(tiles, ct.first[seg.K]);
-  if (S == 2) hipLaunchKernelGGL(conv3_wgrad_tr_kernel<2>, grid, dim3(kThreads), lds, st, p, seg, ct);
-  else hipLaunchKernelGGL(conv3_wgrad_tr_kernel<1>, grid, dim3(kThreads), lds, st, p, seg, ct);
+  hipLaunchKernelGGL(conv3_wgrad_tr_kernel<2>, grid, dim3(kThreads), lds, st, p, seg, ct);
   bool chunked = false;
   for (int k = 0; k < seg.K; ++k) chunked = chunked || ct.first[k + 1] - ct.first[k] > 1;
   if (chunked)
