@@ -188,7 +188,7 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16_t* __restrict_
                                                        const float* __restrict__ gamma, const float* __restrict__ beta,
                                                        int C, int hw, Segments seg, ShareTable tb, int relu,
                                                        bf16_t* __restrict__ out, const bf16_t* __restrict__ skip,
-                                                       int relu_add) {
+                                                       int relu_add, uint8_t* __restrict__ sign_bits) {
   const int c8n = C / 8;
   const int ppar = 256 / c8n;                   // positions per trip
   const int tid = threadIdx.x;
@@ -244,7 +244,23 @@ __global__ __launch_bounds__(256) void bn_apply_kernel(const bf16_t* __restrict_
           o[e] = gm[e] * is[e] * (dv[u][e] - mn1[e] - xh * mn2[e]);
         }
       }
-      Piece<bf16_t>::store(out + q * C + c0, o);
+      if (!BWD && sign_bits) {
+        // (the piece is packed here rather than in Piece::store: the bits are those of the values as stored)
+        u32x4 t;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) t[d] = pack_bf16(o[2 * d], o[2 * d + 1]);
+        *reinterpret_cast<u32x4*>(out + q * C + c0) = t;
+        uint32_t bits = 0;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const uint32_t lo = t[d] & 0xFFFFu, hi = t[d] >> 16;
+          bits |= ((lo != 0u && lo < 0x8000u) ? 1u : 0u) << (2 * d);
+          bits |= ((hi != 0u && hi < 0x8000u) ? 1u : 0u) << (2 * d + 1);
+        }
+        sign_bits[q * c8n + pc] = (uint8_t)bits;
+      } else {
+        Piece<bf16_t>::store(out + q * C + c0, o);
+      }
     }
   }
 }
@@ -378,7 +394,7 @@ bool bn_shape_supported(int C) { return C % 8 == 0 && C >= 8 && C <= 2048; }
 
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
                      const Segments& seg, bool relu, float* stats, double* partial, const bf16_t* skip,
-                     bool relu_add, const ShareTable* presummed) {
+                     bool relu_add, const ShareTable* presummed, uint8_t* sign_bits) {
   const ShareTable sp = presummed ? *presummed : bn_splits(seg, C);
   const int groups = (C + 63) / 64;
   if (!presummed)
@@ -387,7 +403,7 @@ void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* ga
   hipLaunchKernelGGL(bn_finalize_fwd_kernel, dim3(seg.K, groups), dim3(256), 0, st, partial, C, hw, seg, sp, stats);
   const ShareTable ch = bn_chunks(seg, C, hw);
   hipLaunchKernelGGL(bn_apply_kernel<false>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, nullptr, stats, nullptr,
-                     gamma, beta, C, hw, seg, ch, relu ? 1 : 0, y, skip, relu_add ? 1 : 0);
+                     gamma, beta, C, hw, seg, ch, relu ? 1 : 0, y, skip, relu_add ? 1 : 0, sign_bits);
 }
 
 void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
@@ -401,7 +417,7 @@ void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t*
                      g_gamma, g_beta, worker_stride);
   const ShareTable ch = bn_chunks(seg, C, hw);
   hipLaunchKernelGGL(bn_apply_kernel<true>, dim3(ch.first[seg.K]), dim3(256), 0, st, x, dy, stats, means, gamma,
-                     nullptr, C, hw, seg, ch, 0, dx, nullptr, 0);
+                     nullptr, C, hw, seg, ch, 0, dx, nullptr, 0, nullptr);
 }
 
 void add_fwd_bf16(hipStream_t st, const bf16_t* a, const bf16_t* b, bf16_t* out, long elems, bool relu) {

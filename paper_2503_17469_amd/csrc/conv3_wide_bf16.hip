@@ -57,6 +57,7 @@ struct WideParams {
   const void* zero;    // zeros for absent pieces
   const float* bias;
   const bf16_t* mask;     // [rows*H*W][N] or null: the value passes where mask > 0
+  const uint8_t* mask_bits;   // BITS: [rows*H*W][N/8], the mask at one bit per element (N a multiple of 64)
   const bf16_t* addend;   // [rows*H*W][N] or null: added to the product before the mask
   int relu, accumulate;
   // Workgroup g (after the XCD mapping below) takes units of ONE entry of this table: entry k owns the units
@@ -100,9 +101,12 @@ __device__ inline void stat_exchange(float (&sv)[LEN], int j) {
 // positions, two workgroups per compute unit, whose load, store and compute phases overlap each other's).
 // STATS (forward, MA = 2, no bias, no ReLU): the per-channel sums of the group's stored outputs and of their
 // squares go to p.stat_partial, the first pass of the batch norm that follows, without reading the tensor back.
-template <int MA, int NP, bool W8, bool BWD, bool STATS = false>
+// BITS (input gradient): the ReLU mask is read as one bit per element, 8 bytes per position and channel tile
+// instead of 128.
+template <int MA, int NP, bool W8, bool BWD, bool STATS = false, bool BITS = false>
 __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(WideParams p) {
   static_assert(!STATS || (MA == 2 && !BWD), "statistics come with the forward 256-position unit only");
+  static_assert(!BITS || BWD, "mask bits belong to the input gradient");
   constexpr int WPOS = 32 * MA;   // positions per wavefront
   extern __shared__ __attribute__((aligned(16))) unsigned char smemW[];
   const int W = p.W, H = p.H, R = p.R;
@@ -227,8 +231,15 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
     // block row ahead.  MA = 2 (256 registers per lane): a set that is live inside the tap loop spills, so both
     // block rows are fetched when the loop has ended and the other workgroup's matrix instructions cover the wait.
     constexpr int ESETS = 2;
-    u32x4 em[ESETS][BWD ? 4 : 1], ea[ESETS][BWD ? 4 : 1];
+    u32x4 em[ESETS][BWD && !BITS ? 4 : 1], ea[ESETS][BWD ? 4 : 1];
+    u32x2 eb[ESETS];   // BITS: the mask bits of the tile's 64 channels at this lane's position (byte b*4 + q*2 + h: piece (b, q))
     auto load_epi = [&](int a, int set) {
+      if (BITS) {
+        const bool in = ipos[a] < npos;
+        eb[set] = *reinterpret_cast<const u32x2*>(
+            in ? p.mask_bits + ((size_t)(out_base + ipos[a]) * (p.N >> 3) + (col0 >> 3))
+               : static_cast<const uint8_t*>(p.zero));
+      }
 #pragma unroll
       for (int b = 0; b < 2; ++b)
 #pragma unroll
@@ -236,7 +247,7 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
           const int c = col0 + b * 32 + q * 16 + h * 8;
           const bool in = ipos[a] < npos && c < p.N;
           const size_t idx = (size_t)(out_base + ipos[a]) * p.N + c;
-          em[set][b * 2 + q] = *reinterpret_cast<const u32x4*>((in && p.mask) ? p.mask + idx : zp);
+          if (!BITS) em[set][b * 2 + q] = *reinterpret_cast<const u32x4*>((in && p.mask) ? p.mask + idx : zp);
           const bf16_t* other = p.addend ? p.addend : (p.accumulate ? p.out : nullptr);
           ea[set][b * 2 + q] = *reinterpret_cast<const u32x4*>((in && other) ? other + idx : zp);
         }
@@ -357,12 +368,16 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
             for (int e = 0; e < 8; ++e) val[e] = val[e] > 0.f ? val[e] : 0.f;
           }
           if (BWD) {
-            const u32x4 mk = em[a & (ESETS - 1)][b * 2 + q], ad = ea[a & (ESETS - 1)][b * 2 + q];
+            const u32x4 mk = em[a & (ESETS - 1)][BITS ? 0 : b * 2 + q], ad = ea[a & (ESETS - 1)][b * 2 + q];
             if (p.addend) {
 #pragma unroll
               for (int d = 0; d < 4; ++d) { val[2 * d] += bf16_lo(ad[d]); val[2 * d + 1] += bf16_hi(ad[d]); }
             }
-            if (p.mask) {
+            if (BITS) {
+              const uint32_t byte = eb[a & (ESETS - 1)][b] >> (8 * (2 * q + h));
+#pragma unroll
+              for (int e = 0; e < 8; ++e) val[e] = ((byte >> e) & 1u) ? val[e] : 0.f;
+            } else if (p.mask) {
 #pragma unroll
               for (int d = 0; d < 4; ++d) {
                 val[2 * d] = bf16_lo(mk[d]) > 0.f ? val[2 * d] : 0.f;
@@ -425,24 +440,27 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
   }
 }
 
-template <int MA, int NP, bool W8, bool BWD, bool STATS>
+template <int MA, int NP, bool W8, bool BWD, bool STATS, bool BITS>
 void launch_variant(hipStream_t st, const WideParams& p, dim3 grid, size_t lds) {
   static size_t configured = 0;   // raising the dynamic LDS limit is a per-function host call
-  const void* fn = reinterpret_cast<const void*>(&conv3_wide_kernel<MA, NP, W8, BWD, STATS>);
+  const void* fn = reinterpret_cast<const void*>(&conv3_wide_kernel<MA, NP, W8, BWD, STATS, BITS>);
   if (lds > configured) {
     (void)hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     configured = lds;
   }
-  hipLaunchKernelGGL((conv3_wide_kernel<MA, NP, W8, BWD, STATS>), grid, dim3(kThreads), lds, st, p);
+  hipLaunchKernelGGL((conv3_wide_kernel<MA, NP, W8, BWD, STATS, BITS>), grid, dim3(kThreads), lds, st, p);
 }
 
 template <int MA, int NP, bool W8>
 void launch_wide(hipStream_t st, const WideParams& p, dim3 grid, size_t lds, bool bwd, bool stats) {
-  if (bwd) return launch_variant<MA, NP, W8, true, false>(st, p, grid, lds);
-  if constexpr (MA == 2 && !W8) {
-    if (stats) return launch_variant<MA, NP, W8, false, true>(st, p, grid, lds);
+  if (bwd) {
+    if (p.mask_bits) return launch_variant<MA, NP, W8, true, false, true>(st, p, grid, lds);
+    return launch_variant<MA, NP, W8, true, false, false>(st, p, grid, lds);
   }
-  launch_variant<MA, NP, W8, false, false>(st, p, grid, lds);
+  if constexpr (MA == 2 && !W8) {
+    if (stats) return launch_variant<MA, NP, W8, false, true, false>(st, p, grid, lds);
+  }
+  launch_variant<MA, NP, W8, false, false, false>(st, p, grid, lds);
 }
 
 }  // namespace
@@ -492,6 +510,7 @@ bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_
   p.src = src; p.wgt = wgt; p.out = out; p.rows = g.rows; p.H = H; p.W = W; p.Cs = g.Cs; p.N = N;
   p.R = R; p.nimg = nimg; p.flip = g.transposed ? 1 : 0; p.zero = g.zero;
   p.bias = bias; p.mask = mask; p.addend = addend; p.relu = relu ? 1 : 0; p.accumulate = accumulate ? 1 : 0;
+  p.mask_bits = (bwd && mask && N % kTN == 0) ? g.mask_bits : nullptr;
   // several units per workgroup (the next unit's patch and weights travel under the current one's taps) while
   // the grid still covers the chip a few times over
   int upw = 1;

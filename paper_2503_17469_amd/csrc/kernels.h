@@ -110,6 +110,9 @@ struct ConvGeom {
   const void* zero;     // at least 16 bytes of zeros in device memory: where loads of absent pieces are pointed
   int raw3;             // 1: the source tensor holds 3 channels per pixel as given (6 bytes), not the Cs = 8 the
                         // kernels work on; only the first-layer kernels read it (conv_first_layer_raw_supported)
+  const uint8_t* mask_bits;   // may be null; with a mask [M][N], N a multiple of 64: the same information at one bit
+                              // per element ([M][N/8] bytes, bit e of byte c/8 set where mask[m][c - c%8 + e] > 0).
+                              // Kernels that know how read it instead of the mask (a sixteenth of the bytes).
 };
 // True if both the forward and the weight-gradient pass of a first layer with this shape can read a
 // 3-channel source as it is, so that no padded copy of the network input has to be made.
@@ -215,7 +218,9 @@ bool bn_shape_supported(int C);
 // presummed (may be null): the partial records are already in `partial`, laid out by this table.
 void bn_forward_bf16(hipStream_t st, const bf16_t* x, bf16_t* y, const float* gamma, const float* beta, int C, int hw,
                      const Segments& seg, bool relu, float* stats, double* partial, const bf16_t* skip = nullptr,
-                     bool relu_add = false, const ShareTable* presummed = nullptr);
+                     bool relu_add = false, const ShareTable* presummed = nullptr, uint8_t* sign_bits = nullptr);
+// (sign_bits, [positions][C/8] bytes or null: one bit per element of y, set where the stored value is positive:
+// what the input-gradient kernels need of a ReLU's output.)
 // means: [K][C][2] scratch; g_gamma / g_beta: worker k's entries at + k*worker_stride.
 void bn_backward_bf16(hipStream_t st, const bf16_t* x, const bf16_t* dy, bf16_t* dx, const float* gamma, int C, int hw,
                       const Segments& seg, const float* stats, float* means, double* partial, float* g_gamma,

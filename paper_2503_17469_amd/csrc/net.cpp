@@ -29,6 +29,7 @@ struct Tensor {
   size_t esize = 4;        // bytes per element of the stored activation and its gradient
   size_t act_off = 0;      // byte offsets into the workspace
   size_t grad_off = 0;
+  size_t bits_off = 0;     // bf16 tensors with a folded ReLU and a multiple of 64 channels: one bit per element (0: none)
   bool relu = false;       // ReLU folded into the producer; grad buffer is w.r.t. the pre-ReLU value
   int consumers = 0;
 };
@@ -327,6 +328,11 @@ int omni_net_create(const omni_layer_desc* descs, int32_t n, int32_t in_h, int32
   }
   for (Layer& L : net->layers)
     if (L.d.op == OMNI_OP_MAXPOOL2) L.code_off = take((size_t)B_max * net->tensors[L.out].elems);
+  // where a batch norm writes a tensor with a folded ReLU, it also leaves "stored value > 0" at one bit per
+  // element: all that the input-gradient kernels need of that tensor
+  if (bf && net->bn_floats)
+    for (Tensor& t : net->tensors)
+      if (t.relu && t.esize == 2 && t.c % 64 == 0) t.bits_off = take((size_t)B_max * t.elems / 8);
   net->ws_bytes = pos;
   net->grad_view.assign(net->tensors.size(), kNoGrad);
   *out = net;
@@ -700,6 +706,10 @@ void step_bf16(StepCtx& c) {
   // ---- forward over the concatenated batch
   int pooled_layer = -1;   // a max pooling layer whose output the convolution before it has already written
   int added_layer = -1;    // a residual add that the batch norm before it has already done
+  std::vector<char> bits_written(net->tensors.size(), 0);   // tensors whose sign bits this step's forward pass wrote
+  auto sign_bits = [&](int t) {
+    return net->tensors[t].bits_off ? reinterpret_cast<uint8_t*>(c.ws + net->tensors[t].bits_off) : nullptr;
+  };
   int presummed_for = -1;  // a batch norm whose statistics' first pass the convolution before it has already done
   omni::ShareTable presummed{};
   std::vector<char> coded(n_layers, 0);   // ... together with the codes its backward pass then reads
@@ -742,12 +752,16 @@ void step_bf16(StepCtx& c) {
         const int other = A.in0 == L.out ? A.in1 : A.in0;
         omni::bn_forward_bf16(st, act(L.in0), actw(A.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
                               c.seg, false, bn_area + L.stat_off, bn_partial, act(other), net->tensors[A.out].relu,
-                              i == presummed_for ? &presummed : nullptr);
+                              i == presummed_for ? &presummed : nullptr,
+                              net->tensors[A.out].relu ? sign_bits(A.out) : nullptr);
+        if (net->tensors[A.out].relu && sign_bits(A.out)) bits_written[A.out] = 1;
         added_layer = nx;
       } else {
         omni::bn_forward_bf16(st, act(L.in0), actw(L.out), c.params + L.w_off, c.params + L.b_off, L.ic, L.ih * L.iw,
                               c.seg, net->tensors[L.out].relu, bn_area + L.stat_off, bn_partial, nullptr, false,
-                              i == presummed_for ? &presummed : nullptr);
+                              i == presummed_for ? &presummed : nullptr,
+                              net->tensors[L.out].relu ? sign_bits(L.out) : nullptr);
+        if (net->tensors[L.out].relu && sign_bits(L.out)) bits_written[L.out] = 1;
       }
     } else if (L.d.op == OMNI_OP_ADD) {
       if (i != added_layer)
@@ -847,6 +861,7 @@ void step_bf16(StepCtx& c) {
         const int m_rows = conv ? rows * L.ih * L.iw : rows;
         const bf16_t* addend = pending_add[L.in0];
         pending_add[L.in0] = nullptr;
+        d.mask_bits = (ti.relu && bits_written[L.in0]) ? sign_bits(L.in0) : nullptr;
         omni::conv_gemm_bf16(st, grad(L.out), shadow + L.wt_off, grad(L.in0), m_rows, L.cin_pad, d, nullptr,
                              ti.relu ? act(L.in0) : nullptr, false, written[L.in0] != 0, nullptr, nullptr, addend);
         written[L.in0] = 1;
