@@ -228,8 +228,10 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
 
     // epilogue operands of the input gradient (mask; addend or the old output), one 16-byte piece per (b, half)
     // of a block row a, in two sets.  MA = 4: the first set is fetched during the last taps, the others one
-    // block row ahead.  MA = 2 (256 registers per lane): a set that is live inside the tap loop spills, so both
-    // block rows are fetched when the loop has ended and the other workgroup's matrix instructions cover the wait.
+    // block row ahead.  MA = 2 (256 registers per lane): a full set that is live inside the tap loop spills, so
+    // both block rows are fetched when the loop has ended and the other workgroup's matrix instructions cover the
+    // wait; with the mask as bits a set is 18 registers instead of 32 and the first one does travel under the
+    // last taps (except on 8-wide maps, where the seventh patch piece takes the room).
     constexpr int ESETS = 2;
     u32x4 em[ESETS][BWD && !BITS ? 4 : 1], ea[ESETS][BWD ? 4 : 1];
     u32x2 eb[ESETS];   // BITS: the mask bits of the tile's 64 channels at this lane's position (byte b*4 + q*2 + h: piece (b, q))
@@ -271,7 +273,7 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
         const int toff = (p.flip ? (2 - u) * PW + (2 - v) : u * PW + v) * kRow;
         const int un = (tap + 1) / 3, vn = (tap + 1) - un * 3;
         const int toff_next = (p.flip ? (2 - un) * PW + (2 - vn) : un * PW + vn) * kRow;
-        if (BWD && MA == 4 && tap == 6 && last_slice) load_epi(0, 0);
+        if (BWD && (MA == 4 || (BITS && !W8)) && tap == 6 && last_slice) load_epi(0, 0);
 #pragma unroll
         for (int kk = 0; kk < KK; ++kk) {
           const int step = tap * KK + kk;
@@ -331,7 +333,8 @@ __global__ __launch_bounds__(kThreads, MA == 4 ? 1 : 2) void conv3_wide_kernel(W
         for (int e = 0; e < 4; ++e) { bias8[bq][e] = b0[e]; bias8[bq][4 + e] = b1[e]; }
       }
     }
-    if (BWD && MA == 2) { load_epi(0, 0); load_epi(1, 1); }
+    if (BWD && MA == 2 && !(BITS && !W8)) load_epi(0, 0);
+    if (BWD && MA == 2) load_epi(1, 1);
     // STATS: sv[which*32 + (b*2+q)*8 + e]: sums over this lane's positions of the stored values (which = 0) and
     // of their squares (1)
     float sv[STATS ? 64 : 1];

@@ -53,6 +53,7 @@ struct S2Params {
   int units, upw;
   const void* zero;
   const bf16_t* mask;
+  const uint8_t* mask_bits;   // may be null: the mask at one bit per element, [rows*H*W][N/8] (N a multiple of 64)
   const bf16_t* addend;
   int accumulate;
 };
@@ -227,14 +228,19 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
     // ---- epilogue, straight from registers (see conv3_wide_bf16.hip): after the swap of the wavefront's halves
     // lane (j, h) holds channels b*32 + q*16 + 8h .. +7 of its position of class a
     u32x4 em[2][4], ea[2][4];   // mask and addend / old dx of class a: fetched one class ahead
+    u32x2 eb[2];                // the mask as bits: the 8 bytes of the tile's 64 channels at this lane's position
     auto load_epi = [&](int a, int set) {
       const size_t row = (size_t)(out_base + ipos[a]) * p.N;
       const bf16_t* other = p.addend ? p.addend : (p.accumulate ? p.dx : nullptr);
+      const bf16_t* mask = p.mask_bits ? nullptr : p.mask;
+      eb[set] = *reinterpret_cast<const u32x2*>((ipos[a] < npos && p.mask_bits)
+                                                    ? p.mask_bits + ((size_t)(out_base + ipos[a]) * (p.N >> 3) + (col0 >> 3))
+                                                    : static_cast<const uint8_t*>(p.zero));
 #pragma unroll
       for (int bq = 0; bq < 4; ++bq) {
         const int c = col0 + (bq >> 1) * 32 + (bq & 1) * 16 + h * 8;
         const bool in = ipos[a] < npos && c < p.N;
-        em[set][bq] = *reinterpret_cast<const u32x4*>((in && p.mask) ? p.mask + row + c : zp);
+        em[set][bq] = *reinterpret_cast<const u32x4*>((in && mask) ? mask + row + c : zp);
         ea[set][bq] = *reinterpret_cast<const u32x4*>((in && other) ? other + row + c : zp);
       }
     };
@@ -263,7 +269,11 @@ __global__ __launch_bounds__(kThreads, 1) void conv3s2_dgrad_kernel(S2Params p) 
 #pragma unroll
             for (int d = 0; d < 4; ++d) { val[2 * d] += bf16_lo(ad[d]); val[2 * d + 1] += bf16_hi(ad[d]); }
           }
-          if (p.mask) {
+          if (p.mask_bits) {
+            const uint32_t byte = eb[a & 1][b] >> (8 * (2 * qq + h));
+#pragma unroll
+            for (int e = 0; e < 8; ++e) val[e] = ((byte >> e) & 1u) ? val[e] : 0.f;
+          } else if (p.mask) {
 #pragma unroll
             for (int d = 0; d < 4; ++d) {
               val[2 * d] = bf16_lo(mk[d]) > 0.f ? val[2 * d] : 0.f;
@@ -300,7 +310,8 @@ bool conv3s2_dgrad_supported(int rows, int H, int W, int Cin, int Cout, int Cout
 
 bool conv3s2_dgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* wt, int Cout, const bf16_t* dy_sc,
                         const bf16_t* wt_sc, int Cout_sc, bf16_t* dx, int rows, int H, int W, int Cin,
-                        const bf16_t* mask, bool accumulate, const bf16_t* addend, const void* zero) {
+                        const bf16_t* mask, bool accumulate, const bf16_t* addend, const void* zero,
+                        const uint8_t* mask_bits) {
   if (!conv3s2_dgrad_supported(rows, H, W, Cin, Cout, dy_sc ? Cout_sc : 0)) return false;
   if (dy_sc && !wt_sc) return false;
   const int R = std::min(H, kUnit / W);
@@ -312,6 +323,7 @@ bool conv3s2_dgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* wt, int 
   p.dy = dy; p.wt = wt; p.dys = dy_sc; p.wts = wt_sc; p.dx = dx;
   p.rows = rows; p.H = H; p.W = W; p.Cs = Cout; p.Cs2 = dy_sc ? Cout_sc : 0; p.N = Cin;
   p.R = R; p.nimg = nimg; p.zero = zero; p.mask = mask; p.addend = addend; p.accumulate = accumulate ? 1 : 0;
+  p.mask_bits = (mask && Cin % kTN == 0) ? mask_bits : nullptr;
   int upw = 1;
   while (upw < 8 && (long)units * tiles_n / (upw * 2) >= 1024) upw *= 2;
   p.units = units; p.upw = upw;

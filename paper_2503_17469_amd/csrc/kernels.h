@@ -160,7 +160,9 @@ bool conv3_wide_bf16(hipStream_t st, const bf16_t* src, const bf16_t* wgt, bf16_
 bool conv3s2_dgrad_supported(int rows, int H, int W, int Cin, int Cout, int Cout_sc);
 bool conv3s2_dgrad_bf16(hipStream_t st, const bf16_t* dy, const bf16_t* wt, int Cout, const bf16_t* dy_sc,
                         const bf16_t* wt_sc, int Cout_sc, bf16_t* dx, int rows, int H, int W, int Cin,
-                        const bf16_t* mask, bool accumulate, const bf16_t* addend, const void* zero);
+                        const bf16_t* mask, bool accumulate, const bf16_t* addend, const void* zero,
+                        const uint8_t* mask_bits = nullptr);
+// (mask_bits: as ConvGeom::mask_bits.)
 // (addend, [M][N] or null, is added to the product before the mask: the input gradient of a layer
 // whose input also feeds a residual add takes the add's share along instead of a separate pass.)
 // Per worker k: gw_k[Cout][taps][cin_real] = dy_k^T gather(src)_k, gb_k = column sums of dy_k (gb may be null).

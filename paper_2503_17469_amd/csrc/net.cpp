@@ -845,7 +845,8 @@ void step_bf16(StepCtx& c) {
         dgrad_done = omni::conv3s2_dgrad_bf16(
             st, grad(L.out), shadow + L.wt_off, L.d.cout, sc >= 0 ? grad(net->layers[sc].out) : nullptr,
             sc >= 0 ? shadow + net->layers[sc].wt_off : nullptr, sc >= 0 ? net->layers[sc].d.cout : 0, grad(L.in0), rows,
-            L.ih, L.iw, L.cin_pad, ti.relu ? act(L.in0) : nullptr, written[L.in0] != 0, addend, conv_counters);
+            L.ih, L.iw, L.cin_pad, ti.relu ? act(L.in0) : nullptr, written[L.in0] != 0, addend, conv_counters,
+            (ti.relu && bits_written[L.in0]) ? sign_bits(L.in0) : nullptr);
         if (dgrad_done) { pending_add[L.in0] = nullptr; written[L.in0] = 1; }
         // (entry_partner asked conv3s2_dgrad_supported with these very shapes: a projection is never left behind)
       }
