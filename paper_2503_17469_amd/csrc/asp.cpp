@@ -1,40 +1,52 @@
 // Asynchronous training, Algorithm 2, host side: the order in which simulated workers of
 // different speeds push to the parameter server (exact integer arithmetic), and the
-// server's batch-size bookkeeping (procedure evalBsz with its wrkB / wrkTime maps, getBsz
-// as in Algorithm 1).  Doubles are combined one operation per statement and this file is
-// compiled without floating-point contraction, so the integers they decide repeat bit for
-// bit on any conforming host.
+// server's batch-size bookkeeping (what procedure evalBsz of Algorithm 2 keeps and decides).
+// Doubles are combined one operation per statement and this file is compiled without
+// floating-point contraction, so the integers they decide repeat bit for bit on any
+// conforming host.
 #include <cmath>
 #include <new>
 
 #include "common.h"
 
+// The server's view of its workers as plain arrays: the latest batch size and iteration time each one
+// reported, and which of them have reported at all.  Nothing is resized until every worker has been heard
+// from; from then on EVERY report triggers a re-evaluation of all sizes against the mean of the latest times.
 struct omni_asp_ps {
   int32_t K, b_min, b_max;
   double deadband;
-  int32_t reported;                       // how many distinct workers have reported so far
-  bool has[OMNI_MAX_WORKERS];
-  int32_t wrk_b[OMNI_MAX_WORKERS];
-  double wrk_time[OMNI_MAX_WORKERS];
+  int32_t heard;                          // distinct workers heard from so far
+  bool known[OMNI_MAX_WORKERS];
+  int32_t size[OMNI_MAX_WORKERS];
+  double seconds[OMNI_MAX_WORKERS];
 };
 
 namespace {
 
 typedef unsigned __int128 u128;
 
-inline double clampd(double x, double lo, double hi) { return x < lo ? lo : (x > hi ? hi : x); }
-
-// Procedure getBsz of Algorithm 1 for one worker.
-int32_t get_bsz(int32_t b, double t, double t_avg, double deadband, int32_t b_min, int32_t b_max) {
-  const double bk = (double)b;
-  const double T = bk / t;
-  const double tau = t - t_avg;
-  const double delta = T * tau;
-  const double bs = bk - delta;
-  const double diff = bs - bk;
-  const double q = diff / bs;
-  if (std::fabs(q) >= deadband) return (int32_t)std::nearbyint(clampd(bs, (double)b_min, (double)b_max));
-  return b;
+// One pass over all workers (section "Dynamic-Batching", eqs itrtimeerror and dynbszadjust, with the bounds
+// and the dead-band of procedure getBsz): a worker's throughput at its current size, times its distance from
+// the mean iteration time, is how many samples it should hand over (or take on); the move is made only if it
+// changes the size by at least the dead-band fraction of the proposed size, and lands inside [b_min, b_max].
+// One floating-point operation per statement, no contraction: the integers repeat bit for bit elsewhere.
+void resize_all(omni_asp_ps& ps) {
+  double total = 0.0;
+  for (int w = 0; w < ps.K; ++w) total = total + ps.seconds[w];
+  const double mean = total / (double)ps.K;
+  const double lo = (double)ps.b_min, hi = (double)ps.b_max;
+  for (int w = 0; w < ps.K; ++w) {
+    const double now = (double)ps.size[w];
+    const double rate = now / ps.seconds[w];
+    const double late = ps.seconds[w] - mean;
+    const double surplus = rate * late;
+    const double proposed = now - surplus;
+    const double change = proposed - now;
+    const double relative = change / proposed;
+    if (!(std::fabs(relative) >= ps.deadband)) continue;   // inside the dead-band (or not a number): leave it
+    const double bounded = proposed < lo ? lo : (proposed > hi ? hi : proposed);
+    ps.size[w] = (int32_t)std::nearbyint(bounded);
+  }
 }
 
 }  // namespace
@@ -80,8 +92,8 @@ int omni_asp_ps_create(int32_t K, int32_t b_min, int32_t b_max, double deadband,
   if (!(deadband >= 0.0 && deadband < 1.0)) return fail(OMNI_EINVAL, "omni_asp_ps_create: dead-band must lie in [0, 1)");
   omni_asp_ps* p = new (std::nothrow) omni_asp_ps();
   if (!p) return fail(OMNI_EINVAL, "omni_asp_ps_create: out of host memory");
-  p->K = K; p->b_min = b_min; p->b_max = b_max; p->deadband = deadband; p->reported = 0;
-  for (int k = 0; k < K; ++k) { p->has[k] = false; p->wrk_b[k] = 0; p->wrk_time[k] = 0.0; }
+  p->K = K; p->b_min = b_min; p->b_max = b_max; p->deadband = deadband; p->heard = 0;
+  for (int k = 0; k < K; ++k) { p->known[k] = false; p->size[k] = 0; p->seconds[k] = 0.0; }
   *out = p;
   return OMNI_OK;
 }
@@ -92,23 +104,17 @@ int omni_asp_ps_eval_bsz(omni_asp_ps* ps, int32_t k, int32_t b, double t, int32_
   if (k < 0 || k >= ps->K) return fail(OMNI_EINVAL, "omni_asp_ps_eval_bsz: worker %d out of range", k);
   if (b < 1) return fail(OMNI_EINVAL, "omni_asp_ps_eval_bsz: b=%d", b);
   if (!(t > 0.0) || std::isinf(t)) return fail(OMNI_EINVAL, "omni_asp_ps_eval_bsz: t must be positive and finite");
-  if (!ps->has[k]) { ps->has[k] = true; ps->reported += 1; }
-  ps->wrk_b[k] = b;
-  ps->wrk_time[k] = t;
-  if (ps->reported == ps->K) {
-    double s = 0.0;
-    for (int w = 0; w < ps->K; ++w) s = s + ps->wrk_time[w];
-    const double t_avg = s / (double)ps->K;
-    for (int w = 0; w < ps->K; ++w)
-      ps->wrk_b[w] = get_bsz(ps->wrk_b[w], ps->wrk_time[w], t_avg, ps->deadband, ps->b_min, ps->b_max);
-  }
-  *b_out = ps->wrk_b[k];
+  if (!ps->known[k]) { ps->known[k] = true; ps->heard += 1; }
+  ps->size[k] = b;
+  ps->seconds[k] = t;
+  if (ps->heard == ps->K) resize_all(*ps);
+  *b_out = ps->size[k];
   return OMNI_OK;
 }
 
 int omni_asp_ps_sizes(const omni_asp_ps* ps, int32_t* b_out) {
   if (!ps || !b_out) return omni::fail(OMNI_EINVAL, "omni_asp_ps_sizes: NULL argument");
-  for (int k = 0; k < ps->K; ++k) b_out[k] = ps->has[k] ? ps->wrk_b[k] : 0;
+  for (int k = 0; k < ps->K; ++k) b_out[k] = ps->known[k] ? ps->size[k] : 0;
   return OMNI_OK;
 }
 

@@ -247,6 +247,42 @@ def test_asp_schedule_errors():
     assert omni.asp_schedule([3], [2], 0) == ([], [])
 
 
+def test_asp_server_resizes_as_worked_by_hand():
+    """The server's bookkeeping against numbers worked on paper (procedure evalBsz of Algorithm 2 with the
+    proportional rule of section "Dynamic-Batching"), independent of the oracle's code.
+
+    Two workers at size 32 with iteration times 2 s and 1 s: mean 1.5 s.  Worker 0 processes 16 samples/s and
+    is 0.5 s late: it hands over 8 (-> 24).  Worker 1 processes 32 samples/s and is 0.5 s early: it takes
+    on 16 (-> 48).  The changes are a third of the proposed sizes."""
+    def run(dead, b_min, b_max):
+        ps = omni.asp_ps_create(2, b_min, b_max, dead)
+        try:
+            first = omni.asp_ps_eval_bsz(ps, 0, 32, 2.0)        # only one worker heard from: nothing moves
+            assert first == 32 and omni.asp_ps_sizes(ps, 2) == [32, 0]
+            second = omni.asp_ps_eval_bsz(ps, 1, 32, 1.0)       # all heard from: every size is re-evaluated
+            return second, omni.asp_ps_sizes(ps, 2)
+        finally:
+            omni.asp_ps_destroy(ps)
+    assert run(0.0, 1, 1024) == (48, [24, 48])
+    assert run(0.30, 1, 1024) == (48, [24, 48])                 # 1/3 >= 0.30: both moves pass the dead-band
+    assert run(0.34, 1, 1024) == (32, [32, 32])                 # 1/3 < 0.34: both stay
+    assert run(0.0, 28, 40) == (40, [28, 40])                   # clamped to [b_min, b_max]
+    # three workers, times 1, 2, 3 s at size 30: mean 2 s; worker 0: 30 - 30 * (-1) = 60, worker 1 stays,
+    # worker 2: 30 - 10 * 1 = 20; a later report re-evaluates everybody with the latest numbers:
+    # worker 0 at size 60 now takes 2 s: mean 7/3; 60 - 30 * (2 - 7/3) = 70; worker 1: 30 - 15 * (2 - 7/3) = 35;
+    # worker 2 (size 20 as resized, time 3 s as last reported): 20 - (20/3) * (3 - 7/3) = 20 - 40/9 = 15.56 -> 16
+    ps = omni.asp_ps_create(3, 1, 1024, 0.0)
+    try:
+        assert omni.asp_ps_eval_bsz(ps, 0, 30, 1.0) == 30
+        assert omni.asp_ps_eval_bsz(ps, 1, 30, 2.0) == 30
+        assert omni.asp_ps_eval_bsz(ps, 2, 30, 3.0) == 20
+        assert omni.asp_ps_sizes(ps, 3) == [60, 30, 20]
+        assert omni.asp_ps_eval_bsz(ps, 0, 60, 2.0) == 70
+        assert omni.asp_ps_sizes(ps, 3) == [70, 35, 16]
+    finally:
+        omni.asp_ps_destroy(ps)
+
+
 def test_asp_eval_bsz_matches_oracle_bit_for_bit():
     from oracle import asp as OA
     import random
