@@ -115,21 +115,27 @@ def cpu_baseline(w, rows, budget_s=12.0):
 
 
 def measured_traffic(workload, key):
-    """HBM bytes per launch from the committed counter summary of this workload, or None.
+    """HBM bytes (per launch, or per step for a kernel class) from the committed counter summary of this
+    workload, or None.
 
-    The summary carries the hash of the kernel's source file at the time the counters were
-    taken; a figure for a kernel that has changed since is not reported."""
+    The summary carries the hash of every source file the kernels live in, taken when the counters were;
+    a figure for kernels that have changed since is not reported."""
     import hashlib
     import re
     path = os.path.join(ROOT, "profiles", f"step_{workload}_hbm_traffic.md")
     if not os.path.exists(path):
         return None
+
+    def unchanged(src, sha):
+        full = os.path.join(ROOT, src)
+        return os.path.exists(full) and hashlib.sha256(open(full, "rb").read()).hexdigest() == sha
+
     for line in open(path):
-        m = re.match(r"\s*traffic (.+?) bytes=(\S+) source=(\S+) sha256=([0-9a-f]{64})\s*$", line)
+        m = re.match(r"\s*traffic (.+?) bytes=(\S+) ((?:source=\S+ sha256=[0-9a-f]{64}\s*)+)$", line)
         if not m or m.group(1) != key:
             continue
-        src = os.path.join(ROOT, m.group(3))
-        if os.path.exists(src) and hashlib.sha256(open(src, "rb").read()).hexdigest() == m.group(4):
+        pairs = re.findall(r"source=(\S+) sha256=([0-9a-f]{64})", m.group(3))
+        if pairs and all(unchanged(src, sha) for src, sha in pairs):
             return float(m.group(2))
     return None
 
@@ -220,7 +226,9 @@ class Job:
             label = f"{cls}: all {n // steps} launches of a step, layers {idx[0]}..{idx[-1]}, time-weighted"
             out.append({"bound": "mfma", "kernel": label, "achieved": ach, "peak": PEAK_TFLOPS[w.dtype],
                         "unit": "TFLOP/s", "frac": ach / PEAK_TFLOPS[w.dtype],
-                        "traffic": measured_traffic(w.name, cls), "flop_per_step": flops,
+                        "traffic": measured_traffic(w.name, cls),
+                        "traffic_note": "HBM bytes of all the class's launches in a step, by counters",
+                        "flop_per_step": flops,
                         "us_per_step": per_step_s * 1e6, "avg_launch_us": ms * 1e3 / n, "launches": int(n),
                         "steps": steps})
         return out
