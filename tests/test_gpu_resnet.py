@@ -120,6 +120,20 @@ def test_resnet18_block_shapes(cin, cout, stride, hw, B):
     _check(layers, (hw, hw, cin), params, x, y, cuts, 0.1, f"block {cin}->{cout} s{stride} {hw}px")
 
 
+@pytest.mark.parametrize("cin,cout,stride,h,w,B", [
+    (64, 128, 2, 8, 16, 48),     # 4 x 8 output maps: the stride-2 weight gradient takes units of two images
+    (64, 128, 2, 16, 32, 24),    # 8 x 16 output maps
+    (128, 128, 1, 8, 16, 40),    # wider than high: the 3x3 kernels' unit geometry with rows of 16
+    (64, 64, 1, 16, 8, 40),      # higher than wide
+])
+def test_block_on_maps_that_are_not_square(cin, cout, stride, h, w, B):
+    layers = _block_net(cin, cout, stride, 0)
+    params = _params(layers, cin + cout + h)
+    x, y = synth.make_batch(cin * 5 + h, B, (h, w, cin), 10, True)
+    cuts = sorted({0, B // 5 + 1, B // 2 + 3, B})
+    _check(layers, (h, w, cin), params, x, y, cuts, 0.1, f"block {cin}->{cout} s{stride} {h}x{w}")
+
+
 def test_resnet18_reduced_batch():
     """The whole ResNet-18-shaped net.  A freshly initialised ReLU + batch-norm network amplifies
     any perturbation by roughly 1.4x per layer, forwards and backwards, so two correct bf16
