@@ -134,6 +134,31 @@ def test_block_on_maps_that_are_not_square(cin, cout, stride, h, w, B):
     _check(layers, (h, w, cin), params, x, y, cuts, 0.1, f"block {cin}->{cout} s{stride} {h}x{w}")
 
 
+@pytest.mark.parametrize("cin,cout,stride,hw,B", [(64, 64, 1, 32, 24), (64, 128, 2, 32, 24), (256, 512, 2, 8, 96)])
+def test_block_is_reproducible_on_a_dirty_workspace(cin, cout, stride, hw, B):
+    """Real layer shapes (the kernels with statistics summed by the convolution, ReLU masks as bits, chunked
+    weight gradients and their partial tiles): with the whole workspace set to 0xFF before every step, every
+    step gives bit-identical results -- nothing is carried over in the workspace, and no result depends on the
+    order in which workgroups finish."""
+    layers = _block_net(cin, cout, stride, hw)
+    params = _params(layers, cin + 3 * cout)
+    x, y = synth.make_batch(cin + stride + B, B, (hw, hw, cin), 10, True)
+    off = sorted({0, B // 7 + 1, B // 3 + 2, B})
+    run = GpuRun(layers, (hw, hw, cin), "bf16", len(off) - 1, B)
+    try:
+        run.ws.fill_(0xFF)
+        first = run.step(params, x, y, off, 0.1)
+        assert first["status"] == 0 and np.all(np.isfinite(first["worker_grads"]))
+        for _ in range(3):
+            run.ws.fill_(0xFF)
+            again = run.step(params, x, y, off, 0.1)
+            assert np.array_equal(again["params"], first["params"])
+            assert np.array_equal(again["worker_grads"], first["worker_grads"])
+            assert again["loss"] == first["loss"] and again["status"] == 0
+    finally:
+        run.close()
+
+
 def test_resnet18_reduced_batch():
     """The whole ResNet-18-shaped net.  A freshly initialised ReLU + batch-norm network amplifies
     any perturbation by roughly 1.4x per layer, forwards and backwards, so two correct bf16
